@@ -1,0 +1,333 @@
+/*
+ * rps_oracle.c -- plain CPU oracle for the RPS lossy model-averaging round.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, obviously-correct reference
+ * that the HIP library is checked against.  It shares no code with the HIP
+ * path and must never be linked into, imported by, or called from it.  Only the
+ * test-suite, the smoke check and the benchmark's CPU-baseline leg may use it.
+ *
+ * What it computes (paper: "Distributed Learning over Unreliable Networks",
+ * arXiv 1810.07766):
+ *   - the local SGD step  v = x - gamma * g               (Sec. 4.1, Alg. 1 step 5)
+ *   - the Reduce-Scatter step with drops: the server of block j averages the
+ *     copies of block j that reach it                      (Sec. 4.1 RS, Alg. 1 step 6)
+ *   - the All-Gather step with drops: a worker overwrites block j with the
+ *     average iff the reply reaches it, else keeps its own v   (Sec. 4.1 AG,
+ *     eq. (dividex), Alg. 1 steps 7-8)
+ *   - the mixing matrix W of the global view X_{t+1} = V_t W_t  (Sec. 4.2,
+ *     eq. (updatingrule))
+ * The paper fixes only the distribution of the random events (independent
+ * drops with probability p, Sec. 3; server chosen uniformly without
+ * replacement, Alg. 1 step 6).  The bit-level random-number specification
+ * (counter-based Philox4x32 hash, Bernoulli threshold, rank-sort permutation,
+ * synthetic Gaussian gradient noise) is this project's own and is written out
+ * below in full; the HIP side implements the same specification separately.
+ *
+ * Parity status: every function here is pinned by tests that do not call the
+ * HIP path (published Philox known-answer vectors, closed forms, brute-force
+ * enumeration of all mask patterns against the paper's binomial sums, exact
+ * averaging at p = 0, the textbook Box-Muller definition in double precision).
+ * The paper's own convergence-loss numbers (Sec. 6) need its datasets and
+ * framework: parity unpinned for those; they are not computed here.
+ *
+ * Arithmetic: element values are fp32 (or bf16 storage widened to fp32); the
+ * average is accumulated in double and rounded once to fp32, then to storage.
+ * Compile WITHOUT floating-point contraction (-ffp-contract=off): every fused
+ * multiply-add below is an explicit fmaf().
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* ------------------------------------------------------------------------- */
+/* Counter-based hash: Philox4x32 (Salmon, Moraes, Dror, Shaw, SC'11).        */
+/* One round: two 32x32->64 products, a word permutation, xor with the key;   */
+/* the key is bumped by the two Weyl constants between rounds.                */
+/* ------------------------------------------------------------------------- */
+void rps_oracle_philox4x32(uint32_t rounds, const uint32_t ctr[4],
+                           const uint32_t key[2], uint32_t out[4])
+{
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+    uint32_t k0 = key[0], k1 = key[1];
+    for (uint32_t r = 0; r < rounds; ++r) {
+        if (r > 0) { k0 += 0x9E3779B9u; k1 += 0xBB67AE85u; }
+        uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+        uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+        uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        uint32_t n1 = (uint32_t)p1;
+        uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        uint32_t n3 = (uint32_t)p0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+enum { DOMAIN_UPLINK = 0, DOMAIN_DOWNLINK = 1, DOMAIN_SERVER = 2, DOMAIN_NOISE = 3 };
+enum { MASK_ROUNDS = 10, NOISE_ROUNDS = 10 };
+
+/* word 0 of the hash of (a, b, step, domain) under the 64-bit seed.          */
+static void hash_words(uint32_t rounds, uint64_t seed, uint64_t step,
+                       uint32_t a, uint32_t b, uint32_t domain, uint32_t out[4])
+{
+    uint32_t ctr[4] = { a, b, (uint32_t)step,
+                        (domain << 24) | (uint32_t)((step >> 32) & 0xFFFFFFu) };
+    uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) };
+    rps_oracle_philox4x32(rounds, ctr, key, out);
+}
+
+/* ------------------------------------------------------------------------- */
+/* Network outcome of one round (Sec. 3 "Unreliable Network Connection";      */
+/* Alg. 1 steps 6-7).                                                         */
+/*   server[j] : the worker b_t^{(j)} that averages block j.  A uniformly     */
+/*               random permutation: every worker draws a 32-bit sort key,    */
+/*               workers are ranked by (key, index), and block j goes to the  */
+/*               worker of rank j.  identity_server != 0 gives server[j] = j  */
+/*               (the simplification the paper uses in its exposition).       */
+/*   U[i*n+j]  : 1 iff worker i's copy of block j reaches server[j].          */
+/*   D[i*n+j]  : 1 iff server[j]'s reply for block j reaches worker i.        */
+/* Every (worker, block, direction) message is lost independently with        */
+/* probability p: lost iff hash word < floor(p * 2^32).  A worker's message   */
+/* to itself never crosses the network, so U and D are forced to 1 for        */
+/* i == server[j] (supplement, Lemma 7 proof: the server "must receive its    */
+/* own block"; its weight is 1/(m+1) with m copies received from others).     */
+/* ------------------------------------------------------------------------- */
+void rps_oracle_masks(uint64_t seed, uint64_t step, int32_t n, double p,
+                      int32_t identity_server,
+                      int32_t *server, uint8_t *U, uint8_t *D)
+{
+    uint32_t w[4];
+    if (identity_server) {
+        for (int j = 0; j < n; ++j) server[j] = j;
+    } else {
+        uint32_t sortkey[64];
+        for (int i = 0; i < n; ++i) {
+            hash_words(MASK_ROUNDS, seed, step, (uint32_t)i, 0u, DOMAIN_SERVER, w);
+            sortkey[i] = w[0];
+        }
+        for (int i = 0; i < n; ++i) {
+            int rank = 0;
+            for (int k = 0; k < n; ++k)
+                if (sortkey[k] < sortkey[i] || (sortkey[k] == sortkey[i] && k < i))
+                    ++rank;
+            server[rank] = i;
+        }
+    }
+    const uint64_t threshold = (uint64_t)floor(p * 4294967296.0);
+    for (int i = 0; i < n; ++i) {
+        for (int j = 0; j < n; ++j) {
+            hash_words(MASK_ROUNDS, seed, step, (uint32_t)i, (uint32_t)j, DOMAIN_UPLINK, w);
+            U[i * n + j] = ((uint64_t)w[0] < threshold) ? 0 : 1;
+            hash_words(MASK_ROUNDS, seed, step, (uint32_t)i, (uint32_t)j, DOMAIN_DOWNLINK, w);
+            D[i * n + j] = ((uint64_t)w[0] < threshold) ? 0 : 1;
+            if (i == server[j]) { U[i * n + j] = 1; D[i * n + j] = 1; }
+        }
+    }
+}
+
+/* ------------------------------------------------------------------------- */
+/* Synthetic gradient noise (this project's specification; the paper's        */
+/* stochastic gradient is whatever the framework computes, Alg. 1 steps 3-4). */
+/* One hash call yields eight values sigma*z for the eight columns 8g..8g+7   */
+/* of one worker.  Each 32-bit word makes one Box-Muller pair from a 16-bit   */
+/* radius index (low half) and a 16-bit angle index (high half):              */
+/*     u1 = (2k+1)/2^17,  r = sqrt(-2 ln u1),  phi = (2f+1)*pi/65536 (+pi)    */
+/* evaluated with a fixed sequence of fp32 operations (polynomials for the    */
+/* logarithm, sine and cosine; two Newton steps for the reciprocal square     */
+/* root) so that any IEEE-754 machine produces the same bits.                 */
+/* ------------------------------------------------------------------------- */
+static float as_float(uint32_t u) { float f; memcpy(&f, &u, 4); return f; }
+static uint32_t as_uint(float f) { uint32_t u; memcpy(&u, &f, 4); return u; }
+
+static int clz32(uint32_t v)        /* v != 0 */
+{
+    int n = 0;
+    while (!(v & 0x80000000u)) { v <<= 1; ++n; }
+    return n;
+}
+
+static void box_muller_pair(uint32_t word, float sigma, float *even, float *odd)
+{
+    /* radius: u1 = a / 2^17 with a odd; -log2(u1) = lz + (1 - log2 m), m in [1,2) */
+    uint32_t a   = ((word & 0xFFFFu) << 1) | 1u;
+    int      nlz = clz32(a);                          /* 15..31 */
+    float    m   = as_float((a << (nlz - 8)) + 0x3F000000u);
+    float    w   = 2.0f - m;                          /* (0,1], exact */
+    float    lzf = (float)(nlz - 15);
+    /* -2 ln(1 - w/2) = w * Rc(w), degree-4 fit of Rc on [0,1] */
+    float q = fmaf(w, 0x1.767762p-5f, -0x1.6ad1d8p-8f);
+    q = fmaf(w, q, 0x1.9117f8p-4f);
+    q = fmaf(w, q, 0x1.fc1588p-3f);
+    q = fmaf(w, q, 0x1.000288p+0f);
+    float t = w * q;
+    float L = fmaf(lzf, 0x1.62e430p+0f /* 2 ln 2 */, t);   /* = -2 ln u1 */
+    /* r = L * rsqrt(L): bit-trick seed, two Newton steps y <- y (1.5 - (L/2) y^2) */
+    float h = 0.5f * L;
+    float y = as_float(0x5F3759DFu - (as_uint(L) >> 1));
+    y = y * fmaf(-h, y * y, 1.5f);
+    y = y * fmaf(-h, y * y, 1.5f);
+    float r  = L * y;
+    float rs = sigma * r;
+    /* angle: x = (2f+1) pi / 65536, f = signed 15-bit field, |x| < pi/2;
+       bit 31 adds pi, i.e. flips the sign of both outputs */
+    int32_t f  = (int32_t)(word << 1) >> 17;
+    float   x  = (float)(2 * f + 1) * 0x1.921fb6p-15f;     /* pi / 65536 */
+    float   x2 = x * x;
+    float sp = fmaf(x2, -0x1.8b3e4ep-13f, 0x1.10c46cp-7f);
+    sp = fmaf(x2, sp, -0x1.5554aep-3f);
+    float sn = fmaf(x * x2, sp, x);
+    float cp = fmaf(x2, -0x1.54c10ap-10f, 0x1.54aa20p-5f);
+    cp = fmaf(x2, cp, -0x1.fffd12p-2f);
+    float cs = fmaf(x2, cp, 1.0f);
+    float rsgn = as_float(as_uint(rs) | (word & 0x80000000u));
+    *even = rsgn * cs;
+    *odd  = rsgn * sn;
+}
+
+void rps_oracle_noise8(uint64_t seed, uint64_t step, int32_t worker,
+                       uint64_t group, float sigma, float out[8])
+{
+    uint32_t w[4];
+    hash_words(NOISE_ROUNDS, seed, step, (uint32_t)group, (uint32_t)worker, DOMAIN_NOISE, w);
+    for (int q = 0; q < 4; ++q)
+        box_muller_pair(w[q], sigma, &out[2 * q], &out[2 * q + 1]);
+}
+
+/* ------------------------------------------------------------------------- */
+/* Storage formats.  dtype 0: fp32.  dtype 1: bf16 (upper 16 bits of an fp32, */
+/* round-to-nearest-even on every store).                                     */
+/* ------------------------------------------------------------------------- */
+static uint16_t f32_to_bf16(float f)
+{
+    uint32_t u = as_uint(f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x0040u); /* NaN */
+    uint32_t lsb = (u >> 16) & 1u;
+    u += 0x7FFFu + lsb;
+    return (uint16_t)(u >> 16);
+}
+static float bf16_to_f32(uint16_t b) { return as_float((uint32_t)b << 16); }
+
+static float load_elem(const void *base, int32_t dtype, int64_t idx)
+{
+    return dtype == 0 ? ((const float *)base)[idx] : bf16_to_f32(((const uint16_t *)base)[idx]);
+}
+static void store_elem(void *base, int32_t dtype, int64_t idx, float v)
+{
+    if (dtype == 0) ((float *)base)[idx] = v; else ((uint16_t *)base)[idx] = f32_to_bf16(v);
+}
+static float round_storage(int32_t dtype, float v)
+{
+    return dtype == 0 ? v : bf16_to_f32(f32_to_bf16(v));
+}
+
+/* ------------------------------------------------------------------------- */
+/* Local SGD step, Alg. 1 steps 3-5:  v = x - gamma * g  for every worker.    */
+/* X is [n, m] row-major (worker-major), updated in place.  Column k of the   */
+/* array is model coordinate cols[k] (cols == NULL: coordinate k), which      */
+/* only matters for the synthetic gradient's noise index.                     */
+/*   G != NULL : g = G[i,k]                        (caller's gradient)        */
+/*   G == NULL : g = lambda * x + sigma * z        (synthetic gradient)       */
+/* v is rounded to the storage format: the wire carries what is stored.       */
+/* ------------------------------------------------------------------------- */
+void rps_oracle_local_step(void *X, const void *G, int32_t n, int64_t m,
+                           const int64_t *cols, int32_t dtype, float gamma,
+                           float sigma, float lambda, uint64_t seed,
+                           uint64_t step, int32_t threads)
+{
+    (void)threads;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(static) num_threads(threads > 0 ? threads : 1)
+#endif
+    for (int32_t i = 0; i < n; ++i) {
+        uint64_t have_group = UINT64_MAX;   /* the eight noise values of one hash call */
+        float z[8];
+        for (int64_t k = 0; k < m; ++k) {
+            float x = load_elem(X, dtype, i * m + k);
+            float g;
+            if (G) {
+                g = load_elem(G, dtype, i * m + k);
+            } else {
+                int64_t c = cols ? cols[k] : k;
+                uint64_t group = (uint64_t)c >> 3;
+                if (group != have_group) {
+                    rps_oracle_noise8(seed, step, i, group, sigma, z);
+                    have_group = group;
+                }
+                g = fmaf(lambda, x, z[c & 7]);
+            }
+            float v = fmaf(-gamma, g, x);
+            store_elem(X, dtype, i * m + k, v);
+        }
+    }
+}
+
+/* ------------------------------------------------------------------------- */
+/* Lossy average, Alg. 1 steps 6-8.  V is [n, m] row-major, updated in place  */
+/* to X_{t+1}.  offsets[0..n] partitions the model coordinates into the n     */
+/* blocks (Sec. 4.1 eq. (dividev)); block j is [offsets[j], offsets[j+1]).    */
+/* For every column:                                                          */
+/*   RS:  vt = (1/|N_j|) sum_{i : U[i,j]=1} v[i]      (double accumulation,   */
+/*        one rounding to fp32, one to storage)                               */
+/*   AG:  x'[i] = D[i,j] ? vt : v[i]                                          */
+/* ------------------------------------------------------------------------- */
+static int32_t block_of(const int64_t *offsets, int32_t n, int64_t c)
+{
+    int32_t j = 0;
+    while (j + 1 < n && c >= offsets[j + 1]) ++j;
+    return j;
+}
+
+void rps_oracle_lossy_average(void *V, int32_t n, int64_t m, const int64_t *cols,
+                              const int64_t *offsets, const uint8_t *U,
+                              const uint8_t *D, int32_t dtype, int32_t threads)
+{
+    (void)threads;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(static) num_threads(threads > 0 ? threads : 1)
+#endif
+    for (int64_t k = 0; k < m; ++k) {
+        int64_t c = cols ? cols[k] : k;
+        int32_t j = block_of(offsets, n, c);
+        double sum = 0.0;
+        int32_t received = 0;
+        for (int32_t i = 0; i < n; ++i) {
+            if (U[i * n + j]) {
+                sum += (double)load_elem(V, dtype, i * m + k);
+                ++received;
+            }
+        }
+        /* received >= 1: the server always holds its own copy */
+        float vt = round_storage(dtype, (float)(sum / (double)received));
+        for (int32_t i = 0; i < n; ++i)
+            if (D[i * n + j]) store_elem(V, dtype, i * m + k, vt);
+    }
+}
+
+/* ------------------------------------------------------------------------- */
+/* Mixing matrix of block j, Sec. 4.2 eq. (updatingrule): X^{(j)} = V^{(j)} W */
+/* with V^{(j)}'s columns the workers' blocks.  W[m*n + k] is the weight of   */
+/* worker m's block in worker k's result: column k is U[:,j]/|N_j| if the     */
+/* reply reached k, else the unit vector e_k.                                 */
+/* ------------------------------------------------------------------------- */
+void rps_oracle_build_W(int32_t n, int32_t j, const uint8_t *U, const uint8_t *D, double *W)
+{
+    int32_t received = 0;
+    for (int32_t i = 0; i < n; ++i) received += U[i * n + j] ? 1 : 0;
+    for (int32_t k = 0; k < n; ++k)
+        for (int32_t mm = 0; mm < n; ++mm) {
+            if (D[k * n + j]) W[mm * n + k] = U[mm * n + j] ? 1.0 / (double)received : 0.0;
+            else              W[mm * n + k] = (mm == k) ? 1.0 : 0.0;
+        }
+}
+
+int32_t rps_oracle_max_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}

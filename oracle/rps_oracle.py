@@ -1,0 +1,156 @@
+"""ctypes binding of the plain-C CPU oracle (oracle/rps_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, the smoke check and the
+benchmark's CPU-baseline leg; never by the HIP library or its Python binding.
+Every function only marshals numpy arrays; the arithmetic is all in the C file,
+whose comments cite the passages of arXiv 1810.07766 it follows.
+
+Arrays: X, V, G are numpy [n, m], C-contiguous, float32 (dtype code 0) or
+uint16 holding bf16 bit patterns (dtype code 1).  Masks are uint8 [n, n]
+indexed [worker, block]; server is int32 [n].
+"""
+import ctypes
+import os
+
+import numpy as np
+
+from . import build as _build
+
+_lib = ctypes.CDLL(_build.build(force=False))
+
+_u8p = ctypes.POINTER(ctypes.c_uint8)
+_i32p = ctypes.POINTER(ctypes.c_int32)
+_i64p = ctypes.POINTER(ctypes.c_int64)
+_u32p = ctypes.POINTER(ctypes.c_uint32)
+_f32p = ctypes.POINTER(ctypes.c_float)
+_f64p = ctypes.POINTER(ctypes.c_double)
+
+_lib.rps_oracle_philox4x32.argtypes = [ctypes.c_uint32, _u32p, _u32p, _u32p]
+_lib.rps_oracle_philox4x32.restype = None
+_lib.rps_oracle_masks.argtypes = [ctypes.c_uint64, ctypes.c_uint64, ctypes.c_int32, ctypes.c_double,
+                                  ctypes.c_int32, _i32p, _u8p, _u8p]
+_lib.rps_oracle_masks.restype = None
+_lib.rps_oracle_noise8.argtypes = [ctypes.c_uint64, ctypes.c_uint64, ctypes.c_int32, ctypes.c_uint64,
+                                   ctypes.c_float, _f32p]
+_lib.rps_oracle_noise8.restype = None
+_lib.rps_oracle_local_step.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64,
+                                       _i64p, ctypes.c_int32, ctypes.c_float, ctypes.c_float,
+                                       ctypes.c_float, ctypes.c_uint64, ctypes.c_uint64, ctypes.c_int32]
+_lib.rps_oracle_local_step.restype = None
+_lib.rps_oracle_lossy_average.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, _i64p, _i64p,
+                                          _u8p, _u8p, ctypes.c_int32, ctypes.c_int32]
+_lib.rps_oracle_lossy_average.restype = None
+_lib.rps_oracle_build_W.argtypes = [ctypes.c_int32, ctypes.c_int32, _u8p, _u8p, _f64p]
+_lib.rps_oracle_build_W.restype = None
+_lib.rps_oracle_max_threads.argtypes = []
+_lib.rps_oracle_max_threads.restype = ctypes.c_int32
+
+
+def max_threads() -> int:
+    return int(_lib.rps_oracle_max_threads())
+
+
+def philox4x32(ctr, key, rounds: int = 10) -> np.ndarray:
+    c = np.ascontiguousarray(ctr, dtype=np.uint32)
+    k = np.ascontiguousarray(key, dtype=np.uint32)
+    assert c.shape == (4,) and k.shape == (2,)
+    out = np.empty(4, dtype=np.uint32)
+    _lib.rps_oracle_philox4x32(rounds, c.ctypes.data_as(_u32p), k.ctypes.data_as(_u32p),
+                               out.ctypes.data_as(_u32p))
+    return out
+
+
+def masks(seed: int, step: int, n: int, p: float, identity_server: bool = False):
+    """(server[n] int32, U[n,n] uint8, D[n,n] uint8) of one round."""
+    assert 1 <= n <= 64 and 0.0 <= p <= 1.0 and 0 <= step < (1 << 56)
+    server = np.empty(n, dtype=np.int32)
+    U = np.empty((n, n), dtype=np.uint8)
+    D = np.empty((n, n), dtype=np.uint8)
+    _lib.rps_oracle_masks(seed, step, n, p, int(identity_server), server.ctypes.data_as(_i32p),
+                          U.ctypes.data_as(_u8p), D.ctypes.data_as(_u8p))
+    return server, U, D
+
+
+def noise8(seed: int, step: int, worker: int, group: int, sigma: float = 1.0) -> np.ndarray:
+    out = np.empty(8, dtype=np.float32)
+    _lib.rps_oracle_noise8(seed, step, worker, group, sigma, out.ctypes.data_as(_f32p))
+    return out
+
+
+def _dtype_code(a: np.ndarray) -> int:
+    if a.dtype == np.float32:
+        return 0
+    if a.dtype == np.uint16:
+        return 1
+    raise TypeError("oracle arrays are float32 or uint16 (bf16 bits)")
+
+
+def _cols_ptr(cols, m):
+    if cols is None:
+        return None, None
+    c = np.ascontiguousarray(cols, dtype=np.int64)
+    assert c.shape == (m,)
+    return c, c.ctypes.data_as(_i64p)
+
+
+def local_step(X: np.ndarray, G, gamma: float, *, sigma: float = 0.0, weight_decay: float = 0.0,
+               seed: int = 0, step: int = 0, cols=None, threads: int = 1) -> None:
+    """In place X <- X - gamma*G, or with G=None the synthetic gradient
+    weight_decay*x + sigma*z (z from the counter-based noise of (seed, step))."""
+    assert X.ndim == 2 and X.flags.c_contiguous
+    n, m = X.shape
+    code = _dtype_code(X)
+    gp = None
+    if G is not None:
+        assert G.shape == X.shape and G.dtype == X.dtype and G.flags.c_contiguous
+        gp = G.ctypes.data
+    keep, cp = _cols_ptr(cols, m)
+    _lib.rps_oracle_local_step(X.ctypes.data, gp, n, m, cp, code, gamma, sigma, weight_decay,
+                               seed, step, threads)
+
+
+def lossy_average(V: np.ndarray, offsets, U: np.ndarray, D: np.ndarray, *, cols=None,
+                  threads: int = 1) -> None:
+    """In place RS + AG round on V with the given delivery masks."""
+    assert V.ndim == 2 and V.flags.c_contiguous
+    n, m = V.shape
+    off = np.ascontiguousarray(offsets, dtype=np.int64)
+    assert off.shape == (n + 1,)
+    U = np.ascontiguousarray(U, dtype=np.uint8)
+    D = np.ascontiguousarray(D, dtype=np.uint8)
+    assert U.shape == (n, n) and D.shape == (n, n)
+    keep, cp = _cols_ptr(cols, m)
+    _lib.rps_oracle_lossy_average(V.ctypes.data, n, m, cp, off.ctypes.data_as(_i64p),
+                                  U.ctypes.data_as(_u8p), D.ctypes.data_as(_u8p), _dtype_code(V), threads)
+
+
+def build_W(j: int, U: np.ndarray, D: np.ndarray) -> np.ndarray:
+    """Mixing matrix W of block j: X_next^(j) = V^(j) W, W[m, k] = weight of worker m in worker k."""
+    U = np.ascontiguousarray(U, dtype=np.uint8)
+    D = np.ascontiguousarray(D, dtype=np.uint8)
+    n = U.shape[0]
+    W = np.empty((n, n), dtype=np.float64)
+    _lib.rps_oracle_build_W(n, j, U.ctypes.data_as(_u8p), D.ctypes.data_as(_u8p), W.ctypes.data_as(_f64p))
+    return W
+
+
+def equal_offsets(n: int, N: int) -> np.ndarray:
+    """The paper's equally-sized blocks: N must divide by n."""
+    assert N % n == 0
+    return np.arange(n + 1, dtype=np.int64) * (N // n)
+
+
+def round_(X: np.ndarray, G, offsets, *, p: float, gamma: float, seed: int, step: int,
+           sigma: float = 0.0, weight_decay: float = 0.0, identity_server: bool = False,
+           mask_override=None, cols=None, threads: int = 1):
+    """One full RPS round in the order of Alg. 1: local step, then RS, then AG.
+    Returns the masks used."""
+    n = X.shape[0]
+    local_step(X, G, gamma, sigma=sigma, weight_decay=weight_decay, seed=seed, step=step,
+               cols=cols, threads=threads)
+    if mask_override is not None:
+        server, U, D = mask_override
+    else:
+        server, U, D = masks(seed, step, n, p, identity_server)
+    lossy_average(X, offsets, U, D, cols=cols, threads=threads)
+    return server, U, D

@@ -1,0 +1,221 @@
+"""Brute-force pins: enumerate EVERY network outcome of one block on tiny n through the
+oracle's own round and compare with the formulas printed in arXiv 1810.07766:
+
+  - E[W] A_n = A_n,  E[W W^T] = a1 I + (1-a1) A_n,  E[W A_n W^T] = a2 I + (1-a2) A_n,
+    0 < a2 < a1 < 1                                   (Sec. 4.2, eqs. (def_alpha1), (def_alpha2))
+  - a1 = (n E[sum_i W_1i^2] - 1)/(n-1),  a2 = (E[(sum_i W_1i)^2] - 1)/(n-1)
+                                                      (supplement, Lemmas 7 and 8)
+  - the exact conditional binomial sums for E[W11^2 | A], E[W1n^2 | not A, C],
+    E[W1n | not A, C] and the probabilities P(A) = 1/n, P(not A, C) = p(n-1)/n   (same proofs)
+  - the printed upper bounds on a1 and a2 (n >= 3: the proofs' sums assume it)
+  - E_P[dxbar] = -gamma gbar and the second-moment identity     (supplement, Lemma 3)
+
+The outcome space of one block: the server s (uniform over the n workers, Alg. 1 step 6),
+an uplink pattern and a downlink pattern over the other n-1 workers (independent losses
+with probability p, Sec. 3); the server's own links are reliable.
+"""
+import itertools
+from math import comb
+
+import numpy as np
+import pytest
+
+import workloads
+from oracle import rps_oracle as oracle
+
+
+def enumerate_block(n, p):
+    """Yields (probability, server, W) over all outcomes; W is read out of the oracle's round
+    by feeding it V^{(j)} = I_n (then X_{t+1}^{(j)} = W)."""
+    q = 1.0 - p
+    off = np.array([0] + [n] * n, dtype=np.int64)        # block 0 holds all n columns
+    eye = np.eye(n, dtype=np.float32)
+    for s in range(n):
+        others = [i for i in range(n) if i != s]
+        for up in itertools.product((0, 1), repeat=n - 1):
+            for dn in itertools.product((0, 1), repeat=n - 1):
+                U = np.zeros((n, n), dtype=np.uint8); D = np.zeros((n, n), dtype=np.uint8)
+                U[s, 0] = D[s, 0] = 1
+                for o, u, d in zip(others, up, dn):
+                    U[o, 0] = u; D[o, 0] = d
+                prob = (1.0 / n) * np.prod([q if b else p for b in up + dn])
+                X = eye.copy()
+                oracle.lossy_average(X, off, U, D)
+                yield prob, s, D[:, 0].copy(), X.astype(np.float64).T     # X[k, m] = W[m, k]
+
+
+def moments(n, p):
+    A = np.full((n, n), 1.0 / n)
+    EW = np.zeros((n, n)); EWW = np.zeros((n, n)); EWAW = np.zeros((n, n)); tot = 0.0
+    for prob, s, d, W in enumerate_block(n, p):
+        tot += prob; EW += prob * W; EWW += prob * W @ W.T; EWAW += prob * W @ A @ W.T
+    assert abs(tot - 1.0) < 1e-12
+    return EW, EWW, EWAW
+
+
+def alpha_of(M, n):
+    """M = a I + (1-a) A_n  =>  a from the (1,1) entry; also checks the whole structure."""
+    a = (n * M[0, 0] - 1.0) / (n - 1.0)
+    assert np.abs(M - (a * np.eye(n) + (1 - a) * np.full((n, n), 1.0 / n))).max() < 1e-6
+    return a
+
+
+# exact (unrelaxed) expressions from the case analysis of Lemmas 7 and 8
+def E_W11sq_given_A(n, p):
+    q = 1 - p
+    return sum(comb(n - 1, m) * q ** m * p ** (n - 1 - m) / (m + 1) ** 2 for m in range(n))
+
+
+def E_W1nsq_given_notA_C(n, p):
+    q = 1 - p
+    return sum(comb(n - 2, m) * q ** (m + 1) * p ** (n - 2 - m) / (m + 2) ** 2 for m in range(n - 1))
+
+
+def E_W1n_given_notA_C(n, p):
+    q = 1 - p
+    return sum(comb(n - 2, m) * q ** (m + 1) * p ** (n - 2 - m) / (m + 2) for m in range(n - 1))
+
+
+def alpha1_exact(n, p):
+    q = 1 - p
+    c1 = E_W11sq_given_A(n, p) * (1 + (n - 1) * q)
+    c2 = 1 + E_W1nsq_given_notA_C(n, p) * (1 + (n - 2) * q)
+    c3 = E_W1nsq_given_notA_C(n, p) * (2 + (n - 2) * q)
+    e = c1 / n + c2 * p * (n - 1) / n + c3 * q * (n - 1) / n
+    return (n * e - 1) / (n - 1)
+
+
+def alpha2_exact(n, p):
+    q = 1 - p
+    c1 = E_W11sq_given_A(n, p) * ((1 + (n - 1) * q) ** 2 + (n - 1) * p * q)
+    c2 = (1 + 2 * E_W1n_given_notA_C(n, p) * ((n - 2) * q + 1)
+          + E_W1nsq_given_notA_C(n, p) * (1 + 2 * (n - 2) * q + (n - 2) ** 2 * q ** 2 + (n - 2) * p * q))
+    c3 = E_W1nsq_given_notA_C(n, p) * (((n - 2) * q + 2) ** 2 + (n - 2) * p * q)
+    e = c1 / n + c2 * p * (n - 1) / n + c3 * q * (n - 1) / n
+    return (e - 1) / (n - 1)
+
+
+@pytest.mark.parametrize("n,p", [(2, 0.3), (3, 0.1), (3, 0.5), (4, 0.1), (5, 0.2)])
+def test_moment_structure_and_alpha_formulas(n, p):
+    EW, EWW, EWAW = moments(n, p)
+    A = np.full((n, n), 1.0 / n)
+    assert np.abs(EW @ A - A).max() < 1e-7                       # (E W) A_n = A_n
+    a0 = alpha_of(EW, n); a1 = alpha_of(EWW, n); a2 = alpha_of(EWAW, n)
+    assert 0 < a2 < a1 < 1
+    assert abs(a1 - alpha1_exact(n, p)) < 1e-6
+    assert abs(a2 - alpha2_exact(n, p)) < 1e-6
+    # the lemmas' row formulas
+    e_sq = e_sum_sq = 0.0
+    for prob, s, d, W in enumerate_block(n, p):
+        e_sq += prob * (W[0] ** 2).sum(); e_sum_sq += prob * W[0].sum() ** 2
+    assert abs(a1 - (n * e_sq - 1) / (n - 1)) < 1e-6
+    assert abs(a2 - (e_sum_sq - 1) / (n - 1)) < 1e-6
+    assert a0 > 0
+
+
+@pytest.mark.parametrize("n,p", [(3, 0.25), (4, 0.1), (5, 0.4)])
+def test_conditional_sums_of_the_proofs(n, p):
+    PA = PnAC = 0.0; w11 = w1n = w1n1 = 0.0
+    for prob, s, d, W in enumerate_block(n, p):
+        if s == 0:                                   # event A: node 1 serves the block
+            PA += prob; w11 += prob * W[0, 0] ** 2
+        elif s == n - 1 and d[0] == 0:               # server is node n, node 1 got no reply (C)
+            PnAC += prob; w1n += prob * W[0, n - 1] ** 2; w1n1 += prob * W[0, n - 1]
+    assert abs(PA - 1.0 / n) < 1e-12
+    assert abs(PnAC - p / n) < 1e-12                 # one of the n-1 equally likely servers
+    assert abs(w11 / PA - E_W11sq_given_A(n, p)) < 1e-7
+    assert abs(w1n / PnAC - E_W1nsq_given_notA_C(n, p)) < 1e-7
+    assert abs(w1n1 / PnAC - E_W1n_given_notA_C(n, p)) < 1e-7
+
+
+def test_closed_forms_for_two_workers():
+    """n = 2 by hand (q = 1-p).  Server = node 1 (prob 1/2): W11 = 1/2 if node 2's copy arrives
+    (q) else 1; W12 = W11 if node 2 gets the reply (q) else 0.  Server = node 2: W12 = 1/2 if
+    node 1's copy arrives else 0; W11 = W12 if node 1 gets the reply else 1.  Summing:
+    E[W11] = (1 + a0)/2 with a0 = p(1+p)/2;  a1 = 2 E[sum W1i^2] - 1 = 1.5 p - 0.5 p^2;
+    a2 = E[(sum W1i)^2] - 1 = 1.25 p (1-p)."""
+    for p in (0.05, 0.3, 0.9):
+        EW, EWW, EWAW = moments(2, p)
+        assert abs(alpha_of(EW, 2) - 0.5 * p * (1 + p)) < 1e-7
+        assert abs(alpha_of(EWW, 2) - (1.5 * p - 0.5 * p * p)) < 1e-7
+        assert abs(alpha_of(EWAW, 2) - 1.25 * p * (1 - p)) < 1e-7
+
+
+@pytest.mark.parametrize("n,p", [(3, 0.1), (4, 0.2), (5, 0.05), (16, 0.1), (32, 0.05), (64, 0.1)])
+def test_printed_upper_bounds_hold(n, p):
+    q = 1 - p
+    T1 = 2 * (1 - p ** (n + 1) - (n + 1) * q * p ** n - (n + 1) * n * q * q * p ** (n - 1) / 2 - q ** (n + 1)) / (n * (n + 1) * q * q)
+    T2 = (1 - p ** n - n * q * p ** (n - 1) - q ** n) / ((n - 1) * q)
+    T3 = n / (n - 1) * (1 - p ** (n - 1) - q ** (n - 1)) + q ** (n - 1)
+    a1, a2 = alpha1_exact(n, p), alpha2_exact(n, p)
+    assert a1 <= (n * p + q ** n + n * T1 + n * T2 - 1) / (n - 1) + 1e-12
+    assert a2 <= (p * (1 + 2 * T3) + q ** (n - 1)) / n + 2 * p * q ** n / n + p ** n * q / n ** 2 + T1 + T2 + 1e-12
+    assert 0 < a2 < a1 < 1
+
+
+def test_expected_update_formula():
+    """Supplement, Lemma 3: over the drop randomness of round t,
+    E[dxbar] = -gamma gbar  and  E||dxbar||^2 = (a2/n) sum_j Tr(V^(j) (I - A_n) V^(j)T) + gamma^2 ||gbar||^2,
+    checked per block by enumerating every outcome of the oracle's round on random X, G."""
+    n, width, p, gamma = 4, 3, 0.3, 0.2
+    rng = np.random.default_rng(5)
+    Xb = rng.standard_normal((n, width)).astype(np.float32)       # one block, [workers, width]
+    Gb = rng.standard_normal((n, width)).astype(np.float32)
+    V = Xb.copy()
+    oracle.local_step(V, Gb, gamma)
+    Vd = V.astype(np.float64)
+    xbar = Xb.astype(np.float64).mean(axis=0); gbar = Gb.astype(np.float64).mean(axis=0)
+    off = np.array([0] + [width] * n, dtype=np.int64)
+    q = 1 - p
+    e1 = np.zeros(width); e2 = 0.0
+    for s in range(n):
+        others = [i for i in range(n) if i != s]
+        for up in itertools.product((0, 1), repeat=n - 1):
+            for dn in itertools.product((0, 1), repeat=n - 1):
+                U = np.zeros((n, n), dtype=np.uint8); D = np.zeros((n, n), dtype=np.uint8)
+                U[s, 0] = D[s, 0] = 1
+                for o, u, d in zip(others, up, dn):
+                    U[o, 0] = u; D[o, 0] = d
+                prob = (1.0 / n) * np.prod([q if b else p for b in up + dn])
+                Y = V.copy()
+                oracle.lossy_average(Y, off, U, D)
+                dx = Y.astype(np.float64).mean(axis=0) - xbar
+                e1 += prob * dx; e2 += prob * (dx ** 2).sum()
+    assert np.abs(e1 + gamma * gbar).max() < 1e-6
+    a2 = alpha2_exact(n, p)
+    tr = ((Vd - Vd.mean(axis=0)) ** 2).sum()                       # Tr(V^T (I - A_n) V)
+    assert abs(e2 - (a2 / n * tr + gamma ** 2 * (gbar ** 2).sum())) < 1e-6
+
+
+def test_fixed_server_breaks_the_mean_preservation():
+    """Why Alg. 1 draws the server afresh: with the server fixed the expected mixing matrix is
+    not of the a I + (1-a) A_n form (the server's copy is over-weighted), so E[dxbar] != -gamma gbar
+    per block.  Conditioning the enumeration on s = 0 shows it."""
+    n, p = 3, 0.2
+    EW = np.zeros((n, n)); tot = 0.0
+    for prob, s, d, W in enumerate_block(n, p):
+        if s == 0:
+            EW += prob * W; tot += prob
+    EW /= tot
+    rows = EW.sum(axis=1)
+    assert rows[0] > 1.01 and rows[1] < 0.99 and abs(rows.sum() - n) < 1e-6
+
+
+@pytest.mark.parametrize("n,p", [(16, 0.1), (32, 0.05)])
+def test_generated_masks_reproduce_alpha2(n, p):
+    """Monte-Carlo over the oracle's own mask generator at benchmark sizes: the sample mean of
+    (sum_i W_1i)^2 gives a2 (Lemma 8); a2 n / (p (1-p)) stays O(1) (Sec. 5: a2 = O(p(1-p)/n))."""
+    vals = []
+    for step in range(1500):
+        server, U, D = oracle.masks(123, step, n, p)
+        cnt = U.sum(axis=0).astype(np.float64)                     # |N_j|
+        # row 1 of W^(j): W[0,k] = U[0,j]/cnt_j if D[k,j] else (k == 0)
+        recv = D.sum(axis=0).astype(np.float64)
+        row_sum = U[0] / cnt * recv + (1 - D[0])
+        vals.append(row_sum ** 2)
+    vals = np.concatenate(vals)
+    est = (vals.mean() - 1) / (n - 1)
+    se = vals.std() / np.sqrt(vals.size) / (n - 1)
+    exact = alpha2_exact(n, p)
+    assert abs(est - exact) < 5 * se
+    assert 0.5 < exact * n / (p * (1 - p)) < 4.0

@@ -1,0 +1,177 @@
+"""Pins of the oracle's random-number layer against things other than itself.
+
+The paper (arXiv 1810.07766) fixes the distributions only: every message is lost
+independently with probability p (Sec. 3, "Unreliable Network Connection") and
+the server of a block is drawn uniformly without replacement (Alg. 1 step 6).
+The bit-level specification is this project's; these tests pin it to
+  - the published Philox4x32-10 known-answer vectors,
+  - the documented counter layout (re-derived here from the raw hash),
+  - the target distributions (drop frequency, independence, uniform servers),
+  - the textbook Box-Muller transform evaluated in double precision.
+"""
+import os
+
+import numpy as np
+import pytest
+from scipy import stats
+
+from oracle import rps_oracle as oracle
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def test_philox_known_answers():
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "philox4x32_10_kat.txt"))
+            if l.strip() and not l.startswith("#")]
+    assert len(rows) == 3
+    for r in rows:
+        v = [int(x, 16) for x in r]
+        out = oracle.philox4x32(v[0:4], v[4:6], rounds=10)
+        assert [int(x) for x in out] == v[6:10]
+
+
+def test_philox_is_a_bijection_on_small_slices():
+    # distinct counters -> distinct outputs (a counter-based generator is a keyed bijection)
+    outs = {tuple(int(x) for x in oracle.philox4x32([i, 0, 0, 0], [7, 9])) for i in range(2000)}
+    assert len(outs) == 2000
+    # the key matters
+    assert tuple(oracle.philox4x32([1, 2, 3, 4], [0, 0])) != tuple(oracle.philox4x32([1, 2, 3, 4], [1, 0]))
+
+
+def _word0(seed, step, a, b, domain):
+    ctr = [a, b, step & 0xFFFFFFFF, (domain << 24) | ((step >> 32) & 0xFFFFFF)]
+    key = [seed & 0xFFFFFFFF, seed >> 32]
+    return int(oracle.philox4x32(ctr, key, rounds=10)[0])
+
+
+@pytest.mark.parametrize("seed,step,n,p", [(0, 0, 4, 0.5), (12345678901234567, (5 << 32) + 17, 7, 0.3),
+                                           (3, 99, 64, 0.05)])
+def test_masks_follow_the_documented_counter_layout(seed, step, n, p):
+    """drop iff hash word 0 of (worker, block, step, domain) < floor(p 2^32); domain 0 = uplink,
+    1 = downlink, 2 = server sort key; self links forced after the draw."""
+    server, U, D = oracle.masks(seed, step, n, p)
+    keys = [(_word0(seed, step, i, 0, 2), i) for i in range(n)]
+    assert [i for _, i in sorted(keys)] == server.tolist()
+    T = int(np.floor(p * 2.0 ** 32))
+    for i in range(n):
+        for j in range(n):
+            if i == server[j]:
+                assert U[i, j] == 1 and D[i, j] == 1
+            else:
+                assert U[i, j] == (0 if _word0(seed, step, i, j, 0) < T else 1)
+                assert D[i, j] == (0 if _word0(seed, step, i, j, 1) < T else 1)
+
+
+def test_p_zero_and_p_one_are_exact():
+    for step in range(20):
+        server, U, D = oracle.masks(1, step, 9, 0.0)
+        assert U.all() and D.all()
+        server, U, D = oracle.masks(1, step, 9, 1.0)
+        expect = np.zeros((9, 9), dtype=np.uint8)
+        expect[server, np.arange(9)] = 1          # only the server's link to itself survives
+        assert (U == expect).all() and (D == expect).all()
+
+
+def test_server_is_a_uniform_permutation():
+    n, rounds = 8, 4000
+    counts = np.zeros((n, n))
+    for step in range(rounds):
+        server, _, _ = oracle.masks(42, step, n, 0.1)
+        assert sorted(server.tolist()) == list(range(n))     # without replacement
+        counts[np.arange(n), server] += 1
+    # every (block, worker) cell ~ Binomial(rounds, 1/n): P(A) = 1/n in the paper's Lemma 7
+    chi2 = ((counts - rounds / n) ** 2 / (rounds / n)).sum()
+    assert chi2 < stats.chi2.ppf(1 - 1e-6, df=(n - 1) * (n - 1))
+    # identity flag = the exposition's "worker i averages block i"
+    server, _, _ = oracle.masks(42, 3, n, 0.1, identity_server=True)
+    assert server.tolist() == list(range(n))
+
+
+@pytest.mark.parametrize("p", [0.01, 0.1, 0.2])
+def test_drop_frequency_and_independence(p):
+    n, rounds = 16, 600
+    drops_u = drops_d = both = total = 0
+    for step in range(rounds):
+        server, U, D = oracle.masks(7, step, n, p)
+        off = np.ones((n, n), dtype=bool)
+        off[server, np.arange(n)] = False
+        u = U[off] == 0
+        d = D[off] == 0
+        drops_u += u.sum(); drops_d += d.sum(); both += (u & d).sum(); total += off.sum()
+    sd = np.sqrt(p * (1 - p) / total)
+    assert abs(drops_u / total - p) < 5 * sd
+    assert abs(drops_d / total - p) < 5 * sd
+    # uplink and downlink losses are independent: P(both) = p^2
+    sd2 = np.sqrt(p * p * (1 - p * p) / total)
+    assert abs(both / total - p * p) < 5 * sd2
+
+
+def test_masks_change_with_seed_and_step():
+    a = oracle.masks(0, 0, 16, 0.3)
+    b = oracle.masks(0, 1, 16, 0.3)
+    c = oracle.masks(1, 0, 16, 0.3)
+    assert not (a[1] == b[1]).all() and not (a[1] == c[1]).all()
+    d = oracle.masks(0, 0, 16, 0.3)
+    assert all((x == y).all() for x, y in zip(a, d))      # stateless: same (seed, step) -> same bits
+    e = oracle.masks(0, 1 << 32, 16, 0.3)                 # the high half of the step is hashed too
+    assert not (a[1] == e[1]).all()
+
+
+# ---------------------------------------------------------------------------------------------
+# Gaussian noise
+# ---------------------------------------------------------------------------------------------
+def _noise_reference(seed, step, worker, group, sigma):
+    """The textbook Box-Muller transform in double precision on the same hash words:
+    u1 = (2k+1)/2^17 from the low 16 bits, angle (2f+1) pi / 65536 from the signed 15-bit
+    field above them, bit 31 adds pi."""
+    ctr = [group & 0xFFFFFFFF, worker, step & 0xFFFFFFFF, (3 << 24) | ((step >> 32) & 0xFFFFFF)]
+    key = [seed & 0xFFFFFFFF, seed >> 32]
+    words = oracle.philox4x32(ctr, key, rounds=10)
+    out = []
+    for w in words:
+        w = int(w)
+        u1 = (2 * (w & 0xFFFF) + 1) / 2.0 ** 17
+        f = (w >> 16) & 0x7FFF
+        if f >= 0x4000:
+            f -= 0x8000
+        phi = (2 * f + 1) * np.pi / 65536 + (np.pi if w >> 31 else 0.0)
+        r = np.sqrt(-2.0 * np.log(u1))
+        out += [sigma * r * np.cos(phi), sigma * r * np.sin(phi)]
+    return np.array(out)
+
+
+def test_noise_matches_textbook_box_muller():
+    worst = 0.0
+    for (seed, step, worker, group) in [(0, 0, 0, 0), (5, 3, 31, 123456), (2 ** 40 + 1, 2 ** 33, 63, 2 ** 31 + 5)]:
+        for g in range(group, group + 300):
+            z = oracle.noise8(seed, step, worker, g, 1.0).astype(np.float64)
+            ref = _noise_reference(seed, step, worker, g, 1.0)
+            worst = max(worst, np.abs(z - ref).max())
+            assert np.abs(z - ref).max() < 2e-4     # polynomial approximation error of the spec
+    assert worst > 0.0                               # (it is an approximation, not libm)
+
+
+def test_noise_sigma_scaling_and_determinism():
+    a = oracle.noise8(9, 4, 2, 77, 1.0)
+    assert (oracle.noise8(9, 4, 2, 77, 1.0) == a).all()
+    assert (oracle.noise8(9, 4, 2, 77, 0.25) == 0.25 * a).all()      # power of two: exact
+    assert not (oracle.noise8(9, 4, 3, 77, 1.0) == a).all()          # worker enters the counter
+    assert not (oracle.noise8(9, 5, 2, 77, 1.0) == a).all()          # step too
+    assert not (oracle.noise8(9, 4, 2, 78, 1.0) == a).all()
+
+
+def test_noise_is_standard_normal():
+    z = np.concatenate([oracle.noise8(11, 2, w, g, 1.0) for w in range(4) for g in range(50000)]).astype(np.float64)
+    n = z.size                                        # 1.6 M samples
+    assert abs(z.mean()) < 5 / np.sqrt(n)
+    assert abs(z.var() - 1.0) < 5 * np.sqrt(2.0 / n) + 2e-4
+    assert abs((z ** 3).mean()) < 5 * np.sqrt(15.0 / n)
+    assert abs((z ** 4).mean() - 3.0) < 5 * np.sqrt(96.0 / n) + 2e-3
+    assert stats.kstest(z[:200000], "norm").pvalue > 1e-4
+    # the two members of a Box-Muller pair, and neighbouring pairs, are uncorrelated
+    pairs = z.reshape(-1, 2)
+    assert abs(np.corrcoef(pairs[:, 0], pairs[:, 1])[0, 1]) < 5 / np.sqrt(n / 2)
+    assert abs(np.corrcoef(z[:-1], z[1:])[0, 1]) < 5 / np.sqrt(n)
+    assert abs(np.corrcoef(z[:-8] ** 2, z[8:] ** 2)[0, 1]) < 5 / np.sqrt(n)
+    # 16-bit radius index: |z| <= sqrt(2 ln 2^17)
+    assert np.abs(z).max() <= np.sqrt(2 * np.log(2.0 ** 17)) * (1 + 1e-4)
