@@ -1,0 +1,127 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused RPS round on one MI355X.
+
+A "step" is one pass of the whole hot path over the workload: mask generation + fused local
+SGD step (in-register synthetic Gaussian gradient) + Reduce-Scatter average + All-Gather
+write-back, for all n workers and all N parameters, in place in HBM.
+
+Prints ONE JSON line: worker-params averaged per second (n*N per round), the HBM roofline of
+the round kernel (algorithmic bytes = 2*sizeof(dtype) per worker-param, i.e. one read and one
+write of the state, divided by the kernel's mean duration measured with HIP events on the
+library's own stream), and the CPU oracle timed on the host cores on a bounded sample.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0     # MI355X published HBM3E bandwidth
+
+
+def cpu_baseline(cfg, off, budget_cols):
+    """The oracle as it stands on the host cores: `budget_cols` columns of every block's start,
+    all n workers, one round."""
+    import numpy as np
+    from oracle import rps_oracle as oracle
+    threads = oracle.max_threads()
+    per_block = max(8, budget_cols // cfg.n)
+    cols = np.concatenate([np.arange(off[j], min(off[j] + per_block, off[j + 1])) for j in range(cfg.n)]).astype(np.int64)
+    m = cols.size
+    if cfg.dtype == "bf16":
+        X = np.zeros((cfg.n, m), dtype=np.uint16)
+    else:
+        X = np.zeros((cfg.n, m), dtype=np.float32)
+    oracle.round_(X, None, off, p=cfg.p, gamma=cfg.gamma, seed=cfg.seed, step=0, sigma=cfg.sigma,
+                  weight_decay=cfg.weight_decay, cols=cols, threads=threads)          # warm-up
+    t0 = time.perf_counter()
+    reps = 0
+    while True:
+        reps += 1
+        oracle.round_(X, None, off, p=cfg.p, gamma=cfg.gamma, seed=cfg.seed, step=reps, sigma=cfg.sigma,
+                      weight_decay=cfg.weight_decay, cols=cols, threads=threads)
+        dt = time.perf_counter() - t0
+        if dt > 10.0 or reps >= 50:
+            break
+    return {"value": cfg.n * m * reps / dt, "unit": "worker-params/s", "cores": threads, "kind": "oracle",
+            "sample": f"{reps} rounds over {m} columns ({per_block} per block) x {cfg.n} workers of the same workload, "
+                      f"{dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default=None, help="workload name (default: the headline config)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the n workers are simulated in one [n, N] tensor); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import workloads
+    from paper_1810_07766_amd import rps
+
+    cfg = workloads.CONFIGS[args.config or workloads.HEADLINE]
+    off = workloads.config_offsets(cfg)
+    torch.cuda.set_device(0)
+    tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+    X = torch.zeros(cfg.n, cfg.N, device="cuda", dtype=tdt)       # Alg. 1: identical start, X_1 = 0
+    ctx = rps.RpsContext(cfg.n, cfg.N, cfg.p, cfg.gamma, cfg.seed,
+                         rps.RPS_DTYPE_BF16 if cfg.dtype == "bf16" else rps.RPS_DTYPE_F32, block_offsets=off)
+    ctx.set_synthetic_grad(cfg.sigma, cfg.weight_decay)
+
+    step = 0
+    for _ in range(args.warmup):
+        ctx.round(X, None, step); step += 1
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        ctx.round(X, None, step); step += 1
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+
+    # the round kernel alone, bracketed by HIP events on the stream it is launched on
+    ctx.set_profiling(True)
+    for _ in range(args.steps):
+        ctx.round(X, None, step); step += 1
+    kernel_ms, launches = ctx.get_kernel_time()
+    ctx.set_profiling(False)
+    assert launches == args.steps
+    kernel_ms /= launches
+
+    elem = 2 if cfg.dtype == "bf16" else 4
+    alg_bytes = 2.0 * elem * cfg.n * cfg.N                        # read x once, write x' once
+    achieved = alg_bytes / (kernel_ms * 1e-3) / 1e9
+    out = {
+        "metric": "worker-params averaged/sec (n*N per round)",
+        "value": cfg.n * cfg.N * args.steps / dt,
+        "unit": "worker-params/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": dt / args.steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if cfg.dtype == "f32" else "bf16-storage/f32-math",
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "n": cfg.n, "N": cfg.N, "p": cfg.p, "gamma": cfg.gamma,
+                   "gradient": f"in-register N(0,{cfg.sigma ** 2:.3g}) + {cfg.weight_decay}*x",
+                   "blocks": "unequal" if cfg.unequal_blocks else "equal"},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "round_kernel", "kernel_ms": kernel_ms, "algorithmic_bytes": alg_bytes},
+    }
+    ctx.destroy()
+    del X
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, off, budget_cols=1 << 18)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,150 @@
+/*
+ * rps.h -- C ABI of the MI355X (gfx950) library for the lossy partitioned
+ * model-averaging round of RPS, the algorithm of "Distributed Learning over
+ * Unreliable Networks" (arXiv 1810.07766), simulated for n workers held as one
+ * [n, N] array on a single GPU.
+ *
+ * One round (Alg. 1 of the paper):
+ *   1. local SGD step           v_i = x_i - gamma * g_i                (Sec. 4.1; Alg. 1 steps 3-5)
+ *   2. partition                every v_i is cut into the same n blocks (Sec. 4.1 eq. (dividev))
+ *   3. Reduce-Scatter w/ drops  the server b(j) of block j averages the copies of block j that
+ *                               reach it; each copy is lost independently with probability p,
+ *                               the server's own copy never is        (Sec. 3; Sec. 4.1 RS step;
+ *                                                                      supplement, Lemma 7 proof)
+ *   4. All-Gather w/ drops      worker i overwrites block j with that average iff the reply
+ *                               reaches it (lost with probability p), else keeps v_i's block
+ *                                                                     (Sec. 4.1 AG step, eq. (dividex))
+ * The server b(j) is a fresh uniform permutation every round (Alg. 1 step 6).
+ *
+ * Conventions
+ *   - X and G are CALLER-OWNED DEVICE memory: contiguous row-major [n, N] (worker-major), fp32
+ *     or bf16.  The library never allocates, frees or keeps them.  A 16-byte aligned base with
+ *     N % 4 == 0 (fp32) or N % 8 == 0 (bf16) takes the 128-bit load/store path; anything else
+ *     is handled by a slower element-wise path with identical results.
+ *   - All device work is enqueued on the HIP stream given at creation; no call synchronises
+ *     except where stated.  Results are valid in stream order.
+ *   - Every function returns RPS_OK (0) or a negative error code; nothing aborts or throws.
+ *     An error detected before launch leaves X untouched.
+ *   - The round's randomness is a pure function of (seed, step): the caller supplies `step`,
+ *     so a run can be checkpointed and resumed by storing (X, step).  step < 2^56.
+ *   - A context is not thread-safe; distinct contexts are independent.
+ */
+#ifndef RPS_H
+#define RPS_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct rps_ctx rps_ctx;
+
+enum {
+    RPS_OK = 0,
+    RPS_EINVAL = -1,        /* bad argument (see each function) */
+    RPS_ENOMEM = -2,        /* host or device allocation failed */
+    RPS_EHIP = -3,          /* a HIP call failed; see rps_last_hip_error() */
+    RPS_EUNSUPPORTED = -4   /* valid request this build does not implement */
+};
+
+enum { RPS_DTYPE_F32 = 0, RPS_DTYPE_BF16 = 1 };
+
+/* rps_create flags */
+enum {
+    /* Worker j serves block j in every round: the simplification the paper uses when it
+       explains the algorithm (Sec. 4.1).  Default is Alg. 1's per-round random permutation. */
+    RPS_FLAG_SERVER_IDENTITY = 1u
+};
+
+/*
+ * Create a context for n workers with N parameters each (problem statement, Sec. 3; inputs
+ * of Alg. 1: step size gamma; the network is characterised by n and the drop probability p).
+ *   out            receives the handle (host pointer; untouched on error)
+ *   n              workers = blocks = servers, 1..64
+ *   N              parameters per worker, n <= N <= 2^35
+ *   block_offsets  HOST array of n+1 int64 with off[0] = 0 < off[1] < ... < off[n] = N, block j
+ *                  being columns [off[j], off[j+1]); or NULL for the paper's equally-sized
+ *                  blocks, which needs N % n == 0.  Copied; the caller keeps ownership.
+ *   p              drop probability of every worker<->server message, 0 <= p <= 1
+ *   gamma          step size of the local SGD step
+ *   seed           64-bit key of the counter-based random numbers
+ *   dtype          RPS_DTYPE_F32 or RPS_DTYPE_BF16 (storage; arithmetic is fp32, sums fp64)
+ *   flags          RPS_FLAG_*
+ *   hip_stream     hipStream_t on which all work is enqueued (NULL = the default stream)
+ * Allocates O(n) device bytes and a pinned host staging buffer of the same size; nothing
+ * proportional to N.  Errors: RPS_EINVAL, RPS_ENOMEM, RPS_EHIP.
+ */
+int rps_create(rps_ctx **out, int32_t n, int64_t N, const int64_t *block_offsets, double p,
+               float gamma, uint64_t seed, int32_t dtype, uint32_t flags, void *hip_stream);
+
+/* Free the context's tables.  Synchronises the stream first.  NULL is a no-op. */
+int rps_destroy(rps_ctx *ctx);
+
+/*
+ * Synthetic stochastic gradient used when G == NULL:  g = weight_decay * x + sigma * z, with z
+ * standard Gaussian noise generated in registers from (seed, step, worker, column).  Stands in
+ * for Alg. 1 steps 3-4 (sampling data and computing a stochastic gradient).  Default 0, 0.
+ */
+int rps_set_synthetic_grad(rps_ctx *ctx, float sigma, float weight_decay);
+
+/* Change the step size (the paper notes a decayed step size reaches a critical point, Sec. 5). */
+int rps_set_gamma(rps_ctx *ctx, float gamma);
+
+/*
+ * Local SGD step (Sec. 4.1; Alg. 1 step 5), in place:  X <- X - gamma * G.
+ *   X   device [n, N], context dtype
+ *   G   device [n, N], same dtype; or NULL for the synthetic gradient
+ * v is rounded to the storage dtype (what is stored is what would travel).
+ */
+int rps_local_step(rps_ctx *ctx, void *X, const void *G, uint64_t step);
+
+/*
+ * One Reduce-Scatter + All-Gather round with drops (Sec. 4.1; Alg. 1 steps 6-8), in place on
+ * the intermediate models V held in X, with the network outcome of (seed, step) or the
+ * override set by rps_set_mask_override.  Rows whose reply was lost are left untouched.
+ */
+int rps_lossy_average(rps_ctx *ctx, void *X, uint64_t step);
+
+/*
+ * Fused round: same result, bit for bit, as rps_local_step followed by rps_lossy_average, in
+ * one pass over X (each element read at most once and written once).
+ */
+int rps_round(rps_ctx *ctx, void *X, const void *G, uint64_t step);
+
+/*
+ * Test hook: the network outcome the DEVICE generates for `step`, copied to HOST arrays.
+ *   up, down   n*n bytes each, index [worker * n + block]; 1 = delivered
+ *   server     n int32, server[j] = worker that averages block j
+ * Any pointer may be NULL.  Ignores a mask override.  Synchronises the stream.
+ */
+int rps_get_masks(rps_ctx *ctx, uint64_t step, uint8_t *up, uint8_t *down, int32_t *server);
+
+/*
+ * Test hook: force the network outcome of every following round (HOST arrays, layout as in
+ * rps_get_masks; copied).  Every block must have at least one delivered uplink (a server
+ * always holds its own copy).  Passing all three NULL restores the generated masks.
+ * Synchronises the stream.
+ */
+int rps_set_mask_override(rps_ctx *ctx, const uint8_t *up, const uint8_t *down, const int32_t *server);
+
+/*
+ * Kernel timing for benchmarks: while enabled, every rps_round / rps_lossy_average /
+ * rps_local_step brackets its main kernel (not the small mask kernel) with HIP events on the
+ * context's stream.  rps_get_kernel_time synchronises the stream, returns the accumulated
+ * kernel milliseconds and launch count since enabling, and resets both.  At most 4096
+ * launches are recorded between two reads.
+ */
+int rps_set_profiling(rps_ctx *ctx, int32_t enable);
+int rps_get_kernel_time(rps_ctx *ctx, double *total_ms, int64_t *launches);
+
+/* hipError_t of the last failing HIP call in this context (0 = none). */
+int rps_last_hip_error(const rps_ctx *ctx);
+
+/* Static description of an error code. */
+const char *rps_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RPS_H */

@@ -1,0 +1,341 @@
+// C ABI of the RPS library (see include/rps.h for the contract of every entry point).
+// Host-side only: argument validation, the O(n) device table, launches on the caller's stream.
+#include "../../include/rps.h"
+#include "rps_internal.h"
+
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <vector>
+
+using rps::RoundParams;
+using rps::RoundTable;
+
+struct rps_ctx {
+    int32_t n = 0;
+    int64_t N = 0;
+    double p = 0.0;
+    uint64_t threshold = 0;     // a message is lost iff its hash word < threshold = floor(p 2^32)
+    float gamma = 0.0f, sigma = 0.0f, lambda = 0.0f;
+    uint64_t seed = 0;
+    int32_t dtype = 0;
+    uint32_t flags = 0;
+    hipStream_t stream = nullptr;
+    int device = 0;
+    int64_t max_block_cols = 0;
+    std::vector<int64_t> off;
+    RoundTable *tab = nullptr;        // device: table the round kernels read
+    RoundTable *tab_query = nullptr;  // device: scratch table for rps_get_masks
+    RoundTable *staging = nullptr;    // pinned host copy (create, override, query)
+    bool override_on = false;
+    bool profiling = false;
+    std::vector<hipEvent_t> ev_start, ev_stop;
+    size_t ev_used = 0;
+    int last_hip = 0;
+};
+
+namespace {
+
+constexpr size_t kMaxProfiledLaunches = 4096;
+
+int hip_fail(rps_ctx *ctx, hipError_t e) {
+    if (ctx) ctx->last_hip = (int)e;
+    return RPS_EHIP;
+}
+#define RPS_HIP(ctx, call)                                  \
+    do {                                                    \
+        hipError_t e_ = (call);                             \
+        if (e_ != hipSuccess) return hip_fail((ctx), e_);   \
+    } while (0)
+
+bool step_ok(uint64_t step) { return step < (1ull << 56); }
+
+RoundParams make_params(const rps_ctx *ctx, const void *X, const void *G, uint64_t step) {
+    RoundParams prm;
+    prm.N = ctx->N;
+    prm.n = ctx->n;
+    const int64_t vec = ctx->dtype == RPS_DTYPE_F32 ? 4 : 8;   // elements per 16 bytes
+    const bool aligned = ((uintptr_t)X % 16 == 0) && (G == nullptr || (uintptr_t)G % 16 == 0);
+    prm.vec_ok = (aligned && ctx->N % vec == 0) ? 1 : 0;
+    prm.gamma = ctx->gamma;
+    prm.sigma = ctx->sigma;
+    prm.lambda = ctx->lambda;
+    prm.seed_lo = (uint32_t)ctx->seed;
+    prm.seed_hi = (uint32_t)(ctx->seed >> 32);
+    prm.step_lo = (uint32_t)step;
+    prm.step_hi24 = (uint32_t)((step >> 32) & 0xFFFFFFu);
+    return prm;
+}
+
+// Brackets `launch` with events when profiling is on.
+template <typename F>
+int timed_launch(rps_ctx *ctx, F launch) {
+    const bool rec = ctx->profiling && ctx->ev_used < kMaxProfiledLaunches;
+    if (rec) {
+        if (ctx->ev_used == ctx->ev_start.size()) {
+            hipEvent_t a, b;
+            RPS_HIP(ctx, hipEventCreate(&a));
+            hipError_t e = hipEventCreate(&b);
+            if (e != hipSuccess) {
+                (void)hipEventDestroy(a);
+                return hip_fail(ctx, e);
+            }
+            ctx->ev_start.push_back(a);
+            ctx->ev_stop.push_back(b);
+        }
+        RPS_HIP(ctx, hipEventRecord(ctx->ev_start[ctx->ev_used], ctx->stream));
+    }
+    RPS_HIP(ctx, launch());
+    if (rec) {
+        RPS_HIP(ctx, hipEventRecord(ctx->ev_stop[ctx->ev_used], ctx->stream));
+        ++ctx->ev_used;
+    }
+    return RPS_OK;
+}
+
+int enqueue_masks(rps_ctx *ctx, uint64_t step) {
+    if (ctx->override_on) return RPS_OK;   // the table already holds the forced outcome
+    RPS_HIP(ctx, rps::launch_masks(ctx->tab, ctx->n, ctx->seed, step, ctx->threshold,
+                                   (ctx->flags & RPS_FLAG_SERVER_IDENTITY) ? 1 : 0, ctx->stream));
+    return RPS_OK;
+}
+
+struct DeviceGuard {   // make the context's device current for the duration of a call
+    int prev = -1;
+    bool ok = false;
+    explicit DeviceGuard(int dev) {
+        if (hipGetDevice(&prev) == hipSuccess) ok = (prev == dev) || hipSetDevice(dev) == hipSuccess;
+    }
+    ~DeviceGuard() {
+        int cur = -1;
+        if (prev >= 0 && hipGetDevice(&cur) == hipSuccess && cur != prev) (void)hipSetDevice(prev);
+    }
+};
+
+}  // namespace
+
+extern "C" {
+
+int rps_create(rps_ctx **out, int32_t n, int64_t N, const int64_t *block_offsets, double p, float gamma,
+               uint64_t seed, int32_t dtype, uint32_t flags, void *hip_stream) {
+    if (!out) return RPS_EINVAL;
+    if (n < 1 || n > rps::kMaxWorkers) return RPS_EINVAL;
+    if (N < n || N > (1ll << 35)) return RPS_EINVAL;
+    if (!(p >= 0.0 && p <= 1.0)) return RPS_EINVAL;   // also rejects NaN
+    if (!std::isfinite(gamma)) return RPS_EINVAL;
+    if (dtype != RPS_DTYPE_F32 && dtype != RPS_DTYPE_BF16) return RPS_EINVAL;
+    if (flags & ~(uint32_t)RPS_FLAG_SERVER_IDENTITY) return RPS_EINVAL;
+
+    rps_ctx *ctx = new (std::nothrow) rps_ctx;
+    if (!ctx) return RPS_ENOMEM;
+    ctx->off.resize((size_t)n + 1);
+    if (block_offsets) {
+        for (int j = 0; j <= n; ++j) ctx->off[j] = block_offsets[j];
+        bool ok = ctx->off[0] == 0 && ctx->off[n] == N;
+        for (int j = 0; j < n && ok; ++j) ok = ctx->off[j] < ctx->off[j + 1];
+        if (!ok) {
+            delete ctx;
+            return RPS_EINVAL;
+        }
+    } else {
+        if (N % n != 0) {   // the paper's blocks are equally sized
+            delete ctx;
+            return RPS_EINVAL;
+        }
+        for (int j = 0; j <= n; ++j) ctx->off[j] = (N / n) * j;
+    }
+    for (int j = 0; j < n; ++j)
+        if (ctx->off[j + 1] - ctx->off[j] > ctx->max_block_cols) ctx->max_block_cols = ctx->off[j + 1] - ctx->off[j];
+
+    ctx->n = n;
+    ctx->N = N;
+    ctx->p = p;
+    ctx->threshold = (uint64_t)std::floor(p * 4294967296.0);
+    ctx->gamma = gamma;
+    ctx->seed = seed;
+    ctx->dtype = dtype;
+    ctx->flags = flags;
+    ctx->stream = (hipStream_t)hip_stream;
+
+    hipError_t e = hipGetDevice(&ctx->device);
+    if (e == hipSuccess) e = hipMalloc((void **)&ctx->tab, 2 * sizeof(RoundTable));
+    if (e == hipSuccess) {
+        ctx->tab_query = ctx->tab + 1;
+        e = hipHostMalloc((void **)&ctx->staging, sizeof(RoundTable), hipHostMallocDefault);
+    }
+    if (e == hipSuccess) {
+        std::memset(ctx->staging, 0, sizeof(RoundTable));
+        for (int j = 0; j <= n; ++j) ctx->staging->off[j] = ctx->off[j];
+        e = hipMemcpyAsync(ctx->tab, ctx->staging, sizeof(RoundTable), hipMemcpyHostToDevice, ctx->stream);
+        if (e == hipSuccess)
+            e = hipMemcpyAsync(ctx->tab_query, ctx->staging, sizeof(RoundTable), hipMemcpyHostToDevice, ctx->stream);
+        if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+    }
+    if (e != hipSuccess) {
+        const bool oom = (e == hipErrorOutOfMemory);
+        if (ctx->tab) (void)hipFree(ctx->tab);
+        if (ctx->staging) (void)hipHostFree(ctx->staging);
+        delete ctx;
+        return oom ? RPS_ENOMEM : RPS_EHIP;
+    }
+    *out = ctx;
+    return RPS_OK;
+}
+
+int rps_destroy(rps_ctx *ctx) {
+    if (!ctx) return RPS_OK;
+    DeviceGuard guard(ctx->device);
+    int rc = RPS_OK;
+    if (hipStreamSynchronize(ctx->stream) != hipSuccess) rc = RPS_EHIP;
+    for (hipEvent_t ev : ctx->ev_start) (void)hipEventDestroy(ev);
+    for (hipEvent_t ev : ctx->ev_stop) (void)hipEventDestroy(ev);
+    if (ctx->tab && hipFree(ctx->tab) != hipSuccess) rc = RPS_EHIP;
+    if (ctx->staging && hipHostFree(ctx->staging) != hipSuccess) rc = RPS_EHIP;
+    delete ctx;
+    return rc;
+}
+
+int rps_set_synthetic_grad(rps_ctx *ctx, float sigma, float weight_decay) {
+    if (!ctx || !std::isfinite(sigma) || sigma < 0.0f || !std::isfinite(weight_decay)) return RPS_EINVAL;
+    ctx->sigma = sigma;
+    ctx->lambda = weight_decay;
+    return RPS_OK;
+}
+
+int rps_set_gamma(rps_ctx *ctx, float gamma) {
+    if (!ctx || !std::isfinite(gamma)) return RPS_EINVAL;
+    ctx->gamma = gamma;
+    return RPS_OK;
+}
+
+int rps_local_step(rps_ctx *ctx, void *X, const void *G, uint64_t step) {
+    if (!ctx || !X || !step_ok(step)) return RPS_EINVAL;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return RPS_EHIP;
+    const RoundParams prm = make_params(ctx, X, G, step);
+    const int mode = G ? rps::kGradBuffer : rps::kGradSynthetic;
+    return timed_launch(ctx, [&] { return rps::launch_local_step(ctx->dtype, mode, X, G, prm, ctx->stream); });
+}
+
+int rps_lossy_average(rps_ctx *ctx, void *X, uint64_t step) {
+    if (!ctx || !X || !step_ok(step)) return RPS_EINVAL;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return RPS_EHIP;
+    const RoundParams prm = make_params(ctx, X, nullptr, step);
+    const int rc = enqueue_masks(ctx, step);
+    if (rc != RPS_OK) return rc;
+    return timed_launch(ctx, [&] {
+        return rps::launch_round(ctx->dtype, rps::kGradNone, X, nullptr, ctx->tab, prm, ctx->max_block_cols,
+                                 ctx->stream);
+    });
+}
+
+int rps_round(rps_ctx *ctx, void *X, const void *G, uint64_t step) {
+    if (!ctx || !X || !step_ok(step)) return RPS_EINVAL;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return RPS_EHIP;
+    const RoundParams prm = make_params(ctx, X, G, step);
+    const int mode = G ? rps::kGradBuffer : rps::kGradSynthetic;
+    const int rc = enqueue_masks(ctx, step);
+    if (rc != RPS_OK) return rc;
+    return timed_launch(ctx, [&] {
+        return rps::launch_round(ctx->dtype, mode, X, G, ctx->tab, prm, ctx->max_block_cols, ctx->stream);
+    });
+}
+
+int rps_get_masks(rps_ctx *ctx, uint64_t step, uint8_t *up, uint8_t *down, int32_t *server) {
+    if (!ctx || !step_ok(step)) return RPS_EINVAL;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return RPS_EHIP;
+    RPS_HIP(ctx, rps::launch_masks(ctx->tab_query, ctx->n, ctx->seed, step, ctx->threshold,
+                                   (ctx->flags & RPS_FLAG_SERVER_IDENTITY) ? 1 : 0, ctx->stream));
+    RPS_HIP(ctx, hipMemcpyAsync(ctx->staging, ctx->tab_query, sizeof(RoundTable), hipMemcpyDeviceToHost, ctx->stream));
+    RPS_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    const int n = ctx->n;
+    for (int i = 0; i < n; ++i)
+        for (int j = 0; j < n; ++j) {
+            if (up) up[i * n + j] = (uint8_t)((ctx->staging->ucol[j] >> i) & 1);
+            if (down) down[i * n + j] = (uint8_t)((ctx->staging->dcol[j] >> i) & 1);
+        }
+    if (server)
+        for (int j = 0; j < n; ++j) server[j] = ctx->staging->server[j];
+    return RPS_OK;
+}
+
+int rps_set_mask_override(rps_ctx *ctx, const uint8_t *up, const uint8_t *down, const int32_t *server) {
+    if (!ctx) return RPS_EINVAL;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return RPS_EHIP;
+    if (!up && !down && !server) {
+        RPS_HIP(ctx, hipStreamSynchronize(ctx->stream));
+        ctx->override_on = false;
+        return RPS_OK;
+    }
+    if (!up || !down || !server) return RPS_EINVAL;
+    const int n = ctx->n;
+    RoundTable t;
+    std::memset(&t, 0, sizeof(t));
+    for (int j = 0; j <= n; ++j) t.off[j] = ctx->off[j];
+    for (int j = 0; j < n; ++j) {
+        if (server[j] < 0 || server[j] >= n) return RPS_EINVAL;
+        uint64_t u = 0, d = 0;
+        for (int i = 0; i < n; ++i) {
+            if (up[i * n + j]) u |= 1ull << i;
+            if (down[i * n + j]) d |= 1ull << i;
+        }
+        if (u == 0) return RPS_EINVAL;   // a server always holds its own copy
+        t.ucol[j] = u;
+        t.dcol[j] = d;
+        t.cnt[j] = __builtin_popcountll(u);
+        t.inv_cnt[j] = 1.0 / (double)t.cnt[j];
+        t.server[j] = server[j];
+    }
+    RPS_HIP(ctx, hipStreamSynchronize(ctx->stream));   // staging may still be in flight
+    *ctx->staging = t;
+    RPS_HIP(ctx, hipMemcpyAsync(ctx->tab, ctx->staging, sizeof(RoundTable), hipMemcpyHostToDevice, ctx->stream));
+    RPS_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    ctx->override_on = true;
+    return RPS_OK;
+}
+
+int rps_set_profiling(rps_ctx *ctx, int32_t enable) {
+    if (!ctx) return RPS_EINVAL;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return RPS_EHIP;
+    RPS_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    ctx->profiling = enable != 0;
+    ctx->ev_used = 0;
+    return RPS_OK;
+}
+
+int rps_get_kernel_time(rps_ctx *ctx, double *total_ms, int64_t *launches) {
+    if (!ctx || !total_ms || !launches) return RPS_EINVAL;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return RPS_EHIP;
+    RPS_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    double sum = 0.0;
+    for (size_t k = 0; k < ctx->ev_used; ++k) {
+        float ms = 0.0f;
+        RPS_HIP(ctx, hipEventElapsedTime(&ms, ctx->ev_start[k], ctx->ev_stop[k]));
+        sum += (double)ms;
+    }
+    *total_ms = sum;
+    *launches = (int64_t)ctx->ev_used;
+    ctx->ev_used = 0;
+    return RPS_OK;
+}
+
+int rps_last_hip_error(const rps_ctx *ctx) { return ctx ? ctx->last_hip : 0; }
+
+const char *rps_strerror(int code) {
+    switch (code) {
+        case RPS_OK: return "success";
+        case RPS_EINVAL: return "invalid argument";
+        case RPS_ENOMEM: return "out of memory";
+        case RPS_EHIP: return "HIP runtime error (see rps_last_hip_error)";
+        case RPS_EUNSUPPORTED: return "not supported";
+        default: return "unknown error code";
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,47 @@
+// Internal declarations shared by the kernel file and the C-ABI file of the HIP library.
+// (Not installed; the public interface is include/rps.h.)
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace rps {
+
+constexpr int kMaxWorkers = 64;          // one 64-bit lane mask per block and direction
+constexpr int kColsPerLane = 8;          // one noise hash call = 8 columns = 32 B fp32 / 16 B bf16
+constexpr int kTileCols = 64 * kColsPerLane;
+
+// Device-resident description of one round's network outcome plus the block partition.
+// Written by the mask kernel (or copied from the host for a mask override), read by the
+// round kernels through wave-uniform (scalar) loads.
+struct RoundTable {
+    uint64_t ucol[kMaxWorkers];     // bit i of ucol[j]: worker i's copy of block j reached server[j]
+    uint64_t dcol[kMaxWorkers];     // bit i of dcol[j]: server[j]'s reply reached worker i
+    double inv_cnt[kMaxWorkers];    // 1 / popcount(ucol[j])
+    int64_t off[kMaxWorkers + 1];   // block j = columns [off[j], off[j+1])
+    int32_t cnt[kMaxWorkers];       // popcount(ucol[j]) >= 1
+    int32_t server[kMaxWorkers];    // worker that averages block j
+};
+
+struct RoundParams {
+    int64_t N;            // row pitch in elements
+    int32_t n;            // workers
+    int32_t vec_ok;       // 1: every full 8-column group may use 128-bit accesses
+    float gamma;
+    float sigma;          // synthetic gradient: noise std
+    float lambda;         // synthetic gradient: weight decay
+    uint32_t seed_lo, seed_hi;
+    uint32_t step_lo, step_hi24;
+};
+
+enum GradMode { kGradNone = 0, kGradBuffer = 1, kGradSynthetic = 2 };
+
+// Launchers (rps_kernels.hip).  All enqueue on `stream` and return the launch status.
+hipError_t launch_masks(RoundTable *tab, int n, uint64_t seed, uint64_t step, uint64_t threshold,
+                        int identity_server, hipStream_t stream);
+hipError_t launch_round(int dtype, int grad_mode, void *X, const void *G, const RoundTable *tab,
+                        const RoundParams &prm, int64_t max_block_cols, hipStream_t stream);
+hipError_t launch_local_step(int dtype, int grad_mode, void *X, const void *G,
+                             const RoundParams &prm, hipStream_t stream);
+
+}  // namespace rps

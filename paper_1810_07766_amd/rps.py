@@ -1,0 +1,183 @@
+"""Thin ctypes binding of the HIP library's C ABI (include/rps.h).
+
+Argument marshalling only: every step of the round runs in the library's HIP
+kernels.  PyTorch supplies device memory and the stream, nothing else.  There is
+no CPU fallback: if the shared library is missing, importing this module raises.
+"""
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "librps.so")
+
+RPS_OK, RPS_EINVAL, RPS_ENOMEM, RPS_EHIP, RPS_EUNSUPPORTED = 0, -1, -2, -3, -4
+RPS_DTYPE_F32, RPS_DTYPE_BF16 = 0, 1
+RPS_FLAG_SERVER_IDENTITY = 1
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        f"{LIB_PATH} is not built: run `python -m paper_1810_07766_amd.build` (hipcc, gfx950). "
+        "There is no fallback path.")
+_lib = ctypes.CDLL(LIB_PATH)
+
+_ctx_p = ctypes.c_void_p
+_lib.rps_create.argtypes = [ctypes.POINTER(_ctx_p), ctypes.c_int32, ctypes.c_int64,
+                            ctypes.POINTER(ctypes.c_int64), ctypes.c_double, ctypes.c_float,
+                            ctypes.c_uint64, ctypes.c_int32, ctypes.c_uint32, ctypes.c_void_p]
+_lib.rps_destroy.argtypes = [_ctx_p]
+_lib.rps_set_synthetic_grad.argtypes = [_ctx_p, ctypes.c_float, ctypes.c_float]
+_lib.rps_set_gamma.argtypes = [_ctx_p, ctypes.c_float]
+_lib.rps_local_step.argtypes = [_ctx_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64]
+_lib.rps_lossy_average.argtypes = [_ctx_p, ctypes.c_void_p, ctypes.c_uint64]
+_lib.rps_round.argtypes = [_ctx_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64]
+_lib.rps_get_masks.argtypes = [_ctx_p, ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+_lib.rps_set_mask_override.argtypes = [_ctx_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+_lib.rps_set_profiling.argtypes = [_ctx_p, ctypes.c_int32]
+_lib.rps_get_kernel_time.argtypes = [_ctx_p, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
+_lib.rps_last_hip_error.argtypes = [_ctx_p]
+_lib.rps_strerror.argtypes = [ctypes.c_int]
+_lib.rps_strerror.restype = ctypes.c_char_p
+for _name in ("rps_create", "rps_destroy", "rps_set_synthetic_grad", "rps_set_gamma", "rps_local_step",
+              "rps_lossy_average", "rps_round", "rps_get_masks", "rps_set_mask_override",
+              "rps_set_profiling", "rps_get_kernel_time", "rps_last_hip_error"):
+    getattr(_lib, _name).restype = ctypes.c_int
+
+EXPORTS = ("rps_create", "rps_destroy", "rps_set_synthetic_grad", "rps_set_gamma", "rps_local_step",
+           "rps_lossy_average", "rps_round", "rps_get_masks", "rps_set_mask_override",
+           "rps_set_profiling", "rps_get_kernel_time", "rps_last_hip_error", "rps_strerror")
+
+
+class RpsError(RuntimeError):
+    def __init__(self, code, hip=0):
+        self.code, self.hip = code, hip
+        msg = _lib.rps_strerror(code).decode()
+        super().__init__(f"rps error {code}: {msg}" + (f" (hipError_t {hip})" if hip else ""))
+
+
+def _check(code, ctx=None):
+    if code != RPS_OK:
+        raise RpsError(code, _lib.rps_last_hip_error(ctx) if ctx else 0)
+
+
+def rps_strerror(code: int) -> str:
+    return _lib.rps_strerror(code).decode()
+
+
+def _ptr(t, ctx):
+    """Device pointer of a torch tensor after checking it is what the ABI expects."""
+    import torch
+    if t is None:
+        return None
+    want = torch.float32 if ctx.dtype == RPS_DTYPE_F32 else torch.bfloat16
+    if not (t.is_cuda and t.is_contiguous() and t.dtype == want and tuple(t.shape) == (ctx.n, ctx.N)):
+        raise RpsError(RPS_EINVAL)
+    return ctypes.c_void_p(t.data_ptr())
+
+
+class RpsContext:
+    """Owns one rps_ctx handle.  Methods mirror the C entry points one to one."""
+
+    def __init__(self, n, N, p, gamma, seed, dtype=RPS_DTYPE_F32, block_offsets=None, flags=0, stream=None):
+        import torch
+        if stream is None:
+            stream = torch.cuda.current_stream().cuda_stream
+        off = None
+        if block_offsets is not None:
+            vals = [int(v) for v in block_offsets]
+            if len(vals) != n + 1:
+                raise RpsError(RPS_EINVAL)
+            off = (ctypes.c_int64 * (n + 1))(*vals)
+        handle = _ctx_p()
+        _check(_lib.rps_create(ctypes.byref(handle), n, N, off, p, gamma, seed, dtype, flags,
+                               ctypes.c_void_p(stream)))
+        self._h = handle
+        self.n, self.N, self.dtype = n, N, dtype
+
+    def destroy(self):
+        if getattr(self, "_h", None):
+            h, self._h = self._h, None
+            _check(_lib.rps_destroy(h))
+
+    __del__ = destroy
+
+    def set_synthetic_grad(self, sigma, weight_decay=0.0):
+        _check(_lib.rps_set_synthetic_grad(self._h, sigma, weight_decay), self._h)
+
+    def set_gamma(self, gamma):
+        _check(_lib.rps_set_gamma(self._h, gamma), self._h)
+
+    def local_step(self, X, G, step):
+        _check(_lib.rps_local_step(self._h, _ptr(X, self), _ptr(G, self), step), self._h)
+
+    def lossy_average(self, X, step):
+        _check(_lib.rps_lossy_average(self._h, _ptr(X, self), step), self._h)
+
+    def round(self, X, G, step):
+        _check(_lib.rps_round(self._h, _ptr(X, self), _ptr(G, self), step), self._h)
+
+    def get_masks(self, step):
+        import numpy as np
+        n = self.n
+        up = np.empty((n, n), dtype=np.uint8)
+        down = np.empty((n, n), dtype=np.uint8)
+        server = np.empty(n, dtype=np.int32)
+        _check(_lib.rps_get_masks(self._h, step, up.ctypes.data, down.ctypes.data, server.ctypes.data), self._h)
+        return server, up, down
+
+    def set_mask_override(self, server=None, up=None, down=None):
+        import numpy as np
+        if server is None and up is None and down is None:
+            _check(_lib.rps_set_mask_override(self._h, None, None, None), self._h)
+            return
+        up = np.ascontiguousarray(up, dtype=np.uint8)
+        down = np.ascontiguousarray(down, dtype=np.uint8)
+        server = np.ascontiguousarray(server, dtype=np.int32)
+        if up.shape != (self.n, self.n) or down.shape != (self.n, self.n) or server.shape != (self.n,):
+            raise RpsError(RPS_EINVAL)
+        _check(_lib.rps_set_mask_override(self._h, up.ctypes.data, down.ctypes.data, server.ctypes.data), self._h)
+
+    def set_profiling(self, enable):
+        _check(_lib.rps_set_profiling(self._h, 1 if enable else 0), self._h)
+
+    def get_kernel_time(self):
+        """(total kernel milliseconds, launches) since profiling was enabled / last read."""
+        ms, cnt = ctypes.c_double(), ctypes.c_int64()
+        _check(_lib.rps_get_kernel_time(self._h, ctypes.byref(ms), ctypes.byref(cnt)), self._h)
+        return ms.value, cnt.value
+
+
+# function-style aliases with the C names
+def rps_create(n, N, block_offsets, p, gamma, seed, dtype=RPS_DTYPE_F32, flags=0, stream=None):
+    return RpsContext(n, N, p, gamma, seed, dtype, block_offsets, flags, stream)
+
+
+def rps_destroy(ctx):
+    ctx.destroy()
+
+
+def rps_set_synthetic_grad(ctx, sigma, weight_decay=0.0):
+    ctx.set_synthetic_grad(sigma, weight_decay)
+
+
+def rps_set_gamma(ctx, gamma):
+    ctx.set_gamma(gamma)
+
+
+def rps_local_step(ctx, X, G, step):
+    ctx.local_step(X, G, step)
+
+
+def rps_lossy_average(ctx, X, step):
+    ctx.lossy_average(X, step)
+
+
+def rps_round(ctx, X, G, step):
+    ctx.round(X, G, step)
+
+
+def rps_get_masks(ctx, step):
+    return ctx.get_masks(step)
+
+
+def rps_set_mask_override(ctx, server=None, up=None, down=None):
+    ctx.set_mask_override(server, up, down)

@@ -1,0 +1,144 @@
+"""GPU parity at the benchmark configurations, in the launch configuration bench.py times.
+
+Full-size states do not fit an element-by-element oracle run in seconds, so at full size the
+oracle follows a SAMPLE of model coordinates (the first and last 9 columns of every block plus
+random ones, all workers): every column of a round depends only on that column's n values, the
+round's masks and the column's own noise, so the oracle can evolve the sample for the whole
+trajectory from the seeded initial state without ever reading a value the HIP path produced.
+One configuration (n=16, N=11.2M) is also compared in full for two rounds."""
+import numpy as np
+import pytest
+import torch
+
+import workloads
+from oracle import rps_oracle as oracle
+from gpu_common import as_float, assert_close, device_tensor, masks_equal, to_oracle
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def rps():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_1810_07766_amd import rps as mod
+    return mod
+
+
+def _seeded_state(cfg, scale, seed):
+    """[n, N] device tensor of N(0, scale^2) from a seeded device generator (zeros if scale == 0)."""
+    tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+    if scale == 0.0:
+        return torch.zeros(cfg.n, cfg.N, device="cuda", dtype=tdt)
+    g = torch.Generator(device="cuda"); g.manual_seed(seed)
+    X = torch.empty(cfg.n, cfg.N, device="cuda", dtype=tdt)
+    for i in range(cfg.n):                                 # row by row: bounded temporaries
+        X[i] = (torch.randn(cfg.N, device="cuda", generator=g) * scale).to(tdt)
+    return X
+
+
+def _sampled_trajectory(rps, cfg, p, rounds, init_scale, per_block=40):
+    off = workloads.config_offsets(cfg)
+    cols = workloads.sample_columns(off, per_block=per_block, seed=11)
+    X = _seeded_state(cfg, init_scale, seed=5)
+    idx = torch.from_numpy(cols).cuda()
+    Xo = to_oracle(X.index_select(1, idx))
+    ctx = rps.RpsContext(cfg.n, cfg.N, p, cfg.gamma, cfg.seed,
+                         rps.RPS_DTYPE_BF16 if cfg.dtype == "bf16" else rps.RPS_DTYPE_F32, block_offsets=off)
+    ctx.set_synthetic_grad(cfg.sigma, cfg.weight_decay)
+    worst = 0.0
+    for t in range(rounds):
+        ctx.round(X, None, t)
+        oracle.round_(Xo, None, off, p=p, gamma=cfg.gamma, seed=cfg.seed, step=t, sigma=cfg.sigma,
+                      weight_decay=cfg.weight_decay, cols=cols)
+        if t < 3 or t == rounds - 1 or t % 10 == 0:
+            masks_equal(ctx, cfg.seed, t, cfg.n, p)
+            got = to_oracle(X.index_select(1, idx))
+            worst = max(worst, assert_close(got, Xo, off, cfg.dtype, cols=cols, what=f"{cfg.name} p={p} round {t}"))
+    # properties that hold at any size, checked on the whole last state: per block, every worker
+    # whose reply arrived holds the same bits
+    server, U, D = oracle.masks(cfg.seed, rounds - 1, cfg.n, p)
+    for j in (0, cfg.n // 2, cfg.n - 1):
+        recv = np.flatnonzero(D[:, j])
+        blk = X[:, int(off[j]):int(off[j + 1])]
+        ref = blk[int(recv[0])]
+        for i in recv[1:]:
+            assert torch.equal(blk[int(i)], ref)
+    ctx.destroy()
+    return worst
+
+
+def test_config_lsq_n4_trajectory(rps):
+    """n=4, N=10,000, least squares, gamma=0.01, p=0.1, 100 rounds.  Each side computes its own
+    full gradient A_i^T (A_i x_i - b_i) in float64 on the host from its own state."""
+    cfg = workloads.CONFIGS["lsq_n4"]
+    off = workloads.config_offsets(cfg)
+    A, b = workloads.least_squares_problem(cfg.n, cfg.N, cfg.extra["rows"], seed=cfg.seed)
+
+    def grad(X):
+        return np.stack([A[i].T @ (A[i] @ X[i].astype(np.float64) - b[i]) for i in range(cfg.n)]).astype(np.float32)
+
+    def loss(X):
+        return float(np.mean([0.5 * np.sum((A[i] @ X.astype(np.float64).mean(axis=0) - b[i]) ** 2) for i in range(cfg.n)]))
+
+    Xo = np.zeros((cfg.n, cfg.N), dtype=np.float32)
+    Xg = torch.zeros(cfg.n, cfg.N, device="cuda")
+    ctx = rps.RpsContext(cfg.n, cfg.N, cfg.p, cfg.gamma, cfg.seed)
+    l0 = loss(Xo)
+    for t in range(cfg.rounds):
+        Gg = torch.from_numpy(grad(Xg.cpu().numpy())).cuda()
+        ctx.round(Xg, Gg, t)
+        oracle.round_(Xo, grad(Xo), off, p=cfg.p, gamma=cfg.gamma, seed=cfg.seed, step=t)
+        if t % 10 == 9:
+            torch.cuda.synchronize()
+            assert_close(Xg.cpu().numpy(), Xo, off, "f32", what=f"round {t}")
+    lg, lo = loss(Xg.cpu().numpy()), loss(Xo)
+    assert lo < 0.5 * l0                                    # it optimises
+    assert abs(lg - lo) <= 1e-6 * lo
+    ctx.destroy()
+
+
+def test_config_resnet18_n16_full_state_two_rounds(rps):
+    """n=16, N=11.2M, all 179 M elements compared for two rounds (p = 0.1)."""
+    cfg = workloads.CONFIGS["resnet18_n16"]
+    off = workloads.config_offsets(cfg)
+    X = _seeded_state(cfg, 0.01, seed=3)
+    Xo = to_oracle(X)
+    ctx = rps.RpsContext(cfg.n, cfg.N, cfg.p, cfg.gamma, cfg.seed)
+    ctx.set_synthetic_grad(cfg.sigma, cfg.weight_decay)
+    threads = min(16, oracle.max_threads())
+    for t in range(2):
+        ctx.round(X, None, t)
+        oracle.round_(Xo, None, off, p=cfg.p, gamma=cfg.gamma, seed=cfg.seed, step=t, sigma=cfg.sigma,
+                      weight_decay=cfg.weight_decay, threads=threads)
+        torch.cuda.synchronize()
+        got = X.cpu().numpy()
+        # same tolerance as assert_close, vectorised per block for this size
+        for j in range(cfg.n):
+            blk = slice(int(off[j]), int(off[j + 1]))
+            r = Xo[:, blk].astype(np.float64)
+            tol = 1e-6 * (np.abs(r) + np.sqrt(np.mean(r ** 2)))
+            assert (np.abs(got[:, blk] - r) <= tol).all(), f"round {t} block {j}"
+    ctx.destroy()
+
+
+@pytest.mark.parametrize("p", [0.0, 0.01, 0.1])
+def test_config_resnet18_n16_sampled(rps, p):
+    cfg = workloads.CONFIGS["resnet18_n16"]
+    _sampled_trajectory(rps, cfg, p, cfg.rounds, init_scale=0.0)
+
+
+def test_config_resnet50_n32_sampled(rps):
+    """Headline configuration: n=32, N=25.6M, p=0.05, 50 rounds from the all-zero start."""
+    cfg = workloads.CONFIGS["resnet50_n32"]
+    _sampled_trajectory(rps, cfg, cfg.p, cfg.rounds, init_scale=0.0)
+
+
+def test_config_resnet50_n32_sampled_random_start(rps):
+    cfg = workloads.CONFIGS["resnet50_n32"]
+    _sampled_trajectory(rps, cfg, cfg.p, 10, init_scale=0.02)
+
+
+def test_config_bert_n64_bf16_sampled(rps):
+    """n=64, N=110M, bf16 storage, 64 unequal blocks, 20 rounds (14 GB of state)."""
+    cfg = workloads.CONFIGS["bert_n64_bf16"]
+    _sampled_trajectory(rps, cfg, cfg.p, cfg.rounds, init_scale=0.0, per_block=24)

@@ -1,0 +1,273 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle on the same seeded
+inputs, element by element, at sizes that span several 512-column tiles and ragged tails.
+Masks and the server permutation must agree bit for bit; parameters within the tolerance
+documented in gpu_common.py."""
+import numpy as np
+import pytest
+import torch
+
+import workloads
+from oracle import rps_oracle as oracle
+from gpu_common import RTOL, as_float, assert_close, device_tensor, masks_equal, to_oracle
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def rps():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_1810_07766_amd import rps as mod     # raises if librps.so is not built
+    return mod
+
+
+def _dt(rps, dtype):
+    return rps.RPS_DTYPE_BF16 if dtype == "bf16" else rps.RPS_DTYPE_F32
+
+
+def _offsets(n, N, layout, seed=3):
+    if layout == "equal":
+        return workloads.block_offsets(n, N)
+    if layout == "unequal8":
+        return workloads.block_offsets(n, N, unequal=True, block_seed=seed)
+    # arbitrary cut points: blocks start at any column, some of them a single column wide
+    rng = np.random.default_rng(seed)
+    cuts = np.sort(rng.choice(np.arange(1, N), size=n - 1, replace=False)) if n > 1 else np.array([], dtype=np.int64)
+    return np.concatenate([[0], cuts, [N]]).astype(np.int64)
+
+
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("n,p,seed", [(1, 0.5, 0), (2, 0.3, 1), (4, 0.1, 0), (7, 0.25, 99), (16, 0.01, 0),
+                                      (32, 0.05, 0), (33, 0.5, 2 ** 63 + 12345), (64, 0.1, 0)])
+def test_masks_bit_exact(rps, n, p, seed):
+    ctx = rps.RpsContext(n, n * 16, p, 0.1, seed)
+    for step in list(range(25)) + [2 ** 32 - 1, 2 ** 32, 2 ** 40 + 7, 2 ** 56 - 1]:
+        masks_equal(ctx, seed, step, n, p)
+    ctx.destroy()
+    ctx = rps.RpsContext(n, n * 16, p, 0.1, seed, flags=rps.RPS_FLAG_SERVER_IDENTITY)
+    for step in range(5):
+        masks_equal(ctx, seed, step, n, p, identity=True)
+    ctx.destroy()
+
+
+def test_masks_p_extremes(rps):
+    for p in (0.0, 1.0):
+        ctx = rps.RpsContext(16, 256, p, 0.1, 5)
+        for step in range(10):
+            masks_equal(ctx, 5, step, 16, p)
+        ctx.destroy()
+
+
+# ---------------------------------------------------------------------------------------------
+SHAPES = [
+    # n, N, layout, dtype
+    (1, 1500, "equal", "f32"),
+    (2, 2 * 777, "equal", "f32"),            # N % 4 != 0 -> element-wise path (1554 % 4 = 2)
+    (3, 3 * 1301, "equal", "f32"),           # odd pitch: rows not 16-byte aligned
+    (4, 10_000, "equal", "f32"),             # config 1 shape
+    (5, 5 * 1600, "arbitrary", "f32"),
+    (8, 8 * 2048, "equal", "f32"),
+    (13, 13 * 1304, "arbitrary", "f32"),
+    (16, 16 * 1296, "unequal8", "f32"),
+    (32, 32 * 1544, "equal", "f32"),
+    (33, 33 * 1000, "unequal8", "f32"),
+    (64, 64 * 520, "equal", "f32"),
+    (64, 64, "equal", "f32"),                # one column per block
+    (4, 4 * 2056, "equal", "bf16"),
+    (9, 9 * 1000, "arbitrary", "bf16"),
+    (16, 16 * 1544, "unequal8", "bf16"),
+    (64, 64 * 1032, "unequal8", "bf16"),
+    (6, 6 * 999, "equal", "bf16"),           # N % 8 != 0 -> element-wise path
+]
+
+
+@pytest.mark.parametrize("n,N,layout,dtype", SHAPES)
+def test_round_synthetic_gradient(rps, n, N, layout, dtype):
+    """Fused round with the in-register synthetic gradient, three rounds from a random state."""
+    off = _offsets(n, N, layout)
+    p, gamma, sigma, lam, seed = 0.2, 0.1, 0.1, 1e-2, 17
+    X0 = workloads.gaussian_model(n, N, seed=n * 1000 + N % 997, scale=0.05)
+    Xg = device_tensor(X0, dtype)
+    Xo = to_oracle(Xg)
+    ctx = rps.RpsContext(n, N, p, gamma, seed, _dt(rps, dtype), block_offsets=off)
+    ctx.set_synthetic_grad(sigma, lam)
+    for step in (0, 1, 2 ** 33 + 5):
+        masks_equal(ctx, seed, step, n, p)
+        ctx.round(Xg, None, step)
+        oracle.round_(Xo, None, off, p=p, gamma=gamma, seed=seed, step=step, sigma=sigma, weight_decay=lam)
+        torch.cuda.synchronize()
+        assert_close(to_oracle(Xg), Xo, off, dtype, what=f"step {step}")
+    ctx.destroy()
+
+
+@pytest.mark.parametrize("n,N,layout,dtype", SHAPES[::2])
+def test_round_gradient_buffer(rps, n, N, layout, dtype):
+    """Fused round with a caller-supplied gradient (Alg. 1 steps 3-5 done by the caller)."""
+    off = _offsets(n, N, layout, seed=5)
+    p, gamma, seed = 0.3, 0.25, 23
+    Xg = device_tensor(workloads.gaussian_model(n, N, seed=1), dtype)
+    Gg = device_tensor(workloads.gaussian_model(n, N, seed=2), dtype)
+    Xo, Go = to_oracle(Xg), to_oracle(Gg)
+    ctx = rps.RpsContext(n, N, p, gamma, seed, _dt(rps, dtype), block_offsets=off)
+    for step in (3, 4):
+        ctx.round(Xg, Gg, step)
+        oracle.round_(Xo, Go, off, p=p, gamma=gamma, seed=seed, step=step)
+        torch.cuda.synchronize()
+        assert_close(to_oracle(Xg), Xo, off, dtype, what=f"step {step}")
+    ctx.destroy()
+
+
+@pytest.mark.parametrize("n,N,layout,dtype", SHAPES[1::2])
+def test_unfused_entry_points_and_fused_equals_unfused(rps, n, N, layout, dtype):
+    """rps_local_step and rps_lossy_average against the oracle's two steps; and the fused round
+    equals local step followed by lossy average bit for bit."""
+    off = _offsets(n, N, layout, seed=7)
+    p, gamma, sigma, lam, seed, step = 0.15, 0.05, 0.2, 1e-3, 4, 11
+    X0 = workloads.gaussian_model(n, N, seed=3, scale=0.3)
+    ctx = rps.RpsContext(n, N, p, gamma, seed, _dt(rps, dtype), block_offsets=off)
+    ctx.set_synthetic_grad(sigma, lam)
+    Xa = device_tensor(X0, dtype); Xo = to_oracle(Xa)
+    ctx.local_step(Xa, None, step)
+    oracle.local_step(Xo, None, gamma, sigma=sigma, weight_decay=lam, seed=seed, step=step)
+    torch.cuda.synchronize()
+    # the local step is elementwise with the same operation order on both sides: bitwise
+    assert (to_oracle(Xa) == Xo).all()
+    ctx.lossy_average(Xa, step)
+    server, U, D = oracle.masks(seed, step, n, p)
+    oracle.lossy_average(Xo, off, U, D)
+    torch.cuda.synchronize()
+    assert_close(to_oracle(Xa), Xo, off, dtype, what="lossy_average")
+    Xb = device_tensor(X0, dtype)
+    ctx.round(Xb, None, step)
+    torch.cuda.synchronize()
+    assert torch.equal(Xa.view(torch.int16 if dtype == "bf16" else torch.int32),
+                       Xb.view(torch.int16 if dtype == "bf16" else torch.int32))
+    # same with a gradient buffer
+    Gg = device_tensor(workloads.gaussian_model(n, N, seed=4), dtype)
+    Xa = device_tensor(X0, dtype); Xb = device_tensor(X0, dtype)
+    ctx.local_step(Xa, Gg, step); ctx.lossy_average(Xa, step); ctx.round(Xb, Gg, step)
+    torch.cuda.synchronize()
+    assert torch.equal(Xa.view(torch.int16 if dtype == "bf16" else torch.int32),
+                       Xb.view(torch.int16 if dtype == "bf16" else torch.int32))
+    ctx.destroy()
+
+
+# ---------------------------------------------------------------------------------------------
+def test_special_networks(rps):
+    n, N = 8, 8 * 1300
+    off = workloads.block_offsets(n, N)
+    V = workloads.gaussian_model(n, N, seed=21)
+    # p = 0: exact averaging, every worker identical to the column mean
+    ctx = rps.RpsContext(n, N, 0.0, 0.1, 0)
+    X = device_tensor(V, "f32"); ctx.lossy_average(X, 0); torch.cuda.synchronize()
+    got = X.cpu().numpy()
+    mean = V.astype(np.float64).mean(axis=0)
+    assert (got == got[0:1]).all()
+    assert np.abs(got[0] - mean).max() <= 6e-8 * np.abs(mean).max() + 1e-12
+    ctx.destroy()
+    # p = 1: nothing arrives, X_{t+1} = V_t bitwise
+    ctx = rps.RpsContext(n, N, 1.0, 0.1, 0)
+    X = device_tensor(V, "f32"); ctx.lossy_average(X, 3); torch.cuda.synchronize()
+    assert (X.cpu().numpy() == V).all()
+    ctx.destroy()
+
+
+def test_mask_override_forces_outcomes(rps):
+    n, N = 5, 5 * 700
+    off = workloads.block_offsets(n, N)
+    V = workloads.gaussian_model(n, N, seed=22)
+    ctx = rps.RpsContext(n, N, 0.1, 0.1, 0)
+    rng = np.random.default_rng(1)
+    server = rng.permutation(n).astype(np.int32)
+    # block 0: every uplink lost (lonely server still broadcasts its own block);
+    # block 1: every downlink lost (nobody but the server changes); others random
+    U = (rng.random((n, n)) > 0.4).astype(np.uint8); D = (rng.random((n, n)) > 0.4).astype(np.uint8)
+    U[:, 0] = 0; D[:, 1] = 0
+    U[server, np.arange(n)] = 1; D[server, np.arange(n)] = 1
+    ctx.set_mask_override(server, U, D)
+    X = device_tensor(V, "f32"); ctx.lossy_average(X, 0); torch.cuda.synchronize()
+    ref = V.copy(); oracle.lossy_average(ref, off, U, D)
+    got = X.cpu().numpy()
+    assert_close(got, ref, off, "f32")
+    b0 = slice(off[0], off[1])
+    recv = np.flatnonzero(D[:, 0])
+    assert (got[recv][:, b0] == V[server[0], b0][None, :]).all()
+    # per block: receivers bitwise identical, the others untouched
+    for j in range(n):
+        blk = slice(off[j], off[j + 1])
+        r = np.flatnonzero(D[:, j]); k = np.flatnonzero(D[:, j] == 0)
+        assert (got[r][:, blk] == got[r[0]][blk][None, :]).all()
+        assert (got[k][:, blk] == V[k][:, blk]).all()
+    # a block with no delivered uplink is impossible in the model: rejected
+    bad = U.copy(); bad[:, 2] = 0
+    with pytest.raises(rps.RpsError):
+        ctx.set_mask_override(server, bad, D)
+    # clearing the override restores generated masks
+    ctx.set_mask_override()
+    X = device_tensor(V, "f32"); ctx.lossy_average(X, 7); torch.cuda.synchronize()
+    s, U2, D2 = oracle.masks(0, 7, n, 0.1)
+    ref = V.copy(); oracle.lossy_average(ref, off, U2, D2)
+    assert_close(X.cpu().numpy(), ref, off, "f32")
+    ctx.destroy()
+
+
+def test_deterministic_and_stateless_resume(rps):
+    n, N = 16, 16 * 1100
+    X0 = workloads.gaussian_model(n, N, seed=30, scale=0.1)
+    ctx = rps.RpsContext(n, N, 0.1, 0.1, 9)
+    ctx.set_synthetic_grad(0.1, 1e-4)
+    A = device_tensor(X0, "f32"); B = device_tensor(X0, "f32")
+    for t in range(10):
+        ctx.round(A, None, t)
+    for t in range(5):
+        ctx.round(B, None, t)
+    torch.cuda.synchronize()
+    B = B.clone()                       # "reload" the checkpoint (X, step)
+    ctx2 = rps.RpsContext(n, N, 0.1, 0.1, 9)
+    ctx2.set_synthetic_grad(0.1, 1e-4)
+    for t in range(5, 10):
+        ctx2.round(B, None, t)
+    torch.cuda.synchronize()
+    assert torch.equal(A, B)            # bitwise: run-to-run determinism, no hidden state
+    ctx.destroy(); ctx2.destroy()
+
+
+def test_argument_errors(rps):
+    with pytest.raises(rps.RpsError):
+        rps.RpsContext(0, 100, 0.1, 0.1, 0)
+    with pytest.raises(rps.RpsError):
+        rps.RpsContext(65, 6500, 0.1, 0.1, 0)
+    with pytest.raises(rps.RpsError):
+        rps.RpsContext(4, 101, 0.1, 0.1, 0)                  # equal blocks need N % n == 0
+    with pytest.raises(rps.RpsError):
+        rps.RpsContext(4, 100, 1.5, 0.1, 0)
+    with pytest.raises(rps.RpsError):
+        rps.RpsContext(4, 100, 0.1, 0.1, 0, block_offsets=[0, 10, 10, 50, 100])   # empty block
+    with pytest.raises(rps.RpsError):
+        rps.RpsContext(4, 100, 0.1, 0.1, 0, block_offsets=[0, 10, 20, 50, 99])    # does not end at N
+    ctx = rps.RpsContext(4, 100, 0.1, 0.1, 0)
+    X = torch.zeros(4, 100, device="cuda")
+    with pytest.raises(rps.RpsError):
+        ctx.round(X, None, 1 << 56)                           # step out of range
+    with pytest.raises(rps.RpsError):
+        ctx.round(X[:, :50], None, 0)                         # wrong shape / not contiguous
+    with pytest.raises(rps.RpsError):
+        ctx.round(X.to(torch.bfloat16), None, 0)              # wrong dtype
+    ctx.round(X, None, 0); torch.cuda.synchronize()
+    assert (X == 0).all()                                     # sigma = 0, x = 0: nothing moves
+    ctx.destroy()
+
+
+def test_profiling_hooks(rps):
+    n, N = 8, 8 * 4096
+    ctx = rps.RpsContext(n, N, 0.1, 0.1, 0)
+    ctx.set_synthetic_grad(0.1, 0.0)
+    X = torch.zeros(n, N, device="cuda")
+    ctx.set_profiling(True)
+    for t in range(6):
+        ctx.round(X, None, t)
+    ms, cnt = ctx.get_kernel_time()
+    assert cnt == 6 and ms > 0.0
+    ms, cnt = ctx.get_kernel_time()
+    assert cnt == 0 and ms == 0.0
+    ctx.set_profiling(False)
+    ctx.destroy()
