@@ -45,7 +45,7 @@ def cpu_baseline(cfg, off, budget_cols):
         oracle.round_(X, None, off, p=cfg.p, gamma=cfg.gamma, seed=cfg.seed, step=reps, sigma=cfg.sigma,
                       weight_decay=cfg.weight_decay, cols=cols, threads=threads)
         dt = time.perf_counter() - t0
-        if dt > 10.0 or reps >= 50:
+        if dt > 10.0:
             break
     return {"value": cfg.n * m * reps / dt, "unit": "worker-params/s", "cores": threads, "kind": "oracle",
             "sample": f"{reps} rounds over {m} columns ({per_block} per block) x {cfg.n} workers of the same workload, "
@@ -59,6 +59,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", default=None, help="workload name (default: the headline config)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run three plain 1 GiB device copies (a kernel of known traffic) so that one "
+                         "rocprofv3 --pmc run holds both the round kernel and the reference for its counters")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the n workers are simulated in one [n, N] tensor); "
@@ -118,6 +121,13 @@ def main():
     }
     ctx.destroy()
     del X
+    if args.pmc_calibration:
+        src = torch.ones(1 << 28, device="cuda")          # 1 GiB of fp32
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, off, budget_cols=1 << 18)
     print(json.dumps(out))

@@ -62,7 +62,7 @@ enum {
  * of Alg. 1: step size gamma; the network is characterised by n and the drop probability p).
  *   out            receives the handle (host pointer; untouched on error)
  *   n              workers = blocks = servers, 1..64
- *   N              parameters per worker, n <= N <= 2^35
+ *   N              parameters per worker, n <= N <= 2^34
  *   block_offsets  HOST array of n+1 int64 with off[0] = 0 < off[1] < ... < off[n] = N, block j
  *                  being columns [off[j], off[j+1]); or NULL for the paper's equally-sized
  *                  blocks, which needs N % n == 0.  Copied; the caller keeps ownership.
@@ -127,6 +127,16 @@ int rps_get_masks(rps_ctx *ctx, uint64_t step, uint8_t *up, uint8_t *down, int32
  * Synchronises the stream.
  */
 int rps_set_mask_override(rps_ctx *ctx, const uint8_t *up, const uint8_t *down, const int32_t *server);
+
+/*
+ * Launch shape of the round kernel, for tuning sweeps; results never depend on it.
+ *   rows_in_flight       rows per load chunk (a wavefront keeps two chunks in flight): 2 or 4
+ *   waves_per_workgroup  1 or 4 (a workgroup's wavefronts own adjacent tiles)
+ *   max_waves_per_cu     cap on resident wavefronts per compute unit (0 = no cap)
+ * The defaults are the measured best for the benchmark configurations.  RPS_EINVAL otherwise.
+ */
+int rps_set_launch_tuning(rps_ctx *ctx, int32_t rows_in_flight, int32_t waves_per_workgroup,
+                          int32_t max_waves_per_cu);
 
 /*
  * Kernel timing for benchmarks: while enabled, every rps_round / rps_lossy_average /

@@ -67,7 +67,9 @@ void rps_oracle_philox4x32(uint32_t rounds, const uint32_t ctr[4],
 }
 
 enum { DOMAIN_UPLINK = 0, DOMAIN_DOWNLINK = 1, DOMAIN_SERVER = 2, DOMAIN_NOISE = 3 };
-enum { MASK_ROUNDS = 10, NOISE_ROUNDS = 10 };
+/* Masks use the generator's standard 10 rounds; the noise stream uses 7, the smallest round
+   count its authors report as passing the BigCrush battery (it is the hot loop of the round). */
+enum { MASK_ROUNDS = 10, NOISE_ROUNDS = 7 };
 
 /* word 0 of the hash of (a, b, step, domain) under the 64-bit seed.          */
 static void hash_words(uint32_t rounds, uint64_t seed, uint64_t step,
@@ -131,9 +133,12 @@ void rps_oracle_masks(uint64_t seed, uint64_t step, int32_t n, double p,
 /* ------------------------------------------------------------------------- */
 /* Synthetic gradient noise (this project's specification; the paper's        */
 /* stochastic gradient is whatever the framework computes, Alg. 1 steps 3-4). */
-/* One hash call yields eight values sigma*z for the eight columns 8g..8g+7   */
-/* of one worker.  Each 32-bit word makes one Box-Muller pair from a 16-bit   */
-/* radius index (low half) and a 16-bit angle index (high half):              */
+/* One hash call, indexed by (quad q = column/4, worker pair k = worker/2),   */
+/* yields eight values sigma*z: words 0,1 give the four columns 4q..4q+3 of   */
+/* worker 2k, words 2,3 the same columns of worker 2k+1 (a 16-byte-wide,      */
+/* two-row patch of the [n, N] state).  Each 32-bit word makes one Box-Muller */
+/* pair from a 16-bit radius index (low half) and a 16-bit angle index (high  */
+/* half):                                                                     */
 /*     u1 = (2k+1)/2^17,  r = sqrt(-2 ln u1),  phi = (2f+1)*pi/65536 (+pi)    */
 /* evaluated with a fixed sequence of fp32 operations (polynomials for the    */
 /* logarithm, sine and cosine; two Newton steps for the reciprocal square     */
@@ -187,13 +192,22 @@ static void box_muller_pair(uint32_t word, float sigma, float *even, float *odd)
     *odd  = rsgn * sn;
 }
 
-void rps_oracle_noise8(uint64_t seed, uint64_t step, int32_t worker,
-                       uint64_t group, float sigma, float out[8])
+/* out[0..3]: worker 2*pair, columns 4*quad..4*quad+3; out[4..7]: worker 2*pair+1. */
+void rps_oracle_noise_patch(uint64_t seed, uint64_t step, int32_t pair,
+                            uint64_t quad, float sigma, float out[8])
 {
     uint32_t w[4];
-    hash_words(NOISE_ROUNDS, seed, step, (uint32_t)group, (uint32_t)worker, DOMAIN_NOISE, w);
+    hash_words(NOISE_ROUNDS, seed, step, (uint32_t)quad, (uint32_t)pair, DOMAIN_NOISE, w);
     for (int q = 0; q < 4; ++q)
         box_muller_pair(w[q], sigma, &out[2 * q], &out[2 * q + 1]);
+}
+
+/* sigma*z of one (worker, column). */
+float rps_oracle_noise(uint64_t seed, uint64_t step, int32_t worker, int64_t column, float sigma)
+{
+    float patch[8];
+    rps_oracle_noise_patch(seed, step, worker >> 1, (uint64_t)column >> 2, sigma, patch);
+    return patch[4 * (worker & 1) + (int)(column & 3)];
 }
 
 /* ------------------------------------------------------------------------- */
@@ -242,8 +256,6 @@ void rps_oracle_local_step(void *X, const void *G, int32_t n, int64_t m,
 #pragma omp parallel for schedule(static) num_threads(threads > 0 ? threads : 1)
 #endif
     for (int32_t i = 0; i < n; ++i) {
-        uint64_t have_group = UINT64_MAX;   /* the eight noise values of one hash call */
-        float z[8];
         for (int64_t k = 0; k < m; ++k) {
             float x = load_elem(X, dtype, i * m + k);
             float g;
@@ -251,12 +263,7 @@ void rps_oracle_local_step(void *X, const void *G, int32_t n, int64_t m,
                 g = load_elem(G, dtype, i * m + k);
             } else {
                 int64_t c = cols ? cols[k] : k;
-                uint64_t group = (uint64_t)c >> 3;
-                if (group != have_group) {
-                    rps_oracle_noise8(seed, step, i, group, sigma, z);
-                    have_group = group;
-                }
-                g = fmaf(lambda, x, z[c & 7]);
+                g = fmaf(lambda, x, rps_oracle_noise(seed, step, i, c, sigma));
             }
             float v = fmaf(-gamma, g, x);
             store_elem(X, dtype, i * m + k, v);

@@ -30,9 +30,11 @@ _lib.rps_oracle_philox4x32.restype = None
 _lib.rps_oracle_masks.argtypes = [ctypes.c_uint64, ctypes.c_uint64, ctypes.c_int32, ctypes.c_double,
                                   ctypes.c_int32, _i32p, _u8p, _u8p]
 _lib.rps_oracle_masks.restype = None
-_lib.rps_oracle_noise8.argtypes = [ctypes.c_uint64, ctypes.c_uint64, ctypes.c_int32, ctypes.c_uint64,
-                                   ctypes.c_float, _f32p]
-_lib.rps_oracle_noise8.restype = None
+_lib.rps_oracle_noise_patch.argtypes = [ctypes.c_uint64, ctypes.c_uint64, ctypes.c_int32, ctypes.c_uint64,
+                                        ctypes.c_float, _f32p]
+_lib.rps_oracle_noise_patch.restype = None
+_lib.rps_oracle_noise.argtypes = [ctypes.c_uint64, ctypes.c_uint64, ctypes.c_int32, ctypes.c_int64, ctypes.c_float]
+_lib.rps_oracle_noise.restype = ctypes.c_float
 _lib.rps_oracle_local_step.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64,
                                        _i64p, ctypes.c_int32, ctypes.c_float, ctypes.c_float,
                                        ctypes.c_float, ctypes.c_uint64, ctypes.c_uint64, ctypes.c_int32]
@@ -71,10 +73,15 @@ def masks(seed: int, step: int, n: int, p: float, identity_server: bool = False)
     return server, U, D
 
 
-def noise8(seed: int, step: int, worker: int, group: int, sigma: float = 1.0) -> np.ndarray:
+def noise_patch(seed: int, step: int, pair: int, quad: int, sigma: float = 1.0) -> np.ndarray:
+    """[2, 4] float32: sigma*z for workers (2*pair, 2*pair+1) x columns 4*quad..4*quad+3."""
     out = np.empty(8, dtype=np.float32)
-    _lib.rps_oracle_noise8(seed, step, worker, group, sigma, out.ctypes.data_as(_f32p))
-    return out
+    _lib.rps_oracle_noise_patch(seed, step, pair, quad, sigma, out.ctypes.data_as(_f32p))
+    return out.reshape(2, 4)
+
+
+def noise(seed: int, step: int, worker: int, column: int, sigma: float = 1.0) -> float:
+    return float(_lib.rps_oracle_noise(seed, step, worker, column, sigma))
 
 
 def _dtype_code(a: np.ndarray) -> int:

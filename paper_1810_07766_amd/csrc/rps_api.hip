@@ -32,6 +32,7 @@ struct rps_ctx {
     std::vector<hipEvent_t> ev_start, ev_stop;
     size_t ev_used = 0;
     int last_hip = 0;
+    rps::LaunchTuning tune{2, 1, 8};   // overwritten by default_tuning() at creation
 };
 
 namespace {
@@ -49,6 +50,15 @@ int hip_fail(rps_ctx *ctx, hipError_t e) {
     } while (0)
 
 bool step_ok(uint64_t step) { return step < (1ull << 56); }
+
+// Measured best launch shapes on MI355X (sweeps over rows per chunk, workgroup width and the
+// occupancy cap at n = 16 / 32 fp32 and n = 64 bf16).  The in-place update mixes n read streams
+// with n write streams; the memory system handles that best with few wavefronts resident.
+rps::LaunchTuning default_tuning(int32_t n, int32_t dtype) {
+    if (dtype == RPS_DTYPE_BF16) return rps::LaunchTuning{2, 4, 12};
+    if (n >= 24) return rps::LaunchTuning{4, 1, 6};
+    return rps::LaunchTuning{2, 4, 8};
+}
 
 RoundParams make_params(const rps_ctx *ctx, const void *X, const void *G, uint64_t step) {
     RoundParams prm;
@@ -120,7 +130,7 @@ int rps_create(rps_ctx **out, int32_t n, int64_t N, const int64_t *block_offsets
                uint64_t seed, int32_t dtype, uint32_t flags, void *hip_stream) {
     if (!out) return RPS_EINVAL;
     if (n < 1 || n > rps::kMaxWorkers) return RPS_EINVAL;
-    if (N < n || N > (1ll << 35)) return RPS_EINVAL;
+    if (N < n || N > (1ll << 34)) return RPS_EINVAL;
     if (!(p >= 0.0 && p <= 1.0)) return RPS_EINVAL;   // also rejects NaN
     if (!std::isfinite(gamma)) return RPS_EINVAL;
     if (dtype != RPS_DTYPE_F32 && dtype != RPS_DTYPE_BF16) return RPS_EINVAL;
@@ -156,6 +166,7 @@ int rps_create(rps_ctx **out, int32_t n, int64_t N, const int64_t *block_offsets
     ctx->dtype = dtype;
     ctx->flags = flags;
     ctx->stream = (hipStream_t)hip_stream;
+    ctx->tune = default_tuning(n, dtype);
 
     hipError_t e = hipGetDevice(&ctx->device);
     if (e == hipSuccess) e = hipMalloc((void **)&ctx->tab, 2 * sizeof(RoundTable));
@@ -226,7 +237,7 @@ int rps_lossy_average(rps_ctx *ctx, void *X, uint64_t step) {
     if (rc != RPS_OK) return rc;
     return timed_launch(ctx, [&] {
         return rps::launch_round(ctx->dtype, rps::kGradNone, X, nullptr, ctx->tab, prm, ctx->max_block_cols,
-                                 ctx->stream);
+                                 ctx->tune, ctx->stream);
     });
 }
 
@@ -239,7 +250,7 @@ int rps_round(rps_ctx *ctx, void *X, const void *G, uint64_t step) {
     const int rc = enqueue_masks(ctx, step);
     if (rc != RPS_OK) return rc;
     return timed_launch(ctx, [&] {
-        return rps::launch_round(ctx->dtype, mode, X, G, ctx->tab, prm, ctx->max_block_cols, ctx->stream);
+        return rps::launch_round(ctx->dtype, mode, X, G, ctx->tab, prm, ctx->max_block_cols, ctx->tune, ctx->stream);
     });
 }
 
@@ -295,6 +306,15 @@ int rps_set_mask_override(rps_ctx *ctx, const uint8_t *up, const uint8_t *down, 
     RPS_HIP(ctx, hipMemcpyAsync(ctx->tab, ctx->staging, sizeof(RoundTable), hipMemcpyHostToDevice, ctx->stream));
     RPS_HIP(ctx, hipStreamSynchronize(ctx->stream));
     ctx->override_on = true;
+    return RPS_OK;
+}
+
+int rps_set_launch_tuning(rps_ctx *ctx, int32_t rows_in_flight, int32_t waves_per_workgroup, int32_t max_waves_per_cu) {
+    if (!ctx) return RPS_EINVAL;
+    if (rows_in_flight != 2 && rows_in_flight != 4) return RPS_EINVAL;
+    if (waves_per_workgroup != 1 && waves_per_workgroup != 4) return RPS_EINVAL;
+    if (max_waves_per_cu < 0) return RPS_EINVAL;
+    ctx->tune = rps::LaunchTuning{rows_in_flight, waves_per_workgroup, max_waves_per_cu};
     return RPS_OK;
 }
 

@@ -8,8 +8,6 @@
 namespace rps {
 
 constexpr int kMaxWorkers = 64;          // one 64-bit lane mask per block and direction
-constexpr int kColsPerLane = 8;          // one noise hash call = 8 columns = 32 B fp32 / 16 B bf16
-constexpr int kTileCols = 64 * kColsPerLane;
 
 // Device-resident description of one round's network outcome plus the block partition.
 // Written by the mask kernel (or copied from the host for a mask override), read by the
@@ -36,11 +34,20 @@ struct RoundParams {
 
 enum GradMode { kGradNone = 0, kGradBuffer = 1, kGradSynthetic = 2 };
 
+constexpr int kLdsBytesPerCu = 160 * 1024;
+
+// Launch shape of the round kernel (see rps_set_launch_tuning in rps.h).
+struct LaunchTuning {
+    int rows_in_flight;        // rows per load chunk (two chunks are in flight): 2 or 4
+    int waves_per_workgroup;   // 1 or 4 (adjacent tiles)
+    int max_waves_per_cu;      // occupancy cap; 0 or >= 32: none
+};
+
 // Launchers (rps_kernels.hip).  All enqueue on `stream` and return the launch status.
 hipError_t launch_masks(RoundTable *tab, int n, uint64_t seed, uint64_t step, uint64_t threshold,
                         int identity_server, hipStream_t stream);
 hipError_t launch_round(int dtype, int grad_mode, void *X, const void *G, const RoundTable *tab,
-                        const RoundParams &prm, int64_t max_block_cols, hipStream_t stream);
+                        const RoundParams &prm, int64_t max_block_cols, const LaunchTuning &tune, hipStream_t stream);
 hipError_t launch_local_step(int dtype, int grad_mode, void *X, const void *G,
                              const RoundParams &prm, hipStream_t stream);
 

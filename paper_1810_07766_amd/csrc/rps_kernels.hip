@@ -8,8 +8,8 @@
 //   masks_kernel      network outcome of one round: server permutation, uplink and downlink
 //                     delivery bits (Sec. 3; Alg. 1 steps 6-7), n workgroups of one wavefront
 //   round_kernel      local SGD step + Reduce-Scatter average + All-Gather write-back in one
-//                     pass; one workgroup per tile of 512 columns of one block, rows split
-//                     over the workgroup's wavefronts
+//                     pass; every wavefront owns one tile (64 lanes x 16 bytes) of one block
+//                     and walks all n rows of it, no LDS and no barrier
 //   local_step_kernel the local SGD step alone
 // The path is a streaming reduction with < 0.5 flop per byte: it is bound by HBM bandwidth
 // (and, with the in-register Gaussian generator, by plain vector ALU work), never by a dense
@@ -44,7 +44,8 @@ __device__ __forceinline__ void philox4x32(uint32_t c[4], uint32_t k0, uint32_t 
 
 constexpr uint32_t kDomainUplink = 0u << 24, kDomainDownlink = 1u << 24, kDomainServer = 2u << 24,
                    kDomainNoise = 3u << 24;
-constexpr int kMaskRounds = 10, kNoiseRounds = 10;
+constexpr int kMaskRounds = 10;   // network outcome: the generator's standard round count
+constexpr int kNoiseRounds = 7;   // gradient noise: the smallest count its authors report as passing BigCrush
 
 // ---------------------------------------------------------------------------------------
 // Network outcome (Sec. 3: every message lost independently with probability p; Alg. 1
@@ -93,10 +94,9 @@ __global__ __launch_bounds__(64) void masks_kernel(RoundTable *__restrict__ tab,
 }
 
 // ---------------------------------------------------------------------------------------
-// Synthetic gradient noise: one hash call -> eight values sigma*z for columns 8g..8g+7 of one
-// worker.  Each word gives a Box-Muller pair: 16-bit radius index (low half), 16-bit angle
-// index (high half).  Every operation below is an exactly rounded fp32 operation in a fixed
-// order, so the bits do not depend on the machine.
+// Synthetic gradient noise.  Each 32-bit hash word gives a Box-Muller pair sigma*z: 16-bit
+// radius index (low half), 16-bit angle index (high half).  Every operation below is an
+// exactly rounded fp32 operation in a fixed order, so the bits do not depend on the machine.
 // ---------------------------------------------------------------------------------------
 __device__ __forceinline__ void box_muller_pair(uint32_t word, float sigma, float &even, float &odd) {
     // u1 = a / 2^17 (a odd);  -log2 u1 = lz + (1 - log2 m),  m in [1,2),  w = 2 - m
@@ -132,11 +132,15 @@ __device__ __forceinline__ void box_muller_pair(uint32_t word, float sigma, floa
     odd = rsgn * sn;
 }
 
-__device__ __forceinline__ void noise8(const RoundParams &prm, int worker, int64_t group, float z[8]) {
-    uint32_t c[4] = {(uint32_t)group, (uint32_t)worker, prm.step_lo, kDomainNoise | prm.step_hi24};
+// One hash call serves a 4-column x 2-worker patch: words 0,1 -> worker 2*pair, words 2,3 ->
+// worker 2*pair+1, columns 4*quad..4*quad+3 (16 bytes of fp32 per row: one lane's vector).
+__device__ __forceinline__ void noise_patch(const RoundParams &prm, int pair, int64_t quad, float za[4], float zb[4]) {
+    uint32_t c[4] = {(uint32_t)quad, (uint32_t)pair, prm.step_lo, kDomainNoise | prm.step_hi24};
     philox4x32<kNoiseRounds>(c, prm.seed_lo, prm.seed_hi);
-#pragma unroll
-    for (int q = 0; q < 4; ++q) box_muller_pair(c[q], prm.sigma, z[2 * q], z[2 * q + 1]);
+    box_muller_pair(c[0], prm.sigma, za[0], za[1]);
+    box_muller_pair(c[1], prm.sigma, za[2], za[3]);
+    box_muller_pair(c[2], prm.sigma, zb[0], zb[1]);
+    box_muller_pair(c[3], prm.sigma, zb[2], zb[3]);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -150,21 +154,27 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
     return u >> 16;
 }
 
+// 128-bit accesses carry the non-temporal hint: the state is far larger than the caches and
+// every element is touched once per round, so nothing is gained by keeping lines resident.
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// One lane's vector is 16 bytes (Raw): 4 fp32 columns or 8 bf16 columns.  Rows wait in
+// registers in Raw form and are unpacked to fp32 only when they are processed.
 template <typename ST>
 struct Storage;
 
 template <>
 struct Storage<float> {
+    static constexpr int VEC = 4;
+    using Raw = f32x4;
     static __device__ __forceinline__ float round(float v) { return v; }
-    static __device__ __forceinline__ void load8(const float *p, float x[8]) {
-        const float4 a = reinterpret_cast<const float4 *>(p)[0];
-        const float4 b = reinterpret_cast<const float4 *>(p)[1];
+    static __device__ __forceinline__ void unpack(Raw a, float x[VEC]) {
         x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w;
-        x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
     }
-    static __device__ __forceinline__ void store8(float *p, const float x[8]) {
-        reinterpret_cast<float4 *>(p)[0] = make_float4(x[0], x[1], x[2], x[3]);
-        reinterpret_cast<float4 *>(p)[1] = make_float4(x[4], x[5], x[6], x[7]);
+    static __device__ __forceinline__ Raw pack(const float x[VEC]) {
+        const Raw a = {x[0], x[1], x[2], x[3]};
+        return a;
     }
     static __device__ __forceinline__ float load1(const float *p) { return *p; }
     static __device__ __forceinline__ void store1(float *p, float v) { *p = v; }
@@ -172,207 +182,365 @@ struct Storage<float> {
 
 template <>
 struct Storage<uint16_t> {
+    static constexpr int VEC = 8;
+    using Raw = u32x4;
     static __device__ __forceinline__ float round(float v) { return bf16_bits_to_f32(f32_to_bf16_bits(v)); }
-    static __device__ __forceinline__ void load8(const uint16_t *p, float x[8]) {
-        const uint4 a = *reinterpret_cast<const uint4 *>(p);
+    static __device__ __forceinline__ void unpack(Raw a, float x[VEC]) {
         x[0] = __uint_as_float(a.x << 16); x[1] = __uint_as_float(a.x & 0xFFFF0000u);
         x[2] = __uint_as_float(a.y << 16); x[3] = __uint_as_float(a.y & 0xFFFF0000u);
         x[4] = __uint_as_float(a.z << 16); x[5] = __uint_as_float(a.z & 0xFFFF0000u);
         x[6] = __uint_as_float(a.w << 16); x[7] = __uint_as_float(a.w & 0xFFFF0000u);
     }
-    // values are already bf16-representable (rounded by round()): packing is a truncation
-    static __device__ __forceinline__ void store8(uint16_t *p, const float x[8]) {
-        uint4 a;
+    // for values that are already bf16-representable (rounded by round()): a truncation
+    static __device__ __forceinline__ Raw pack(const float x[VEC]) {
+        Raw a;
         a.x = (__float_as_uint(x[0]) >> 16) | (__float_as_uint(x[1]) & 0xFFFF0000u);
         a.y = (__float_as_uint(x[2]) >> 16) | (__float_as_uint(x[3]) & 0xFFFF0000u);
         a.z = (__float_as_uint(x[4]) >> 16) | (__float_as_uint(x[5]) & 0xFFFF0000u);
         a.w = (__float_as_uint(x[6]) >> 16) | (__float_as_uint(x[7]) & 0xFFFF0000u);
-        *reinterpret_cast<uint4 *>(p) = a;
+        return a;
     }
     static __device__ __forceinline__ float load1(const uint16_t *p) { return bf16_bits_to_f32(*p); }
     static __device__ __forceinline__ void store1(uint16_t *p, float v) { *p = (uint16_t)(__float_as_uint(v) >> 16); }
 };
 
-// Load / store the lane's eight columns [c0, c0+8) of one row; `full` lanes use 128-bit
-// accesses, ragged lanes touch only columns inside [lo, hi).
-template <typename ST>
-__device__ __forceinline__ void load_cols(const ST *row, int64_t c0, int64_t lo, int64_t hi, bool full, float x[8]) {
-    if (full) {
-        Storage<ST>::load8(row + c0, x);
+// Where one lane works: VEC columns [c0, c0+VEC) of the column range [lo, hi), c0 = tile0 + loff
+// with tile0 wave-uniform and loff = lane * VEC.  Row pointers handed to load_raw / store_raw
+// already include tile0 (wave-uniform base + 32-bit lane offset: no per-lane 64-bit address
+// arithmetic).  In a FULL wavefront every lane's vector lies inside the range and is 16-byte
+// aligned: one 128-bit access per row and no per-lane test (keeps all loads of a row chunk in
+// one basic block, in flight together).  Otherwise (block edges, unaligned pitch) lanes touch
+// only their own columns inside the range, element by element.
+struct LaneCols {
+    int64_t tile0, lo, hi;
+    uint32_t loff;
+    __device__ __forceinline__ int64_t c0() const { return tile0 + loff; }
+};
+
+template <typename ST, bool FULL>
+__device__ __forceinline__ typename Storage<ST>::Raw load_raw(const ST *tile_row, const LaneCols &lc) {
+    using S = Storage<ST>;
+    if (FULL) {
+        return __builtin_nontemporal_load(reinterpret_cast<const typename S::Raw *>(tile_row + lc.loff));
     } else {
+        float x[S::VEC];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int64_t c = c0 + e;
-            x[e] = (c >= lo && c < hi) ? Storage<ST>::load1(row + c) : 0.0f;
+        for (int e = 0; e < S::VEC; ++e) {
+            const int64_t c = lc.c0() + e;
+            x[e] = (c >= lc.lo && c < lc.hi) ? S::load1(tile_row + lc.loff + e) : 0.0f;
         }
+        return S::pack(x);
     }
 }
-template <typename ST>
-__device__ __forceinline__ void store_cols(ST *row, int64_t c0, int64_t lo, int64_t hi, bool full, const float x[8]) {
-    if (full) {
-        Storage<ST>::store8(row + c0, x);
+template <typename ST, bool FULL>
+__device__ __forceinline__ void store_raw(ST *tile_row, const LaneCols &lc, typename Storage<ST>::Raw v) {
+    using S = Storage<ST>;
+    if (FULL) {
+        __builtin_nontemporal_store(v, reinterpret_cast<typename S::Raw *>(tile_row + lc.loff));
     } else {
+        float x[S::VEC];
+        S::unpack(v, x);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int64_t c = c0 + e;
-            if (c >= lo && c < hi) Storage<ST>::store1(row + c, x[e]);
+        for (int e = 0; e < S::VEC; ++e) {
+            const int64_t c = lc.c0() + e;
+            if (c >= lc.lo && c < lc.hi) S::store1(tile_row + lc.loff + e, x[e]);
         }
     }
 }
 
-// v = x - gamma * g, rounded to storage (Alg. 1 step 5).  x holds the row's eight values on
-// entry and v on exit.
-template <typename ST, int GRAD>
-__device__ __forceinline__ void sgd_step(const RoundParams &prm, const ST *Grow, int worker, int64_t c0, int64_t lo,
-                                         int64_t hi, bool full, float x[8]) {
-    if (GRAD == kGradBuffer) {
-        float g[8];
-        load_cols<ST>(Grow, c0, lo, hi, full, g);
+// Noise of the lane's VEC columns for the worker pair (2*pair, 2*pair+1).
+template <int VEC>
+__device__ __forceinline__ void noise_rows(const RoundParams &prm, int pair, int64_t c0, float za[VEC], float zb[VEC]) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) x[e] = Storage<ST>::round(__builtin_fmaf(-prm.gamma, g[e], x[e]));
+    for (int q = 0; q < VEC / 4; ++q) noise_patch(prm, pair, (c0 >> 2) + q, za + 4 * q, zb + 4 * q);
+}
+
+// v = x - gamma * g, rounded to storage (Alg. 1 step 5); g = the caller's gradient or
+// lambda * x + noise.  x is overwritten by v.
+template <typename ST, int GRAD>
+__device__ __forceinline__ void sgd_step(const RoundParams &prm, const float *g_or_z, float x[Storage<ST>::VEC]) {
+    constexpr int VEC = Storage<ST>::VEC;
+    if (GRAD == kGradBuffer) {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) x[e] = Storage<ST>::round(__builtin_fmaf(-prm.gamma, g_or_z[e], x[e]));
     } else if (GRAD == kGradSynthetic) {
-        float z[8];
-        noise8(prm, worker, c0 >> 3, z);
         if (prm.lambda != 0.0f) {   // fma(0, x, z) == z for finite x: skipped when there is no decay
 #pragma unroll
-            for (int e = 0; e < 8; ++e) z[e] = __builtin_fmaf(prm.lambda, x[e], z[e]);
-        }
+            for (int e = 0; e < VEC; ++e)
+                x[e] = Storage<ST>::round(__builtin_fmaf(-prm.gamma, __builtin_fmaf(prm.lambda, x[e], g_or_z[e]), x[e]));
+        } else {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) x[e] = Storage<ST>::round(__builtin_fmaf(-prm.gamma, z[e], x[e]));
+            for (int e = 0; e < VEC; ++e) x[e] = Storage<ST>::round(__builtin_fmaf(-prm.gamma, g_or_z[e], x[e]));
+        }
     }
 }
 
 // ---------------------------------------------------------------------------------------
-// Fused round.  grid = (tiles of the largest block, n blocks); workgroup = W wavefronts.
-// Lane l of every wavefront owns columns base + (tile*64 + l)*8 .. +8 of block j, where base
-// is the block start rounded down to a multiple of 8 (so lanes coincide with noise groups and
-// 128-bit segments).  Wavefront w owns rows w, w+W, ...: the "is this copy delivered" tests
-// are wave-uniform scalar branches.  Partial column sums are accumulated in fp64, exchanged
-// through LDS once per tile, and every wavefront forms the same average in the same order
-// (so all receivers hold identical bits).  Each element is read at most once and written at
-// most once; a row that neither contributes (uplink lost) nor keeps its own value (reply
-// received) is not read at all.
+// Fused round.  grid = (ceil(tiles of the largest block / WPB), n blocks); a workgroup is WPB
+// independent wavefronts, each owning one tile of 64 x VEC columns of block j (tiles start at
+// the block start rounded down to a vector boundary, so lanes coincide with 16-byte segments
+// and noise quads).  The wavefront walks the n rows of its tile:
+//   pass 1  read x[i, tile], form v (Alg. 1 step 5); if worker i's copy reached the server
+//           (uplink bit) add it to the fp64 column sums; if the reply will not reach worker i
+//           (downlink bit clear) its final value is v: store it now
+//   pass 2  vt = sum / |N_j| once per column; store vt to every row whose downlink bit is set
+// Every element is read once and written once, nothing is staged in LDS, there is no barrier.
+// Delivery tests are wave-uniform scalar branches (row index and mask words live in SGPRs).
+// All receivers get the same registers, so they hold identical bits.
 // ---------------------------------------------------------------------------------------
-template <typename ST, int GRAD, int W, int RPW>
-__global__ __launch_bounds__(W * 64) void round_kernel(ST *__restrict__ X, const ST *__restrict__ G,
-                                                       const RoundTable *__restrict__ tab, const RoundParams prm) {
-    __shared__ double2 part[W][4][64];
+
+// Running position of the loads: the next row to load and its tile pointer(s).  Rows past n
+// repeat row n-1 (loaded, never used), so every load of a chunk is unconditional.
+template <typename ST>
+struct LoadCursor {
+    const ST *x, *g;
+    int row;
+};
+
+template <typename ST, int GRAD, int R, bool FULL>
+__device__ __forceinline__ void load_chunk(LoadCursor<ST> &cur, const RoundParams &prm, const LaneCols &lc,
+                                           typename Storage<ST>::Raw x[R],
+                                           typename Storage<ST>::Raw g[GRAD == kGradBuffer ? R : 1]) {
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        x[r] = load_raw<ST, FULL>(cur.x, lc);
+        if (GRAD == kGradBuffer) g[r] = load_raw<ST, FULL>(cur.g, lc);
+        if (cur.row + 1 < prm.n) {   // scalar
+            ++cur.row;
+            cur.x += prm.N;
+            if (GRAD == kGradBuffer) cur.g += prm.N;
+        }
+    }
+}
+
+// Pass 1 for the chunk of rows i0..i0+R-1: v for every row that needs it, column sums, and
+// the final value of the rows that will not receive the reply.
+template <typename ST, int GRAD, int R, bool FULL>
+__device__ __forceinline__ void process_chunk(ST *__restrict__ Xt, const RoundParams &prm, const LaneCols &lc,
+                                              uint64_t ucol, uint64_t dcol, int i0,
+                                              const typename Storage<ST>::Raw xr[R],
+                                              const typename Storage<ST>::Raw gr[GRAD == kGradBuffer ? R : 1],
+                                              double acc[Storage<ST>::VEC]) {
+    using S = Storage<ST>;
+    constexpr int VEC = S::VEC;
+    const int n = prm.n;
+#pragma unroll
+    for (int r = 0; r < R; r += 2) {   // worker pairs (i0 is even)
+        const int ia = i0 + r, ib = ia + 1;
+        if (ia < n) {
+            const bool ua = (ucol >> ia) & 1, da = (dcol >> ia) & 1;
+            const bool ub = ib < n && ((ucol >> ib) & 1), db = ib >= n || ((dcol >> ib) & 1);
+            // v is needed if it enters the average or stays as the worker's own value
+            const bool need_a = ua || (GRAD != kGradNone && !da);
+            const bool need_b = ub || (GRAD != kGradNone && !db);
+            if (need_a || need_b) {
+                float za[VEC], zb[VEC];
+                if (GRAD == kGradSynthetic) noise_rows<VEC>(prm, ia >> 1, lc.c0(), za, zb);
+                if (need_a) {
+                    float v[VEC];
+                    S::unpack(xr[r], v);
+                    if (GRAD == kGradBuffer) S::unpack(gr[GRAD == kGradBuffer ? r : 0], za);
+                    sgd_step<ST, GRAD>(prm, za, v);
+                    if (ua) {
+#pragma unroll
+                        for (int e = 0; e < VEC; ++e) acc[e] += (double)v[e];
+                    }
+                    if (GRAD != kGradNone && !da) store_raw<ST, FULL>(Xt + (int64_t)ia * prm.N, lc, S::pack(v));
+                }
+                if (need_b) {
+                    float v[VEC];
+                    S::unpack(xr[r + 1], v);
+                    if (GRAD == kGradBuffer) S::unpack(gr[GRAD == kGradBuffer ? r + 1 : 0], zb);
+                    sgd_step<ST, GRAD>(prm, zb, v);
+                    if (ub) {
+#pragma unroll
+                        for (int e = 0; e < VEC; ++e) acc[e] += (double)v[e];
+                    }
+                    if (GRAD != kGradNone && !db) store_raw<ST, FULL>(Xt + (int64_t)ib * prm.N, lc, S::pack(v));
+                }
+            }
+        }
+    }
+    // A row that was skipped above has never been waited for.  Consume every register of the
+    // chunk here, so that no load is still pending on them when the caller's loop issues the
+    // next loads into the same registers (otherwise the compiler must drain the whole memory
+    // queue at the loop head, which serialises the prefetch).
+#pragma unroll
+    for (int r = 0; r < R; ++r) asm volatile("" ::"v"(xr[r]));
+    if (GRAD == kGradBuffer) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) asm volatile("" ::"v"(gr[r]));
+    }
+}
+
+// One tile, all n rows.  The row loop is software-pipelined by hand: the loads of chunk k+1
+// are issued before chunk k is processed, so a wavefront overlaps its own memory latency with
+// its own arithmetic and few resident wavefronts suffice.
+template <typename ST, int GRAD, int R, bool FULL>
+__device__ __forceinline__ void round_tile(ST *__restrict__ X, const ST *__restrict__ G, const RoundParams &prm,
+                                           const LaneCols &lc, uint64_t ucol, uint64_t dcol, double inv) {
+    using S = Storage<ST>;
+    using Raw = typename S::Raw;
+    constexpr int VEC = S::VEC;
+    constexpr int RG = GRAD == kGradBuffer ? R : 1;
+    const int n = prm.n;
+    ST *Xt = X + lc.tile0;   // row 0 of the tile (wave-uniform)
+
+    double acc[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) acc[e] = 0.0;
+
+    LoadCursor<ST> cur;
+    cur.x = Xt;
+    cur.g = GRAD == kGradBuffer ? G + lc.tile0 : nullptr;
+    cur.row = 0;
+    Raw xa[R], xb[R], ga[RG], gb[RG];
+    load_chunk<ST, GRAD, R, FULL>(cur, prm, lc, xa, ga);
+    int i0 = 0;
+    // steady state: every load is unconditional, so the number of requests in flight at each
+    // point is static and the waits inserted by the compiler leave the prefetch outstanding
+    for (; i0 + 2 * R < n; i0 += 2 * R) {
+        load_chunk<ST, GRAD, R, FULL>(cur, prm, lc, xb, gb);
+        process_chunk<ST, GRAD, R, FULL>(Xt, prm, lc, ucol, dcol, i0, xa, ga, acc);
+        load_chunk<ST, GRAD, R, FULL>(cur, prm, lc, xa, ga);
+        process_chunk<ST, GRAD, R, FULL>(Xt, prm, lc, ucol, dcol, i0 + R, xb, gb, acc);
+    }
+    if (i0 + R < n) {   // two chunks left
+        load_chunk<ST, GRAD, R, FULL>(cur, prm, lc, xb, gb);
+        process_chunk<ST, GRAD, R, FULL>(Xt, prm, lc, ucol, dcol, i0, xa, ga, acc);
+        process_chunk<ST, GRAD, R, FULL>(Xt, prm, lc, ucol, dcol, i0 + R, xb, gb, acc);
+    } else {            // one chunk left
+        process_chunk<ST, GRAD, R, FULL>(Xt, prm, lc, ucol, dcol, i0, xa, ga, acc);
+    }
+
+    float vt[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) vt[e] = S::round((float)(acc[e] * inv));
+    const Raw vt_raw = S::pack(vt);
+    ST *row = Xt;
+    for (int i = 0; i < n; ++i, row += prm.N)
+        if ((dcol >> i) & 1) store_raw<ST, FULL>(row, lc, vt_raw);
+}
+
+template <typename ST, int GRAD, int R, int WPB>
+__global__ __launch_bounds__(WPB * 64) void round_kernel(ST *__restrict__ X, const ST *__restrict__ G,
+                                                         const RoundTable *__restrict__ tab, const RoundParams prm) {
+    constexpr int VEC = Storage<ST>::VEC;
+    constexpr int TILE = 64 * VEC;
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int j = blockIdx.y;
     const int64_t lo = tab->off[j], hi = tab->off[j + 1];
-    const int64_t base = lo & ~(int64_t)7;
-    const int64_t tile0 = base + (int64_t)blockIdx.x * kTileCols;
-    if (tile0 >= hi) return;   // uniform: this block has fewer tiles than the largest one
+    const int64_t tile0 = (lo & ~(int64_t)(VEC - 1)) + ((int64_t)blockIdx.x * WPB + wave) * TILE;
+    if (tile0 >= hi) return;   // wave-uniform: this block has fewer tiles than the largest one
     const uint64_t ucol = tab->ucol[j], dcol = tab->dcol[j];
     const double inv = tab->inv_cnt[j];
 
-    const int64_t c0 = tile0 + (int64_t)lane * kColsPerLane;
-    const bool any = c0 < hi;   // (c0 + 8 > lo always holds)
-    const bool full = prm.vec_ok && c0 >= lo && c0 + kColsPerLane <= hi;
+    LaneCols lc;
+    lc.tile0 = tile0;
+    lc.loff = (uint32_t)lane * VEC;   // c0 + VEC > lo always holds
+    lc.lo = lo;
+    lc.hi = hi;
+    if (prm.vec_ok && tile0 >= lo && tile0 + TILE <= hi)   // wave-uniform
+        round_tile<ST, GRAD, R, true>(X, G, prm, lc, ucol, dcol, inv);
+    else
+        round_tile<ST, GRAD, 2, false>(X, G, prm, lc, ucol, dcol, inv);
+}
 
-    float v[RPW][8];
-    double acc[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) acc[e] = 0.0;
-
-#pragma unroll
-    for (int r = 0; r < RPW; ++r) {
-        const int i = wave + r * W;
-        if (i < prm.n) {
-            const bool u = (ucol >> i) & 1, d = (dcol >> i) & 1;
-            if ((u || (!d && GRAD != kGradNone)) && any) {
-                const ST *row = X + (int64_t)i * prm.N;
-                load_cols<ST>(row, c0, lo, hi, full, v[r]);
-                sgd_step<ST, GRAD>(prm, G ? G + (int64_t)i * prm.N : nullptr, i, c0, lo, hi, full, v[r]);
-                if (u) {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) acc[e] += (double)v[r][e];
-                }
-            }
-        }
+// Local SGD step alone: grid = (vector chunks, worker pairs); a lane owns one 16-byte vector
+// of the two rows of a worker pair (one noise hash call per 4 columns x 2 rows).
+template <typename ST, int GRAD, bool FULL>
+__device__ __forceinline__ void local_step_pair(ST *__restrict__ X, const ST *__restrict__ G, const RoundParams &prm,
+                                                const LaneCols &lc, int ia) {
+    using S = Storage<ST>;
+    constexpr int VEC = S::VEC;
+    const int ib = ia + 1;
+    const bool has_b = ib < prm.n;
+    ST *rowa = X + (int64_t)ia * prm.N + lc.tile0, *rowb = X + (int64_t)(has_b ? ib : ia) * prm.N + lc.tile0;
+    float xa[VEC], xb[VEC], ga[VEC], gb[VEC];
+    S::unpack(load_raw<ST, FULL>(rowa, lc), xa);
+    S::unpack(load_raw<ST, FULL>(rowb, lc), xb);
+    if (GRAD == kGradBuffer) {
+        S::unpack(load_raw<ST, FULL>(G + (int64_t)ia * prm.N + lc.tile0, lc), ga);
+        S::unpack(load_raw<ST, FULL>(G + (int64_t)(has_b ? ib : ia) * prm.N + lc.tile0, lc), gb);
+    } else {
+        noise_rows<VEC>(prm, ia >> 1, lc.c0(), ga, gb);
     }
-
-#pragma unroll
-    for (int k = 0; k < 4; ++k) part[wave][k][lane] = make_double2(acc[2 * k], acc[2 * k + 1]);
-    __syncthreads();
-    float vt[8];
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        double2 t = part[0][k][lane];
-#pragma unroll
-        for (int w = 1; w < W; ++w) {
-            const double2 o = part[w][k][lane];
-            t.x += o.x;
-            t.y += o.y;
-        }
-        vt[2 * k] = Storage<ST>::round((float)(t.x * inv));
-        vt[2 * k + 1] = Storage<ST>::round((float)(t.y * inv));
-    }
-
-#pragma unroll
-    for (int r = 0; r < RPW; ++r) {
-        const int i = wave + r * W;
-        if (i < prm.n && any) {
-            ST *row = X + (int64_t)i * prm.N;
-            if ((dcol >> i) & 1)
-                store_cols<ST>(row, c0, lo, hi, full, vt);
-            else if (GRAD != kGradNone)
-                store_cols<ST>(row, c0, lo, hi, full, v[r]);
-        }
+    sgd_step<ST, GRAD>(prm, ga, xa);
+    store_raw<ST, FULL>(rowa, lc, S::pack(xa));
+    if (has_b) {
+        sgd_step<ST, GRAD>(prm, gb, xb);
+        store_raw<ST, FULL>(rowb, lc, S::pack(xb));
     }
 }
 
-// Local SGD step alone: grid = (column-group chunks, n rows), lane = one 8-column group.
 template <typename ST, int GRAD>
 __global__ __launch_bounds__(256) void local_step_kernel(ST *__restrict__ X, const ST *__restrict__ G,
                                                          const RoundParams prm) {
-    const int i = blockIdx.y;
-    const int64_t c0 = ((int64_t)blockIdx.x * 256 + threadIdx.x) * kColsPerLane;
-    if (c0 >= prm.N) return;
-    const bool full = prm.vec_ok && c0 + kColsPerLane <= prm.N;
-    ST *row = X + (int64_t)i * prm.N;
-    float x[8];
-    load_cols<ST>(row, c0, 0, prm.N, full, x);
-    sgd_step<ST, GRAD>(prm, G ? G + (int64_t)i * prm.N : nullptr, i, c0, 0, prm.N, full, x);
-    store_cols<ST>(row, c0, 0, prm.N, full, x);
+    constexpr int VEC = Storage<ST>::VEC;
+    constexpr int TILE = 64 * VEC;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t tile0 = ((int64_t)blockIdx.x * 4 + wave) * TILE;
+    if (tile0 >= prm.N) return;   // wave-uniform
+    LaneCols lc;
+    lc.tile0 = tile0;
+    lc.loff = (uint32_t)lane * VEC;
+    lc.lo = 0;
+    lc.hi = prm.N;
+    if (prm.vec_ok && tile0 + TILE <= prm.N)
+        local_step_pair<ST, GRAD, true>(X, G, prm, lc, 2 * blockIdx.y);
+    else
+        local_step_pair<ST, GRAD, false>(X, G, prm, lc, 2 * blockIdx.y);
+}
+
+// Launch shape of the round kernel.  The memory system of this GPU is at its best when the
+// chip-wide footprint of requests in flight is a few MB: occupancy is therefore capped by a
+// dynamic LDS allocation that the kernel never touches.
+template <typename ST, int GRAD, int R, int WPB>
+hipError_t launch_round_v(ST *X, const ST *G, const RoundTable *tab, const RoundParams &prm, int64_t max_block_cols,
+                          int max_waves_per_cu, hipStream_t stream) {
+    constexpr int TILE = 64 * Storage<ST>::VEC;
+    // a block that starts off a vector boundary may need one extra tile
+    const int64_t tiles = (max_block_cols + Storage<ST>::VEC - 1 + TILE - 1) / TILE;
+    const dim3 grid((unsigned)((tiles + WPB - 1) / WPB), (unsigned)prm.n, 1);
+    size_t lds = 0;
+    if (max_waves_per_cu > 0 && max_waves_per_cu < 32) {
+        int wgs = max_waves_per_cu / WPB;
+        if (wgs < 1) wgs = 1;
+        lds = ((size_t)kLdsBytesPerCu / wgs) & ~(size_t)255;
+        if (lds > 65536) lds = 65536;   // the default per-workgroup limit
+    }
+    hipLaunchKernelGGL((round_kernel<ST, GRAD, R, WPB>), grid, dim3(WPB * 64), lds, stream, X, G, tab, prm);
+    return hipGetLastError();
 }
 
 template <typename ST, int GRAD>
-hipError_t launch_round_t(ST *X, const ST *G, const RoundTable *tab, const RoundParams &prm,
-                          int64_t max_block_cols, hipStream_t stream) {
-    // a block that starts off an 8-column boundary may need one extra tile
-    const int64_t tiles = (max_block_cols + 7 + kTileCols - 1) / kTileCols;
-    const dim3 grid((unsigned)tiles, (unsigned)prm.n, 1);
-    const int n = prm.n;
-    if (n <= 4)
-        hipLaunchKernelGGL((round_kernel<ST, GRAD, 4, 1>), grid, dim3(256), 0, stream, X, G, tab, prm);
-    else if (n <= 8)
-        hipLaunchKernelGGL((round_kernel<ST, GRAD, 4, 2>), grid, dim3(256), 0, stream, X, G, tab, prm);
-    else if (n <= 16)
-        hipLaunchKernelGGL((round_kernel<ST, GRAD, 4, 4>), grid, dim3(256), 0, stream, X, G, tab, prm);
-    else if (n <= 32)
-        hipLaunchKernelGGL((round_kernel<ST, GRAD, 4, 8>), grid, dim3(256), 0, stream, X, G, tab, prm);
-    else
-        hipLaunchKernelGGL((round_kernel<ST, GRAD, 8, 8>), grid, dim3(512), 0, stream, X, G, tab, prm);
-    return hipGetLastError();
+hipError_t launch_round_t(ST *X, const ST *G, const RoundTable *tab, const RoundParams &prm, int64_t max_block_cols,
+                          const LaunchTuning &tune, hipStream_t stream) {
+#define RPS_V(R, W) launch_round_v<ST, GRAD, R, W>(X, G, tab, prm, max_block_cols, tune.max_waves_per_cu, stream)
+    const int r = tune.rows_in_flight, w = tune.waves_per_workgroup;
+    if (w == 1) return r <= 2 ? RPS_V(2, 1) : RPS_V(4, 1);
+    return r <= 2 ? RPS_V(2, 4) : RPS_V(4, 4);
+#undef RPS_V
 }
 
 template <typename ST>
 hipError_t launch_round_g(int grad_mode, ST *X, const ST *G, const RoundTable *tab, const RoundParams &prm,
-                          int64_t max_block_cols, hipStream_t stream) {
+                          int64_t max_block_cols, const LaunchTuning &tune, hipStream_t stream) {
     switch (grad_mode) {
-        case kGradNone: return launch_round_t<ST, kGradNone>(X, G, tab, prm, max_block_cols, stream);
-        case kGradBuffer: return launch_round_t<ST, kGradBuffer>(X, G, tab, prm, max_block_cols, stream);
-        default: return launch_round_t<ST, kGradSynthetic>(X, G, tab, prm, max_block_cols, stream);
+        case kGradNone: return launch_round_t<ST, kGradNone>(X, G, tab, prm, max_block_cols, tune, stream);
+        case kGradBuffer: return launch_round_t<ST, kGradBuffer>(X, G, tab, prm, max_block_cols, tune, stream);
+        default: return launch_round_t<ST, kGradSynthetic>(X, G, tab, prm, max_block_cols, tune, stream);
     }
 }
 
 template <typename ST>
 hipError_t launch_local_step_g(int grad_mode, ST *X, const ST *G, const RoundParams &prm, hipStream_t stream) {
-    const int64_t groups = (prm.N + kColsPerLane - 1) / kColsPerLane;
-    const dim3 grid((unsigned)((groups + 255) / 256), (unsigned)prm.n, 1);
+    constexpr int VEC = Storage<ST>::VEC;
+    const int64_t vecs = (prm.N + VEC - 1) / VEC;
+    const dim3 grid((unsigned)((vecs + 255) / 256), (unsigned)((prm.n + 1) / 2), 1);
     if (grad_mode == kGradBuffer)
         hipLaunchKernelGGL((local_step_kernel<ST, kGradBuffer>), grid, dim3(256), 0, stream, X, G, prm);
     else
@@ -391,10 +559,11 @@ hipError_t launch_masks(RoundTable *tab, int n, uint64_t seed, uint64_t step, ui
 }
 
 hipError_t launch_round(int dtype, int grad_mode, void *X, const void *G, const RoundTable *tab,
-                        const RoundParams &prm, int64_t max_block_cols, hipStream_t stream) {
+                        const RoundParams &prm, int64_t max_block_cols, const LaunchTuning &tune, hipStream_t stream) {
     if (dtype == 0)
-        return launch_round_g<float>(grad_mode, (float *)X, (const float *)G, tab, prm, max_block_cols, stream);
-    return launch_round_g<uint16_t>(grad_mode, (uint16_t *)X, (const uint16_t *)G, tab, prm, max_block_cols, stream);
+        return launch_round_g<float>(grad_mode, (float *)X, (const float *)G, tab, prm, max_block_cols, tune, stream);
+    return launch_round_g<uint16_t>(grad_mode, (uint16_t *)X, (const uint16_t *)G, tab, prm, max_block_cols, tune,
+                                    stream);
 }
 
 hipError_t launch_local_step(int dtype, int grad_mode, void *X, const void *G, const RoundParams &prm,

@@ -32,6 +32,7 @@ _lib.rps_lossy_average.argtypes = [_ctx_p, ctypes.c_void_p, ctypes.c_uint64]
 _lib.rps_round.argtypes = [_ctx_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64]
 _lib.rps_get_masks.argtypes = [_ctx_p, ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
 _lib.rps_set_mask_override.argtypes = [_ctx_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+_lib.rps_set_launch_tuning.argtypes = [_ctx_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32]
 _lib.rps_set_profiling.argtypes = [_ctx_p, ctypes.c_int32]
 _lib.rps_get_kernel_time.argtypes = [_ctx_p, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
 _lib.rps_last_hip_error.argtypes = [_ctx_p]
@@ -39,12 +40,13 @@ _lib.rps_strerror.argtypes = [ctypes.c_int]
 _lib.rps_strerror.restype = ctypes.c_char_p
 for _name in ("rps_create", "rps_destroy", "rps_set_synthetic_grad", "rps_set_gamma", "rps_local_step",
               "rps_lossy_average", "rps_round", "rps_get_masks", "rps_set_mask_override",
-              "rps_set_profiling", "rps_get_kernel_time", "rps_last_hip_error"):
+              "rps_set_launch_tuning", "rps_set_profiling", "rps_get_kernel_time", "rps_last_hip_error"):
     getattr(_lib, _name).restype = ctypes.c_int
 
 EXPORTS = ("rps_create", "rps_destroy", "rps_set_synthetic_grad", "rps_set_gamma", "rps_local_step",
            "rps_lossy_average", "rps_round", "rps_get_masks", "rps_set_mask_override",
-           "rps_set_profiling", "rps_get_kernel_time", "rps_last_hip_error", "rps_strerror")
+           "rps_set_launch_tuning", "rps_set_profiling", "rps_get_kernel_time", "rps_last_hip_error",
+           "rps_strerror")
 
 
 class RpsError(RuntimeError):
@@ -94,7 +96,7 @@ class RpsContext:
         self.n, self.N, self.dtype = n, N, dtype
 
     def destroy(self):
-        if getattr(self, "_h", None):
+        if getattr(self, "_h", None) and _lib is not None:   # (_lib is None at interpreter shutdown)
             h, self._h = self._h, None
             _check(_lib.rps_destroy(h))
 
@@ -135,6 +137,9 @@ class RpsContext:
         if up.shape != (self.n, self.n) or down.shape != (self.n, self.n) or server.shape != (self.n,):
             raise RpsError(RPS_EINVAL)
         _check(_lib.rps_set_mask_override(self._h, up.ctypes.data, down.ctypes.data, server.ctypes.data), self._h)
+
+    def set_launch_tuning(self, rows_in_flight, waves_per_workgroup, max_waves_per_cu=0):
+        _check(_lib.rps_set_launch_tuning(self._h, rows_in_flight, waves_per_workgroup, max_waves_per_cu), self._h)
 
     def set_profiling(self, enable):
         _check(_lib.rps_set_profiling(self._h, 1 if enable else 0), self._h)

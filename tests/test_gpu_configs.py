@@ -92,7 +92,7 @@ def test_config_lsq_n4_trajectory(rps):
             torch.cuda.synchronize()
             assert_close(Xg.cpu().numpy(), Xo, off, "f32", what=f"round {t}")
     lg, lo = loss(Xg.cpu().numpy()), loss(Xo)
-    assert lo < 0.5 * l0                                    # it optimises
+    assert lo < 0.8 * l0                                    # it optimises
     assert abs(lg - lo) <= 1e-6 * lo
     ctx.destroy()
 

@@ -120,13 +120,14 @@ def test_masks_change_with_seed_and_step():
 # ---------------------------------------------------------------------------------------------
 # Gaussian noise
 # ---------------------------------------------------------------------------------------------
-def _noise_reference(seed, step, worker, group, sigma):
+def _noise_reference(seed, step, pair, quad, sigma):
     """The textbook Box-Muller transform in double precision on the same hash words:
     u1 = (2k+1)/2^17 from the low 16 bits, angle (2f+1) pi / 65536 from the signed 15-bit
-    field above them, bit 31 adds pi."""
-    ctr = [group & 0xFFFFFFFF, worker, step & 0xFFFFFFFF, (3 << 24) | ((step >> 32) & 0xFFFFFF)]
+    field above them, bit 31 adds pi.  Words 0,1 -> worker 2*pair, words 2,3 -> worker 2*pair+1,
+    columns 4*quad..4*quad+3."""
+    ctr = [quad & 0xFFFFFFFF, pair, step & 0xFFFFFFFF, (3 << 24) | ((step >> 32) & 0xFFFFFF)]
     key = [seed & 0xFFFFFFFF, seed >> 32]
-    words = oracle.philox4x32(ctr, key, rounds=10)
+    words = oracle.philox4x32(ctr, key, rounds=7)      # the noise stream uses 7 rounds
     out = []
     for w in words:
         w = int(w)
@@ -137,41 +138,57 @@ def _noise_reference(seed, step, worker, group, sigma):
         phi = (2 * f + 1) * np.pi / 65536 + (np.pi if w >> 31 else 0.0)
         r = np.sqrt(-2.0 * np.log(u1))
         out += [sigma * r * np.cos(phi), sigma * r * np.sin(phi)]
-    return np.array(out)
+    return np.array(out).reshape(2, 4)
 
 
 def test_noise_matches_textbook_box_muller():
     worst = 0.0
-    for (seed, step, worker, group) in [(0, 0, 0, 0), (5, 3, 31, 123456), (2 ** 40 + 1, 2 ** 33, 63, 2 ** 31 + 5)]:
-        for g in range(group, group + 300):
-            z = oracle.noise8(seed, step, worker, g, 1.0).astype(np.float64)
-            ref = _noise_reference(seed, step, worker, g, 1.0)
+    for (seed, step, pair, quad) in [(0, 0, 0, 0), (5, 3, 15, 123456), (2 ** 40 + 1, 2 ** 33, 31, 2 ** 31 + 5)]:
+        for q in range(quad, quad + 300):
+            z = oracle.noise_patch(seed, step, pair, q, 1.0).astype(np.float64)
+            ref = _noise_reference(seed, step, pair, q, 1.0)
             worst = max(worst, np.abs(z - ref).max())
             assert np.abs(z - ref).max() < 2e-4     # polynomial approximation error of the spec
     assert worst > 0.0                               # (it is an approximation, not libm)
 
 
+def test_noise_indexing_by_worker_and_column():
+    """noise(worker, column) is entry [worker % 2, column % 4] of the patch (worker // 2, column // 4)."""
+    for worker in (0, 1, 6, 7, 63):
+        for column in (0, 1, 2, 3, 4, 1001, 2 ** 33 + 6):
+            patch = oracle.noise_patch(3, 8, worker // 2, column // 4, 0.5)
+            assert oracle.noise(3, 8, worker, column, 0.5) == patch[worker % 2, column % 4]
+
+
 def test_noise_sigma_scaling_and_determinism():
-    a = oracle.noise8(9, 4, 2, 77, 1.0)
-    assert (oracle.noise8(9, 4, 2, 77, 1.0) == a).all()
-    assert (oracle.noise8(9, 4, 2, 77, 0.25) == 0.25 * a).all()      # power of two: exact
-    assert not (oracle.noise8(9, 4, 3, 77, 1.0) == a).all()          # worker enters the counter
-    assert not (oracle.noise8(9, 5, 2, 77, 1.0) == a).all()          # step too
-    assert not (oracle.noise8(9, 4, 2, 78, 1.0) == a).all()
+    a = oracle.noise_patch(9, 4, 2, 77, 1.0)
+    assert (oracle.noise_patch(9, 4, 2, 77, 1.0) == a).all()
+    assert (oracle.noise_patch(9, 4, 2, 77, 0.25) == 0.25 * a).all()      # power of two: exact
+    assert not (oracle.noise_patch(9, 4, 3, 77, 1.0) == a).any()          # worker pair enters the counter
+    assert not (oracle.noise_patch(9, 5, 2, 77, 1.0) == a).any()          # step too
+    assert not (oracle.noise_patch(9, 4, 2, 78, 1.0) == a).any()
+    assert not (oracle.noise_patch(10, 4, 2, 77, 1.0) == a).any()         # and the seed
 
 
 def test_noise_is_standard_normal():
-    z = np.concatenate([oracle.noise8(11, 2, w, g, 1.0) for w in range(4) for g in range(50000)]).astype(np.float64)
-    n = z.size                                        # 1.6 M samples
-    assert abs(z.mean()) < 5 / np.sqrt(n)
-    assert abs(z.var() - 1.0) < 5 * np.sqrt(2.0 / n) + 2e-4
-    assert abs((z ** 3).mean()) < 5 * np.sqrt(15.0 / n)
-    assert abs((z ** 4).mean() - 3.0) < 5 * np.sqrt(96.0 / n) + 2e-3
-    assert stats.kstest(z[:200000], "norm").pvalue > 1e-4
-    # the two members of a Box-Muller pair, and neighbouring pairs, are uncorrelated
-    pairs = z.reshape(-1, 2)
-    assert abs(np.corrcoef(pairs[:, 0], pairs[:, 1])[0, 1]) < 5 / np.sqrt(n / 2)
-    assert abs(np.corrcoef(z[:-1], z[1:])[0, 1]) < 5 / np.sqrt(n)
-    assert abs(np.corrcoef(z[:-8] ** 2, z[8:] ** 2)[0, 1]) < 5 / np.sqrt(n)
+    z = np.stack([oracle.noise_patch(11, 2, k, q, 1.0) for k in range(4) for q in range(50000)]).astype(np.float64)
+    z = z.reshape(4, 50000, 2, 4)                     # [pair, quad, worker-in-pair, column-in-quad]
+    flat = z.reshape(-1)
+    n = flat.size                                     # 1.6 M samples
+    assert abs(flat.mean()) < 5 / np.sqrt(n)
+    assert abs(flat.var() - 1.0) < 5 * np.sqrt(2.0 / n) + 2e-4
+    assert abs((flat ** 3).mean()) < 5 * np.sqrt(15.0 / n)
+    assert abs((flat ** 4).mean() - 3.0) < 5 * np.sqrt(96.0 / n) + 2e-3
+    assert stats.kstest(flat[:200000], "norm").pvalue > 1e-4
+    # the two members of a Box-Muller pair, the two workers of a patch, neighbouring columns:
+    # all uncorrelated (also in their squares)
+    def corr(a, b):
+        return abs(np.corrcoef(a.reshape(-1), b.reshape(-1))[0, 1])
+    m = z[..., 0].size
+    assert corr(z[..., 0], z[..., 1]) < 5 / np.sqrt(m)
+    assert corr(z[:, :, 0, :], z[:, :, 1, :]) < 5 / np.sqrt(2 * m)
+    assert corr(z[:, :-1, :, 3], z[:, 1:, :, 0]) < 5 / np.sqrt(m / 2)
+    assert corr(z[..., 0] ** 2, z[..., 1] ** 2) < 5 / np.sqrt(m)
+    assert corr(z[:, :, 0, :] ** 2, z[:, :, 1, :] ** 2) < 5 / np.sqrt(2 * m)
     # 16-bit radius index: |z| <= sqrt(2 ln 2^17)
-    assert np.abs(z).max() <= np.sqrt(2 * np.log(2.0 ** 17)) * (1 + 1e-4)
+    assert np.abs(flat).max() <= np.sqrt(2 * np.log(2.0 ** 17)) * (1 + 1e-4)

@@ -52,7 +52,7 @@ def test_synthetic_gradient_is_decay_plus_noise():
     V = X.copy()
     oracle.local_step(V, None, gamma, sigma=sigma, weight_decay=lam, seed=8, step=6)
     for i in range(n):
-        z = np.concatenate([oracle.noise8(8, 6, i, g, sigma) for g in range((N + 7) // 8)])[:N].astype(np.float64)
+        z = np.array([oracle.noise(8, 6, i, c, sigma) for c in range(N)], dtype=np.float64)
         exact = X[i].astype(np.float64) - gamma * (lam * X[i].astype(np.float64) + z)
         assert np.abs(V[i] - exact).max() < 2e-7 * (1 + np.abs(exact).max())
 
