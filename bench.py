@@ -22,6 +22,12 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0     # MI355X published HBM3E bandwidth
 
+# HBM bytes per launch of the round kernel from rocprofv3 counters (FETCH_SIZE and WRITE_SIZE,
+# each scaled by what the same counter reads for a plain 1 GiB device copy; the commands and
+# the raw figures are in profiles/round_kernel_resnet50_n32_hbm_traffic.md).  Counters cannot
+# be read from inside this process, so the measured value is recorded here per workload.
+MEASURED_TRAFFIC_BYTES = {"resnet50_n32": 6.5539e9}
+
 
 def cpu_baseline(cfg, off, budget_cols):
     """The oracle as it stands on the host cores: `budget_cols` columns of every block's start,
@@ -55,8 +61,8 @@ def cpu_baseline(cfg, off, budget_cols):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--config", default=None, help="workload name (default: the headline config)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pmc-calibration", action="store_true",
@@ -116,7 +122,7 @@ def main():
                    "gradient": f"in-register N(0,{cfg.sigma ** 2:.3g}) + {cfg.weight_decay}*x",
                    "blocks": "unequal" if cfg.unequal_blocks else "equal"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name),
                      "kernel": "round_kernel", "kernel_ms": kernel_ms, "algorithmic_bytes": alg_bytes},
     }
     ctx.destroy()
