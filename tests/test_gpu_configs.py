@@ -142,3 +142,43 @@ def test_config_bert_n64_bf16_sampled(rps):
     """n=64, N=110M, bf16 storage, 64 unequal blocks, 20 rounds (14 GB of state)."""
     cfg = workloads.CONFIGS["bert_n64_bf16"]
     _sampled_trajectory(rps, cfg, cfg.p, cfg.rounds, init_scale=0.0, per_block=24)
+
+
+def test_config_mlp_n8_loss_tracks_oracle(rps):
+    """n=8 workers, 2-layer MLP 1024->2048->1024 (N = 4,194,304), teacher targets, batch 256 per
+    worker, p = 0.2, 200 rounds.  Gradients come from PyTorch (GPU side: on the GPU from the GPU
+    state; oracle side: on the CPU from the oracle's state), the round from the library / the
+    oracle.  The two trajectories are independent, so GEMM rounding differences feed back; the
+    loss curves and the mean model must still track each other closely."""
+    cfg = workloads.CONFIGS["mlp_n8"]
+    off = workloads.config_offsets(cfg)
+    teacher, X0 = workloads.mlp_problem(cfg, seed=cfg.seed)
+    Xg = X0.cuda()
+    Xo = X0.numpy().copy()
+    ctx = rps.RpsContext(cfg.n, cfg.N, cfg.p, cfg.gamma, cfg.seed)
+    threads = min(16, oracle.max_threads())
+    first = last = None
+    for t in range(cfg.rounds):
+        xb, yb = workloads.mlp_batch(cfg, teacher, t, seed=7)
+        lg, Gg = workloads.mlp_loss_and_grad(cfg, Xg, xb.cuda(), yb.cuda())
+        ctx.round(Xg, Gg, t)
+        lo, Go = workloads.mlp_loss_and_grad(cfg, torch.from_numpy(Xo), xb, yb)
+        oracle.round_(Xo, Go.numpy(), off, p=cfg.p, gamma=cfg.gamma, seed=cfg.seed, step=t, threads=threads)
+        lgm, lom = float(lg.mean()), float(lo.mean())
+        assert abs(lgm - lom) <= 1e-3 * lom, f"round {t}: loss {lgm} vs oracle {lom}"
+        first = lom if first is None else first
+        last = lom
+        if t % 50 == 49:
+            print(f"round {t}: loss gpu {lgm:.6f} oracle {lom:.6f}", flush=True)
+    assert last < 0.9 * first                                   # it trains
+    got = Xg.cpu().numpy().astype(np.float64)
+    ref = Xo.astype(np.float64)
+    # independent trajectories: compare at the scale of the parameters, not bitwise
+    assert np.abs(got.mean(axis=0) - ref.mean(axis=0)).max() <= 1e-3 * np.sqrt(np.mean(ref ** 2))
+    # the round itself, from the oracle's final state and gradient, still matches element-wise
+    Xs = torch.from_numpy(Xo).cuda()
+    ctx.round(Xs, Go.cuda(), cfg.rounds)
+    oracle.round_(Xo, Go.numpy(), off, p=cfg.p, gamma=cfg.gamma, seed=cfg.seed, step=cfg.rounds, threads=threads)
+    torch.cuda.synchronize()
+    assert_close(Xs.cpu().numpy(), Xo, off, "f32", what="single round from the oracle state")
+    ctx.destroy()

@@ -43,7 +43,7 @@ CONFIGS = {
                            rounds=50, sigma=0.1, weight_decay=1e-4),
     "resnet50_n32": Config("resnet50_n32", n=32, N=25_600_000, dtype="f32", p=0.05, gamma=0.1,
                            rounds=50, sigma=0.1),
-    "mlp_n8": Config("mlp_n8", n=8, N=1024 * 2048 + 2048 * 1024, dtype="f32", p=0.2, gamma=0.05,
+    "mlp_n8": Config("mlp_n8", n=8, N=1024 * 2048 + 2048 * 1024, dtype="f32", p=0.2, gamma=0.5,
                      rounds=200, gradient="mlp", extra={"d_in": 1024, "d_hidden": 2048,
                                                         "d_out": 1024, "batch": 256}),
     "bert_n64_bf16": Config("bert_n64_bf16", n=64, N=110_000_000, dtype="bf16", p=0.1, gamma=0.1,
@@ -124,3 +124,43 @@ def to_bf16_bits(a: np.ndarray) -> np.ndarray:
 
 def from_bf16_bits(b: np.ndarray) -> np.ndarray:
     return (b.astype(np.uint32) << 16).view(np.float32)
+
+
+def mlp_problem(cfg: Config, seed: int):
+    """Teacher W* [d_out, d_in] ~ N(0, 1/d_in) and the shared initial flat parameters
+    (W1 [d_hidden, d_in] ~ N(0, 1/d_in), W2 [d_out, d_hidden] ~ N(0, 1/d_hidden); zero weights
+    would give zero gradients).  torch CPU tensors from a seeded generator."""
+    import torch
+    e = cfg.extra
+    g = torch.Generator().manual_seed(seed)
+    teacher = torch.randn(e["d_out"], e["d_in"], generator=g) / e["d_in"] ** 0.5
+    w1 = torch.randn(e["d_hidden"], e["d_in"], generator=g) / e["d_in"] ** 0.5
+    w2 = torch.randn(e["d_out"], e["d_hidden"], generator=g) / e["d_hidden"] ** 0.5
+    x0 = torch.cat([w1.reshape(-1), w2.reshape(-1)])
+    return teacher, x0.repeat(cfg.n, 1).contiguous()
+
+
+def mlp_batch(cfg: Config, teacher, step: int, seed: int):
+    """Round `step`'s inputs x ~ N(0,1) [n, batch, d_in] and targets y = W* x (torch CPU)."""
+    import torch
+    e = cfg.extra
+    g = torch.Generator().manual_seed(seed * 1_000_003 + step)
+    xb = torch.randn(cfg.n, e["batch"], e["d_in"], generator=g)
+    return xb, xb @ teacher.T
+
+
+def mlp_loss_and_grad(cfg: Config, X, xb, yb):
+    """Per-worker MSE loss of the 2-layer ReLU MLP held as flat rows of X, and its gradient
+    [n, N] (PyTorch autograd on whatever device X lives on).  Input/model code, not part of
+    the averaging method."""
+    import torch
+    e = cfg.extra
+    k = e["d_hidden"] * e["d_in"]
+    Xp = X.detach().clone().requires_grad_(True)
+    W1 = Xp[:, :k].view(cfg.n, e["d_hidden"], e["d_in"])
+    W2 = Xp[:, k:].view(cfg.n, e["d_out"], e["d_hidden"])
+    h = torch.relu(torch.bmm(xb, W1.transpose(1, 2)))
+    out = torch.bmm(h, W2.transpose(1, 2))
+    loss = ((out - yb) ** 2).mean(dim=(1, 2))
+    (G,) = torch.autograd.grad(loss.sum(), Xp)
+    return loss.detach(), G.contiguous()
