@@ -72,8 +72,8 @@ enum {
  *   dtype          RPS_DTYPE_F32 or RPS_DTYPE_BF16 (storage; arithmetic is fp32, sums fp64)
  *   flags          RPS_FLAG_*
  *   hip_stream     hipStream_t on which all work is enqueued (NULL = the default stream)
- * Allocates O(n) device bytes and a pinned host staging buffer of the same size; nothing
- * proportional to N.  Errors: RPS_EINVAL, RPS_ENOMEM, RPS_EHIP.
+ * Allocates a fixed ~40 KB of device memory (per-round tables, reduction scratch) and a pinned
+ * host staging buffer of a few KB; nothing proportional to N.  Errors: RPS_EINVAL, RPS_ENOMEM, RPS_EHIP.
  */
 int rps_create(rps_ctx **out, int32_t n, int64_t N, const int64_t *block_offsets, double p,
                float gamma, uint64_t seed, int32_t dtype, uint32_t flags, void *hip_stream);
@@ -127,6 +127,16 @@ int rps_get_masks(rps_ctx *ctx, uint64_t step, uint8_t *up, uint8_t *down, int32
  * Synchronises the stream.
  */
 int rps_set_mask_override(rps_ctx *ctx, const uint8_t *up, const uint8_t *down, const int32_t *server);
+
+/*
+ * Consensus statistics of the state in one streaming read of X (supplement, Lemma 1: the
+ * disagreement sum_i ||x_i - xbar||^2 = ||X (I - A_n)||_F^2 that the convergence proof bounds):
+ *   distance  HOST double, receives sum over workers of ||x_i - xbar||^2   (may be NULL)
+ *   mean_sq   HOST double, receives ||xbar||^2, xbar = (1/n) sum_i x_i       (may be NULL)
+ * fp64 accumulation in a fixed order (deterministic).  Uses a fixed 32 KB reduction scratch
+ * allocated by rps_create.  Synchronises the stream.
+ */
+int rps_consensus(rps_ctx *ctx, const void *X, double *distance, double *mean_sq);
 
 /*
  * Launch shape of the round kernel, for tuning sweeps; results never depend on it.

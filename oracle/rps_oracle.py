@@ -161,3 +161,11 @@ def round_(X: np.ndarray, G, offsets, *, p: float, gamma: float, seed: int, step
         server, U, D = masks(seed, step, n, p, identity_server)
     lossy_average(X, offsets, U, D, cols=cols, threads=threads)
     return server, U, D
+
+
+def consensus(X: np.ndarray):
+    """(sum_i ||x_i - xbar||^2, ||xbar||^2) by the plain definition in float64: the disagreement
+    ||X (I - A_n)||_F^2 of the supplement's Lemma 1 (rows of X are the workers)."""
+    Xd = (X.astype(np.uint32) << 16).view(np.float32).astype(np.float64) if X.dtype == np.uint16 else X.astype(np.float64)
+    xbar = Xd.mean(axis=0)
+    return float(((Xd - xbar[None, :]) ** 2).sum()), float((xbar ** 2).sum())

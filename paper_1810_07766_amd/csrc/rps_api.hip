@@ -27,6 +27,7 @@ struct rps_ctx {
     RoundTable *tab = nullptr;        // device: table the round kernels read
     RoundTable *tab_query = nullptr;  // device: scratch table for rps_get_masks
     RoundTable *staging = nullptr;    // pinned host copy (create, override, query)
+    double *partials = nullptr;       // device: 2 * kMaxPartials + 2 doubles (consensus reduction scratch + result)
     bool override_on = false;
     bool profiling = false;
     std::vector<hipEvent_t> ev_start, ev_stop;
@@ -169,9 +170,11 @@ int rps_create(rps_ctx **out, int32_t n, int64_t N, const int64_t *block_offsets
     ctx->tune = default_tuning(n, dtype);
 
     hipError_t e = hipGetDevice(&ctx->device);
-    if (e == hipSuccess) e = hipMalloc((void **)&ctx->tab, 2 * sizeof(RoundTable));
+    const size_t scratch_bytes = (2 * (size_t)rps::kMaxPartials + 2) * sizeof(double);
+    if (e == hipSuccess) e = hipMalloc((void **)&ctx->tab, 2 * sizeof(RoundTable) + scratch_bytes);
     if (e == hipSuccess) {
         ctx->tab_query = ctx->tab + 1;
+        ctx->partials = reinterpret_cast<double *>(ctx->tab + 2);
         e = hipHostMalloc((void **)&ctx->staging, sizeof(RoundTable), hipHostMallocDefault);
     }
     if (e == hipSuccess) {
@@ -306,6 +309,21 @@ int rps_set_mask_override(rps_ctx *ctx, const uint8_t *up, const uint8_t *down, 
     RPS_HIP(ctx, hipMemcpyAsync(ctx->tab, ctx->staging, sizeof(RoundTable), hipMemcpyHostToDevice, ctx->stream));
     RPS_HIP(ctx, hipStreamSynchronize(ctx->stream));
     ctx->override_on = true;
+    return RPS_OK;
+}
+
+int rps_consensus(rps_ctx *ctx, const void *X, double *distance, double *mean_sq) {
+    if (!ctx || !X) return RPS_EINVAL;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return RPS_EHIP;
+    const RoundParams prm = make_params(ctx, X, nullptr, 0);
+    double *out = ctx->partials + 2 * rps::kMaxPartials;
+    RPS_HIP(ctx, rps::launch_consensus(ctx->dtype, X, prm, ctx->partials, rps::kMaxPartials, out, ctx->stream));
+    double host[2] = {0.0, 0.0};
+    RPS_HIP(ctx, hipMemcpyAsync(host, out, sizeof(host), hipMemcpyDeviceToHost, ctx->stream));
+    RPS_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    if (distance) *distance = host[0];
+    if (mean_sq) *mean_sq = host[1];
     return RPS_OK;
 }
 

@@ -548,6 +548,127 @@ hipError_t launch_local_step_g(int grad_mode, ST *X, const ST *G, const RoundPar
     return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------------------
+// Consensus statistics (supplement, Lemma 1: the quantity sum_i ||x_i - xbar||^2 =
+// ||X (I - A_n)||_F^2 that the proof bounds) and ||xbar||^2.  One streaming read of X: a
+// wavefront walks the n rows of a tile with row 0 as pivot (y_i = x_i - x_0 in fp64, so that
+// sum y^2 - (sum y)^2 / n does not cancel when the workers nearly agree), tiles are taken
+// grid-stride, and the reduction order is fixed: lanes (butterfly), the four wavefronts of a
+// workgroup, then one workgroup over the per-workgroup partials.
+// ---------------------------------------------------------------------------------------
+template <typename ST, bool FULL>
+__device__ __forceinline__ void consensus_tile(const ST *__restrict__ X, const RoundParams &prm, const LaneCols &lc,
+                                               double &dist, double &msq) {
+    using S = Storage<ST>;
+    constexpr int VEC = S::VEC;
+    constexpr int R = 4;
+    const int n = prm.n;
+    const ST *row = X + lc.tile0;
+    float p[VEC];
+    S::unpack(load_raw<ST, FULL>(row, lc), p);
+    double s1[VEC], s2[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) s1[e] = s2[e] = 0.0;
+    int i = 1;
+    row += prm.N;
+    for (; i + R <= n; i += R) {
+        typename S::Raw x[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r, row += prm.N) x[r] = load_raw<ST, FULL>(row, lc);
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            float v[VEC];
+            S::unpack(x[r], v);
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) {
+                const double y = (double)v[e] - (double)p[e];
+                s1[e] += y;
+                s2[e] = __builtin_fma(y, y, s2[e]);
+            }
+        }
+    }
+    for (; i < n; ++i, row += prm.N) {
+        float v[VEC];
+        S::unpack(load_raw<ST, FULL>(row, lc), v);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+            const double y = (double)v[e] - (double)p[e];
+            s1[e] += y;
+            s2[e] = __builtin_fma(y, y, s2[e]);
+        }
+    }
+    const double inv_n = 1.0 / (double)n;
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {   // columns outside [lo, hi) were loaded as 0 and add 0
+        const double m = s1[e] * inv_n;
+        dist += s2[e] - s1[e] * m;
+        const double mean = (double)p[e] + m;
+        msq = __builtin_fma(mean, mean, msq);
+    }
+}
+
+template <typename ST>
+__global__ __launch_bounds__(256) void consensus_kernel(const ST *__restrict__ X, const RoundParams prm,
+                                                        double *__restrict__ partials) {
+    constexpr int VEC = Storage<ST>::VEC;
+    constexpr int TILE = 64 * VEC;
+    __shared__ double red[4][2];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t ntiles = (prm.N + TILE - 1) / TILE;
+    double dist = 0.0, msq = 0.0;
+    for (int64_t t = (int64_t)blockIdx.x * 4 + wave; t < ntiles; t += (int64_t)gridDim.x * 4) {
+        LaneCols lc;
+        lc.tile0 = t * TILE;
+        lc.loff = (uint32_t)lane * VEC;
+        lc.lo = 0;
+        lc.hi = prm.N;
+        if (prm.vec_ok && lc.tile0 + TILE <= prm.N)
+            consensus_tile<ST, true>(X, prm, lc, dist, msq);
+        else
+            consensus_tile<ST, false>(X, prm, lc, dist, msq);
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        dist += __shfl_xor(dist, off, 64);
+        msq += __shfl_xor(msq, off, 64);
+    }
+    if (lane == 0) {
+        red[wave][0] = dist;
+        red[wave][1] = msq;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        partials[2 * blockIdx.x + 0] = (red[0][0] + red[1][0]) + (red[2][0] + red[3][0]);
+        partials[2 * blockIdx.x + 1] = (red[0][1] + red[1][1]) + (red[2][1] + red[3][1]);
+    }
+}
+
+// One workgroup: fixed-order sum of the per-workgroup partials -> out[0] = distance, out[1] = ||xbar||^2.
+__global__ __launch_bounds__(256) void consensus_final_kernel(const double *__restrict__ partials, int count,
+                                                              double *__restrict__ out) {
+    __shared__ double red[256][2];
+    double d = 0.0, m = 0.0;
+    for (int k = threadIdx.x; k < count; k += 256) {
+        d += partials[2 * k];
+        m += partials[2 * k + 1];
+    }
+    red[threadIdx.x][0] = d;
+    red[threadIdx.x][1] = m;
+    __syncthreads();
+    for (int half = 128; half >= 1; half >>= 1) {
+        if ((int)threadIdx.x < half) {
+            red[threadIdx.x][0] += red[threadIdx.x + half][0];
+            red[threadIdx.x][1] += red[threadIdx.x + half][1];
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        out[0] = red[0][0];
+        out[1] = red[0][1];
+    }
+}
+
 }  // namespace
 
 hipError_t launch_masks(RoundTable *tab, int n, uint64_t seed, uint64_t step, uint64_t threshold,
@@ -570,6 +691,24 @@ hipError_t launch_local_step(int dtype, int grad_mode, void *X, const void *G, c
                              hipStream_t stream) {
     if (dtype == 0) return launch_local_step_g<float>(grad_mode, (float *)X, (const float *)G, prm, stream);
     return launch_local_step_g<uint16_t>(grad_mode, (uint16_t *)X, (const uint16_t *)G, prm, stream);
+}
+
+hipError_t launch_consensus(int dtype, const void *X, const RoundParams &prm, double *partials, int max_partials,
+                            double *out, hipStream_t stream) {
+    const int64_t tile = dtype == 0 ? 256 : 512;
+    const int64_t ntiles = (prm.N + tile - 1) / tile;
+    int64_t wgs = (ntiles + 3) / 4;
+    if (wgs > max_partials) wgs = max_partials;
+    if (dtype == 0)
+        hipLaunchKernelGGL(consensus_kernel<float>, dim3((unsigned)wgs), dim3(256), 0, stream, (const float *)X, prm,
+                           partials);
+    else
+        hipLaunchKernelGGL(consensus_kernel<uint16_t>, dim3((unsigned)wgs), dim3(256), 0, stream,
+                           (const uint16_t *)X, prm, partials);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(consensus_final_kernel, dim3(1), dim3(256), 0, stream, partials, (int)wgs, out);
+    return hipGetLastError();
 }
 
 }  // namespace rps

@@ -32,6 +32,7 @@ _lib.rps_lossy_average.argtypes = [_ctx_p, ctypes.c_void_p, ctypes.c_uint64]
 _lib.rps_round.argtypes = [_ctx_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64]
 _lib.rps_get_masks.argtypes = [_ctx_p, ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
 _lib.rps_set_mask_override.argtypes = [_ctx_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+_lib.rps_consensus.argtypes = [_ctx_p, ctypes.c_void_p, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
 _lib.rps_set_launch_tuning.argtypes = [_ctx_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32]
 _lib.rps_set_profiling.argtypes = [_ctx_p, ctypes.c_int32]
 _lib.rps_get_kernel_time.argtypes = [_ctx_p, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
@@ -40,12 +41,13 @@ _lib.rps_strerror.argtypes = [ctypes.c_int]
 _lib.rps_strerror.restype = ctypes.c_char_p
 for _name in ("rps_create", "rps_destroy", "rps_set_synthetic_grad", "rps_set_gamma", "rps_local_step",
               "rps_lossy_average", "rps_round", "rps_get_masks", "rps_set_mask_override",
-              "rps_set_launch_tuning", "rps_set_profiling", "rps_get_kernel_time", "rps_last_hip_error"):
+              "rps_consensus", "rps_set_launch_tuning", "rps_set_profiling", "rps_get_kernel_time", "rps_last_hip_error"):
     getattr(_lib, _name).restype = ctypes.c_int
 
 EXPORTS = ("rps_create", "rps_destroy", "rps_set_synthetic_grad", "rps_set_gamma", "rps_local_step",
            "rps_lossy_average", "rps_round", "rps_get_masks", "rps_set_mask_override",
-           "rps_set_launch_tuning", "rps_set_profiling", "rps_get_kernel_time", "rps_last_hip_error",
+           "rps_consensus", "rps_set_launch_tuning", "rps_set_profiling", "rps_get_kernel_time",
+           "rps_last_hip_error",
            "rps_strerror")
 
 
@@ -138,6 +140,12 @@ class RpsContext:
             raise RpsError(RPS_EINVAL)
         _check(_lib.rps_set_mask_override(self._h, up.ctypes.data, down.ctypes.data, server.ctypes.data), self._h)
 
+    def consensus(self, X):
+        """(sum_i ||x_i - xbar||^2, ||xbar||^2) of the state."""
+        d, m = ctypes.c_double(), ctypes.c_double()
+        _check(_lib.rps_consensus(self._h, _ptr(X, self), ctypes.byref(d), ctypes.byref(m)), self._h)
+        return d.value, m.value
+
     def set_launch_tuning(self, rows_in_flight, waves_per_workgroup, max_waves_per_cu=0):
         _check(_lib.rps_set_launch_tuning(self._h, rows_in_flight, waves_per_workgroup, max_waves_per_cu), self._h)
 
@@ -182,6 +190,10 @@ def rps_round(ctx, X, G, step):
 
 def rps_get_masks(ctx, step):
     return ctx.get_masks(step)
+
+
+def rps_consensus(ctx, X):
+    return ctx.consensus(X)
 
 
 def rps_set_mask_override(ctx, server=None, up=None, down=None):

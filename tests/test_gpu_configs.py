@@ -182,3 +182,36 @@ def test_config_mlp_n8_loss_tracks_oracle(rps):
     torch.cuda.synchronize()
     assert_close(Xs.cpu().numpy(), Xo, off, "f32", what="single round from the oracle state")
     ctx.destroy()
+
+
+def test_config_resnet50_n32_contraction_rate(rps):
+    """A property that holds at any size: one averaging round without gradients shrinks the
+    disagreement sum_i ||x_i - xbar||^2 by beta = alpha_1 - alpha_2 in expectation (supplement,
+    proof of Lemma 1).  At n = 32, p = 0.05 the 32 blocks x 3 fresh states average the ratio well; the
+    exact beta comes from the supplement's case analysis (Lemmas 7 and 8), recomputed here."""
+    from math import comb
+    cfg = workloads.CONFIGS["resnet50_n32"]
+    n, p = cfg.n, cfg.p
+    q = 1 - p
+    w11 = sum(comb(n - 1, m) * q ** m * p ** (n - 1 - m) / (m + 1) ** 2 for m in range(n))
+    w1n2 = sum(comb(n - 2, m) * q ** (m + 1) * p ** (n - 2 - m) / (m + 2) ** 2 for m in range(n - 1))
+    w1n = sum(comb(n - 2, m) * q ** (m + 1) * p ** (n - 2 - m) / (m + 2) for m in range(n - 1))
+    e1 = (w11 * (1 + (n - 1) * q) + (1 + w1n2 * (1 + (n - 2) * q)) * p * (n - 1) + w1n2 * (2 + (n - 2) * q) * q * (n - 1)) / n
+    a1 = (n * e1 - 1) / (n - 1)
+    e2 = (w11 * ((1 + (n - 1) * q) ** 2 + (n - 1) * p * q)
+          + (1 + 2 * w1n * ((n - 2) * q + 1) + w1n2 * (1 + 2 * (n - 2) * q + (n - 2) ** 2 * q * q + (n - 2) * p * q)) * p * (n - 1)
+          + w1n2 * (((n - 2) * q + 2) ** 2 + (n - 2) * p * q) * q * (n - 1)) / n
+    a2 = (e2 - 1) / (n - 1)
+    beta = a1 - a2
+    ctx = rps.RpsContext(cfg.n, cfg.N, cfg.p, cfg.gamma, cfg.seed)
+    ratios = []
+    for t in range(3):                                   # fresh i.i.d. state each time: the identity is an
+        X = _seeded_state(cfg, 1.0, seed=21 + t)         # expectation over the masks for a FIXED state, and
+        d0, _ = ctx.consensus(X)                         # after a round the disagreement sits in a few outlier
+        ctx.lossy_average(X, t)                          # rows, which makes later single draws heavy-tailed
+        d1, _ = ctx.consensus(X)
+        ratios.append(d1 / d0)
+        del X
+    # each of the 32 blocks is an independent draw of the masks: 96 draws, a 30 % band
+    assert abs(np.mean(ratios) - beta) < 0.30 * beta, (ratios, beta)
+    ctx.destroy()

@@ -271,3 +271,23 @@ def test_profiling_hooks(rps):
     assert cnt == 0 and ms == 0.0
     ctx.set_profiling(False)
     ctx.destroy()
+
+
+@pytest.mark.parametrize("n,N,dtype", [(1, 777, "f32"), (4, 10_000, "f32"), (7, 7 * 1301, "f32"), (32, 32 * 1544, "f32"),
+                                       (64, 64 * 520, "bf16"), (9, 9001, "bf16"), (16, 16 * 40_000, "f32")])
+def test_consensus_statistics(rps, n, N, dtype):
+    """rps_consensus against the plain float64 definition, including a state where the workers
+    agree to 1e-6 (the pivoted sums must not cancel)."""
+    ctx = rps.RpsContext(n, N, 0.1, 0.1, 0, _dt(rps, dtype), block_offsets=_offsets(n, N, "arbitrary") if N % n else None)
+    for kind in ("spread", "tight"):
+        X0 = workloads.gaussian_model(n, N, seed=40 + n)
+        if kind == "tight":
+            X0 = (1.0 + X0[0:1]) + 1e-6 * X0
+        Xg = device_tensor(X0, dtype)
+        d_ref, m_ref = oracle.consensus(to_oracle(Xg))
+        d, m = ctx.consensus(Xg)
+        assert abs(m - m_ref) <= 1e-11 * m_ref
+        assert abs(d - d_ref) <= 1e-9 * d_ref + 1e-18 * m_ref * n
+        d2, m2 = ctx.consensus(Xg)
+        assert (d2, m2) == (d, m)                              # fixed reduction order
+    ctx.destroy()

@@ -219,3 +219,36 @@ def test_generated_masks_reproduce_alpha2(n, p):
     exact = alpha2_exact(n, p)
     assert abs(est - exact) < 5 * se
     assert 0.5 < exact * n / (p * (1 - p)) < 4.0
+
+
+def test_consensus_distance_definition_and_contraction():
+    """sum_i ||x_i - xbar||^2 = ||X (I - A_n)||_F^2 = Tr(X (I - A_n) X^T) (supplement, proof of Lemma 1),
+    and over the drop randomness of one round E||X W (I - A_n)||_F^2 = (a1 - a2) ||X (I - A_n)||_F^2
+    (same proof: E[W (I - A_n) W^T] = (a1 - a2)(I - A_n)), checked by enumerating every outcome."""
+    n, width, p = 4, 5, 0.3
+    rng = np.random.default_rng(9)
+    V = rng.standard_normal((n, width)).astype(np.float32)
+    Vd = V.astype(np.float64).T                                   # columns = workers
+    A = np.full((n, n), 1.0 / n)
+    d0, m0 = oracle.consensus(V)
+    assert abs(d0 - np.trace(Vd @ (np.eye(n) - A) @ Vd.T)) < 1e-12 * d0
+    assert abs((V.astype(np.float64) ** 2).sum() - (d0 + n * m0)) < 1e-12 * d0      # Pythagoras
+    same = np.tile(V[0:1], (n, 1))
+    assert oracle.consensus(same)[0] == 0.0
+    off = np.array([0] + [width] * n, dtype=np.int64)
+    q = 1 - p
+    expect = 0.0
+    for s in range(n):
+        others = [i for i in range(n) if i != s]
+        for up in itertools.product((0, 1), repeat=n - 1):
+            for dn in itertools.product((0, 1), repeat=n - 1):
+                U = np.zeros((n, n), dtype=np.uint8); D = np.zeros((n, n), dtype=np.uint8)
+                U[s, 0] = D[s, 0] = 1
+                for o, u, d in zip(others, up, dn):
+                    U[o, 0] = u; D[o, 0] = d
+                prob = (1.0 / n) * np.prod([q if b else p for b in up + dn])
+                Y = V.copy()
+                oracle.lossy_average(Y, off, U, D)
+                expect += prob * oracle.consensus(Y)[0]
+    beta = alpha1_exact(n, p) - alpha2_exact(n, p)
+    assert abs(expect - beta * d0) < 1e-5 * d0
