@@ -113,6 +113,18 @@ int rps_lossy_average(rps_ctx *ctx, void *X, uint64_t step);
 int rps_round(rps_ctx *ctx, void *X, const void *G, uint64_t step);
 
 /*
+ * Gradient averaging under loss -- the comparison the paper runs in Sec. 6 (averaging gradients
+ * instead of models under message drops converges worse): the Reduce-Scatter / All-Gather with
+ * drops of (seed, step) is applied to G instead of V, then every worker takes its local step with
+ * what it holds:   x'[i] = x[i] - gamma * (reply for block j reached i ? average of the gradient
+ * copies that reached the server : its own g[i]),  the average rounded to the storage dtype.
+ *   X   device [n, N], updated in place;   G   device [n, N] (required), read only
+ * Worker models drift apart under this scheme (nothing ever pulls them together again), which
+ * rps_consensus makes visible.
+ */
+int rps_round_gradient_averaging(rps_ctx *ctx, void *X, const void *G, uint64_t step);
+
+/*
  * Test hook: the network outcome the DEVICE generates for `step`, copied to HOST arrays.
  *   up, down   n*n bytes each, index [worker * n + block]; 1 = delivered
  *   server     n int32, server[j] = worker that averages block j

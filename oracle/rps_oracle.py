@@ -169,3 +169,21 @@ def consensus(X: np.ndarray):
     Xd = (X.astype(np.uint32) << 16).view(np.float32).astype(np.float64) if X.dtype == np.uint16 else X.astype(np.float64)
     xbar = Xd.mean(axis=0)
     return float(((Xd - xbar[None, :]) ** 2).sum()), float((xbar ** 2).sum())
+
+
+def round_gradient_averaging(X: np.ndarray, G: np.ndarray, offsets, *, p: float, gamma: float, seed: int,
+                             step: int, identity_server: bool = False, mask_override=None, cols=None,
+                             threads: int = 1):
+    """The paper's gradient-averaging comparison (Sec. 6): the lossy Reduce-Scatter / All-Gather
+    is applied to the gradients, then each worker takes its local step with what it holds.
+    Literally the composition of the two oracle steps: lossy_average on a copy of G, then
+    local_step with that.  Returns the masks used."""
+    n = X.shape[0]
+    if mask_override is not None:
+        server, U, D = mask_override
+    else:
+        server, U, D = masks(seed, step, n, p, identity_server)
+    Gh = G.copy()
+    lossy_average(Gh, offsets, U, D, cols=cols, threads=threads)
+    local_step(X, Gh, gamma, threads=threads)
+    return server, U, D

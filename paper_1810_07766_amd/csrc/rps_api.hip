@@ -257,6 +257,19 @@ int rps_round(rps_ctx *ctx, void *X, const void *G, uint64_t step) {
     });
 }
 
+int rps_round_gradient_averaging(rps_ctx *ctx, void *X, const void *G, uint64_t step) {
+    if (!ctx || !X || !G || !step_ok(step)) return RPS_EINVAL;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return RPS_EHIP;
+    const RoundParams prm = make_params(ctx, X, G, step);
+    const int rc = enqueue_masks(ctx, step);
+    if (rc != RPS_OK) return rc;
+    return timed_launch(ctx, [&] {
+        return rps::launch_gradavg(ctx->dtype, X, G, ctx->tab, prm, ctx->max_block_cols, ctx->tune.max_waves_per_cu,
+                                   ctx->stream);
+    });
+}
+
 int rps_get_masks(rps_ctx *ctx, uint64_t step, uint8_t *up, uint8_t *down, int32_t *server) {
     if (!ctx || !step_ok(step)) return RPS_EINVAL;
     DeviceGuard guard(ctx->device);

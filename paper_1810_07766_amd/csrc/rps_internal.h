@@ -51,6 +51,9 @@ hipError_t launch_round(int dtype, int grad_mode, void *X, const void *G, const 
 hipError_t launch_local_step(int dtype, int grad_mode, void *X, const void *G,
                              const RoundParams &prm, hipStream_t stream);
 
+hipError_t launch_gradavg(int dtype, void *X, const void *G, const RoundTable *tab, const RoundParams &prm,
+                          int64_t max_block_cols, int max_waves_per_cu, hipStream_t stream);
+
 // Consensus statistics: partials = device scratch of 2*max_partials doubles, out = 2 device doubles.
 constexpr int kMaxPartials = 2048;
 hipError_t launch_consensus(int dtype, const void *X, const RoundParams &prm, double *partials, int max_partials,

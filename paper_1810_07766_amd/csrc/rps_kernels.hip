@@ -549,6 +549,101 @@ hipError_t launch_local_step_g(int grad_mode, ST *X, const ST *G, const RoundPar
 }
 
 // ---------------------------------------------------------------------------------------
+// Gradient averaging under loss (the baseline of Sec. 6 that the paper shows converging worse
+// than model averaging): the same Reduce-Scatter / All-Gather with drops is applied to the
+// GRADIENTS, and each worker then takes its local step with what it ended up holding:
+//   gt[c]    = (1/|N_j|) sum_{i : U[i,j]} g[i,c]         (rounded to storage: it travels)
+//   x'[i,c]  = x[i,c] - gamma * (D[i,j] ? gt[c] : g[i,c])
+// Pass 1 walks the rows of G (column sums), pass 2 walks the rows of X (a worker whose reply
+// was lost re-reads its own gradient row).  12 B fp32 per worker-param: G once, X read + write.
+// ---------------------------------------------------------------------------------------
+template <typename ST, bool FULL>
+__device__ __forceinline__ void gradavg_tile(ST *__restrict__ X, const ST *__restrict__ G, const RoundParams &prm,
+                                             const LaneCols &lc, uint64_t ucol, uint64_t dcol, double inv) {
+    using S = Storage<ST>;
+    using Raw = typename S::Raw;
+    constexpr int VEC = S::VEC;
+    constexpr int R = 4;
+    const int n = prm.n;
+
+    double acc[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) acc[e] = 0.0;
+    const ST *grow = G + lc.tile0;
+    for (int i0 = 0; i0 < n; i0 += R) {
+        Raw g[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {   // rows past n repeat row n-1, unused
+            g[r] = load_raw<ST, FULL>(grow, lc);
+            if (i0 + r + 1 < n) grow += prm.N;
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int i = i0 + r;
+            if (i < n && ((ucol >> i) & 1)) {
+                float v[VEC];
+                S::unpack(g[r], v);
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) acc[e] += (double)v[e];
+            }
+        }
+    }
+    float gt[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) gt[e] = S::round((float)(acc[e] * inv));
+
+    ST *xrow = X + lc.tile0;
+    for (int i0 = 0; i0 < n; i0 += R) {
+        Raw x[R];
+        const ST *ld = xrow;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            x[r] = load_raw<ST, FULL>(ld, lc);
+            if (i0 + r + 1 < n) ld += prm.N;
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int i = i0 + r;
+            if (i < n) {
+                float v[VEC], own[VEC];
+                S::unpack(x[r], v);
+                const float *gsrc = gt;
+                if (!((dcol >> i) & 1)) {   // reply lost: the worker applies its own gradient
+                    S::unpack(load_raw<ST, FULL>(G + lc.tile0 + (int64_t)i * prm.N, lc), own);
+                    gsrc = own;
+                }
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) v[e] = S::round(__builtin_fmaf(-prm.gamma, gsrc[e], v[e]));
+                store_raw<ST, FULL>(xrow, lc, S::pack(v));
+                xrow += prm.N;
+            }
+        }
+    }
+}
+
+template <typename ST>
+__global__ __launch_bounds__(256) void gradavg_kernel(ST *__restrict__ X, const ST *__restrict__ G,
+                                                      const RoundTable *__restrict__ tab, const RoundParams prm) {
+    constexpr int VEC = Storage<ST>::VEC;
+    constexpr int TILE = 64 * VEC;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int j = blockIdx.y;
+    const int64_t lo = tab->off[j], hi = tab->off[j + 1];
+    const int64_t tile0 = (lo & ~(int64_t)(VEC - 1)) + ((int64_t)blockIdx.x * 4 + wave) * TILE;
+    if (tile0 >= hi) return;   // wave-uniform
+    LaneCols lc;
+    lc.tile0 = tile0;
+    lc.loff = (uint32_t)lane * VEC;
+    lc.lo = lo;
+    lc.hi = hi;
+    if (prm.vec_ok && tile0 >= lo && tile0 + TILE <= hi)
+        gradavg_tile<ST, true>(X, G, prm, lc, tab->ucol[j], tab->dcol[j], tab->inv_cnt[j]);
+    else
+        gradavg_tile<ST, false>(X, G, prm, lc, tab->ucol[j], tab->dcol[j], tab->inv_cnt[j]);
+}
+
+// ---------------------------------------------------------------------------------------
 // Consensus statistics (supplement, Lemma 1: the quantity sum_i ||x_i - xbar||^2 =
 // ||X (I - A_n)||_F^2 that the proof bounds) and ||xbar||^2.  One streaming read of X: a
 // wavefront walks the n rows of a tile with row 0 as pivot (y_i = x_i - x_0 in fp64, so that
@@ -691,6 +786,27 @@ hipError_t launch_local_step(int dtype, int grad_mode, void *X, const void *G, c
                              hipStream_t stream) {
     if (dtype == 0) return launch_local_step_g<float>(grad_mode, (float *)X, (const float *)G, prm, stream);
     return launch_local_step_g<uint16_t>(grad_mode, (uint16_t *)X, (const uint16_t *)G, prm, stream);
+}
+
+hipError_t launch_gradavg(int dtype, void *X, const void *G, const RoundTable *tab, const RoundParams &prm,
+                          int64_t max_block_cols, int max_waves_per_cu, hipStream_t stream) {
+    const int vec = dtype == 0 ? 4 : 8;
+    const int64_t tile = 64 * vec;
+    const int64_t tiles = (max_block_cols + vec - 1 + tile - 1) / tile;
+    const dim3 grid((unsigned)((tiles + 3) / 4), (unsigned)prm.n, 1);
+    size_t lds = 0;
+    if (max_waves_per_cu > 0 && max_waves_per_cu < 32) {
+        int wgs = max_waves_per_cu / 4;
+        if (wgs < 1) wgs = 1;
+        lds = ((size_t)kLdsBytesPerCu / wgs) & ~(size_t)255;
+        if (lds > 65536) lds = 65536;
+    }
+    if (dtype == 0)
+        hipLaunchKernelGGL(gradavg_kernel<float>, grid, dim3(256), lds, stream, (float *)X, (const float *)G, tab, prm);
+    else
+        hipLaunchKernelGGL(gradavg_kernel<uint16_t>, grid, dim3(256), lds, stream, (uint16_t *)X, (const uint16_t *)G,
+                           tab, prm);
+    return hipGetLastError();
 }
 
 hipError_t launch_consensus(int dtype, const void *X, const RoundParams &prm, double *partials, int max_partials,

@@ -30,6 +30,7 @@ _lib.rps_set_gamma.argtypes = [_ctx_p, ctypes.c_float]
 _lib.rps_local_step.argtypes = [_ctx_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64]
 _lib.rps_lossy_average.argtypes = [_ctx_p, ctypes.c_void_p, ctypes.c_uint64]
 _lib.rps_round.argtypes = [_ctx_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64]
+_lib.rps_round_gradient_averaging.argtypes = [_ctx_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64]
 _lib.rps_get_masks.argtypes = [_ctx_p, ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
 _lib.rps_set_mask_override.argtypes = [_ctx_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
 _lib.rps_consensus.argtypes = [_ctx_p, ctypes.c_void_p, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
@@ -40,12 +41,12 @@ _lib.rps_last_hip_error.argtypes = [_ctx_p]
 _lib.rps_strerror.argtypes = [ctypes.c_int]
 _lib.rps_strerror.restype = ctypes.c_char_p
 for _name in ("rps_create", "rps_destroy", "rps_set_synthetic_grad", "rps_set_gamma", "rps_local_step",
-              "rps_lossy_average", "rps_round", "rps_get_masks", "rps_set_mask_override",
+              "rps_lossy_average", "rps_round", "rps_round_gradient_averaging", "rps_get_masks", "rps_set_mask_override",
               "rps_consensus", "rps_set_launch_tuning", "rps_set_profiling", "rps_get_kernel_time", "rps_last_hip_error"):
     getattr(_lib, _name).restype = ctypes.c_int
 
 EXPORTS = ("rps_create", "rps_destroy", "rps_set_synthetic_grad", "rps_set_gamma", "rps_local_step",
-           "rps_lossy_average", "rps_round", "rps_get_masks", "rps_set_mask_override",
+           "rps_lossy_average", "rps_round", "rps_round_gradient_averaging", "rps_get_masks", "rps_set_mask_override",
            "rps_consensus", "rps_set_launch_tuning", "rps_set_profiling", "rps_get_kernel_time",
            "rps_last_hip_error",
            "rps_strerror")
@@ -119,6 +120,11 @@ class RpsContext:
     def round(self, X, G, step):
         _check(_lib.rps_round(self._h, _ptr(X, self), _ptr(G, self), step), self._h)
 
+    def round_gradient_averaging(self, X, G, step):
+        if G is None:
+            raise RpsError(RPS_EINVAL)
+        _check(_lib.rps_round_gradient_averaging(self._h, _ptr(X, self), _ptr(G, self), step), self._h)
+
     def get_masks(self, step):
         import numpy as np
         n = self.n
@@ -186,6 +192,10 @@ def rps_lossy_average(ctx, X, step):
 
 def rps_round(ctx, X, G, step):
     ctx.round(X, G, step)
+
+
+def rps_round_gradient_averaging(ctx, X, G, step):
+    ctx.round_gradient_averaging(X, G, step)
 
 
 def rps_get_masks(ctx, step):

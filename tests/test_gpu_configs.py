@@ -215,3 +215,26 @@ def test_config_resnet50_n32_contraction_rate(rps):
     # each of the 32 blocks is an independent draw of the masks: 96 draws, a 30 % band
     assert abs(np.mean(ratios) - beta) < 0.30 * beta, (ratios, beta)
     ctx.destroy()
+
+
+def test_config_lsq_n4_gradient_averaging_drifts(rps):
+    """The paper's Sec. 6 observation on the least-squares workload: with 10 % loss, averaging
+    gradients lets the worker models drift apart, averaging models does not.  Both runs use the
+    library end to end (rounds and rps_consensus)."""
+    cfg = workloads.CONFIGS["lsq_n4"]
+    A, b = workloads.least_squares_problem(cfg.n, cfg.N, cfg.extra["rows"], seed=cfg.seed)
+    At = torch.from_numpy(A).cuda(); bt = torch.from_numpy(b).cuda()
+
+    def grad(X):
+        r = torch.bmm(At, X.double().unsqueeze(2)).squeeze(2) - bt
+        return torch.bmm(At.transpose(1, 2), r.unsqueeze(2)).squeeze(2).float().contiguous()
+
+    ctx = rps.RpsContext(cfg.n, cfg.N, cfg.p, cfg.gamma, cfg.seed)
+    Xm = torch.zeros(cfg.n, cfg.N, device="cuda"); Xg = torch.zeros(cfg.n, cfg.N, device="cuda")
+    for t in range(cfg.rounds):
+        ctx.round(Xm, grad(Xm), t)
+        ctx.round_gradient_averaging(Xg, grad(Xg), t)
+    dm, _ = ctx.consensus(Xm)
+    dg, _ = ctx.consensus(Xg)
+    assert dg > 10 * dm, (dg, dm)
+    ctx.destroy()

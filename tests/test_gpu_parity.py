@@ -291,3 +291,23 @@ def test_consensus_statistics(rps, n, N, dtype):
         d2, m2 = ctx.consensus(Xg)
         assert (d2, m2) == (d, m)                              # fixed reduction order
     ctx.destroy()
+
+
+@pytest.mark.parametrize("n,N,layout,dtype", [SHAPES[k] for k in (1, 3, 4, 8, 9, 10, 13, 15, 16)])
+def test_gradient_averaging_variant(rps, n, N, layout, dtype):
+    """rps_round_gradient_averaging against the oracle composition (lossy average of G, then the
+    local step), three rounds."""
+    off = _offsets(n, N, layout, seed=11)
+    p, gamma, seed = 0.25, 0.3, 77
+    Xg = device_tensor(workloads.gaussian_model(n, N, seed=5), dtype)
+    Xo = to_oracle(Xg)
+    ctx = rps.RpsContext(n, N, p, gamma, seed, _dt(rps, dtype), block_offsets=off)
+    for step in (0, 1, 2):
+        Gg = device_tensor(workloads.gaussian_model(n, N, seed=60 + step), dtype)
+        ctx.round_gradient_averaging(Xg, Gg, step)
+        oracle.round_gradient_averaging(Xo, to_oracle(Gg), off, p=p, gamma=gamma, seed=seed, step=step)
+        torch.cuda.synchronize()
+        assert_close(to_oracle(Xg), Xo, off, dtype, what=f"step {step}")
+    with pytest.raises(rps.RpsError):
+        ctx.round_gradient_averaging(Xg, None, 3)
+    ctx.destroy()

@@ -245,3 +245,32 @@ def test_averaging_contracts_disagreement():
     server, U, D = oracle.masks(1, 0, n, 0.1)
     oracle.lossy_average(X, off, U, D)
     assert dist(X) < 0.25 * d0                                       # beta ~ p for small p
+
+
+def test_gradient_averaging_variant_special_cases_and_drift():
+    """Sec. 6's comparison: averaging GRADIENTS under loss.  p = 0: every worker applies the mean
+    gradient (identical workers stay identical); p = 1: plain local steps.  With loss, workers
+    that start identical drift apart and nothing contracts the disagreement again, while model
+    averaging (RPS) keeps it bounded: the mechanism behind the paper's 'worse convergence'."""
+    n, N, rows, gamma = 4, 400, 32, 0.05
+    off = workloads.block_offsets(n, N)
+    A, b = workloads.least_squares_problem(n, N, rows, seed=31)
+    grad = lambda X: np.stack([A[i].T @ (A[i] @ X[i].astype(np.float64) - b[i]) for i in range(n)]).astype(np.float32)
+    X = workloads.gaussian_model(n, N, seed=32, identical=True)
+    G = grad(X)
+    Y = X.copy()
+    oracle.round_gradient_averaging(Y, G, off, p=0.0, gamma=gamma, seed=0, step=0)
+    ref = X[0].astype(np.float64) - gamma * G.astype(np.float64).mean(axis=0)
+    assert (Y == Y[0:1]).all() and np.abs(Y[0] - ref).max() < 1e-6
+    Y = X.copy(); Z = X.copy()
+    oracle.round_gradient_averaging(Y, G, off, p=1.0, gamma=gamma, seed=0, step=0)
+    oracle.local_step(Z, G, gamma)
+    assert (Y == Z).all()
+    Xg = X.copy(); Xm = X.copy()
+    dg, dm = [], []
+    for t in range(300):
+        oracle.round_gradient_averaging(Xg, grad(Xg), off, p=0.2, gamma=gamma, seed=5, step=t)
+        oracle.round_(Xm, grad(Xm), off, p=0.2, gamma=gamma, seed=5, step=t)
+        dg.append(oracle.consensus(Xg)[0]); dm.append(oracle.consensus(Xm)[0])
+    assert dg[-1] > 20 * dm[-1]                     # gradient averaging: disagreement accumulates
+    assert max(dm[100:]) < 10 * np.mean(dm[50:100]) # model averaging: bounded steady state
