@@ -78,6 +78,18 @@ enum {
 int rps_create(rps_ctx **out, int32_t n, int64_t N, const int64_t *block_offsets, double p,
                float gamma, uint64_t seed, int32_t dtype, uint32_t flags, void *hip_stream);
 
+/*
+ * Same, for `servers` external parameter servers that are not workers (the paper's Fig. 1
+ * draws three servers and four workers and notes that the analysis extends to any numbers):
+ * the model is cut into `servers` blocks (1..64; block_offsets has servers+1 entries, or NULL
+ * for equal blocks with N % servers == 0), every one of the n x servers uplinks and downlinks
+ * is lossy -- there is no reliable self link -- and a server that received no copy sends
+ * nothing, so every worker keeps its v for that block (the paper does not treat this case).
+ * Masks of such a context are [worker * servers + block]; rps_get_masks reports server = -1.
+ */
+int rps_create_external(rps_ctx **out, int32_t n, int32_t servers, int64_t N, const int64_t *block_offsets,
+                        double p, float gamma, uint64_t seed, int32_t dtype, void *hip_stream);
+
 /* Free the context's tables.  Synchronises the stream first.  NULL is a no-op. */
 int rps_destroy(rps_ctx *ctx);
 
@@ -126,8 +138,8 @@ int rps_round_gradient_averaging(rps_ctx *ctx, void *X, const void *G, uint64_t 
 
 /*
  * Test hook: the network outcome the DEVICE generates for `step`, copied to HOST arrays.
- *   up, down   n*n bytes each, index [worker * n + block]; 1 = delivered
- *   server     n int32, server[j] = worker that averages block j
+ *   up, down   n*B bytes each (B = number of blocks), index [worker * B + block]; 1 = delivered
+ *   server     B int32, server[j] = worker that averages block j (-1: external server)
  * Any pointer may be NULL.  Ignores a mask override.  Synchronises the stream.
  */
 int rps_get_masks(rps_ctx *ctx, uint64_t step, uint8_t *up, uint8_t *down, int32_t *server);

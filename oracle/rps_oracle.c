@@ -83,27 +83,36 @@ static void hash_words(uint32_t rounds, uint64_t seed, uint64_t step,
 
 /* ------------------------------------------------------------------------- */
 /* Network outcome of one round (Sec. 3 "Unreliable Network Connection";      */
-/* Alg. 1 steps 6-7).                                                         */
-/*   server[j] : the worker b_t^{(j)} that averages block j.  A uniformly     */
-/*               random permutation: every worker draws a 32-bit sort key,    */
-/*               workers are ranked by (key, index), and block j goes to the  */
-/*               worker of rank j.  identity_server != 0 gives server[j] = j  */
-/*               (the simplification the paper uses in its exposition).       */
-/*   U[i*n+j]  : 1 iff worker i's copy of block j reaches server[j].          */
-/*   D[i*n+j]  : 1 iff server[j]'s reply for block j reaches worker i.        */
+/* Alg. 1 steps 6-7).  n workers, nb blocks; masks are indexed [i*nb + j].    */
+/*   server[j] : the worker b_t^{(j)} that averages block j (mode 0, nb = n): */
+/*               a uniformly random permutation -- every worker draws a       */
+/*               32-bit sort key, workers are ranked by (key, index), and     */
+/*               block j goes to the worker of rank j.  Mode 1 (nb = n):      */
+/*               server[j] = j, the simplification of the paper's exposition. */
+/*               Mode 2: nb external parameter servers that are not workers   */
+/*               (the paper's Fig. 1 shows three servers and four workers;    */
+/*               its footnote says the analysis extends to any numbers):      */
+/*               server[j] = -1.                                              */
+/*   U[i*nb+j] : 1 iff worker i's copy of block j reaches the server.         */
+/*   D[i*nb+j] : 1 iff the server's reply for block j reaches worker i.       */
 /* Every (worker, block, direction) message is lost independently with        */
 /* probability p: lost iff hash word < floor(p * 2^32).  A worker's message   */
 /* to itself never crosses the network, so U and D are forced to 1 for        */
 /* i == server[j] (supplement, Lemma 7 proof: the server "must receive its    */
 /* own block"; its weight is 1/(m+1) with m copies received from others).     */
+/* External servers have no such link: all n uplinks of a block can be lost.  */
 /* ------------------------------------------------------------------------- */
-void rps_oracle_masks(uint64_t seed, uint64_t step, int32_t n, double p,
-                      int32_t identity_server,
+enum { SERVER_RANDOM = 0, SERVER_IDENTITY = 1, SERVER_EXTERNAL = 2 };
+
+void rps_oracle_masks(uint64_t seed, uint64_t step, int32_t n, int32_t nb, double p,
+                      int32_t server_mode,
                       int32_t *server, uint8_t *U, uint8_t *D)
 {
     uint32_t w[4];
-    if (identity_server) {
-        for (int j = 0; j < n; ++j) server[j] = j;
+    if (server_mode == SERVER_EXTERNAL) {
+        for (int j = 0; j < nb; ++j) server[j] = -1;
+    } else if (server_mode == SERVER_IDENTITY) {
+        for (int j = 0; j < nb; ++j) server[j] = j;
     } else {
         uint32_t sortkey[64];
         for (int i = 0; i < n; ++i) {
@@ -120,12 +129,12 @@ void rps_oracle_masks(uint64_t seed, uint64_t step, int32_t n, double p,
     }
     const uint64_t threshold = (uint64_t)floor(p * 4294967296.0);
     for (int i = 0; i < n; ++i) {
-        for (int j = 0; j < n; ++j) {
+        for (int j = 0; j < nb; ++j) {
             hash_words(MASK_ROUNDS, seed, step, (uint32_t)i, (uint32_t)j, DOMAIN_UPLINK, w);
-            U[i * n + j] = ((uint64_t)w[0] < threshold) ? 0 : 1;
+            U[i * nb + j] = ((uint64_t)w[0] < threshold) ? 0 : 1;
             hash_words(MASK_ROUNDS, seed, step, (uint32_t)i, (uint32_t)j, DOMAIN_DOWNLINK, w);
-            D[i * n + j] = ((uint64_t)w[0] < threshold) ? 0 : 1;
-            if (i == server[j]) { U[i * n + j] = 1; D[i * n + j] = 1; }
+            D[i * nb + j] = ((uint64_t)w[0] < threshold) ? 0 : 1;
+            if (i == server[j]) { U[i * nb + j] = 1; D[i * nb + j] = 1; }
         }
     }
 }
@@ -273,22 +282,26 @@ void rps_oracle_local_step(void *X, const void *G, int32_t n, int64_t m,
 
 /* ------------------------------------------------------------------------- */
 /* Lossy average, Alg. 1 steps 6-8.  V is [n, m] row-major, updated in place  */
-/* to X_{t+1}.  offsets[0..n] partitions the model coordinates into the n     */
+/* to X_{t+1}.  offsets[0..nb] partitions the model coordinates into the nb   */
 /* blocks (Sec. 4.1 eq. (dividev)); block j is [offsets[j], offsets[j+1]).    */
 /* For every column:                                                          */
 /*   RS:  vt = (1/|N_j|) sum_{i : U[i,j]=1} v[i]      (double accumulation,   */
 /*        one rounding to fp32, one to storage)                               */
 /*   AG:  x'[i] = D[i,j] ? vt : v[i]                                          */
+/* With worker-servers |N_j| >= 1 always (the server holds its own copy).     */
+/* An external server that received nothing has nothing to send: every        */
+/* worker keeps v (the paper does not discuss this case; this is the only     */
+/* outcome that needs no invented value).                                     */
 /* ------------------------------------------------------------------------- */
-static int32_t block_of(const int64_t *offsets, int32_t n, int64_t c)
+static int32_t block_of(const int64_t *offsets, int32_t nb, int64_t c)
 {
     int32_t j = 0;
-    while (j + 1 < n && c >= offsets[j + 1]) ++j;
+    while (j + 1 < nb && c >= offsets[j + 1]) ++j;
     return j;
 }
 
 void rps_oracle_lossy_average(void *V, int32_t n, int64_t m, const int64_t *cols,
-                              const int64_t *offsets, const uint8_t *U,
+                              int32_t nb, const int64_t *offsets, const uint8_t *U,
                               const uint8_t *D, int32_t dtype, int32_t threads)
 {
     (void)threads;
@@ -297,19 +310,19 @@ void rps_oracle_lossy_average(void *V, int32_t n, int64_t m, const int64_t *cols
 #endif
     for (int64_t k = 0; k < m; ++k) {
         int64_t c = cols ? cols[k] : k;
-        int32_t j = block_of(offsets, n, c);
+        int32_t j = block_of(offsets, nb, c);
         double sum = 0.0;
         int32_t received = 0;
         for (int32_t i = 0; i < n; ++i) {
-            if (U[i * n + j]) {
+            if (U[i * nb + j]) {
                 sum += (double)load_elem(V, dtype, i * m + k);
                 ++received;
             }
         }
-        /* received >= 1: the server always holds its own copy */
+        if (received == 0) continue;
         float vt = round_storage(dtype, (float)(sum / (double)received));
         for (int32_t i = 0; i < n; ++i)
-            if (D[i * n + j]) store_elem(V, dtype, i * m + k, vt);
+            if (D[i * nb + j]) store_elem(V, dtype, i * m + k, vt);
     }
 }
 
@@ -317,16 +330,16 @@ void rps_oracle_lossy_average(void *V, int32_t n, int64_t m, const int64_t *cols
 /* Mixing matrix of block j, Sec. 4.2 eq. (updatingrule): X^{(j)} = V^{(j)} W */
 /* with V^{(j)}'s columns the workers' blocks.  W[m*n + k] is the weight of   */
 /* worker m's block in worker k's result: column k is U[:,j]/|N_j| if the     */
-/* reply reached k, else the unit vector e_k.                                 */
+/* reply reached k (and the server had something to send), else e_k.          */
 /* ------------------------------------------------------------------------- */
-void rps_oracle_build_W(int32_t n, int32_t j, const uint8_t *U, const uint8_t *D, double *W)
+void rps_oracle_build_W(int32_t n, int32_t nb, int32_t j, const uint8_t *U, const uint8_t *D, double *W)
 {
     int32_t received = 0;
-    for (int32_t i = 0; i < n; ++i) received += U[i * n + j] ? 1 : 0;
+    for (int32_t i = 0; i < n; ++i) received += U[i * nb + j] ? 1 : 0;
     for (int32_t k = 0; k < n; ++k)
         for (int32_t mm = 0; mm < n; ++mm) {
-            if (D[k * n + j]) W[mm * n + k] = U[mm * n + j] ? 1.0 / (double)received : 0.0;
-            else              W[mm * n + k] = (mm == k) ? 1.0 : 0.0;
+            if (D[k * nb + j] && received > 0) W[mm * n + k] = U[mm * nb + j] ? 1.0 / (double)received : 0.0;
+            else                               W[mm * n + k] = (mm == k) ? 1.0 : 0.0;
         }
 }
 

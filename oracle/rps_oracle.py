@@ -27,7 +27,7 @@ _f64p = ctypes.POINTER(ctypes.c_double)
 
 _lib.rps_oracle_philox4x32.argtypes = [ctypes.c_uint32, _u32p, _u32p, _u32p]
 _lib.rps_oracle_philox4x32.restype = None
-_lib.rps_oracle_masks.argtypes = [ctypes.c_uint64, ctypes.c_uint64, ctypes.c_int32, ctypes.c_double,
+_lib.rps_oracle_masks.argtypes = [ctypes.c_uint64, ctypes.c_uint64, ctypes.c_int32, ctypes.c_int32, ctypes.c_double,
                                   ctypes.c_int32, _i32p, _u8p, _u8p]
 _lib.rps_oracle_masks.restype = None
 _lib.rps_oracle_noise_patch.argtypes = [ctypes.c_uint64, ctypes.c_uint64, ctypes.c_int32, ctypes.c_uint64,
@@ -39,10 +39,10 @@ _lib.rps_oracle_local_step.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.
                                        _i64p, ctypes.c_int32, ctypes.c_float, ctypes.c_float,
                                        ctypes.c_float, ctypes.c_uint64, ctypes.c_uint64, ctypes.c_int32]
 _lib.rps_oracle_local_step.restype = None
-_lib.rps_oracle_lossy_average.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, _i64p, _i64p,
-                                          _u8p, _u8p, ctypes.c_int32, ctypes.c_int32]
+_lib.rps_oracle_lossy_average.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, _i64p, ctypes.c_int32,
+                                          _i64p, _u8p, _u8p, ctypes.c_int32, ctypes.c_int32]
 _lib.rps_oracle_lossy_average.restype = None
-_lib.rps_oracle_build_W.argtypes = [ctypes.c_int32, ctypes.c_int32, _u8p, _u8p, _f64p]
+_lib.rps_oracle_build_W.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, _u8p, _u8p, _f64p]
 _lib.rps_oracle_build_W.restype = None
 _lib.rps_oracle_max_threads.argtypes = []
 _lib.rps_oracle_max_threads.restype = ctypes.c_int32
@@ -62,13 +62,17 @@ def philox4x32(ctr, key, rounds: int = 10) -> np.ndarray:
     return out
 
 
-def masks(seed: int, step: int, n: int, p: float, identity_server: bool = False):
-    """(server[n] int32, U[n,n] uint8, D[n,n] uint8) of one round."""
-    assert 1 <= n <= 64 and 0.0 <= p <= 1.0 and 0 <= step < (1 << 56)
-    server = np.empty(n, dtype=np.int32)
-    U = np.empty((n, n), dtype=np.uint8)
-    D = np.empty((n, n), dtype=np.uint8)
-    _lib.rps_oracle_masks(seed, step, n, p, int(identity_server), server.ctypes.data_as(_i32p),
+def masks(seed: int, step: int, n: int, p: float, identity_server: bool = False, external_servers: int = 0):
+    """(server[nb] int32, U[n,nb] uint8, D[n,nb] uint8) of one round.  nb = n blocks served by the
+    workers themselves, or `external_servers` blocks served by parameter servers that are not
+    workers (server = -1, no reliable self link)."""
+    assert 1 <= n <= 64 and 0.0 <= p <= 1.0 and 0 <= step < (1 << 56) and 0 <= external_servers <= 64
+    nb = external_servers if external_servers else n
+    mode = 2 if external_servers else (1 if identity_server else 0)
+    server = np.empty(nb, dtype=np.int32)
+    U = np.empty((n, nb), dtype=np.uint8)
+    D = np.empty((n, nb), dtype=np.uint8)
+    _lib.rps_oracle_masks(seed, step, n, nb, p, mode, server.ctypes.data_as(_i32p),
                           U.ctypes.data_as(_u8p), D.ctypes.data_as(_u8p))
     return server, U, D
 
@@ -118,16 +122,16 @@ def local_step(X: np.ndarray, G, gamma: float, *, sigma: float = 0.0, weight_dec
 
 def lossy_average(V: np.ndarray, offsets, U: np.ndarray, D: np.ndarray, *, cols=None,
                   threads: int = 1) -> None:
-    """In place RS + AG round on V with the given delivery masks."""
+    """In place RS + AG round on V with the given delivery masks ([n, nb]; nb = len(offsets) - 1)."""
     assert V.ndim == 2 and V.flags.c_contiguous
     n, m = V.shape
     off = np.ascontiguousarray(offsets, dtype=np.int64)
-    assert off.shape == (n + 1,)
+    nb = off.shape[0] - 1
     U = np.ascontiguousarray(U, dtype=np.uint8)
     D = np.ascontiguousarray(D, dtype=np.uint8)
-    assert U.shape == (n, n) and D.shape == (n, n)
+    assert U.shape == (n, nb) and D.shape == (n, nb)
     keep, cp = _cols_ptr(cols, m)
-    _lib.rps_oracle_lossy_average(V.ctypes.data, n, m, cp, off.ctypes.data_as(_i64p),
+    _lib.rps_oracle_lossy_average(V.ctypes.data, n, m, cp, nb, off.ctypes.data_as(_i64p),
                                   U.ctypes.data_as(_u8p), D.ctypes.data_as(_u8p), _dtype_code(V), threads)
 
 
@@ -135,9 +139,9 @@ def build_W(j: int, U: np.ndarray, D: np.ndarray) -> np.ndarray:
     """Mixing matrix W of block j: X_next^(j) = V^(j) W, W[m, k] = weight of worker m in worker k."""
     U = np.ascontiguousarray(U, dtype=np.uint8)
     D = np.ascontiguousarray(D, dtype=np.uint8)
-    n = U.shape[0]
+    n, nb = U.shape
     W = np.empty((n, n), dtype=np.float64)
-    _lib.rps_oracle_build_W(n, j, U.ctypes.data_as(_u8p), D.ctypes.data_as(_u8p), W.ctypes.data_as(_f64p))
+    _lib.rps_oracle_build_W(n, nb, j, U.ctypes.data_as(_u8p), D.ctypes.data_as(_u8p), W.ctypes.data_as(_f64p))
     return W
 
 
@@ -149,7 +153,7 @@ def equal_offsets(n: int, N: int) -> np.ndarray:
 
 def round_(X: np.ndarray, G, offsets, *, p: float, gamma: float, seed: int, step: int,
            sigma: float = 0.0, weight_decay: float = 0.0, identity_server: bool = False,
-           mask_override=None, cols=None, threads: int = 1):
+           external_servers: int = 0, mask_override=None, cols=None, threads: int = 1):
     """One full RPS round in the order of Alg. 1: local step, then RS, then AG.
     Returns the masks used."""
     n = X.shape[0]
@@ -158,7 +162,7 @@ def round_(X: np.ndarray, G, offsets, *, p: float, gamma: float, seed: int, step
     if mask_override is not None:
         server, U, D = mask_override
     else:
-        server, U, D = masks(seed, step, n, p, identity_server)
+        server, U, D = masks(seed, step, n, p, identity_server, external_servers)
     lossy_average(X, offsets, U, D, cols=cols, threads=threads)
     return server, U, D
 

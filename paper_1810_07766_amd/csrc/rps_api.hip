@@ -13,6 +13,8 @@ using rps::RoundTable;
 
 struct rps_ctx {
     int32_t n = 0;
+    int32_t nb = 0;                   // blocks: n, or the number of external servers
+    bool external = false;
     int64_t N = 0;
     double p = 0.0;
     uint64_t threshold = 0;     // a message is lost iff its hash word < threshold = floor(p 2^32)
@@ -65,6 +67,7 @@ RoundParams make_params(const rps_ctx *ctx, const void *X, const void *G, uint64
     RoundParams prm;
     prm.N = ctx->N;
     prm.n = ctx->n;
+    prm.blocks = ctx->nb;
     const int64_t vec = ctx->dtype == RPS_DTYPE_F32 ? 4 : 8;   // elements per 16 bytes
     const bool aligned = ((uintptr_t)X % 16 == 0) && (G == nullptr || (uintptr_t)G % 16 == 0);
     prm.vec_ok = (aligned && ctx->N % vec == 0) ? 1 : 0;
@@ -104,10 +107,14 @@ int timed_launch(rps_ctx *ctx, F launch) {
     return RPS_OK;
 }
 
+int server_mode(const rps_ctx *ctx) {
+    return ctx->external ? 2 : ((ctx->flags & RPS_FLAG_SERVER_IDENTITY) ? 1 : 0);
+}
+
 int enqueue_masks(rps_ctx *ctx, uint64_t step) {
     if (ctx->override_on) return RPS_OK;   // the table already holds the forced outcome
-    RPS_HIP(ctx, rps::launch_masks(ctx->tab, ctx->n, ctx->seed, step, ctx->threshold,
-                                   (ctx->flags & RPS_FLAG_SERVER_IDENTITY) ? 1 : 0, ctx->stream));
+    RPS_HIP(ctx, rps::launch_masks(ctx->tab, ctx->n, ctx->nb, ctx->seed, step, ctx->threshold, server_mode(ctx),
+                                   ctx->stream));
     return RPS_OK;
 }
 
@@ -127,11 +134,12 @@ struct DeviceGuard {   // make the context's device current for the duration of 
 
 extern "C" {
 
-int rps_create(rps_ctx **out, int32_t n, int64_t N, const int64_t *block_offsets, double p, float gamma,
-               uint64_t seed, int32_t dtype, uint32_t flags, void *hip_stream) {
+static int create_impl(rps_ctx **out, int32_t n, int32_t nb, bool external, int64_t N, const int64_t *block_offsets,
+                       double p, float gamma, uint64_t seed, int32_t dtype, uint32_t flags, void *hip_stream) {
     if (!out) return RPS_EINVAL;
     if (n < 1 || n > rps::kMaxWorkers) return RPS_EINVAL;
-    if (N < n || N > (1ll << 34)) return RPS_EINVAL;
+    if (nb < 1 || nb > rps::kMaxWorkers) return RPS_EINVAL;
+    if (N < nb || N > (1ll << 34)) return RPS_EINVAL;
     if (!(p >= 0.0 && p <= 1.0)) return RPS_EINVAL;   // also rejects NaN
     if (!std::isfinite(gamma)) return RPS_EINVAL;
     if (dtype != RPS_DTYPE_F32 && dtype != RPS_DTYPE_BF16) return RPS_EINVAL;
@@ -139,26 +147,28 @@ int rps_create(rps_ctx **out, int32_t n, int64_t N, const int64_t *block_offsets
 
     rps_ctx *ctx = new (std::nothrow) rps_ctx;
     if (!ctx) return RPS_ENOMEM;
-    ctx->off.resize((size_t)n + 1);
+    ctx->off.resize((size_t)nb + 1);
     if (block_offsets) {
-        for (int j = 0; j <= n; ++j) ctx->off[j] = block_offsets[j];
-        bool ok = ctx->off[0] == 0 && ctx->off[n] == N;
-        for (int j = 0; j < n && ok; ++j) ok = ctx->off[j] < ctx->off[j + 1];
+        for (int j = 0; j <= nb; ++j) ctx->off[j] = block_offsets[j];
+        bool ok = ctx->off[0] == 0 && ctx->off[nb] == N;
+        for (int j = 0; j < nb && ok; ++j) ok = ctx->off[j] < ctx->off[j + 1];
         if (!ok) {
             delete ctx;
             return RPS_EINVAL;
         }
     } else {
-        if (N % n != 0) {   // the paper's blocks are equally sized
+        if (N % nb != 0) {   // the paper's blocks are equally sized
             delete ctx;
             return RPS_EINVAL;
         }
-        for (int j = 0; j <= n; ++j) ctx->off[j] = (N / n) * j;
+        for (int j = 0; j <= nb; ++j) ctx->off[j] = (N / nb) * j;
     }
-    for (int j = 0; j < n; ++j)
+    for (int j = 0; j < nb; ++j)
         if (ctx->off[j + 1] - ctx->off[j] > ctx->max_block_cols) ctx->max_block_cols = ctx->off[j + 1] - ctx->off[j];
 
     ctx->n = n;
+    ctx->nb = nb;
+    ctx->external = external;
     ctx->N = N;
     ctx->p = p;
     ctx->threshold = (uint64_t)std::floor(p * 4294967296.0);
@@ -179,7 +189,7 @@ int rps_create(rps_ctx **out, int32_t n, int64_t N, const int64_t *block_offsets
     }
     if (e == hipSuccess) {
         std::memset(ctx->staging, 0, sizeof(RoundTable));
-        for (int j = 0; j <= n; ++j) ctx->staging->off[j] = ctx->off[j];
+        for (int j = 0; j <= nb; ++j) ctx->staging->off[j] = ctx->off[j];
         e = hipMemcpyAsync(ctx->tab, ctx->staging, sizeof(RoundTable), hipMemcpyHostToDevice, ctx->stream);
         if (e == hipSuccess)
             e = hipMemcpyAsync(ctx->tab_query, ctx->staging, sizeof(RoundTable), hipMemcpyHostToDevice, ctx->stream);
@@ -194,6 +204,16 @@ int rps_create(rps_ctx **out, int32_t n, int64_t N, const int64_t *block_offsets
     }
     *out = ctx;
     return RPS_OK;
+}
+
+int rps_create(rps_ctx **out, int32_t n, int64_t N, const int64_t *block_offsets, double p, float gamma,
+               uint64_t seed, int32_t dtype, uint32_t flags, void *hip_stream) {
+    return create_impl(out, n, n, false, N, block_offsets, p, gamma, seed, dtype, flags, hip_stream);
+}
+
+int rps_create_external(rps_ctx **out, int32_t n, int32_t servers, int64_t N, const int64_t *block_offsets, double p,
+                        float gamma, uint64_t seed, int32_t dtype, void *hip_stream) {
+    return create_impl(out, n, servers, true, N, block_offsets, p, gamma, seed, dtype, 0u, hip_stream);
 }
 
 int rps_destroy(rps_ctx *ctx) {
@@ -274,18 +294,18 @@ int rps_get_masks(rps_ctx *ctx, uint64_t step, uint8_t *up, uint8_t *down, int32
     if (!ctx || !step_ok(step)) return RPS_EINVAL;
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return RPS_EHIP;
-    RPS_HIP(ctx, rps::launch_masks(ctx->tab_query, ctx->n, ctx->seed, step, ctx->threshold,
-                                   (ctx->flags & RPS_FLAG_SERVER_IDENTITY) ? 1 : 0, ctx->stream));
+    RPS_HIP(ctx, rps::launch_masks(ctx->tab_query, ctx->n, ctx->nb, ctx->seed, step, ctx->threshold, server_mode(ctx),
+                                   ctx->stream));
     RPS_HIP(ctx, hipMemcpyAsync(ctx->staging, ctx->tab_query, sizeof(RoundTable), hipMemcpyDeviceToHost, ctx->stream));
     RPS_HIP(ctx, hipStreamSynchronize(ctx->stream));
-    const int n = ctx->n;
+    const int n = ctx->n, nb = ctx->nb;
     for (int i = 0; i < n; ++i)
-        for (int j = 0; j < n; ++j) {
-            if (up) up[i * n + j] = (uint8_t)((ctx->staging->ucol[j] >> i) & 1);
-            if (down) down[i * n + j] = (uint8_t)((ctx->staging->dcol[j] >> i) & 1);
+        for (int j = 0; j < nb; ++j) {
+            if (up) up[i * nb + j] = (uint8_t)((ctx->staging->ucol[j] >> i) & 1);
+            if (down) down[i * nb + j] = (uint8_t)((ctx->staging->dcol_drawn[j] >> i) & 1);
         }
     if (server)
-        for (int j = 0; j < n; ++j) server[j] = ctx->staging->server[j];
+        for (int j = 0; j < nb; ++j) server[j] = ctx->staging->server[j];
     return RPS_OK;
 }
 
@@ -299,23 +319,24 @@ int rps_set_mask_override(rps_ctx *ctx, const uint8_t *up, const uint8_t *down, 
         return RPS_OK;
     }
     if (!up || !down || !server) return RPS_EINVAL;
-    const int n = ctx->n;
+    const int n = ctx->n, nb = ctx->nb;
     RoundTable t;
     std::memset(&t, 0, sizeof(t));
-    for (int j = 0; j <= n; ++j) t.off[j] = ctx->off[j];
-    for (int j = 0; j < n; ++j) {
-        if (server[j] < 0 || server[j] >= n) return RPS_EINVAL;
+    for (int j = 0; j <= nb; ++j) t.off[j] = ctx->off[j];
+    for (int j = 0; j < nb; ++j) {
+        if (!ctx->external && (server[j] < 0 || server[j] >= n)) return RPS_EINVAL;
         uint64_t u = 0, d = 0;
         for (int i = 0; i < n; ++i) {
-            if (up[i * n + j]) u |= 1ull << i;
-            if (down[i * n + j]) d |= 1ull << i;
+            if (up[i * nb + j]) u |= 1ull << i;
+            if (down[i * nb + j]) d |= 1ull << i;
         }
-        if (u == 0) return RPS_EINVAL;   // a server always holds its own copy
+        if (u == 0 && !ctx->external) return RPS_EINVAL;   // a worker-server always holds its own copy
         t.ucol[j] = u;
-        t.dcol[j] = d;
+        t.dcol_drawn[j] = d;
+        t.dcol[j] = u ? d : 0;
         t.cnt[j] = __builtin_popcountll(u);
-        t.inv_cnt[j] = 1.0 / (double)t.cnt[j];
-        t.server[j] = server[j];
+        t.inv_cnt[j] = u ? 1.0 / (double)t.cnt[j] : 0.0;
+        t.server[j] = ctx->external ? -1 : server[j];
     }
     RPS_HIP(ctx, hipStreamSynchronize(ctx->stream));   // staging may still be in flight
     *ctx->staging = t;

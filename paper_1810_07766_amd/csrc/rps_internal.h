@@ -14,7 +14,8 @@ constexpr int kMaxWorkers = 64;          // one 64-bit lane mask per block and d
 // round kernels through wave-uniform (scalar) loads.
 struct RoundTable {
     uint64_t ucol[kMaxWorkers];     // bit i of ucol[j]: worker i's copy of block j reached server[j]
-    uint64_t dcol[kMaxWorkers];     // bit i of dcol[j]: server[j]'s reply reached worker i
+    uint64_t dcol[kMaxWorkers];     // bit i of dcol[j]: server[j]'s reply reached worker i (0 if it had nothing to send)
+    uint64_t dcol_drawn[kMaxWorkers];   // the downlink bits as drawn (what rps_get_masks reports)
     double inv_cnt[kMaxWorkers];    // 1 / popcount(ucol[j])
     int64_t off[kMaxWorkers + 1];   // block j = columns [off[j], off[j+1])
     int32_t cnt[kMaxWorkers];       // popcount(ucol[j]) >= 1
@@ -24,6 +25,7 @@ struct RoundTable {
 struct RoundParams {
     int64_t N;            // row pitch in elements
     int32_t n;            // workers
+    int32_t blocks;       // blocks (= n unless the servers are external)
     int32_t vec_ok;       // 1: every full 8-column group may use 128-bit accesses
     float gamma;
     float sigma;          // synthetic gradient: noise std
@@ -44,8 +46,10 @@ struct LaunchTuning {
 };
 
 // Launchers (rps_kernels.hip).  All enqueue on `stream` and return the launch status.
-hipError_t launch_masks(RoundTable *tab, int n, uint64_t seed, uint64_t step, uint64_t threshold,
-                        int identity_server, hipStream_t stream);
+// server_mode: 0 = per-round random permutation of the workers, 1 = worker j serves block j,
+// 2 = external servers (no reliable self link; blocks may differ from n)
+hipError_t launch_masks(RoundTable *tab, int n, int blocks, uint64_t seed, uint64_t step, uint64_t threshold,
+                        int server_mode, hipStream_t stream);
 hipError_t launch_round(int dtype, int grad_mode, void *X, const void *G, const RoundTable *tab,
                         const RoundParams &prm, int64_t max_block_cols, const LaunchTuning &tune, hipStream_t stream);
 hipError_t launch_local_step(int dtype, int grad_mode, void *X, const void *G,

@@ -55,13 +55,14 @@ constexpr int kNoiseRounds = 7;   // gradient noise: the smallest count its auth
 // ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(64) void masks_kernel(RoundTable *__restrict__ tab, int n, uint32_t seed_lo,
                                                    uint32_t seed_hi, uint32_t step_lo, uint32_t step_hi24,
-                                                   uint64_t threshold, int identity_server) {
+                                                   uint64_t threshold, int server_mode) {
     const int j = blockIdx.x;
     const int i = threadIdx.x;
     const bool active = i < n;
 
-    int s = j;
-    if (!identity_server) {
+    // external parameter servers (the paper's Fig. 1) are not workers: no lane is the server
+    int s = server_mode == 2 ? -1 : j;
+    if (server_mode == 0) {
         uint32_t c[4] = {(uint32_t)i, 0u, step_lo, kDomainServer | step_hi24};
         philox4x32<kMaskRounds>(c, seed_lo, seed_hi);
         const uint32_t key = c[0];
@@ -86,9 +87,11 @@ __global__ __launch_bounds__(64) void masks_kernel(RoundTable *__restrict__ tab,
     if (i == 0) {
         const int cnt = __popcll(ucol);
         tab->ucol[j] = ucol;
-        tab->dcol[j] = dcol;
+        tab->dcol_drawn[j] = dcol;
+        // an external server that received nothing has nothing to send: nobody overwrites
+        tab->dcol[j] = cnt > 0 ? dcol : 0;
         tab->cnt[j] = cnt;
-        tab->inv_cnt[j] = 1.0 / (double)cnt;
+        tab->inv_cnt[j] = cnt > 0 ? 1.0 / (double)cnt : 0.0;
         tab->server[j] = s;
     }
 }
@@ -504,7 +507,7 @@ hipError_t launch_round_v(ST *X, const ST *G, const RoundTable *tab, const Round
     constexpr int TILE = 64 * Storage<ST>::VEC;
     // a block that starts off a vector boundary may need one extra tile
     const int64_t tiles = (max_block_cols + Storage<ST>::VEC - 1 + TILE - 1) / TILE;
-    const dim3 grid((unsigned)((tiles + WPB - 1) / WPB), (unsigned)prm.n, 1);
+    const dim3 grid((unsigned)((tiles + WPB - 1) / WPB), (unsigned)prm.blocks, 1);
     size_t lds = 0;
     if (max_waves_per_cu > 0 && max_waves_per_cu < 32) {
         int wgs = max_waves_per_cu / WPB;
@@ -766,11 +769,11 @@ __global__ __launch_bounds__(256) void consensus_final_kernel(const double *__re
 
 }  // namespace
 
-hipError_t launch_masks(RoundTable *tab, int n, uint64_t seed, uint64_t step, uint64_t threshold,
-                        int identity_server, hipStream_t stream) {
-    hipLaunchKernelGGL(masks_kernel, dim3((unsigned)n), dim3(64), 0, stream, tab, n, (uint32_t)seed,
+hipError_t launch_masks(RoundTable *tab, int n, int blocks, uint64_t seed, uint64_t step, uint64_t threshold,
+                        int server_mode, hipStream_t stream) {
+    hipLaunchKernelGGL(masks_kernel, dim3((unsigned)blocks), dim3(64), 0, stream, tab, n, (uint32_t)seed,
                        (uint32_t)(seed >> 32), (uint32_t)step, (uint32_t)((step >> 32) & 0xFFFFFFu), threshold,
-                       identity_server);
+                       server_mode);
     return hipGetLastError();
 }
 
@@ -793,7 +796,7 @@ hipError_t launch_gradavg(int dtype, void *X, const void *G, const RoundTable *t
     const int vec = dtype == 0 ? 4 : 8;
     const int64_t tile = 64 * vec;
     const int64_t tiles = (max_block_cols + vec - 1 + tile - 1) / tile;
-    const dim3 grid((unsigned)((tiles + 3) / 4), (unsigned)prm.n, 1);
+    const dim3 grid((unsigned)((tiles + 3) / 4), (unsigned)prm.blocks, 1);
     size_t lds = 0;
     if (max_waves_per_cu > 0 && max_waves_per_cu < 32) {
         int wgs = max_waves_per_cu / 4;

@@ -24,6 +24,9 @@ _ctx_p = ctypes.c_void_p
 _lib.rps_create.argtypes = [ctypes.POINTER(_ctx_p), ctypes.c_int32, ctypes.c_int64,
                             ctypes.POINTER(ctypes.c_int64), ctypes.c_double, ctypes.c_float,
                             ctypes.c_uint64, ctypes.c_int32, ctypes.c_uint32, ctypes.c_void_p]
+_lib.rps_create_external.argtypes = [ctypes.POINTER(_ctx_p), ctypes.c_int32, ctypes.c_int32, ctypes.c_int64,
+                                     ctypes.POINTER(ctypes.c_int64), ctypes.c_double, ctypes.c_float,
+                                     ctypes.c_uint64, ctypes.c_int32, ctypes.c_void_p]
 _lib.rps_destroy.argtypes = [_ctx_p]
 _lib.rps_set_synthetic_grad.argtypes = [_ctx_p, ctypes.c_float, ctypes.c_float]
 _lib.rps_set_gamma.argtypes = [_ctx_p, ctypes.c_float]
@@ -40,12 +43,12 @@ _lib.rps_get_kernel_time.argtypes = [_ctx_p, ctypes.POINTER(ctypes.c_double), ct
 _lib.rps_last_hip_error.argtypes = [_ctx_p]
 _lib.rps_strerror.argtypes = [ctypes.c_int]
 _lib.rps_strerror.restype = ctypes.c_char_p
-for _name in ("rps_create", "rps_destroy", "rps_set_synthetic_grad", "rps_set_gamma", "rps_local_step",
+for _name in ("rps_create", "rps_create_external", "rps_destroy", "rps_set_synthetic_grad", "rps_set_gamma", "rps_local_step",
               "rps_lossy_average", "rps_round", "rps_round_gradient_averaging", "rps_get_masks", "rps_set_mask_override",
               "rps_consensus", "rps_set_launch_tuning", "rps_set_profiling", "rps_get_kernel_time", "rps_last_hip_error"):
     getattr(_lib, _name).restype = ctypes.c_int
 
-EXPORTS = ("rps_create", "rps_destroy", "rps_set_synthetic_grad", "rps_set_gamma", "rps_local_step",
+EXPORTS = ("rps_create", "rps_create_external", "rps_destroy", "rps_set_synthetic_grad", "rps_set_gamma", "rps_local_step",
            "rps_lossy_average", "rps_round", "rps_round_gradient_averaging", "rps_get_masks", "rps_set_mask_override",
            "rps_consensus", "rps_set_launch_tuning", "rps_set_profiling", "rps_get_kernel_time",
            "rps_last_hip_error",
@@ -82,21 +85,27 @@ def _ptr(t, ctx):
 class RpsContext:
     """Owns one rps_ctx handle.  Methods mirror the C entry points one to one."""
 
-    def __init__(self, n, N, p, gamma, seed, dtype=RPS_DTYPE_F32, block_offsets=None, flags=0, stream=None):
+    def __init__(self, n, N, p, gamma, seed, dtype=RPS_DTYPE_F32, block_offsets=None, flags=0, stream=None,
+                 external_servers=0):
         import torch
         if stream is None:
             stream = torch.cuda.current_stream().cuda_stream
+        nb = external_servers if external_servers else n
         off = None
         if block_offsets is not None:
             vals = [int(v) for v in block_offsets]
-            if len(vals) != n + 1:
+            if len(vals) != nb + 1:
                 raise RpsError(RPS_EINVAL)
-            off = (ctypes.c_int64 * (n + 1))(*vals)
+            off = (ctypes.c_int64 * (nb + 1))(*vals)
         handle = _ctx_p()
-        _check(_lib.rps_create(ctypes.byref(handle), n, N, off, p, gamma, seed, dtype, flags,
-                               ctypes.c_void_p(stream)))
+        if external_servers:
+            _check(_lib.rps_create_external(ctypes.byref(handle), n, external_servers, N, off, p, gamma, seed, dtype,
+                                            ctypes.c_void_p(stream)))
+        else:
+            _check(_lib.rps_create(ctypes.byref(handle), n, N, off, p, gamma, seed, dtype, flags,
+                                   ctypes.c_void_p(stream)))
         self._h = handle
-        self.n, self.N, self.dtype = n, N, dtype
+        self.n, self.N, self.dtype, self.blocks = n, N, dtype, nb
 
     def destroy(self):
         if getattr(self, "_h", None) and _lib is not None:   # (_lib is None at interpreter shutdown)
@@ -127,10 +136,10 @@ class RpsContext:
 
     def get_masks(self, step):
         import numpy as np
-        n = self.n
-        up = np.empty((n, n), dtype=np.uint8)
-        down = np.empty((n, n), dtype=np.uint8)
-        server = np.empty(n, dtype=np.int32)
+        n, nb = self.n, self.blocks
+        up = np.empty((n, nb), dtype=np.uint8)
+        down = np.empty((n, nb), dtype=np.uint8)
+        server = np.empty(nb, dtype=np.int32)
         _check(_lib.rps_get_masks(self._h, step, up.ctypes.data, down.ctypes.data, server.ctypes.data), self._h)
         return server, up, down
 
@@ -142,7 +151,7 @@ class RpsContext:
         up = np.ascontiguousarray(up, dtype=np.uint8)
         down = np.ascontiguousarray(down, dtype=np.uint8)
         server = np.ascontiguousarray(server, dtype=np.int32)
-        if up.shape != (self.n, self.n) or down.shape != (self.n, self.n) or server.shape != (self.n,):
+        if up.shape != (self.n, self.blocks) or down.shape != (self.n, self.blocks) or server.shape != (self.blocks,):
             raise RpsError(RPS_EINVAL)
         _check(_lib.rps_set_mask_override(self._h, up.ctypes.data, down.ctypes.data, server.ctypes.data), self._h)
 
@@ -168,6 +177,10 @@ class RpsContext:
 # function-style aliases with the C names
 def rps_create(n, N, block_offsets, p, gamma, seed, dtype=RPS_DTYPE_F32, flags=0, stream=None):
     return RpsContext(n, N, p, gamma, seed, dtype, block_offsets, flags, stream)
+
+
+def rps_create_external(n, servers, N, block_offsets, p, gamma, seed, dtype=RPS_DTYPE_F32, stream=None):
+    return RpsContext(n, N, p, gamma, seed, dtype, block_offsets, 0, stream, external_servers=servers)
 
 
 def rps_destroy(ctx):

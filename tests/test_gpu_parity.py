@@ -311,3 +311,49 @@ def test_gradient_averaging_variant(rps, n, N, layout, dtype):
     with pytest.raises(rps.RpsError):
         ctx.round_gradient_averaging(Xg, None, 3)
     ctx.destroy()
+
+
+@pytest.mark.parametrize("n,m,N,dtype,p", [(4, 3, 3 * 1300, "f32", 0.3), (3, 7, 7 * 600, "f32", 0.7), (16, 5, 5 * 2056, "f32", 0.1),
+                                           (64, 64, 64 * 520, "bf16", 0.2), (5, 2, 2 * 4099, "bf16", 0.6), (2, 1, 1500, "f32", 0.8)])
+def test_external_parameter_servers(rps, n, m, N, dtype, p):
+    """m external servers, n workers (the paper's Fig. 1 setting): no reliable self link, a server
+    that received nothing sends nothing.  Masks bit-exact, rounds against the oracle (high p makes
+    empty servers frequent)."""
+    off = workloads.block_offsets(m, N)
+    gamma, sigma, lam, seed = 0.1, 0.1, 1e-2, 31
+    ctx = rps.RpsContext(n, N, p, gamma, seed, _dt(rps, dtype), block_offsets=off, external_servers=m)
+    ctx.set_synthetic_grad(sigma, lam)
+    Xg = device_tensor(workloads.gaussian_model(n, N, seed=8, scale=0.05), dtype)
+    Xo = to_oracle(Xg)
+    empties = 0
+    for step in range(6):
+        s_g, u_g, d_g = ctx.get_masks(step)
+        s_o, u_o, d_o = oracle.masks(seed, step, n, p, external_servers=m)
+        assert (s_g == s_o).all() and (u_g == u_o).all() and (d_g == d_o).all()
+        empties += int((u_o.sum(axis=0) == 0).sum())
+        ctx.round(Xg, None, step)
+        oracle.round_(Xo, None, off, p=p, gamma=gamma, seed=seed, step=step, sigma=sigma, weight_decay=lam,
+                      external_servers=m)
+        torch.cuda.synchronize()
+        assert_close(to_oracle(Xg), Xo, off, dtype, what=f"step {step}")
+    # the gradient-averaging variant and the unfused average take the same masks
+    Gg = device_tensor(workloads.gaussian_model(n, N, seed=9), dtype)
+    ctx.round_gradient_averaging(Xg, Gg, 6)
+    oracle.round_gradient_averaging(Xo, to_oracle(Gg), off, p=p, gamma=gamma, seed=seed, step=6,
+                                    mask_override=oracle.masks(seed, 6, n, p, external_servers=m))
+    ctx.lossy_average(Xg, 7)
+    s7, u7, d7 = oracle.masks(seed, 7, n, p, external_servers=m)
+    oracle.lossy_average(Xo, off, u7, d7)
+    torch.cuda.synchronize()
+    assert_close(to_oracle(Xg), Xo, off, dtype, what="gradavg + average")
+    # forcing an empty server through the override: nothing in that block may change
+    U = np.ones((n, m), dtype=np.uint8); D = np.ones((n, m), dtype=np.uint8); U[:, 0] = 0
+    ctx.set_mask_override(np.full(m, -1, dtype=np.int32), U, D)
+    before = Xg.clone()
+    ctx.lossy_average(Xg, 8); torch.cuda.synchronize()
+    assert torch.equal(Xg[:, : int(off[1])], before[:, : int(off[1])])
+    if m > 1:
+        assert (Xg[:, int(off[1]):] == Xg[0:1, int(off[1]):]).all()     # the other blocks: exact averaging
+    ctx.destroy()
+    if p >= 0.6:
+        assert empties > 0

@@ -252,3 +252,35 @@ def test_consensus_distance_definition_and_contraction():
                 expect += prob * oracle.consensus(Y)[0]
     beta = alpha1_exact(n, p) - alpha2_exact(n, p)
     assert abs(expect - beta * d0) < 1e-5 * d0
+
+
+@pytest.mark.parametrize("n,p", [(2, 0.3), (3, 0.2), (4, 0.5)])
+def test_external_servers_expected_mixing(n, p):
+    """Parameter servers that are not workers (the paper's Fig. 1: three servers, four workers; its
+    footnote: the analysis extends to any numbers).  No link is reliable.  Enumerating all 4^n
+    outcomes of one block: W is column-stochastic, and by exchangeability E[W] = a I + (1-a) A_n.
+    By hand (q = 1-p): worker k keeps its own block if its reply is lost (p) or the server got
+    nothing (q p^n); otherwise its column is U/|N|, and E[U_k/|N| ; |N|>0] = (1 - p^n)/n by
+    symmetry.  So E[W_kk] = p + q p^n + q (1 - p^n)/n and E[W_mk] = q (1 - p^n)/n for m != k."""
+    q = 1 - p
+    off = np.array([0, n], dtype=np.int64)                      # one block of n columns, one server
+    eye = np.eye(n, dtype=np.float32)
+    EW = np.zeros((n, n)); tot = 0.0
+    for up in itertools.product((0, 1), repeat=n):
+        for dn in itertools.product((0, 1), repeat=n):
+            U = np.array(up, dtype=np.uint8).reshape(n, 1); D = np.array(dn, dtype=np.uint8).reshape(n, 1)
+            prob = np.prod([q if b else p for b in up + dn])
+            X = eye.copy()
+            oracle.lossy_average(X, off, U, D)
+            W = X.astype(np.float64).T
+            assert np.allclose(W.sum(axis=0), 1.0, atol=1e-6)   # column-stochastic, also when empty
+            assert np.abs(W - oracle.build_W(0, U, D)).max() < 1e-6
+            if sum(up) == 0:
+                assert (X == eye).all()                         # server got nothing: nobody changes
+            EW += prob * W; tot += prob
+    assert abs(tot - 1) < 1e-12
+    off_diag = q * (1 - p ** n) / n
+    diag = p + q * p ** n + off_diag
+    assert np.abs(np.diag(EW) - diag).max() < 1e-6
+    assert np.abs(EW - np.diag(np.diag(EW)) - off_diag * (1 - np.eye(n))).max() < 1e-6
+    assert np.allclose(EW.sum(axis=1), 1.0, atol=1e-6)          # mean preserved in expectation

@@ -117,6 +117,23 @@ def test_masks_change_with_seed_and_step():
     assert not (a[1] == e[1]).all()
 
 
+def test_external_server_masks():
+    """n workers, nb != n external servers: same hash layout, nothing forced, server = -1."""
+    n, nb, p, seed = 4, 3, 0.3, 11
+    T = int(np.floor(p * 2.0 ** 32))
+    drops = total = 0
+    for step in range(400):
+        server, U, D = oracle.masks(seed, step, n, p, external_servers=nb)
+        assert U.shape == (n, nb) and D.shape == (n, nb) and (server == -1).all()
+        if step < 5:
+            for i in range(n):
+                for j in range(nb):
+                    assert U[i, j] == (0 if _word0(seed, step, i, j, 0) < T else 1)
+                    assert D[i, j] == (0 if _word0(seed, step, i, j, 1) < T else 1)
+        drops += (U == 0).sum() + (D == 0).sum(); total += 2 * n * nb
+    assert abs(drops / total - p) < 5 * np.sqrt(p * (1 - p) / total)
+
+
 # ---------------------------------------------------------------------------------------------
 # Gaussian noise
 # ---------------------------------------------------------------------------------------------
