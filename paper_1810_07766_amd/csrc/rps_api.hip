@@ -58,9 +58,9 @@ bool step_ok(uint64_t step) { return step < (1ull << 56); }
 // occupancy cap at n = 16 / 32 fp32 and n = 64 bf16).  The in-place update mixes n read streams
 // with n write streams; the memory system handles that best with few wavefronts resident.
 rps::LaunchTuning default_tuning(int32_t n, int32_t dtype) {
-    if (dtype == RPS_DTYPE_BF16) return rps::LaunchTuning{2, 4, 12};
+    if (dtype == RPS_DTYPE_BF16) return rps::LaunchTuning{2, 1, 0};   // close to ALU-bound: full occupancy
     if (n >= 24) return rps::LaunchTuning{4, 1, 6};
-    return rps::LaunchTuning{2, 4, 8};
+    return rps::LaunchTuning{4, 1, 8};
 }
 
 RoundParams make_params(const rps_ctx *ctx, const void *X, const void *G, uint64_t step) {

@@ -289,9 +289,10 @@ __device__ __forceinline__ void sgd_step(const RoundParams &prm, const float *g_
 
 // ---------------------------------------------------------------------------------------
 // Fused round.  grid = (ceil(tiles of the largest block / WPB), n blocks); a workgroup is WPB
-// independent wavefronts, each owning one tile of 64 x VEC columns of block j (tiles start at
-// the block start rounded down to a vector boundary, so lanes coincide with 16-byte segments
-// and noise quads).  The wavefront walks the n rows of its tile:
+// independent wavefronts, each owning one tile of 64 x VEC columns of block j (tiles sit on
+// absolute multiples of the tile width, so every wavefront access is one aligned 1 KB segment
+// whatever the block offsets are, and lanes coincide with 16-byte segments and noise quads;
+// the first and last tile of a block may be partial).  The wavefront walks the n rows of its tile:
 //   pass 1  read x[i, tile], form v (Alg. 1 step 5); if worker i's copy reached the server
 //           (uplink bit) add it to the fp64 column sums; if the reply will not reach worker i
 //           (downlink bit clear) its final value is v: store it now
@@ -444,14 +445,14 @@ __global__ __launch_bounds__(WPB * 64) void round_kernel(ST *__restrict__ X, con
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int j = blockIdx.y;
     const int64_t lo = tab->off[j], hi = tab->off[j + 1];
-    const int64_t tile0 = (lo & ~(int64_t)(VEC - 1)) + ((int64_t)blockIdx.x * WPB + wave) * TILE;
+    const int64_t tile0 = (lo / TILE) * TILE + ((int64_t)blockIdx.x * WPB + wave) * TILE;
     if (tile0 >= hi) return;   // wave-uniform: this block has fewer tiles than the largest one
     const uint64_t ucol = tab->ucol[j], dcol = tab->dcol[j];
     const double inv = tab->inv_cnt[j];
 
     LaneCols lc;
     lc.tile0 = tile0;
-    lc.loff = (uint32_t)lane * VEC;   // c0 + VEC > lo always holds
+    lc.loff = (uint32_t)lane * VEC;
     lc.lo = lo;
     lc.hi = hi;
     if (prm.vec_ok && tile0 >= lo && tile0 + TILE <= hi)   // wave-uniform
@@ -514,8 +515,8 @@ template <typename ST, int GRAD, int R, int WPB>
 hipError_t launch_round_v(ST *X, const ST *G, const RoundTable *tab, const RoundParams &prm, int64_t max_block_cols,
                           int max_waves_per_cu, hipStream_t stream) {
     constexpr int TILE = 64 * Storage<ST>::VEC;
-    // a block that starts off a vector boundary may need one extra tile
-    const int64_t tiles = (max_block_cols + Storage<ST>::VEC - 1 + TILE - 1) / TILE;
+    // tiles sit on absolute multiples of TILE columns: a block may overhang one tile on each side
+    const int64_t tiles = (max_block_cols + 2 * TILE - 2) / TILE;
     const dim3 grid((unsigned)((tiles + WPB - 1) / WPB), (unsigned)prm.blocks, 1);
     size_t lds = 0;
     if (max_waves_per_cu > 0 && max_waves_per_cu < 32) {
@@ -642,7 +643,7 @@ __global__ __launch_bounds__(256) void gradavg_kernel(ST *__restrict__ X, const 
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int j = blockIdx.y;
     const int64_t lo = tab->off[j], hi = tab->off[j + 1];
-    const int64_t tile0 = (lo & ~(int64_t)(VEC - 1)) + ((int64_t)blockIdx.x * 4 + wave) * TILE;
+    const int64_t tile0 = (lo / TILE) * TILE + ((int64_t)blockIdx.x * 4 + wave) * TILE;
     if (tile0 >= hi) return;   // wave-uniform
     LaneCols lc;
     lc.tile0 = tile0;
@@ -804,7 +805,7 @@ hipError_t launch_gradavg(int dtype, void *X, const void *G, const RoundTable *t
                           int64_t max_block_cols, int max_waves_per_cu, hipStream_t stream) {
     const int vec = dtype == 0 ? 4 : 8;
     const int64_t tile = 64 * vec;
-    const int64_t tiles = (max_block_cols + vec - 1 + tile - 1) / tile;
+    const int64_t tiles = (max_block_cols + 2 * tile - 2) / tile;
     const dim3 grid((unsigned)((tiles + 3) / 4), (unsigned)prm.blocks, 1);
     size_t lds = 0;
     if (max_waves_per_cu > 0 && max_waves_per_cu < 32) {
