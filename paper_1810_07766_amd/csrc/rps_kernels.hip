@@ -179,6 +179,8 @@ struct Storage<float> {
         const Raw a = {x[0], x[1], x[2], x[3]};
         return a;
     }
+    // round x to storage in place and return it packed (fp32: nothing to round)
+    static __device__ __forceinline__ Raw round_vec(float x[VEC]) { return pack(x); }
     static __device__ __forceinline__ float load1(const float *p) { return *p; }
     static __device__ __forceinline__ void store1(float *p, float v) { *p = v; }
 };
@@ -201,6 +203,23 @@ struct Storage<uint16_t> {
         a.y = (__float_as_uint(x[2]) >> 16) | (__float_as_uint(x[3]) & 0xFFFF0000u);
         a.z = (__float_as_uint(x[4]) >> 16) | (__float_as_uint(x[5]) & 0xFFFF0000u);
         a.w = (__float_as_uint(x[6]) >> 16) | (__float_as_uint(x[7]) & 0xFFFF0000u);
+        return a;
+    }
+    // round x to bf16 (nearest even) in place and return the packed bits: one hardware
+    // conversion (v_cvt_pk_bf16_f32) per pair of values, then re-widened for the fp64 sums
+    static __device__ __forceinline__ Raw round_vec(float x[VEC]) {
+        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+        typedef float f32x2 __attribute__((ext_vector_type(2)));
+        uint32_t w[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const f32x2 v = {x[2 * k], x[2 * k + 1]};
+            const bf16x2 r = __builtin_convertvector(v, bf16x2);
+            __builtin_memcpy(&w[k], &r, 4);
+            x[2 * k] = __uint_as_float(w[k] << 16);
+            x[2 * k + 1] = __uint_as_float(w[k] & 0xFFFF0000u);
+        }
+        const Raw a = {w[0], w[1], w[2], w[3]};
         return a;
     }
     static __device__ __forceinline__ float load1(const uint16_t *p) { return bf16_bits_to_f32(*p); }
@@ -268,23 +287,21 @@ __device__ __forceinline__ void noise_rows(const RoundParams &prm, int pair, int
 }
 
 // v = x - gamma * g, rounded to storage (Alg. 1 step 5); g = the caller's gradient or
-// lambda * x + noise.  x is overwritten by v.
+// lambda * x + noise.  x is overwritten by v; the packed form of v is returned.
 template <typename ST, int GRAD>
-__device__ __forceinline__ void sgd_step(const RoundParams &prm, const float *g_or_z, float x[Storage<ST>::VEC]) {
+__device__ __forceinline__ typename Storage<ST>::Raw sgd_step(const RoundParams &prm, const float *g_or_z,
+                                                              float x[Storage<ST>::VEC]) {
     constexpr int VEC = Storage<ST>::VEC;
-    if (GRAD == kGradBuffer) {
+    if (GRAD == kGradSynthetic && prm.lambda != 0.0f) {   // fma(0, x, z) == z for finite x: skipped without decay
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) x[e] = Storage<ST>::round(__builtin_fmaf(-prm.gamma, g_or_z[e], x[e]));
-    } else if (GRAD == kGradSynthetic) {
-        if (prm.lambda != 0.0f) {   // fma(0, x, z) == z for finite x: skipped when there is no decay
+        for (int e = 0; e < VEC; ++e)
+            x[e] = __builtin_fmaf(-prm.gamma, __builtin_fmaf(prm.lambda, x[e], g_or_z[e]), x[e]);
+    } else if (GRAD != kGradNone) {
 #pragma unroll
-            for (int e = 0; e < VEC; ++e)
-                x[e] = Storage<ST>::round(__builtin_fmaf(-prm.gamma, __builtin_fmaf(prm.lambda, x[e], g_or_z[e]), x[e]));
-        } else {
-#pragma unroll
-            for (int e = 0; e < VEC; ++e) x[e] = Storage<ST>::round(__builtin_fmaf(-prm.gamma, g_or_z[e], x[e]));
-        }
+        for (int e = 0; e < VEC; ++e) x[e] = __builtin_fmaf(-prm.gamma, g_or_z[e], x[e]);
     }
+    if (GRAD == kGradNone) return Storage<ST>::pack(x);   // loaded from storage: already representable
+    return Storage<ST>::round_vec(x);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -353,23 +370,23 @@ __device__ __forceinline__ void process_chunk(ST *__restrict__ Xt, const RoundPa
                     float v[VEC];
                     S::unpack(xr[r], v);
                     if (GRAD == kGradBuffer) S::unpack(gr[GRAD == kGradBuffer ? r : 0], za);
-                    sgd_step<ST, GRAD>(prm, za, v);
+                    const typename S::Raw vr = sgd_step<ST, GRAD>(prm, za, v);
                     if (ua) {
 #pragma unroll
                         for (int e = 0; e < VEC; ++e) acc[e] += (double)v[e];
                     }
-                    if (GRAD != kGradNone && !da) store_raw<ST, FULL>(Xt + (int64_t)ia * prm.N, lc, S::pack(v));
+                    if (GRAD != kGradNone && !da) store_raw<ST, FULL>(Xt + (int64_t)ia * prm.N, lc, vr);
                 }
                 if (need_b) {
                     float v[VEC];
                     S::unpack(xr[r + 1], v);
                     if (GRAD == kGradBuffer) S::unpack(gr[GRAD == kGradBuffer ? r + 1 : 0], zb);
-                    sgd_step<ST, GRAD>(prm, zb, v);
+                    const typename S::Raw vr = sgd_step<ST, GRAD>(prm, zb, v);
                     if (ub) {
 #pragma unroll
                         for (int e = 0; e < VEC; ++e) acc[e] += (double)v[e];
                     }
-                    if (GRAD != kGradNone && !db) store_raw<ST, FULL>(Xt + (int64_t)ib * prm.N, lc, S::pack(v));
+                    if (GRAD != kGradNone && !db) store_raw<ST, FULL>(Xt + (int64_t)ib * prm.N, lc, vr);
                 }
             }
         }
@@ -428,8 +445,8 @@ __device__ __forceinline__ void round_tile(ST *__restrict__ X, const ST *__restr
 
     float vt[VEC];
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) vt[e] = S::round((float)(acc[e] * inv));
-    const Raw vt_raw = S::pack(vt);
+    for (int e = 0; e < VEC; ++e) vt[e] = (float)(acc[e] * inv);
+    const Raw vt_raw = S::round_vec(vt);
     ST *row = Xt;
     for (int i = 0; i < n; ++i, row += prm.N)
         if ((dcol >> i) & 1) store_raw<ST, FULL>(row, lc, vt_raw);
@@ -480,12 +497,8 @@ __device__ __forceinline__ void local_step_pair(ST *__restrict__ X, const ST *__
     } else {
         noise_rows<VEC>(prm, ia >> 1, lc.c0(), ga, gb);
     }
-    sgd_step<ST, GRAD>(prm, ga, xa);
-    store_raw<ST, FULL>(rowa, lc, S::pack(xa));
-    if (has_b) {
-        sgd_step<ST, GRAD>(prm, gb, xb);
-        store_raw<ST, FULL>(rowb, lc, S::pack(xb));
-    }
+    store_raw<ST, FULL>(rowa, lc, sgd_step<ST, GRAD>(prm, ga, xa));
+    if (has_b) store_raw<ST, FULL>(rowb, lc, sgd_step<ST, GRAD>(prm, gb, xb));
 }
 
 template <typename ST, int GRAD>
@@ -603,7 +616,8 @@ __device__ __forceinline__ void gradavg_tile(ST *__restrict__ X, const ST *__res
     }
     float gt[VEC];
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) gt[e] = S::round((float)(acc[e] * inv));
+    for (int e = 0; e < VEC; ++e) gt[e] = (float)(acc[e] * inv);
+    (void)S::round_vec(gt);
 
     ST *xrow = X + lc.tile0;
     for (int i0 = 0; i0 < n; i0 += R) {
@@ -626,8 +640,8 @@ __device__ __forceinline__ void gradavg_tile(ST *__restrict__ X, const ST *__res
                     gsrc = own;
                 }
 #pragma unroll
-                for (int e = 0; e < VEC; ++e) v[e] = S::round(__builtin_fmaf(-prm.gamma, gsrc[e], v[e]));
-                store_raw<ST, FULL>(xrow, lc, S::pack(v));
+                for (int e = 0; e < VEC; ++e) v[e] = __builtin_fmaf(-prm.gamma, gsrc[e], v[e]);
+                store_raw<ST, FULL>(xrow, lc, S::round_vec(v));
                 xrow += prm.N;
             }
         }

@@ -357,3 +357,35 @@ def test_external_parameter_servers(rps, n, m, N, dtype, p):
     ctx.destroy()
     if p >= 0.6:
         assert empties > 0
+
+
+def test_bf16_rounding_edge_cases(rps):
+    """bf16 storage rounds to nearest even on every store (the GPU uses the hardware pair
+    conversion, the oracle a bit trick): ties, carries into the exponent, the smallest normals,
+    subnormals, large magnitudes and signed zeros must give identical bits."""
+    vals = np.array([0.0, -0.0, 1.0, -1.0, 1.5, 1.0 + 2.0 ** -7, -(1.0 + 2.0 ** -7), 255.0, 0.99609375, 3.0e38, -3.0e38,
+                     2.0 ** -126, -(2.0 ** -126), 2.0 ** -130, 2.0 ** -133, 1.0e-20, 65280.0, 0.333251953125], dtype=np.float32)
+    k = vals.size
+    n, N = 2, k * k                                     # every (x, g) pair once per worker, N % 8 != 0 -> pad
+    N8 = (N + 7) // 8 * 8
+    x = np.zeros((n, N8), dtype=np.float32); g = np.zeros((n, N8), dtype=np.float32)
+    x[:, :N] = np.repeat(vals, k)[None, :]; g[:, :N] = np.tile(vals, k)[None, :]
+    for gamma in (2.0 ** -9, 2.0 ** -8, 0.3, 1.0):
+        Xg = device_tensor(x, "bf16"); Gg = device_tensor(g, "bf16")
+        Xo, Go = to_oracle(Xg), to_oracle(Gg)
+        ctx = rps.RpsContext(n, N8, 0.5, gamma, 3, rps.RPS_DTYPE_BF16)
+        ctx.local_step(Xg, Gg, 0)
+        oracle.local_step(Xo, Go, gamma)
+        torch.cuda.synchronize()
+        got = to_oracle(Xg)
+        finite = np.isfinite(workloads.from_bf16_bits(Xo))
+        assert (got[finite] == Xo[finite]).all(), f"gamma {gamma}"
+        assert (np.isfinite(workloads.from_bf16_bits(got)) == finite).all()
+        # and through the fused round against the oracle's round (two identical workers: the
+        # average is exact, so this is bitwise too, including the +0 a sum of -0's gives)
+        Xg2 = device_tensor(x, "bf16"); Xo2 = to_oracle(Xg2)
+        ctx.round(Xg2, Gg, 0); torch.cuda.synchronize()
+        oracle.round_(Xo2, Go, workloads.block_offsets(n, N8), p=0.5, gamma=gamma, seed=3, step=0)
+        got2 = to_oracle(Xg2)
+        assert (got2[finite] == Xo2[finite]).all(), f"fused, gamma {gamma}"
+        ctx.destroy()
