@@ -163,6 +163,20 @@ int rps_set_mask_override(rps_ctx *ctx, const uint8_t *up, const uint8_t *down, 
 int rps_consensus(rps_ctx *ctx, const void *X, double *distance, double *mean_sq);
 
 /*
+ * Monte-Carlo estimate of the constants alpha1 and alpha2 of the mixing matrix W_t of
+ * X_{t+1} = V_t W_t (Sec. 4.2, eqs. (def_alpha1), (def_alpha2):  E[W W^T] = alpha1 I + (1-alpha1) A_n,
+ * E[W A_n W^T] = alpha2 I + (1-alpha2) A_n;  Fig. 2 plots alpha2 and Fig. 3 beta = alpha1 - alpha2 over
+ * n and p) from the network outcomes the device generates for the `rounds` steps starting at
+ * first_step (every block of every round is one sample of W; no model data is touched):
+ *   alpha1 = (n e1 - 1)/(n - 1),  e1 = mean over samples and rows m of sum_k W_mk^2     (supplement, Lemma 7)
+ *   alpha2 = (e2 - 1)/(n - 1),    e2 = mean over samples and rows m of (sum_k W_mk)^2   (supplement, Lemma 8)
+ *   alpha1, alpha2   HOST doubles (either may be NULL);   1 <= rounds <= 2^24;   n >= 2
+ * Ignores a mask override.  fp64, fixed summation order (deterministic).  Uses the context's
+ * reduction scratch; synchronises the stream.  Errors: RPS_EINVAL, RPS_EHIP.
+ */
+int rps_estimate_mixing(rps_ctx *ctx, uint64_t first_step, int64_t rounds, double *alpha1, double *alpha2);
+
+/*
  * Launch shape of the round kernel, for tuning sweeps; results never depend on it.
  *   rows_in_flight       rows per load chunk (a wavefront keeps two chunks in flight): 2 or 4
  *   waves_per_workgroup  1 or 4 (a workgroup's wavefronts own adjacent tiles)

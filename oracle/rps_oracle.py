@@ -191,3 +191,20 @@ def round_gradient_averaging(X: np.ndarray, G: np.ndarray, offsets, *, p: float,
     lossy_average(Gh, offsets, U, D, cols=cols, threads=threads)
     local_step(X, Gh, gamma, threads=threads)
     return server, U, D
+
+
+def estimate_mixing(seed: int, first_step: int, rounds: int, n: int, p: float, *, identity_server: bool = False,
+                    external_servers: int = 0):
+    """Monte-Carlo (alpha1, alpha2) by the definitions of Sec. 4.2: average W W^T and W A_n W^T over
+    every block's mixing matrix of the outcomes generated for `rounds` steps, then read the constants
+    off the diagonal of  a I + (1 - a) A_n  (mean diagonal entry = a + (1 - a)/n)."""
+    A = np.full((n, n), 1.0 / n)
+    WW = np.zeros((n, n)); WAW = np.zeros((n, n)); samples = 0
+    for t in range(first_step, first_step + rounds):
+        _, U, D = masks(seed, t, n, p, identity_server, external_servers)
+        for j in range(U.shape[1]):
+            W = build_W(j, U, D)
+            WW += W @ W.T; WAW += W @ A @ W.T; samples += 1
+    a1 = (n * np.trace(WW / samples) / n - 1.0) / (n - 1.0)
+    a2 = (n * np.trace(WAW / samples) / n - 1.0) / (n - 1.0)
+    return float(a1), float(a2)

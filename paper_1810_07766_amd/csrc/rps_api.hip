@@ -3,6 +3,7 @@
 #include "../../include/rps.h"
 #include "rps_internal.h"
 
+#include <algorithm>
 #include <cmath>
 #include <cstring>
 #include <new>
@@ -358,6 +359,30 @@ int rps_consensus(rps_ctx *ctx, const void *X, double *distance, double *mean_sq
     RPS_HIP(ctx, hipStreamSynchronize(ctx->stream));
     if (distance) *distance = host[0];
     if (mean_sq) *mean_sq = host[1];
+    return RPS_OK;
+}
+
+int rps_estimate_mixing(rps_ctx *ctx, uint64_t first_step, int64_t rounds, double *alpha1, double *alpha2) {
+    if (!ctx || rounds < 1 || rounds > (1ll << 24) || ctx->n < 2) return RPS_EINVAL;
+    if (!step_ok(first_step) || !step_ok(first_step + (uint64_t)rounds - 1)) return RPS_EINVAL;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return RPS_EHIP;
+    const int groups = (int)std::min<int64_t>(rounds, rps::kMaxPartials);
+    RPS_HIP(ctx, rps::launch_mixing_moments(ctx->partials, groups, rounds, ctx->n, ctx->nb, ctx->seed, first_step,
+                                            ctx->threshold, server_mode(ctx), ctx->stream));
+    std::vector<double> host(2 * (size_t)groups);
+    RPS_HIP(ctx, hipMemcpyAsync(host.data(), ctx->partials, host.size() * sizeof(double), hipMemcpyDeviceToHost,
+                                ctx->stream));
+    RPS_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    double sq = 0.0, sum_sq = 0.0;
+    for (int w = 0; w < groups; ++w) {
+        sq += host[2 * w];
+        sum_sq += host[2 * w + 1];
+    }
+    // means over rounds, blocks and the n rows of W: E[(W W^T)_mm] and n E[(W A_n W^T)_mm]
+    const double n = (double)ctx->n, samples = (double)rounds * (double)ctx->nb * n;
+    if (alpha1) *alpha1 = (n * (sq / samples) - 1.0) / (n - 1.0);
+    if (alpha2) *alpha2 = (sum_sq / samples - 1.0) / (n - 1.0);
     return RPS_OK;
 }
 

@@ -50,6 +50,11 @@ struct LaunchTuning {
 // 2 = external servers (no reliable self link; blocks may differ from n)
 hipError_t launch_masks(RoundTable *tab, int n, int blocks, uint64_t seed, uint64_t step, uint64_t threshold,
                         int server_mode, hipStream_t stream);
+// Mixing-matrix moments of the outcomes of steps first_step .. first_step+rounds-1: out = device
+// array of 2*workgroups doubles, workgroup w's sums (over its rounds, all blocks, all rows m of W)
+// of sum_k W_mk^2 and of (sum_k W_mk)^2.
+hipError_t launch_mixing_moments(double *out, int workgroups, int64_t rounds, int n, int blocks, uint64_t seed,
+                                 uint64_t first_step, uint64_t threshold, int server_mode, hipStream_t stream);
 hipError_t launch_round(int dtype, int grad_mode, void *X, const void *G, const RoundTable *tab,
                         const RoundParams &prm, int64_t max_block_cols, const LaunchTuning &tune, hipStream_t stream);
 hipError_t launch_local_step(int dtype, int grad_mode, void *X, const void *G,

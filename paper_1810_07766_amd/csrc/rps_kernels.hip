@@ -7,6 +7,8 @@
 // Kernels
 //   masks_kernel      network outcome of one round: server permutation, uplink and downlink
 //                     delivery bits (Sec. 3; Alg. 1 steps 6-7), n workgroups of one wavefront
+//   mixing_moments_kernel  Monte-Carlo sums for the constants alpha1, alpha2 of the mixing matrix
+//                     (Sec. 4.2), one wavefront per simulated round
 //   round_kernel      local SGD step + Reduce-Scatter average + All-Gather write-back in one
 //                     pass; every wavefront owns one tile (64 lanes x 16 bytes) of one block
 //                     and walks all n rows of it, no LDS and no barrier
@@ -53,37 +55,50 @@ constexpr int kNoiseRounds = 7;   // gradient noise: the smallest count its auth
 // worker i.  The permutation is a rank sort of per-worker hash keys: natively parallel,
 // n compare steps through wavefront shuffles.
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(64) void masks_kernel(RoundTable *__restrict__ tab, int n, uint32_t seed_lo,
-                                                   uint32_t seed_hi, uint32_t step_lo, uint32_t step_hi24,
-                                                   uint64_t threshold, int server_mode) {
-    const int j = blockIdx.x;
-    const int i = threadIdx.x;
-    const bool active = i < n;
-
-    // external parameter servers (the paper's Fig. 1) are not workers: no lane is the server
-    int s = server_mode == 2 ? -1 : j;
-    if (server_mode == 0) {
-        uint32_t c[4] = {(uint32_t)i, 0u, step_lo, kDomainServer | step_hi24};
-        philox4x32<kMaskRounds>(c, seed_lo, seed_hi);
-        const uint32_t key = c[0];
-        int rank = 0;
-        for (int k = 0; k < n; ++k) {
-            const uint32_t other = __shfl(key, k, 64);
-            rank += (other < key || (other == key && k < i)) ? 1 : 0;
-        }
-        const uint64_t hit = __ballot(active && rank == j);
-        s = __ffsll((long long)hit) - 1;   // exactly one lane has rank j
+// Server of block j for this lane's round: the worker whose hash key has rank j (lane i = worker i).
+__device__ __forceinline__ int draw_server(int n, int i, int j, uint32_t key) {
+    int rank = 0;
+    for (int k = 0; k < n; ++k) {
+        const uint32_t other = __shfl(key, k, 64);
+        rank += (other < key || (other == key && k < i)) ? 1 : 0;
     }
+    const uint64_t hit = __ballot(i < n && rank == j);
+    return __ffsll((long long)hit) - 1;   // exactly one lane has rank j
+}
 
+__device__ __forceinline__ uint32_t server_key(int i, uint32_t seed_lo, uint32_t seed_hi, uint32_t step_lo,
+                                               uint32_t step_hi24) {
+    uint32_t c[4] = {(uint32_t)i, 0u, step_lo, kDomainServer | step_hi24};
+    philox4x32<kMaskRounds>(c, seed_lo, seed_hi);
+    return c[0];
+}
+
+// Delivery bits of block j (one bit per worker) with server s (-1: external, no reliable link).
+__device__ __forceinline__ void draw_links(int n, int i, int j, int s, uint32_t seed_lo, uint32_t seed_hi,
+                                           uint32_t step_lo, uint32_t step_hi24, uint64_t threshold,
+                                           uint64_t &ucol, uint64_t &dcol) {
+    const bool active = i < n;
     uint32_t cu[4] = {(uint32_t)i, (uint32_t)j, step_lo, kDomainUplink | step_hi24};
     philox4x32<kMaskRounds>(cu, seed_lo, seed_hi);
     uint32_t cd[4] = {(uint32_t)i, (uint32_t)j, step_lo, kDomainDownlink | step_hi24};
     philox4x32<kMaskRounds>(cd, seed_lo, seed_hi);
     // a worker's link to itself is not a network message: forced after the draw
-    const bool up = active && ((uint64_t)cu[0] >= threshold || i == s);
-    const bool down = active && ((uint64_t)cd[0] >= threshold || i == s);
-    const uint64_t ucol = __ballot(up);
-    const uint64_t dcol = __ballot(down);
+    ucol = __ballot(active && ((uint64_t)cu[0] >= threshold || i == s));
+    dcol = __ballot(active && ((uint64_t)cd[0] >= threshold || i == s));
+}
+
+__global__ __launch_bounds__(64) void masks_kernel(RoundTable *__restrict__ tab, int n, uint32_t seed_lo,
+                                                   uint32_t seed_hi, uint32_t step_lo, uint32_t step_hi24,
+                                                   uint64_t threshold, int server_mode) {
+    const int j = blockIdx.x;
+    const int i = threadIdx.x;
+
+    // external parameter servers (the paper's Fig. 1) are not workers: no lane is the server
+    int s = server_mode == 2 ? -1 : j;
+    if (server_mode == 0) s = draw_server(n, i, j, server_key(i, seed_lo, seed_hi, step_lo, step_hi24));
+
+    uint64_t ucol, dcol;
+    draw_links(n, i, j, s, seed_lo, seed_hi, step_lo, step_hi24, threshold, ucol, dcol);
     if (i == 0) {
         const int cnt = __popcll(ucol);
         tab->ucol[j] = ucol;
@@ -93,6 +108,52 @@ __global__ __launch_bounds__(64) void masks_kernel(RoundTable *__restrict__ tab,
         tab->cnt[j] = cnt;
         tab->inv_cnt[j] = cnt > 0 ? 1.0 / (double)cnt : 0.0;
         tab->server[j] = s;
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// Monte-Carlo moments of the mixing matrix W of X_{t+1} = V_t W_t (Sec. 4.2): entry (m,k) of
+// a block's W is the weight of v_m in x'_k, i.e. 1/c if m reached the server and the reply
+// reached k, plus 1 on the diagonal if the reply did not reach k.  Row m therefore has
+//   sum_k W_mk   = U_m d / c + (1 - D_m),      sum_k W_mk^2 = U_m d / c^2 + (1 - D_m)
+// with c copies received and d replies delivered.  Lane m = worker m; workgroup w takes rounds
+// first_step + w, + w + gridDim.x, ... and writes out[2w] = its sum over rounds, blocks and rows
+// of sum_k W_mk^2, out[2w+1] = of (sum_k W_mk)^2.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void mixing_moments_kernel(double *__restrict__ out, int64_t rounds, int n,
+                                                            int blocks, uint32_t seed_lo, uint32_t seed_hi,
+                                                            uint64_t first_step, uint64_t threshold,
+                                                            int server_mode) {
+    const int m = threadIdx.x;
+    double sq = 0.0, sum_sq = 0.0;
+    for (int64_t r = blockIdx.x; r < rounds; r += gridDim.x) {
+        const uint64_t step = first_step + (uint64_t)r;
+        const uint32_t step_lo = (uint32_t)step, step_hi24 = (uint32_t)((step >> 32) & 0xFFFFFFu);
+        const uint32_t key = server_mode == 0 ? server_key(m, seed_lo, seed_hi, step_lo, step_hi24) : 0u;
+        for (int j = 0; j < blocks; ++j) {
+            int s = server_mode == 2 ? -1 : j;
+            if (server_mode == 0) s = draw_server(n, m, j, key);
+            uint64_t ucol, dcol;
+            draw_links(n, m, j, s, seed_lo, seed_hi, step_lo, step_hi24, threshold, ucol, dcol);
+            const int c = __popcll(ucol);
+            if (c == 0) dcol = 0;   // nothing to send: W = I for this block
+            const double d = (double)__popcll(dcol);
+            const double um = (double)((ucol >> m) & 1), keep = 1.0 - (double)((dcol >> m) & 1);
+            const double inv = c > 0 ? 1.0 / (double)c : 0.0;
+            const double row_sum = um * d * inv + keep;
+            if (m < n) {
+                sq += um * d * inv * inv + keep;
+                sum_sq += row_sum * row_sum;
+            }
+        }
+    }
+    for (int o = 32; o > 0; o >>= 1) {
+        sq += __shfl_xor(sq, o, 64);
+        sum_sq += __shfl_xor(sum_sq, o, 64);
+    }
+    if (m == 0) {
+        out[2 * (size_t)blockIdx.x] = sq;
+        out[2 * (size_t)blockIdx.x + 1] = sum_sq;
     }
 }
 
@@ -798,6 +859,13 @@ hipError_t launch_masks(RoundTable *tab, int n, int blocks, uint64_t seed, uint6
     hipLaunchKernelGGL(masks_kernel, dim3((unsigned)blocks), dim3(64), 0, stream, tab, n, (uint32_t)seed,
                        (uint32_t)(seed >> 32), (uint32_t)step, (uint32_t)((step >> 32) & 0xFFFFFFu), threshold,
                        server_mode);
+    return hipGetLastError();
+}
+
+hipError_t launch_mixing_moments(double *out, int workgroups, int64_t rounds, int n, int blocks, uint64_t seed,
+                                 uint64_t first_step, uint64_t threshold, int server_mode, hipStream_t stream) {
+    hipLaunchKernelGGL(mixing_moments_kernel, dim3((unsigned)workgroups), dim3(64), 0, stream, out, rounds, n, blocks,
+                       (uint32_t)seed, (uint32_t)(seed >> 32), first_step, threshold, server_mode);
     return hipGetLastError();
 }
 

@@ -37,6 +37,8 @@ _lib.rps_round_gradient_averaging.argtypes = [_ctx_p, ctypes.c_void_p, ctypes.c_
 _lib.rps_get_masks.argtypes = [_ctx_p, ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
 _lib.rps_set_mask_override.argtypes = [_ctx_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
 _lib.rps_consensus.argtypes = [_ctx_p, ctypes.c_void_p, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
+_lib.rps_estimate_mixing.argtypes = [_ctx_p, ctypes.c_uint64, ctypes.c_int64, ctypes.POINTER(ctypes.c_double),
+                                     ctypes.POINTER(ctypes.c_double)]
 _lib.rps_set_launch_tuning.argtypes = [_ctx_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32]
 _lib.rps_set_profiling.argtypes = [_ctx_p, ctypes.c_int32]
 _lib.rps_get_kernel_time.argtypes = [_ctx_p, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
@@ -45,12 +47,12 @@ _lib.rps_strerror.argtypes = [ctypes.c_int]
 _lib.rps_strerror.restype = ctypes.c_char_p
 for _name in ("rps_create", "rps_create_external", "rps_destroy", "rps_set_synthetic_grad", "rps_set_gamma", "rps_local_step",
               "rps_lossy_average", "rps_round", "rps_round_gradient_averaging", "rps_get_masks", "rps_set_mask_override",
-              "rps_consensus", "rps_set_launch_tuning", "rps_set_profiling", "rps_get_kernel_time", "rps_last_hip_error"):
+              "rps_consensus", "rps_estimate_mixing", "rps_set_launch_tuning", "rps_set_profiling", "rps_get_kernel_time", "rps_last_hip_error"):
     getattr(_lib, _name).restype = ctypes.c_int
 
 EXPORTS = ("rps_create", "rps_create_external", "rps_destroy", "rps_set_synthetic_grad", "rps_set_gamma", "rps_local_step",
            "rps_lossy_average", "rps_round", "rps_round_gradient_averaging", "rps_get_masks", "rps_set_mask_override",
-           "rps_consensus", "rps_set_launch_tuning", "rps_set_profiling", "rps_get_kernel_time",
+           "rps_consensus", "rps_estimate_mixing", "rps_set_launch_tuning", "rps_set_profiling", "rps_get_kernel_time",
            "rps_last_hip_error",
            "rps_strerror")
 
@@ -161,6 +163,12 @@ class RpsContext:
         _check(_lib.rps_consensus(self._h, _ptr(X, self), ctypes.byref(d), ctypes.byref(m)), self._h)
         return d.value, m.value
 
+    def estimate_mixing(self, first_step, rounds):
+        """Monte-Carlo (alpha1, alpha2) of the mixing matrix over the generated outcomes of `rounds` steps."""
+        a1, a2 = ctypes.c_double(), ctypes.c_double()
+        _check(_lib.rps_estimate_mixing(self._h, first_step, rounds, ctypes.byref(a1), ctypes.byref(a2)), self._h)
+        return a1.value, a2.value
+
     def set_launch_tuning(self, rows_in_flight, waves_per_workgroup, max_waves_per_cu=0):
         _check(_lib.rps_set_launch_tuning(self._h, rows_in_flight, waves_per_workgroup, max_waves_per_cu), self._h)
 
@@ -217,6 +225,10 @@ def rps_get_masks(ctx, step):
 
 def rps_consensus(ctx, X):
     return ctx.consensus(X)
+
+
+def rps_estimate_mixing(ctx, first_step, rounds):
+    return ctx.estimate_mixing(first_step, rounds)
 
 
 def rps_set_mask_override(ctx, server=None, up=None, down=None):

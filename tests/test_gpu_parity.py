@@ -293,6 +293,53 @@ def test_consensus_statistics(rps, n, N, dtype):
     ctx.destroy()
 
 
+@pytest.mark.parametrize("n,p,mode,first,rounds", [(4, 0.1, "perm", 0, 300), (3, 0.3, "perm", 5, 2500),
+                                                    (16, 0.05, "perm", (1 << 40) + 3, 120), (7, 0.2, "identity", 9, 200),
+                                                    (64, 0.01, "perm", 0, 40), (5, 0.4, "external3", 2, 400),
+                                                    (2, 0.5, "perm", 0, 1000)])
+def test_mixing_estimator_parity(rps, n, p, mode, first, rounds):
+    """rps_estimate_mixing against the oracle's definition-level estimate (averages of W W^T and
+    W A_n W^T over the same generated outcomes): same samples, so equal up to fp64 summation order.
+    2500 rounds exceed the kernel's workgroup count (rounds are strided over workgroups)."""
+    servers = 3 if mode == "external3" else 0
+    N = 64 * 3 * 5 * 7
+    ctx = rps.RpsContext(n, N, p, 0.1, 4242, rps.RPS_DTYPE_F32, block_offsets=None,
+                         flags=rps.RPS_FLAG_SERVER_IDENTITY if mode == "identity" else 0, external_servers=servers)
+    a1, a2 = ctx.estimate_mixing(first, rounds)
+    r1, r2 = oracle.estimate_mixing(4242, first, rounds, n, p, identity_server=(mode == "identity"),
+                                    external_servers=servers)
+    assert abs(a1 - r1) <= 1e-12 * max(1.0, abs(r1)) and abs(a2 - r2) <= 1e-12 * max(1.0, abs(r2))
+    assert ctx.estimate_mixing(first, rounds) == (a1, a2)
+    ctx.destroy()
+
+
+@pytest.mark.parametrize("n,p", [(16, 0.1), (32, 0.05), (64, 0.01)])
+def test_mixing_estimator_reproduces_the_exact_constants(rps, n, p):
+    """2^17 simulated rounds at the benchmark worker counts against the exact sums of the
+    supplement's Lemmas 7 and 8 (the content of Fig. 2 / Fig. 3 at these n, p): 16 batches give
+    the standard error."""
+    from test_oracle_moments import alpha1_exact, alpha2_exact
+    ctx = rps.RpsContext(n, 64 * n, p, 0.1, 99, rps.RPS_DTYPE_F32)
+    batches = np.array([ctx.estimate_mixing(b << 13, 1 << 13) for b in range(16)])
+    est = batches.mean(axis=0); se = batches.std(axis=0, ddof=1) / 4.0
+    assert abs(est[0] - alpha1_exact(n, p)) < 5 * se[0] and se[0] < 0.01 * est[0]
+    assert abs(est[1] - alpha2_exact(n, p)) < 5 * se[1] and se[1] < 0.01 * est[1]
+    assert 0 < est[1] < est[0] < 1
+    ctx.destroy()
+
+
+def test_mixing_estimator_argument_errors(rps):
+    ctx = rps.RpsContext(1, 64, 0.1, 0.1, 0, rps.RPS_DTYPE_F32)
+    with pytest.raises(rps.RpsError):
+        ctx.estimate_mixing(0, 10)             # alpha is undefined for a single worker
+    ctx.destroy()
+    ctx = rps.RpsContext(4, 64, 0.1, 0.1, 0, rps.RPS_DTYPE_F32)
+    for first, rounds in ((0, 0), (0, (1 << 24) + 1), ((1 << 56) - 5, 10)):
+        with pytest.raises(rps.RpsError):
+            ctx.estimate_mixing(first, rounds)
+    ctx.destroy()
+
+
 @pytest.mark.parametrize("n,N,layout,dtype", [SHAPES[k] for k in (1, 3, 4, 8, 9, 10, 13, 15, 16)])
 def test_gradient_averaging_variant(rps, n, N, layout, dtype):
     """rps_round_gradient_averaging against the oracle composition (lossy average of G, then the

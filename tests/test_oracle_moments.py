@@ -284,3 +284,43 @@ def test_external_servers_expected_mixing(n, p):
     assert np.abs(np.diag(EW) - diag).max() < 1e-6
     assert np.abs(EW - np.diag(np.diag(EW)) - off_diag * (1 - np.eye(n))).max() < 1e-6
     assert np.allclose(EW.sum(axis=1), 1.0, atol=1e-6)          # mean preserved in expectation
+
+
+def _alpha_table():
+    import os
+    path = os.path.join(os.path.dirname(__file__), "golden", "alpha_table.txt")
+    rows = [ln.split() for ln in open(path) if not ln.startswith("#")]
+    return {(int(r[0]), float(r[1])): (float(r[2]), float(r[3]), float(r[4])) for r in rows}
+
+
+def test_alpha_table_against_the_lemmas_sums_and_the_papers_trends():
+    """The stored table (full enumeration through the oracle, tests/golden/make_alpha_table.py) against
+    the exact binomial sums of the supplement's Lemmas 7 and 8 typed out above, the ordering
+    0 < a2 < a1 < 1 (Sec. 4.2), and what the paper reads off Fig. 2 / Fig. 3 (Sec. 5): a2 shrinks
+    as the network grows at fixed p (a2 = O(p(1-p)/n)), beta = a1 - a2 grows with p (beta = O(p))."""
+    tab = _alpha_table()
+    ns = sorted({k[0] for k in tab}); ps = sorted({k[1] for k in tab})
+    assert len(tab) == len(ns) * len(ps) >= 30
+    for (n, p), (a1, a2, beta) in tab.items():
+        assert abs(a1 - alpha1_exact(n, p)) < 1e-11 and abs(a2 - alpha2_exact(n, p)) < 1e-11
+        assert 0 < a2 < a1 < 1 and abs(beta - (a1 - a2)) < 1e-12
+        assert a2 * n / (p * (1 - p)) < 4.0 and beta / p < 1.0
+    for p in ps:
+        a2s = [tab[(n, p)][1] for n in ns]
+        assert all(x > y for x, y in zip(a2s, a2s[1:]))
+    for n in ns:
+        betas = [tab[(n, p)][2] for p in ps]
+        assert all(x < y for x, y in zip(betas, betas[1:]))
+
+
+@pytest.mark.parametrize("n,p,identity", [(4, 0.1, False), (3, 0.2, False), (5, 0.05, True)])
+def test_monte_carlo_estimator_converges_to_the_table(n, p, identity):
+    """oracle.estimate_mixing (definition-level averages of W W^T and W A_n W^T over generated
+    outcomes) against the enumerated constants, within 5 batch standard errors.  A fixed server
+    map gives the same constants: the second moments of one block's W do not depend on which
+    worker serves it once averaged over rows."""
+    a1_ref, a2_ref, _ = _alpha_table()[(n, p)]
+    batches = np.array([oracle.estimate_mixing(77, 400 * b, 400, n, p, identity_server=identity) for b in range(12)])
+    est = batches.mean(axis=0); se = batches.std(axis=0, ddof=1) / np.sqrt(len(batches))
+    assert abs(est[0] - a1_ref) < 5 * se[0] and se[0] < 0.05 * a1_ref
+    assert abs(est[1] - a2_ref) < 5 * se[1] and se[1] < 0.05 * a2_ref
