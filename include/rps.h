@@ -181,7 +181,8 @@ int rps_estimate_mixing(rps_ctx *ctx, uint64_t first_step, int64_t rounds, doubl
  *   rows_in_flight       rows per load chunk (a wavefront keeps two chunks in flight): 2 or 4
  *   waves_per_workgroup  1 or 4 (a workgroup's wavefronts own adjacent tiles)
  *   max_waves_per_cu     cap on resident wavefronts per compute unit (0 = no cap)
- * The defaults are the measured best for the benchmark configurations.  RPS_EINVAL otherwise.
+ * Until this is called every launch takes the measured best shape for its worker count, dtype
+ * and gradient source (none / buffer / in-register).  RPS_EINVAL for other values.
  */
 int rps_set_launch_tuning(rps_ctx *ctx, int32_t rows_in_flight, int32_t waves_per_workgroup,
                           int32_t max_waves_per_cu);

@@ -36,7 +36,8 @@ struct rps_ctx {
     std::vector<hipEvent_t> ev_start, ev_stop;
     size_t ev_used = 0;
     int last_hip = 0;
-    rps::LaunchTuning tune{2, 1, 8};   // overwritten by default_tuning() at creation
+    bool tune_set = false;             // rps_set_launch_tuning was called: `tune` replaces the defaults
+    rps::LaunchTuning tune{2, 1, 8};
 };
 
 namespace {
@@ -56,12 +57,19 @@ int hip_fail(rps_ctx *ctx, hipError_t e) {
 bool step_ok(uint64_t step) { return step < (1ull << 56); }
 
 // Measured best launch shapes on MI355X (sweeps over rows per chunk, workgroup width and the
-// occupancy cap at n = 16 / 32 fp32 and n = 64 bf16).  The in-place update mixes n read streams
-// with n write streams; the memory system handles that best with few wavefronts resident.
-rps::LaunchTuning default_tuning(int32_t n, int32_t dtype) {
+// occupancy cap at n = 8 / 16 / 32 fp32 and n = 64 bf16, for each gradient source).  The in-place
+// update mixes n read streams with n write streams; the memory system handles that best with few
+// wavefronts resident -- fewer still when a gradient buffer doubles the loads in flight.
+rps::LaunchTuning default_tuning(int32_t n, int32_t dtype, int grad_mode) {
+    if (grad_mode == rps::kGradNone) return rps::LaunchTuning{4, 1, 5};
+    if (grad_mode == rps::kGradBuffer) return n >= 12 ? rps::LaunchTuning{2, 1, 5} : rps::LaunchTuning{4, 1, 6};
     if (dtype == RPS_DTYPE_BF16) return rps::LaunchTuning{2, 1, 0};   // close to ALU-bound: full occupancy
     if (n >= 24) return rps::LaunchTuning{4, 1, 6};
     return rps::LaunchTuning{4, 1, 8};
+}
+
+rps::LaunchTuning tuning_for(const rps_ctx *ctx, int grad_mode) {
+    return ctx->tune_set ? ctx->tune : default_tuning(ctx->n, ctx->dtype, grad_mode);
 }
 
 RoundParams make_params(const rps_ctx *ctx, const void *X, const void *G, uint64_t step) {
@@ -178,7 +186,6 @@ static int create_impl(rps_ctx **out, int32_t n, int32_t nb, bool external, int6
     ctx->dtype = dtype;
     ctx->flags = flags;
     ctx->stream = (hipStream_t)hip_stream;
-    ctx->tune = default_tuning(n, dtype);
 
     hipError_t e = hipGetDevice(&ctx->device);
     const size_t scratch_bytes = (2 * (size_t)rps::kMaxPartials + 2) * sizeof(double);
@@ -261,7 +268,7 @@ int rps_lossy_average(rps_ctx *ctx, void *X, uint64_t step) {
     if (rc != RPS_OK) return rc;
     return timed_launch(ctx, [&] {
         return rps::launch_round(ctx->dtype, rps::kGradNone, X, nullptr, ctx->tab, prm, ctx->max_block_cols,
-                                 ctx->tune, ctx->stream);
+                                 tuning_for(ctx, rps::kGradNone), ctx->stream);
     });
 }
 
@@ -274,7 +281,8 @@ int rps_round(rps_ctx *ctx, void *X, const void *G, uint64_t step) {
     const int rc = enqueue_masks(ctx, step);
     if (rc != RPS_OK) return rc;
     return timed_launch(ctx, [&] {
-        return rps::launch_round(ctx->dtype, mode, X, G, ctx->tab, prm, ctx->max_block_cols, ctx->tune, ctx->stream);
+        return rps::launch_round(ctx->dtype, mode, X, G, ctx->tab, prm, ctx->max_block_cols, tuning_for(ctx, mode),
+                                 ctx->stream);
     });
 }
 
@@ -286,8 +294,8 @@ int rps_round_gradient_averaging(rps_ctx *ctx, void *X, const void *G, uint64_t 
     const int rc = enqueue_masks(ctx, step);
     if (rc != RPS_OK) return rc;
     return timed_launch(ctx, [&] {
-        return rps::launch_gradavg(ctx->dtype, X, G, ctx->tab, prm, ctx->max_block_cols, ctx->tune.max_waves_per_cu,
-                                   ctx->stream);
+        return rps::launch_gradavg(ctx->dtype, X, G, ctx->tab, prm, ctx->max_block_cols,
+                                   tuning_for(ctx, rps::kGradBuffer).max_waves_per_cu, ctx->stream);
     });
 }
 
@@ -392,6 +400,7 @@ int rps_set_launch_tuning(rps_ctx *ctx, int32_t rows_in_flight, int32_t waves_pe
     if (waves_per_workgroup != 1 && waves_per_workgroup != 4) return RPS_EINVAL;
     if (max_waves_per_cu < 0) return RPS_EINVAL;
     ctx->tune = rps::LaunchTuning{rows_in_flight, waves_per_workgroup, max_waves_per_cu};
+    ctx->tune_set = true;
     return RPS_OK;
 }
 
