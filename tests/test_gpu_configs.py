@@ -238,3 +238,36 @@ def test_config_lsq_n4_gradient_averaging_drifts(rps):
     dg, _ = ctx.consensus(Xg)
     assert dg > 10 * dm, (dg, dm)
     ctx.destroy()
+
+
+@pytest.mark.parametrize("n,N,dtype,split", [(2, 1 << 34, "bf16", (1 << 33) + 1288), (1, (1 << 32) + 3, "f32", None)])
+def test_maximum_width(rps, n, N, dtype, split):
+    """The interface's widest model (N = 2^34 columns; column indices, noise counters and byte
+    offsets all pass 2^32) and an odd width just past 2^32 (element-wise path, one worker).
+    Starts from X = 0 (Alg. 1's identical start); the oracle evolves sampled columns -- both ends,
+    both sides of 2^32, of the block boundary and of the last tile -- by itself for three rounds."""
+    free, _ = torch.cuda.mem_get_info()
+    elem = 2 if dtype == "bf16" else 4
+    if free < n * N * elem + (8 << 30):
+        pytest.skip("not enough free device memory for the maximum-width state")
+    off = np.array([0, N] if split is None else [0, split, N], dtype=np.int64)
+    marks = [0, 1 << 32, N - 600] + ([split] if split else []) + [N - 40]
+    cols = np.unique(np.concatenate([np.arange(max(m - 20, 0), min(m + 20, N)) for m in marks] +
+                                    [workloads.sample_columns(off, per_block=60, seed=3)]))
+    idx = torch.from_numpy(cols).cuda()
+    p, gamma, seed = 0.3, 0.5, 2024
+    X = torch.zeros(n, N, device="cuda", dtype=torch.bfloat16 if dtype == "bf16" else torch.float32)
+    Xo = to_oracle(X.index_select(1, idx))
+    ctx = rps.RpsContext(n, N, p, gamma, seed, rps.RPS_DTYPE_BF16 if dtype == "bf16" else rps.RPS_DTYPE_F32,
+                         block_offsets=off)
+    ctx.set_synthetic_grad(1.0, 0.01)
+    for t in range(3):
+        ctx.round(X, None, t)
+        oracle.round_(Xo, None, off, p=p, gamma=gamma, seed=seed, step=t, sigma=1.0, weight_decay=0.01, cols=cols)
+        masks_equal(ctx, seed, t, n, p)
+        got = to_oracle(X.index_select(1, idx))
+        assert_close(got, Xo, off, dtype, cols=cols, what=f"N={N} round {t}")
+    assert np.abs(as_float(Xo)).max() > 0.1                     # the noise really moved the state
+    ctx.destroy()
+    del X
+    torch.cuda.empty_cache()
