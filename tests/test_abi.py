@@ -48,3 +48,24 @@ def test_argument_validation_needs_no_gpu():
     assert lib.rps_destroy(None) == 0
     assert lib.rps_strerror(-1) == b"invalid argument"
     assert ctx.value is None
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/rps.h compiles as C99 and as C++ on its own (no HIP or torch types in the signatures),
+    and a C translation unit that names every entry point links against the library."""
+    import subprocess
+    _ensure_built()
+    inc = os.path.join(ROOT, "include")
+    header = re.sub(r"/\*.*?\*/", "", open(os.path.join(inc, "rps.h")).read(), flags=re.S)
+    names = sorted(set(re.findall(r"\b(rps_[a-z_]+)\s*\(", header)))
+    src = tmp_path / "use_rps.c"
+    src.write_text('#include "rps.h"\n#include <stdio.h>\ntypedef void (*fn)(void);\nint main(void) {\n  fn f[] = {'
+                   + ", ".join(f"(fn){n}" for n in names)
+                   + "};\n  printf(\"%d %s\\n\", (int)(sizeof f / sizeof f[0]), rps_strerror(RPS_EINVAL));\n"
+                     "  return rps_destroy(0);\n}\n")
+    exe = tmp_path / "use_rps"
+    subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-I", inc, str(src), "-o", str(exe),
+                    "-L", os.path.dirname(LIB), "-l:librps.so", f"-Wl,-rpath,{os.path.dirname(LIB)}"], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split(None, 1)
+    assert int(out[0]) == len(names) and out[1].strip() == "invalid argument"
+    subprocess.run(["g++", "-std=c++17", "-fsyntax-only", "-x", "c++", "-I", inc, os.path.join(inc, "rps.h")], check=True)
