@@ -64,6 +64,35 @@ def cpu_baseline(cfg, off, budget_cols):
                       f"{dt:.1f} s on {threads} threads (+ {reps1} rounds, {dt1:.1f} s, on one)"}
 
 
+def other_paths(ctx, cfg, X, G, step, torch, launches=30):
+    """Kernel time (HIP events on the launch stream) of the other entry points on the same state:
+    each against the bytes it has to move -- per worker-param, in units of the element size:
+    local step 2 (3 with a gradient buffer), averaging alone 2 - p(1 - 1/n) (rows whose reply is
+    lost are not written), fused round on a gradient buffer 3."""
+    elem = 2 if cfg.dtype == "bf16" else 4
+    wp = cfg.n * cfg.N
+    Gb = G if G is not None else torch.zeros_like(X).normal_(0.0, 1e-3)
+    lost = cfg.p * (1.0 - 1.0 / cfg.n)
+    cases = (("local_step, in-register gradient", lambda t: ctx.local_step(X, None, t), 2.0),
+             ("local_step, gradient buffer", lambda t: ctx.local_step(X, Gb, t), 3.0),
+             ("lossy_average alone", lambda t: ctx.lossy_average(X, t), 2.0 - lost),
+             ("round, gradient buffer", lambda t: ctx.round(X, Gb, t), 3.0))
+    res = {}
+    for name, fn, units in cases:
+        for t in range(5):
+            fn(step + t)
+        ctx.set_profiling(True)
+        for t in range(launches):
+            fn(step + t)
+        ms, cnt = ctx.get_kernel_time()
+        ctx.set_profiling(False)
+        ms /= cnt
+        gbs = units * elem * wp / (ms * 1e-3) / 1e9
+        res[name] = {"kernel_ms": ms, "bytes_per_worker_param": units * elem, "achieved": gbs, "unit": "GB/s",
+                     "frac": gbs / HBM_PEAK_GBS}
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -71,6 +100,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--config", default=None, help="workload name (default: the headline config)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--other-paths", action="store_true",
+                    help="also time the unfused entry points and the gradient-buffer round on the same workload "
+                         "(needs a second [n, N] array) and report each against its own algorithmic bytes")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run three plain 1 GiB device copies (a kernel of known traffic) so that one "
                          "rocprofv3 --pmc run holds both the round kernel and the reference for its counters")
@@ -139,6 +171,8 @@ def main():
                      "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name),
                      "kernel": "round_kernel", "kernel_ms": kernel_ms, "algorithmic_bytes": alg_bytes},
     }
+    if args.other_paths:
+        out["other_paths"] = other_paths(ctx, cfg, X, G, step, torch)
     ctx.destroy()
     del X, G
     if args.pmc_calibration:
