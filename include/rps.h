@@ -18,9 +18,10 @@
  *
  * Conventions
  *   - X and G are CALLER-OWNED DEVICE memory: contiguous row-major [n, N] (worker-major), fp32
- *     or bf16.  The library never allocates, frees or keeps them.  A 16-byte aligned base with
- *     N % 4 == 0 (fp32) or N % 8 == 0 (bf16) takes the 128-bit load/store path; anything else
- *     is handled by a slower element-wise path with identical results.
+ *     or bf16 -- or tile-major, see RPS_FLAG_LAYOUT_TILED.  The library never allocates, frees or
+ *     keeps them.  A 16-byte aligned base with N % 4 == 0 (fp32) or N % 8 == 0 (bf16; any N in
+ *     the tiled layout) takes the 128-bit load/store path; anything else is handled by a slower
+ *     element-wise path with identical results.
  *   - All device work is enqueued on the HIP stream given at creation; no call synchronises
  *     except where stated.  Results are valid in stream order.
  *   - Every function returns RPS_OK (0) or a negative error code; nothing aborts or throws.
@@ -54,8 +55,27 @@ enum { RPS_DTYPE_F32 = 0, RPS_DTYPE_BF16 = 1 };
 enum {
     /* Worker j serves block j in every round: the simplification the paper uses when it
        explains the algorithm (Sec. 4.1).  Default is Alg. 1's per-round random permutation. */
-    RPS_FLAG_SERVER_IDENTITY = 1u
+    RPS_FLAG_SERVER_IDENTITY = 1u,
+    /* X and G are stored tile-major instead of row-major: the model is cut into tiles of
+       RPS_TILE_BYTES per worker (32 fp32 or 64 bf16 columns) and the n workers' segments of a
+       tile are adjacent, i.e. element (worker i, column c) lives at ((c / T) * n + i) * T + c % T
+       with T = RPS_TILE_BYTES / sizeof(element).  The array holds ceil(N / T) * n * T elements
+       (rps_storage_elems); the columns of the last tile beyond N are padding that is never read
+       or written.  All n values of a column then sit within n * 128 bytes of each other, and a
+       round streams through memory in address order, reading only a few KB before it writes
+       them back -- measured 9-14 % faster than row-major on this GPU.  Results are those of the
+       row-major layout up to the summation order of the fp64 column sums (still fixed, and the
+       same for every receiver of a block).  Worker i's model is the strided view [:, i, :].
+       rps_round_gradient_averaging is row-major only (RPS_EUNSUPPORTED).  Not available with
+       external servers. */
+    RPS_FLAG_LAYOUT_TILED = 2u
 };
+
+#define RPS_TILE_BYTES 128
+
+/* Number of elements an X or G array must hold for n workers, N columns, the dtype and the
+   layout chosen by `flags` (n * N for row-major).  Returns -1 for invalid arguments. */
+int64_t rps_storage_elems(int32_t n, int64_t N, int32_t dtype, uint32_t flags);
 
 /*
  * Create a context for n workers with N parameters each (problem statement, Sec. 3; inputs
@@ -70,7 +90,7 @@ enum {
  *   gamma          step size of the local SGD step
  *   seed           64-bit key of the counter-based random numbers
  *   dtype          RPS_DTYPE_F32 or RPS_DTYPE_BF16 (storage; arithmetic is fp32, sums fp64)
- *   flags          RPS_FLAG_*
+ *   flags          RPS_FLAG_* (server assignment, storage layout)
  *   hip_stream     hipStream_t on which all work is enqueued (NULL = the default stream)
  * Allocates a fixed ~40 KB of device memory (per-round tables, reduction scratch) and a pinned
  * host staging buffer of a few KB; nothing proportional to N.  Errors: RPS_EINVAL, RPS_ENOMEM, RPS_EHIP.

@@ -69,7 +69,10 @@ rps::LaunchTuning default_tuning(int32_t n, int32_t dtype, int grad_mode) {
 }
 
 rps::LaunchTuning tuning_for(const rps_ctx *ctx, int grad_mode) {
-    return ctx->tune_set ? ctx->tune : default_tuning(ctx->n, ctx->dtype, grad_mode);
+    if (ctx->tune_set) return ctx->tune;
+    if (ctx->flags & RPS_FLAG_LAYOUT_TILED)   // small tiles, one piece of memory each: more wavefronts resident
+        return rps::LaunchTuning{4, 1, grad_mode == rps::kGradSynthetic ? 16 : 12};
+    return default_tuning(ctx->n, ctx->dtype, grad_mode);
 }
 
 RoundParams make_params(const rps_ctx *ctx, const void *X, const void *G, uint64_t step) {
@@ -79,7 +82,9 @@ RoundParams make_params(const rps_ctx *ctx, const void *X, const void *G, uint64
     prm.blocks = ctx->nb;
     const int64_t vec = ctx->dtype == RPS_DTYPE_F32 ? 4 : 8;   // elements per 16 bytes
     const bool aligned = ((uintptr_t)X % 16 == 0) && (G == nullptr || (uintptr_t)G % 16 == 0);
-    prm.vec_ok = (aligned && ctx->N % vec == 0) ? 1 : 0;
+    prm.tiled = (ctx->flags & RPS_FLAG_LAYOUT_TILED) ? 1 : 0;
+    prm.stride = prm.tiled ? (RPS_TILE_BYTES / 16) * vec : ctx->N;   // tiled: every tile row is one short segment, whatever N is
+    prm.vec_ok = (aligned && (prm.tiled || ctx->N % vec == 0)) ? 1 : 0;
     prm.gamma = ctx->gamma;
     prm.sigma = ctx->sigma;
     prm.lambda = ctx->lambda;
@@ -152,7 +157,7 @@ static int create_impl(rps_ctx **out, int32_t n, int32_t nb, bool external, int6
     if (!(p >= 0.0 && p <= 1.0)) return RPS_EINVAL;   // also rejects NaN
     if (!std::isfinite(gamma)) return RPS_EINVAL;
     if (dtype != RPS_DTYPE_F32 && dtype != RPS_DTYPE_BF16) return RPS_EINVAL;
-    if (flags & ~(uint32_t)RPS_FLAG_SERVER_IDENTITY) return RPS_EINVAL;
+    if (flags & ~(uint32_t)(RPS_FLAG_SERVER_IDENTITY | RPS_FLAG_LAYOUT_TILED)) return RPS_EINVAL;
 
     rps_ctx *ctx = new (std::nothrow) rps_ctx;
     if (!ctx) return RPS_ENOMEM;
@@ -217,6 +222,14 @@ static int create_impl(rps_ctx **out, int32_t n, int32_t nb, bool external, int6
 int rps_create(rps_ctx **out, int32_t n, int64_t N, const int64_t *block_offsets, double p, float gamma,
                uint64_t seed, int32_t dtype, uint32_t flags, void *hip_stream) {
     return create_impl(out, n, n, false, N, block_offsets, p, gamma, seed, dtype, flags, hip_stream);
+}
+
+int64_t rps_storage_elems(int32_t n, int64_t N, int32_t dtype, uint32_t flags) {
+    if (n < 1 || n > rps::kMaxWorkers || N < 1 || N > (1ll << 34)) return -1;
+    if (dtype != RPS_DTYPE_F32 && dtype != RPS_DTYPE_BF16) return -1;
+    if (!(flags & RPS_FLAG_LAYOUT_TILED)) return (int64_t)n * N;
+    const int64_t T = RPS_TILE_BYTES / (dtype == RPS_DTYPE_F32 ? 4 : 2);
+    return ((N + T - 1) / T) * n * T;
 }
 
 int rps_create_external(rps_ctx **out, int32_t n, int32_t servers, int64_t N, const int64_t *block_offsets, double p,
@@ -288,6 +301,7 @@ int rps_round(rps_ctx *ctx, void *X, const void *G, uint64_t step) {
 
 int rps_round_gradient_averaging(rps_ctx *ctx, void *X, const void *G, uint64_t step) {
     if (!ctx || !X || !G || !step_ok(step)) return RPS_EINVAL;
+    if (ctx->flags & RPS_FLAG_LAYOUT_TILED) return RPS_EUNSUPPORTED;   // the comparison baseline is row-major only
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return RPS_EHIP;
     const RoundParams prm = make_params(ctx, X, G, step);

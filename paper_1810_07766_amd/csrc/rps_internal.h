@@ -23,7 +23,9 @@ struct RoundTable {
 };
 
 struct RoundParams {
-    int64_t N;            // row pitch in elements
+    int64_t N;            // columns (parameters per worker)
+    int64_t stride;       // storage distance between consecutive rows of a tile: N (row-major) or the tile width (tiled: 128 bytes of elements)
+    int32_t tiled;        // 1: storage is [tiles][n][tile width] (rps.h, RPS_FLAG_LAYOUT_TILED)
     int32_t n;            // workers
     int32_t blocks;       // blocks (= n unless the servers are external)
     int32_t vec_ok;       // 1: every full 8-column group may use 128-bit accesses

@@ -291,16 +291,23 @@ struct Storage<uint16_t> {
 
 // Where one lane works: VEC columns [c0, c0+VEC) of the column range [lo, hi), c0 = tile0 + loff
 // with tile0 wave-uniform and loff = lane * VEC.  Row pointers handed to load_raw / store_raw
-// already include tile0 (wave-uniform base + 32-bit lane offset: no per-lane 64-bit address
+// already include the tile's storage offset (wave-uniform base + 32-bit lane offset: no per-lane 64-bit address
 // arithmetic).  In a FULL wavefront every lane's vector lies inside the range and is 16-byte
 // aligned: one 128-bit access per row and no per-lane test (keeps all loads of a row chunk in
 // one basic block, in flight together).  Otherwise (block edges, unaligned pitch) lanes touch
 // only their own columns inside the range, element by element.
 struct LaneCols {
     int64_t tile0, lo, hi;
+    int64_t base;    // storage offset of (row 0, column tile0); rows of the tile follow at prm.stride
     uint32_t loff;
     __device__ __forceinline__ int64_t c0() const { return tile0 + loff; }
 };
+
+// Storage offset of (row 0, column tile0), tile0 a multiple of the tile width.  Row-major [n, N]:
+// tile0, rows N apart.  Tiled [tiles][n][tile width]: the n rows of a tile are adjacent.
+__device__ __forceinline__ int64_t tile_base(const RoundParams &prm, int64_t tile0) {
+    return prm.tiled ? tile0 * prm.n : tile0;
+}
 
 template <typename ST, bool FULL>
 __device__ __forceinline__ typename Storage<ST>::Raw load_raw(const ST *tile_row, const LaneCols &lc) {
@@ -400,8 +407,8 @@ __device__ __forceinline__ void load_chunk(LoadCursor<ST> &cur, const RoundParam
         if (GRAD == kGradBuffer) g[r] = load_raw<ST, FULL>(cur.g, lc);
         if (cur.row + 1 < prm.n) {   // scalar
             ++cur.row;
-            cur.x += prm.N;
-            if (GRAD == kGradBuffer) cur.g += prm.N;
+            cur.x += prm.stride;
+            if (GRAD == kGradBuffer) cur.g += prm.stride;
         }
     }
 }
@@ -438,7 +445,7 @@ __device__ __forceinline__ void process_chunk(ST *__restrict__ Xt, const RoundPa
 #pragma unroll
                         for (int e = 0; e < VEC; ++e) acc[e] += (double)v[e];
                     }
-                    if (GRAD != kGradNone && !da) store_raw<ST, FULL>(Xt + (int64_t)ia * prm.N, lc, vr);
+                    if (GRAD != kGradNone && !da) store_raw<ST, FULL>(Xt + (int64_t)ia * prm.stride, lc, vr);
                 }
                 if (need_b) {
                     float v[VEC];
@@ -449,7 +456,7 @@ __device__ __forceinline__ void process_chunk(ST *__restrict__ Xt, const RoundPa
 #pragma unroll
                         for (int e = 0; e < VEC; ++e) acc[e] += (double)v[e];
                     }
-                    if (GRAD != kGradNone && !db) store_raw<ST, FULL>(Xt + (int64_t)ib * prm.N, lc, vr);
+                    if (GRAD != kGradNone && !db) store_raw<ST, FULL>(Xt + (int64_t)ib * prm.stride, lc, vr);
                 }
             }
         }
@@ -477,7 +484,7 @@ __device__ __forceinline__ void round_tile(ST *__restrict__ X, const ST *__restr
     constexpr int VEC = S::VEC;
     constexpr int RG = GRAD == kGradBuffer ? R : 1;
     const int n = prm.n;
-    ST *Xt = X + lc.tile0;   // row 0 of the tile (wave-uniform)
+    ST *Xt = X + lc.base;   // row 0 of the tile (wave-uniform)
 
     double acc[VEC];
 #pragma unroll
@@ -485,7 +492,7 @@ __device__ __forceinline__ void round_tile(ST *__restrict__ X, const ST *__restr
 
     LoadCursor<ST> cur;
     cur.x = Xt;
-    cur.g = GRAD == kGradBuffer ? G + lc.tile0 : nullptr;
+    cur.g = GRAD == kGradBuffer ? G + lc.base : nullptr;
     cur.row = 0;
     Raw xa[R], xb[R], ga[RG], gb[RG];
     load_chunk<ST, GRAD, R, FULL>(cur, prm, lc, xa, ga);
@@ -511,7 +518,7 @@ __device__ __forceinline__ void round_tile(ST *__restrict__ X, const ST *__restr
     for (int e = 0; e < VEC; ++e) vt[e] = (float)(acc[e] * inv);
     const Raw vt_raw = S::round_vec(vt);
     ST *row = Xt;
-    for (int i = 0; i < n; ++i, row += prm.N)
+    for (int i = 0; i < n; ++i, row += prm.stride)
         if ((dcol >> i) & 1) store_raw<ST, FULL>(row, lc, vt_raw);
 }
 
@@ -532,6 +539,7 @@ __global__ __launch_bounds__(WPB * 64) void round_kernel(ST *__restrict__ X, con
 
     LaneCols lc;
     lc.tile0 = tile0;
+    lc.base = tile_base(prm, tile0);
     lc.loff = (uint32_t)lane * VEC;
     lc.lo = lo;
     lc.hi = hi;
@@ -539,6 +547,177 @@ __global__ __launch_bounds__(WPB * 64) void round_kernel(ST *__restrict__ X, con
         round_tile<ST, GRAD, R, true>(X, G, prm, lc, ucol, dcol, inv);
     else
         round_tile<ST, GRAD, 2, false>(X, G, prm, lc, ucol, dcol, inv);
+}
+
+// ---------------------------------------------------------------------------------------
+// Narrow tiles: the same round with LPR < 64 lanes per row segment.  A tile is LPR x 16 bytes
+// wide; one wavefront instruction covers 64 / LPR rows of it (lane group lg = lane / LPR), and a
+// lane owns the row pairs lg, lg + 64/LPR, ... of its 16-byte column group, so that the noise
+// hash of a (4 columns x 2 rows) patch still serves one lane.  A wavefront then reads only
+// n x LPR x 16 bytes before it writes them back (8 KB at n = 32, LPR = 16, against 32 KB with
+// 64 lanes per row), which is what the memory system rewards; in the tiled layout these bytes
+// are one contiguous piece of memory.  Column sums: every lane group sums its own rows in
+// ascending order, the groups are then combined by a butterfly over the lanes (a fixed order,
+// the same for every receiver, but not the plain ascending order of the wide kernel).
+// ---------------------------------------------------------------------------------------
+constexpr int kTiledLanes = 8;   // lanes per row segment of the tiled layout: 8 x 16 B = 128 B (RPS_TILE_BYTES)
+
+template <typename ST, bool FULL>
+__device__ __forceinline__ typename Storage<ST>::Raw load_seg(const ST *p, int64_t c0, int64_t lo, int64_t hi) {
+    using S = Storage<ST>;
+    if (FULL) {
+        return __builtin_nontemporal_load(reinterpret_cast<const typename S::Raw *>(p));
+    } else {
+        float x[S::VEC];
+#pragma unroll
+        for (int e = 0; e < S::VEC; ++e) x[e] = (c0 + e >= lo && c0 + e < hi) ? S::load1(p + e) : 0.0f;
+        return S::pack(x);
+    }
+}
+template <typename ST, bool FULL>
+__device__ __forceinline__ void store_seg(ST *p, int64_t c0, int64_t lo, int64_t hi, typename Storage<ST>::Raw v) {
+    using S = Storage<ST>;
+    if (FULL) {
+        __builtin_nontemporal_store(v, reinterpret_cast<typename S::Raw *>(p));
+    } else {
+        float x[S::VEC];
+        S::unpack(v, x);
+#pragma unroll
+        for (int e = 0; e < S::VEC; ++e)
+            if (c0 + e >= lo && c0 + e < hi) S::store1(p + e, x[e]);
+    }
+}
+
+template <typename ST, int GRAD, int LPR, bool FULL>
+struct NarrowTile {
+    using S = Storage<ST>;
+    using Raw = typename S::Raw;
+    static constexpr int VEC = S::VEC;
+    static constexpr int GROUPS = 64 / LPR;   // lane groups = rows per wavefront instruction
+    static constexpr int CP = 2;              // row pairs per lane and load chunk (4 rows in flight per chunk)
+    static constexpr int CG = GRAD == kGradBuffer ? 2 * CP : 1;
+
+    const RoundParams &prm;
+    ST *Xl;            // (row 0, this lane's columns)
+    const ST *Gl;
+    int64_t c0, lo, hi;
+    uint64_t ucol, dcol;
+    int lg;
+
+    // rows of the lane's k-th pair
+    __device__ __forceinline__ int row_a(int k) const { return 2 * (lg + GROUPS * k); }
+
+    __device__ __forceinline__ void load_chunk(int k0, Raw x[2 * CP], Raw g[CG]) const {
+        const int last = prm.n - 1;
+#pragma unroll
+        for (int q = 0; q < CP; ++q) {
+            const int ia = row_a(k0 + q);
+            const int64_t oa = (int64_t)(ia < last ? ia : last) * prm.stride;          // rows past n repeat row n-1, unused
+            const int64_t ob = (int64_t)(ia + 1 < last ? ia + 1 : last) * prm.stride;
+            x[2 * q] = load_seg<ST, FULL>(Xl + oa, c0, lo, hi);
+            x[2 * q + 1] = load_seg<ST, FULL>(Xl + ob, c0, lo, hi);
+            if (GRAD == kGradBuffer) {
+                g[GRAD == kGradBuffer ? 2 * q : 0] = load_seg<ST, FULL>(Gl + oa, c0, lo, hi);
+                g[GRAD == kGradBuffer ? 2 * q + 1 : 0] = load_seg<ST, FULL>(Gl + ob, c0, lo, hi);
+            }
+        }
+    }
+
+    __device__ __forceinline__ void row(int i, Raw xr, Raw gr, const float *z, double acc[VEC]) const {
+        if (i >= prm.n) return;
+        const bool u = (ucol >> i) & 1, d = (dcol >> i) & 1;
+        if (!(u || (GRAD != kGradNone && !d))) return;
+        float v[VEC], g[VEC];
+        S::unpack(xr, v);
+        if (GRAD == kGradBuffer) S::unpack(gr, g);
+        const Raw vr = sgd_step<ST, GRAD>(prm, GRAD == kGradBuffer ? g : z, v);
+        if (u) {
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) acc[e] += (double)v[e];
+        }
+        if (GRAD != kGradNone && !d) store_seg<ST, FULL>(Xl + (int64_t)i * prm.stride, c0, lo, hi, vr);
+    }
+
+    __device__ __forceinline__ void process_chunk(int k0, const Raw x[2 * CP], const Raw g[CG], double acc[VEC]) const {
+#pragma unroll
+        for (int q = 0; q < CP; ++q) {
+            const int ia = row_a(k0 + q);
+            float za[VEC], zb[VEC];
+            if (GRAD == kGradSynthetic) noise_rows<VEC>(prm, ia >> 1, c0, za, zb);
+            row(ia, x[2 * q], g[GRAD == kGradBuffer ? 2 * q : 0], za, acc);
+            row(ia + 1, x[2 * q + 1], g[GRAD == kGradBuffer ? 2 * q + 1 : 0], zb, acc);
+        }
+#pragma unroll
+        for (int q = 0; q < 2 * CP; ++q) asm volatile("" ::"v"(x[q]));   // see process_chunk of the wide kernel
+        if (GRAD == kGradBuffer) {
+#pragma unroll
+            for (int q = 0; q < CG; ++q) asm volatile("" ::"v"(g[q]));
+        }
+    }
+
+    __device__ __forceinline__ void run(double inv) const {
+        const int n = prm.n;
+        const int steps = ((n + 1) / 2 + GROUPS - 1) / GROUPS;   // row pairs per lane (wave-uniform)
+        double acc[VEC];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) acc[e] = 0.0;
+        Raw xa[2 * CP], xb[2 * CP], ga[CG], gb[CG];
+        load_chunk(0, xa, ga);
+        int k = 0;
+        for (; k + 2 * CP < steps; k += 2 * CP) {
+            load_chunk(k + CP, xb, gb);
+            process_chunk(k, xa, ga, acc);
+            load_chunk(k + 2 * CP, xa, ga);
+            process_chunk(k + CP, xb, gb, acc);
+        }
+        if (k + CP < steps) {
+            load_chunk(k + CP, xb, gb);
+            process_chunk(k, xa, ga, acc);
+            process_chunk(k + CP, xb, gb, acc);
+        } else {
+            process_chunk(k, xa, ga, acc);
+        }
+        // combine the lane groups: after the butterfly every lane of a column group holds the same sum
+#pragma unroll
+        for (int o = LPR; o < 64; o <<= 1) {
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) acc[e] += __shfl_xor(acc[e], o, 64);
+        }
+        float vt[VEC];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) vt[e] = (float)(acc[e] * inv);
+        const Raw vt_raw = S::round_vec(vt);
+        for (int q = 0; q < steps; ++q) {
+            const int ia = row_a(q);
+            if (ia < n && ((dcol >> ia) & 1)) store_seg<ST, FULL>(Xl + (int64_t)ia * prm.stride, c0, lo, hi, vt_raw);
+            if (ia + 1 < n && ((dcol >> (ia + 1)) & 1))
+                store_seg<ST, FULL>(Xl + (int64_t)(ia + 1) * prm.stride, c0, lo, hi, vt_raw);
+        }
+    }
+};
+
+template <typename ST, int GRAD, int LPR>
+__global__ __launch_bounds__(64) void round_kernel_narrow(ST *__restrict__ X, const ST *__restrict__ G,
+                                                          const RoundTable *__restrict__ tab, const RoundParams prm) {
+    constexpr int VEC = Storage<ST>::VEC;
+    constexpr int TILE = LPR * VEC;
+    const int lane = threadIdx.x;
+    const int j = blockIdx.y;
+    const int64_t lo = tab->off[j], hi = tab->off[j + 1];
+    const int64_t tile0 = (lo / TILE) * TILE + (int64_t)blockIdx.x * TILE;
+    if (tile0 >= hi) return;   // wave-uniform
+    const int sub = lane % LPR;
+    const int64_t lane_off = tile_base(prm, tile0) + sub * VEC;
+    const bool full = prm.vec_ok && tile0 >= lo && tile0 + TILE <= hi;   // wave-uniform
+    if (full) {
+        const NarrowTile<ST, GRAD, LPR, true> t{prm, X + lane_off, G ? G + lane_off : nullptr, tile0 + sub * VEC, lo, hi,
+                                                tab->ucol[j], tab->dcol[j], lane / LPR};
+        t.run(tab->inv_cnt[j]);
+    } else {
+        const NarrowTile<ST, GRAD, LPR, false> t{prm, X + lane_off, G ? G + lane_off : nullptr, tile0 + sub * VEC, lo, hi,
+                                                 tab->ucol[j], tab->dcol[j], lane / LPR};
+        t.run(tab->inv_cnt[j]);
+    }
 }
 
 // Local SGD step alone: grid = (vector chunks, workers); a lane owns one 16-byte vector of one
@@ -551,11 +730,11 @@ __device__ __forceinline__ void local_step_row(ST *__restrict__ X, const ST *__r
                                                const LaneCols &lc, int i) {
     using S = Storage<ST>;
     constexpr int VEC = S::VEC;
-    ST *row = X + (int64_t)i * prm.N + lc.tile0;
+    ST *row = X + (int64_t)i * prm.stride + lc.base;
     float x[VEC], g[VEC], other[VEC];
     S::unpack(load_raw<ST, FULL>(row, lc), x);
     if (GRAD == kGradBuffer) {
-        S::unpack(load_raw<ST, FULL>(G + (int64_t)i * prm.N + lc.tile0, lc), g);
+        S::unpack(load_raw<ST, FULL>(G + (int64_t)i * prm.stride + lc.base, lc), g);
     } else if (i & 1) {
         noise_rows<VEC>(prm, i >> 1, lc.c0(), other, g);
     } else {
@@ -572,16 +751,57 @@ __global__ __launch_bounds__(256) void local_step_kernel(ST *__restrict__ X, con
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t tile0 = ((int64_t)blockIdx.x * 4 + wave) * TILE;
+    const int row = blockIdx.y;
     if (tile0 >= prm.N) return;   // wave-uniform
     LaneCols lc;
     lc.tile0 = tile0;
+    lc.base = tile_base(prm, tile0);
     lc.loff = (uint32_t)lane * VEC;
     lc.lo = 0;
     lc.hi = prm.N;
     if (prm.vec_ok && tile0 + TILE <= prm.N)
-        local_step_row<ST, GRAD, true>(X, G, prm, lc, blockIdx.y);
+        local_step_row<ST, GRAD, true>(X, G, prm, lc, row);
     else
-        local_step_row<ST, GRAD, false>(X, G, prm, lc, blockIdx.y);
+        local_step_row<ST, GRAD, false>(X, G, prm, lc, row);
+}
+
+// Local step on the tiled layout: the storage is one run of (tile, worker) segments of
+// kTiledLanes x 16 bytes; a wavefront takes 1 KB of it in storage order (8 segments), so the pass is
+// a plain sequential stream.  Lane -> segment s = 8 * wavefront + lane / 8 -> (tile, row) = (s / n, s % n).
+template <typename ST, int GRAD>
+__global__ __launch_bounds__(256) void local_step_tiled_kernel(ST *__restrict__ X, const ST *__restrict__ G,
+                                                               const RoundParams prm) {
+    using S = Storage<ST>;
+    constexpr int VEC = S::VEC;
+    constexpr int LPR = kTiledLanes, TILE = LPR * VEC;
+    const int64_t q = (int64_t)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    const int64_t seg0 = q * (64 / LPR);          // first segment of the wavefront: scalar division
+    int64_t tile = seg0 / prm.n;
+    int i = (int)(seg0 % prm.n) + lane / LPR;     // then at most 64 / LPR rows further
+    while (i >= prm.n) {
+        i -= prm.n;
+        ++tile;
+    }
+    const int64_t seg = seg0 + lane / LPR;
+    const int64_t c0 = tile * TILE + (lane % LPR) * VEC;
+    if (c0 >= prm.N) return;   // padding columns of the last tile, or past the last tile
+    const int64_t off = seg * TILE + (lane % LPR) * VEC;
+    float x[VEC], g[VEC], other[VEC];
+    const bool full = prm.vec_ok && c0 + VEC <= prm.N;
+    S::unpack(full ? load_seg<ST, true>(X + off, c0, 0, prm.N) : load_seg<ST, false>(X + off, c0, 0, prm.N), x);
+    if (GRAD == kGradBuffer) {
+        S::unpack(full ? load_seg<ST, true>(G + off, c0, 0, prm.N) : load_seg<ST, false>(G + off, c0, 0, prm.N), g);
+    } else if (i & 1) {
+        noise_rows<VEC>(prm, i >> 1, c0, other, g);
+    } else {
+        noise_rows<VEC>(prm, i >> 1, c0, g, other);
+    }
+    const typename S::Raw v = sgd_step<ST, GRAD>(prm, g, x);
+    if (full)
+        store_seg<ST, true>(X + off, c0, 0, prm.N, v);
+    else
+        store_seg<ST, false>(X + off, c0, 0, prm.N, v);
 }
 
 // Launch shape of the round kernel.  The memory system of this GPU is at its best when the
@@ -605,9 +825,26 @@ hipError_t launch_round_v(ST *X, const ST *G, const RoundTable *tab, const Round
     return hipGetLastError();
 }
 
+template <typename ST, int GRAD, int LPR>
+hipError_t launch_round_narrow(ST *X, const ST *G, const RoundTable *tab, const RoundParams &prm, int64_t max_block_cols,
+                               int max_waves_per_cu, hipStream_t stream) {
+    constexpr int TILE = LPR * Storage<ST>::VEC;
+    const int64_t tiles = (max_block_cols + 2 * TILE - 2) / TILE;
+    const dim3 grid((unsigned)tiles, (unsigned)prm.blocks, 1);
+    size_t lds = 0;
+    if (max_waves_per_cu > 0 && max_waves_per_cu < 32) {
+        lds = ((size_t)kLdsBytesPerCu / max_waves_per_cu) & ~(size_t)255;
+        if (lds > 65536) lds = 65536;
+    }
+    hipLaunchKernelGGL((round_kernel_narrow<ST, GRAD, LPR>), grid, dim3(64), lds, stream, X, G, tab, prm);
+    return hipGetLastError();
+}
+
 template <typename ST, int GRAD>
 hipError_t launch_round_t(ST *X, const ST *G, const RoundTable *tab, const RoundParams &prm, int64_t max_block_cols,
                           const LaunchTuning &tune, hipStream_t stream) {
+    if (prm.tiled)
+        return launch_round_narrow<ST, GRAD, kTiledLanes>(X, G, tab, prm, max_block_cols, tune.max_waves_per_cu, stream);
 #define RPS_V(R, W) launch_round_v<ST, GRAD, R, W>(X, G, tab, prm, max_block_cols, tune.max_waves_per_cu, stream)
     const int r = tune.rows_in_flight, w = tune.waves_per_workgroup;
     if (w == 1) return r <= 2 ? RPS_V(2, 1) : RPS_V(4, 1);
@@ -628,8 +865,18 @@ hipError_t launch_round_g(int grad_mode, ST *X, const ST *G, const RoundTable *t
 template <typename ST>
 hipError_t launch_local_step_g(int grad_mode, ST *X, const ST *G, const RoundParams &prm, hipStream_t stream) {
     constexpr int VEC = Storage<ST>::VEC;
-    const int64_t vecs = (prm.N + VEC - 1) / VEC;
-    const dim3 grid((unsigned)((vecs + 255) / 256), (unsigned)prm.n, 1);
+    if (prm.tiled) {
+        const int64_t tiles = (prm.N + kTiledLanes * VEC - 1) / (kTiledLanes * VEC);
+        const int64_t kb = (tiles * prm.n * kTiledLanes + 63) / 64;   // wavefronts: 1 KB of storage each
+        const dim3 grid((unsigned)((kb + 3) / 4), 1, 1);
+        if (grad_mode == kGradBuffer)
+            hipLaunchKernelGGL((local_step_tiled_kernel<ST, kGradBuffer>), grid, dim3(256), 0, stream, X, G, prm);
+        else
+            hipLaunchKernelGGL((local_step_tiled_kernel<ST, kGradSynthetic>), grid, dim3(256), 0, stream, X, G, prm);
+        return hipGetLastError();
+    }
+    const int64_t tiles = (prm.N + 64 * VEC - 1) / (64 * VEC);
+    const dim3 grid((unsigned)((tiles + 3) / 4), (unsigned)prm.n, 1);
     if (grad_mode == kGradBuffer)
         hipLaunchKernelGGL((local_step_kernel<ST, kGradBuffer>), grid, dim3(256), 0, stream, X, G, prm);
     else
@@ -658,13 +905,13 @@ __device__ __forceinline__ void gradavg_tile(ST *__restrict__ X, const ST *__res
     double acc[VEC];
 #pragma unroll
     for (int e = 0; e < VEC; ++e) acc[e] = 0.0;
-    const ST *grow = G + lc.tile0;
+    const ST *grow = G + lc.base;
     for (int i0 = 0; i0 < n; i0 += R) {
         Raw g[R];
 #pragma unroll
         for (int r = 0; r < R; ++r) {   // rows past n repeat row n-1, unused
             g[r] = load_raw<ST, FULL>(grow, lc);
-            if (i0 + r + 1 < n) grow += prm.N;
+            if (i0 + r + 1 < n) grow += prm.stride;
         }
 #pragma unroll
         for (int r = 0; r < R; ++r) {
@@ -682,14 +929,14 @@ __device__ __forceinline__ void gradavg_tile(ST *__restrict__ X, const ST *__res
     for (int e = 0; e < VEC; ++e) gt[e] = (float)(acc[e] * inv);
     (void)S::round_vec(gt);
 
-    ST *xrow = X + lc.tile0;
+    ST *xrow = X + lc.base;
     for (int i0 = 0; i0 < n; i0 += R) {
         Raw x[R];
         const ST *ld = xrow;
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             x[r] = load_raw<ST, FULL>(ld, lc);
-            if (i0 + r + 1 < n) ld += prm.N;
+            if (i0 + r + 1 < n) ld += prm.stride;
         }
 #pragma unroll
         for (int r = 0; r < R; ++r) {
@@ -699,13 +946,13 @@ __device__ __forceinline__ void gradavg_tile(ST *__restrict__ X, const ST *__res
                 S::unpack(x[r], v);
                 const float *gsrc = gt;
                 if (!((dcol >> i) & 1)) {   // reply lost: the worker applies its own gradient
-                    S::unpack(load_raw<ST, FULL>(G + lc.tile0 + (int64_t)i * prm.N, lc), own);
+                    S::unpack(load_raw<ST, FULL>(G + lc.base + (int64_t)i * prm.stride, lc), own);
                     gsrc = own;
                 }
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) v[e] = __builtin_fmaf(-prm.gamma, gsrc[e], v[e]);
                 store_raw<ST, FULL>(xrow, lc, S::round_vec(v));
-                xrow += prm.N;
+                xrow += prm.stride;
             }
         }
     }
@@ -724,6 +971,7 @@ __global__ __launch_bounds__(256) void gradavg_kernel(ST *__restrict__ X, const 
     if (tile0 >= hi) return;   // wave-uniform
     LaneCols lc;
     lc.tile0 = tile0;
+    lc.base = tile_base(prm, tile0);
     lc.loff = (uint32_t)lane * VEC;
     lc.lo = lo;
     lc.hi = hi;
@@ -748,18 +996,18 @@ __device__ __forceinline__ void consensus_tile(const ST *__restrict__ X, const R
     constexpr int VEC = S::VEC;
     constexpr int R = 4;
     const int n = prm.n;
-    const ST *row = X + lc.tile0;
+    const ST *row = X + lc.base;
     float p[VEC];
     S::unpack(load_raw<ST, FULL>(row, lc), p);
     double s1[VEC], s2[VEC];
 #pragma unroll
     for (int e = 0; e < VEC; ++e) s1[e] = s2[e] = 0.0;
     int i = 1;
-    row += prm.N;
+    row += prm.stride;
     for (; i + R <= n; i += R) {
         typename S::Raw x[R];
 #pragma unroll
-        for (int r = 0; r < R; ++r, row += prm.N) x[r] = load_raw<ST, FULL>(row, lc);
+        for (int r = 0; r < R; ++r, row += prm.stride) x[r] = load_raw<ST, FULL>(row, lc);
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             float v[VEC];
@@ -772,7 +1020,7 @@ __device__ __forceinline__ void consensus_tile(const ST *__restrict__ X, const R
             }
         }
     }
-    for (; i < n; ++i, row += prm.N) {
+    for (; i < n; ++i, row += prm.stride) {
         float v[VEC];
         S::unpack(load_raw<ST, FULL>(row, lc), v);
 #pragma unroll
@@ -792,26 +1040,86 @@ __device__ __forceinline__ void consensus_tile(const ST *__restrict__ X, const R
     }
 }
 
+// The same statistics on the tiled layout: lane group lg takes rows lg, lg + 8, ... of its 16-byte
+// column group (every lane also loads the pivot row 0), the groups are combined by a butterfly,
+// and the lanes of group 0 carry the tile's contribution.
+template <typename ST, bool FULL>
+__device__ __forceinline__ void consensus_tile_tiled(const ST *__restrict__ X, const RoundParams &prm, int64_t tile0,
+                                                     int lane, double &dist, double &msq) {
+    using S = Storage<ST>;
+    constexpr int VEC = S::VEC;
+    constexpr int LPR = kTiledLanes, GROUPS = 64 / LPR;
+    const int n = prm.n;
+    const int lg = lane / LPR, sub = lane % LPR;
+    const int64_t c0 = tile0 + sub * VEC;
+    const ST *Xl = X + tile0 * n + sub * VEC;
+    float p[VEC];
+    S::unpack(load_seg<ST, FULL>(Xl, c0, 0, prm.N), p);
+    double s1[VEC], s2[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) s1[e] = s2[e] = 0.0;
+    for (int i = lg; i < n; i += GROUPS) {   // row 0 (group 0) contributes y = 0
+        float v[VEC];
+        S::unpack(load_seg<ST, FULL>(Xl + (int64_t)i * prm.stride, c0, 0, prm.N), v);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+            const double y = (double)v[e] - (double)p[e];
+            s1[e] += y;
+            s2[e] = __builtin_fma(y, y, s2[e]);
+        }
+    }
+#pragma unroll
+    for (int o = LPR; o < 64; o <<= 1) {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+            s1[e] += __shfl_xor(s1[e], o, 64);
+            s2[e] += __shfl_xor(s2[e], o, 64);
+        }
+    }
+    if (lg == 0) {
+        const double inv_n = 1.0 / (double)n;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {   // columns outside [0, N) were loaded as 0 and add 0
+            const double m = s1[e] * inv_n;
+            dist += s2[e] - s1[e] * m;
+            const double mean = (double)p[e] + m;
+            msq = __builtin_fma(mean, mean, msq);
+        }
+    }
+}
+
 template <typename ST>
 __global__ __launch_bounds__(256) void consensus_kernel(const ST *__restrict__ X, const RoundParams prm,
                                                         double *__restrict__ partials) {
     constexpr int VEC = Storage<ST>::VEC;
-    constexpr int TILE = 64 * VEC;
     __shared__ double red[4][2];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t ntiles = (prm.N + TILE - 1) / TILE;
     double dist = 0.0, msq = 0.0;
-    for (int64_t t = (int64_t)blockIdx.x * 4 + wave; t < ntiles; t += (int64_t)gridDim.x * 4) {
-        LaneCols lc;
-        lc.tile0 = t * TILE;
-        lc.loff = (uint32_t)lane * VEC;
-        lc.lo = 0;
-        lc.hi = prm.N;
-        if (prm.vec_ok && lc.tile0 + TILE <= prm.N)
-            consensus_tile<ST, true>(X, prm, lc, dist, msq);
-        else
-            consensus_tile<ST, false>(X, prm, lc, dist, msq);
+    if (prm.tiled) {
+        constexpr int TILE = kTiledLanes * VEC;
+        const int64_t ntiles = (prm.N + TILE - 1) / TILE;
+        for (int64_t t = (int64_t)blockIdx.x * 4 + wave; t < ntiles; t += (int64_t)gridDim.x * 4) {
+            if (prm.vec_ok && (t + 1) * TILE <= prm.N)
+                consensus_tile_tiled<ST, true>(X, prm, t * TILE, lane, dist, msq);
+            else
+                consensus_tile_tiled<ST, false>(X, prm, t * TILE, lane, dist, msq);
+        }
+    } else {
+        constexpr int TILE = 64 * VEC;
+        const int64_t ntiles = (prm.N + TILE - 1) / TILE;
+        for (int64_t t = (int64_t)blockIdx.x * 4 + wave; t < ntiles; t += (int64_t)gridDim.x * 4) {
+            LaneCols lc;
+            lc.tile0 = t * TILE;
+            lc.base = lc.tile0;
+            lc.loff = (uint32_t)lane * VEC;
+            lc.lo = 0;
+            lc.hi = prm.N;
+            if (prm.vec_ok && lc.tile0 + TILE <= prm.N)
+                consensus_tile<ST, true>(X, prm, lc, dist, msq);
+            else
+                consensus_tile<ST, false>(X, prm, lc, dist, msq);
+        }
     }
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) {

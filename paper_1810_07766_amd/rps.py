@@ -13,6 +13,8 @@ LIB_PATH = os.path.join(_HERE, "librps.so")
 RPS_OK, RPS_EINVAL, RPS_ENOMEM, RPS_EHIP, RPS_EUNSUPPORTED = 0, -1, -2, -3, -4
 RPS_DTYPE_F32, RPS_DTYPE_BF16 = 0, 1
 RPS_FLAG_SERVER_IDENTITY = 1
+RPS_FLAG_LAYOUT_TILED = 2
+RPS_TILE_BYTES = 128
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(
@@ -27,6 +29,8 @@ _lib.rps_create.argtypes = [ctypes.POINTER(_ctx_p), ctypes.c_int32, ctypes.c_int
 _lib.rps_create_external.argtypes = [ctypes.POINTER(_ctx_p), ctypes.c_int32, ctypes.c_int32, ctypes.c_int64,
                                      ctypes.POINTER(ctypes.c_int64), ctypes.c_double, ctypes.c_float,
                                      ctypes.c_uint64, ctypes.c_int32, ctypes.c_void_p]
+_lib.rps_storage_elems.argtypes = [ctypes.c_int32, ctypes.c_int64, ctypes.c_int32, ctypes.c_uint32]
+_lib.rps_storage_elems.restype = ctypes.c_int64
 _lib.rps_destroy.argtypes = [_ctx_p]
 _lib.rps_set_synthetic_grad.argtypes = [_ctx_p, ctypes.c_float, ctypes.c_float]
 _lib.rps_set_gamma.argtypes = [_ctx_p, ctypes.c_float]
@@ -50,7 +54,7 @@ for _name in ("rps_create", "rps_create_external", "rps_destroy", "rps_set_synth
               "rps_consensus", "rps_estimate_mixing", "rps_set_launch_tuning", "rps_set_profiling", "rps_get_kernel_time", "rps_last_hip_error"):
     getattr(_lib, _name).restype = ctypes.c_int
 
-EXPORTS = ("rps_create", "rps_create_external", "rps_destroy", "rps_set_synthetic_grad", "rps_set_gamma", "rps_local_step",
+EXPORTS = ("rps_create", "rps_create_external", "rps_storage_elems", "rps_destroy", "rps_set_synthetic_grad", "rps_set_gamma", "rps_local_step",
            "rps_lossy_average", "rps_round", "rps_round_gradient_averaging", "rps_get_masks", "rps_set_mask_override",
            "rps_consensus", "rps_estimate_mixing", "rps_set_launch_tuning", "rps_set_profiling", "rps_get_kernel_time",
            "rps_last_hip_error",
@@ -79,7 +83,13 @@ def _ptr(t, ctx):
     if t is None:
         return None
     want = torch.float32 if ctx.dtype == RPS_DTYPE_F32 else torch.bfloat16
-    if not (t.is_cuda and t.is_contiguous() and t.dtype == want and tuple(t.shape) == (ctx.n, ctx.N)):
+    if not (t.is_cuda and t.is_contiguous() and t.dtype == want):
+        raise RpsError(RPS_EINVAL)
+    if ctx.flags & RPS_FLAG_LAYOUT_TILED:      # [tiles, n, tile width], see rps.h
+        T = RPS_TILE_BYTES // t.element_size()
+        if tuple(t.shape) != ((ctx.N + T - 1) // T, ctx.n, T):
+            raise RpsError(RPS_EINVAL)
+    elif tuple(t.shape) != (ctx.n, ctx.N):
         raise RpsError(RPS_EINVAL)
     return ctypes.c_void_p(t.data_ptr())
 
@@ -107,7 +117,7 @@ class RpsContext:
             _check(_lib.rps_create(ctypes.byref(handle), n, N, off, p, gamma, seed, dtype, flags,
                                    ctypes.c_void_p(stream)))
         self._h = handle
-        self.n, self.N, self.dtype, self.blocks = n, N, dtype, nb
+        self.n, self.N, self.dtype, self.blocks, self.flags = n, N, dtype, nb, flags
 
     def destroy(self):
         if getattr(self, "_h", None) and _lib is not None:   # (_lib is None at interpreter shutdown)
@@ -189,6 +199,10 @@ def rps_create(n, N, block_offsets, p, gamma, seed, dtype=RPS_DTYPE_F32, flags=0
 
 def rps_create_external(n, servers, N, block_offsets, p, gamma, seed, dtype=RPS_DTYPE_F32, stream=None):
     return RpsContext(n, N, p, gamma, seed, dtype, block_offsets, 0, stream, external_servers=servers)
+
+
+def rps_storage_elems(n, N, dtype=RPS_DTYPE_F32, flags=0):
+    return _lib.rps_storage_elems(n, N, dtype, flags)
 
 
 def rps_destroy(ctx):

@@ -436,3 +436,79 @@ def test_bf16_rounding_edge_cases(rps):
         got2 = to_oracle(Xg2)
         assert (got2[finite] == Xo2[finite]).all(), f"fused, gamma {gamma}"
         ctx.destroy()
+
+
+# ---------------------------------------------------------------------------------------------
+# Tile-major storage (RPS_FLAG_LAYOUT_TILED): same arithmetic on a re-arranged array.
+@pytest.mark.parametrize("n,N,layout,dtype", [SHAPES[k] for k in (0, 1, 3, 4, 6, 7, 8, 9, 10, 11, 12, 14, 15, 16)])
+def test_tiled_layout_every_entry_point(rps, n, N, layout, dtype):
+    """Each entry point on the tile-major array against the oracle (the library's tolerance) and
+    against the row-major run (same values; the fp64 column sums are taken in a different fixed
+    order, so a rare last-bit difference is allowed); the padding columns of the last tile are
+    never written; fused == unfused bit for bit within the layout."""
+    off = _offsets(n, N, layout, seed=21)
+    p, gamma, seed = 0.25, 0.3, 77
+    X0 = workloads.gaussian_model(n, N, seed=3)
+    G0 = workloads.gaussian_model(n, N, seed=4)
+    dt = _dt(rps, dtype)
+    assert rps.rps_storage_elems(n, N, dt, rps.RPS_FLAG_LAYOUT_TILED) == workloads.to_tiled(device_tensor(X0, dtype)).numel()
+    assert rps.rps_storage_elems(n, N, dt, 0) == n * N
+    rm = rps.RpsContext(n, N, p, gamma, seed, dt, block_offsets=off)
+    tl = rps.RpsContext(n, N, p, gamma, seed, dt, block_offsets=off, flags=rps.RPS_FLAG_LAYOUT_TILED)
+    for c in (rm, tl):
+        c.set_synthetic_grad(0.5, 0.01)
+    Xr, Gr = device_tensor(X0, dtype), device_tensor(G0, dtype)
+    T = workloads.TILE_BYTES // Xr.element_size()
+    sentinel = 12288.0   # exactly representable in bf16
+
+    def tiled(t):
+        tt = workloads.to_tiled(t)
+        if N % T:
+            tt[-1, :, N % T:] = sentinel
+        return tt
+
+    Xt, Gt = tiled(Xr), tiled(Gr)
+    Xo = to_oracle(Xr)
+    calls = [("round", None), ("round", "G"), ("local_step", None), ("lossy_average", None), ("local_step", "G"),
+             ("round", None), ("lossy_average", None)]
+    for t, (what, g) in enumerate(calls):
+        if what == "round":
+            unfused = Xt.clone()
+            rm.round(Xr, Gr if g else None, t); tl.round(Xt, Gt if g else None, t)
+            tl.local_step(unfused, Gt if g else None, t); tl.lossy_average(unfused, t)
+            assert torch.equal(unfused, Xt), f"call {t}: fused and unfused differ in the tiled layout"
+            oracle.round_(Xo, to_oracle(Gr) if g else None, off, p=p, gamma=gamma, seed=seed, step=t, sigma=0.5,
+                          weight_decay=0.01)
+        elif what == "local_step":
+            rm.local_step(Xr, Gr if g else None, t); tl.local_step(Xt, Gt if g else None, t)
+            oracle.local_step(Xo, to_oracle(Gr) if g else None, gamma, sigma=0.5, weight_decay=0.01, seed=seed, step=t)
+        else:
+            rm.lossy_average(Xr, t); tl.lossy_average(Xt, t)
+            _, U, D = oracle.masks(seed, t, n, p)
+            oracle.lossy_average(Xo, off, U, D)
+        back = workloads.from_tiled(Xt, N)
+        assert_close(to_oracle(back), Xo, off, dtype, what=f"tiled call {t} ({what}) against the oracle")
+        if what == "local_step":
+            assert torch.equal(back, Xr)                              # no sums involved: bit for bit
+        else:
+            assert int((back != Xr).sum()) <= max(1, n * N // 10_000), "tiled and row-major differ in more than stray last bits"
+            assert_close(to_oracle(back), to_oracle(Xr), off, dtype, what=f"tiled call {t} ({what}) against row-major")
+            Xt.copy_(tiled(Xr))                                       # continue from a common state
+        if N % T:
+            assert bool((Xt[-1, :, N % T:] == sentinel).all()), "padding was written"
+    d_t, m_t = tl.consensus(Xt)
+    d_r, m_r = rm.consensus(Xr)
+    assert abs(d_t - d_r) <= 1e-12 * d_r and abs(m_t - m_r) <= 1e-12 * m_r
+    with pytest.raises(rps.RpsError) as err:
+        tl.round_gradient_averaging(Xt, Gt, 0)
+    assert err.value.code == rps.RPS_EUNSUPPORTED
+    rm.destroy(); tl.destroy()
+
+
+def test_tiled_layout_shape_is_checked(rps):
+    ctx = rps.RpsContext(4, 1000, 0.1, 0.1, 0, flags=rps.RPS_FLAG_LAYOUT_TILED)
+    with pytest.raises(rps.RpsError):
+        ctx.round(torch.zeros(4, 1000, device="cuda"), None, 0)        # row-major array handed to a tiled context
+    ctx.round(torch.zeros(32, 4, 32, device="cuda"), None, 0)
+    ctx.destroy()
+    assert rps.rps_storage_elems(0, 10, 0, 0) == -1 and rps.rps_storage_elems(4, 1000, 1, 2) == 16 * 4 * 64

@@ -164,3 +164,26 @@ def mlp_loss_and_grad(cfg: Config, X, xb, yb):
     loss = ((out - yb) ** 2).mean(dim=(1, 2))
     (G,) = torch.autograd.grad(loss.sum(), Xp)
     return loss.detach(), G.contiguous()
+
+
+TILE_BYTES = 128   # the library's tile-major storage: segments of 128 bytes per (tile, worker)
+
+
+def to_tiled(X):
+    """[n, N] -> [ceil(N/T), n, T] (T = 128 bytes of elements; columns beyond N are zero padding).
+    Pure re-arrangement of a torch tensor or numpy array; no arithmetic."""
+    import torch
+    t = torch.as_tensor(X)
+    n, N = t.shape
+    T = TILE_BYTES // t.element_size()
+    tiles = (N + T - 1) // T
+    if tiles * T != N:
+        pad = torch.zeros(n, tiles * T - N, dtype=t.dtype, device=t.device)
+        t = torch.cat([t, pad], dim=1)
+    return t.reshape(n, tiles, T).permute(1, 0, 2).contiguous()
+
+
+def from_tiled(Xt, N):
+    """Inverse of to_tiled: [tiles, n, T] -> [n, N]."""
+    tiles, n, T = Xt.shape
+    return Xt.permute(1, 0, 2).reshape(n, tiles * T)[:, :N].contiguous()
