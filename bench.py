@@ -5,6 +5,9 @@ A "step" is one pass of the whole hot path over the workload: mask generation + 
 SGD step (in-register synthetic Gaussian gradient) + Reduce-Scatter average + All-Gather
 write-back, for all n workers and all N parameters, in place in HBM.
 
+The state is held in the library's tile-major layout by default (row-major with --layout
+row-major; the other layout is measured as well and reported under "other_layout").
+
 Prints ONE JSON line: worker-params averaged per second (n*N per round), the HBM roofline of
 the round kernel (algorithmic bytes = 2*sizeof(dtype) per worker-param, i.e. one read and one
 write of the state, divided by the kernel's mean duration measured with HIP events on the
@@ -26,7 +29,7 @@ HBM_PEAK_GBS = 8000.0     # MI355X published HBM3E bandwidth
 # each scaled by what the same counter reads for a plain 1 GiB device copy; the commands and
 # the raw figures are in profiles/round_kernel_resnet50_n32_hbm_traffic.md).  Counters cannot
 # be read from inside this process, so the measured value is recorded here per workload.
-MEASURED_TRAFFIC_BYTES = {"resnet50_n32": 6.5539e9}
+MEASURED_TRAFFIC_BYTES = {("resnet50_n32", "row-major"): 6.5539e9}
 
 
 def cpu_baseline(cfg, off, budget_cols):
@@ -93,36 +96,20 @@ def other_paths(ctx, cfg, X, G, step, torch, launches=30):
     return res
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=100)
-    ap.add_argument("--warmup", type=int, default=30)
-    ap.add_argument("--config", default=None, help="workload name (default: the headline config)")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--other-paths", action="store_true",
-                    help="also time the unfused entry points and the gradient-buffer round on the same workload "
-                         "(needs a second [n, N] array) and report each against its own algorithmic bytes")
-    ap.add_argument("--pmc-calibration", action="store_true",
-                    help="also run three plain 1 GiB device copies (a kernel of known traffic) so that one "
-                         "rocprofv3 --pmc run holds both the round kernel and the reference for its counters")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (the n workers are simulated in one [n, N] tensor); "
-              "--gpus must be 1", file=sys.stderr)
-        sys.exit(2)
-
-    import torch
-    import workloads
-    from paper_1810_07766_amd import rps
-
-    cfg = workloads.CONFIGS[args.config or workloads.HEADLINE]
-    off = workloads.config_offsets(cfg)
-    torch.cuda.set_device(0)
+def measure(cfg, off, layout, args, torch, rps, want_other_paths):
+    """Warm-up, the timed region, then the event-bracketed pass of the round kernel, for one storage layout."""
+    tiled = layout == "tiled"
     tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
-    X = torch.zeros(cfg.n, cfg.N, device="cuda", dtype=tdt)       # Alg. 1: identical start, X_1 = 0
+    elem = 2 if cfg.dtype == "bf16" else 4
+    if tiled:
+        T = rps.RPS_TILE_BYTES // elem
+        shape = ((cfg.N + T - 1) // T, cfg.n, T)
+    else:
+        shape = (cfg.n, cfg.N)
+    X = torch.zeros(shape, device="cuda", dtype=tdt)              # Alg. 1: identical start, X_1 = 0
     ctx = rps.RpsContext(cfg.n, cfg.N, cfg.p, cfg.gamma, cfg.seed,
-                         rps.RPS_DTYPE_BF16 if cfg.dtype == "bf16" else rps.RPS_DTYPE_F32, block_offsets=off)
+                         rps.RPS_DTYPE_BF16 if cfg.dtype == "bf16" else rps.RPS_DTYPE_F32, block_offsets=off,
+                         flags=rps.RPS_FLAG_LAYOUT_TILED if tiled else 0)
     ctx.set_synthetic_grad(cfg.sigma, cfg.weight_decay)
     # workloads whose gradient comes from a model (least squares, MLP): the library's part of a
     # step is the fused round on a caller-supplied gradient buffer; a fixed seeded buffer stands
@@ -130,7 +117,7 @@ def main():
     G = None
     if cfg.gradient != "synthetic":
         gen = torch.Generator(device="cuda"); gen.manual_seed(1)
-        G = (torch.randn(cfg.n, cfg.N, device="cuda", generator=gen) * 1e-3).to(tdt)
+        G = (torch.randn(shape, device="cuda", generator=gen) * 1e-3).to(tdt)
 
     step = 0
     for _ in range(args.warmup):
@@ -151,30 +138,77 @@ def main():
     assert launches == args.steps
     kernel_ms /= launches
 
-    elem = 2 if cfg.dtype == "bf16" else 4
     alg_bytes = (3.0 if G is not None else 2.0) * elem * cfg.n * cfg.N   # read x (and g) once, write x' once
-    achieved = alg_bytes / (kernel_ms * 1e-3) / 1e9
+    res = {"value": cfg.n * cfg.N * args.steps / dt, "ms_per_step": dt / args.steps * 1e3, "kernel_ms": kernel_ms,
+           "alg_bytes": alg_bytes, "achieved": alg_bytes / (kernel_ms * 1e-3) / 1e9, "has_G": G is not None}
+    if want_other_paths:
+        res["other_paths"] = other_paths(ctx, cfg, X, G, step, torch)
+    ctx.destroy()
+    del X, G
+    torch.cuda.empty_cache()
+    return res
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=30)
+    ap.add_argument("--config", default=None, help="workload name (default: the headline config)")
+    ap.add_argument("--layout", choices=("tiled", "row-major"), default=None,
+                    help="storage layout of X and G (default: tiled for fp32 workloads, row-major for bf16; "
+                         "the other layout is measured too and reported under other_layout)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--other-paths", action="store_true",
+                    help="also time the unfused entry points and the gradient-buffer round on the same workload "
+                         "(needs a second array of the state's size) and report each against its own algorithmic bytes")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run three plain 1 GiB device copies (a kernel of known traffic) so that one "
+                         "rocprofv3 --pmc run holds both the round kernel and the reference for its counters; "
+                         "measures the chosen layout only")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the n workers are simulated in one [n, N] tensor); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import workloads
+    from paper_1810_07766_amd import rps
+
+    cfg = workloads.CONFIGS[args.config or workloads.HEADLINE]
+    off = workloads.config_offsets(cfg)
+    torch.cuda.set_device(0)
+    layout = args.layout or ("row-major" if cfg.dtype == "bf16" else "tiled")
+    other = "row-major" if layout == "tiled" else "tiled"
+
+    m = measure(cfg, off, layout, args, torch, rps, args.other_paths)
+    kernel = "round_kernel_narrow" if layout == "tiled" else "round_kernel"
     out = {
         "metric": "worker-params averaged/sec (n*N per round)",
-        "value": cfg.n * cfg.N * args.steps / dt,
+        "value": m["value"],
         "unit": "worker-params/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": dt / args.steps * 1e3,
+        "ms_per_step": m["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32" if cfg.dtype == "f32" else "bf16-storage/f32-math",
         "data": "synthetic",
         "config": {"workload": cfg.name, "n": cfg.n, "N": cfg.N, "p": cfg.p, "gamma": cfg.gamma,
-                   "gradient": (f"in-register N(0,{cfg.sigma ** 2:.3g}) + {cfg.weight_decay}*x" if G is None
+                   "gradient": (f"in-register N(0,{cfg.sigma ** 2:.3g}) + {cfg.weight_decay}*x" if not m["has_G"]
                                 else "caller-supplied buffer G[n,N] (seeded stand-in)"),
-                   "blocks": "unequal" if cfg.unequal_blocks else "equal"},
-        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name),
-                     "kernel": "round_kernel", "kernel_ms": kernel_ms, "algorithmic_bytes": alg_bytes},
+                   "blocks": "unequal" if cfg.unequal_blocks else "equal",
+                   "layout": ("tile-major [N/T][n][T], T = 128 bytes" if layout == "tiled" else "row-major [n][N]")},
+        "roofline": {"bound": "hbm", "achieved": m["achieved"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": m["achieved"] / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.name, layout)),
+                     "kernel": kernel, "kernel_ms": m["kernel_ms"], "algorithmic_bytes": m["alg_bytes"]},
     }
-    if args.other_paths:
-        out["other_paths"] = other_paths(ctx, cfg, X, G, step, torch)
-    ctx.destroy()
-    del X, G
+    if "other_paths" in m:
+        out["other_paths"] = m["other_paths"]
+    if not args.pmc_calibration:
+        o = measure(cfg, off, other, args, torch, rps, False)
+        out["other_layout"] = {"layout": other, "value": o["value"], "ms_per_step": o["ms_per_step"],
+                               "kernel_ms": o["kernel_ms"], "achieved": o["achieved"], "unit": "GB/s",
+                               "frac": o["achieved"] / HBM_PEAK_GBS}
     if args.pmc_calibration:
         src = torch.ones(1 << 28, device="cuda")          # 1 GiB of fp32
         dst = torch.empty_like(src)

@@ -70,8 +70,14 @@ rps::LaunchTuning default_tuning(int32_t n, int32_t dtype, int grad_mode) {
 
 rps::LaunchTuning tuning_for(const rps_ctx *ctx, int grad_mode) {
     if (ctx->tune_set) return ctx->tune;
-    if (ctx->flags & RPS_FLAG_LAYOUT_TILED)   // small tiles, one piece of memory each: more wavefronts resident
-        return rps::LaunchTuning{4, 1, grad_mode == rps::kGradSynthetic ? 16 : 12};
+    if (ctx->flags & RPS_FLAG_LAYOUT_TILED) {   // small tiles, one piece of memory each: more wavefronts resident
+        const int n = ctx->n;                    // (measured at n = 8 / 16 / 32 fp32 and n = 64 bf16)
+        int cap;
+        if (grad_mode == rps::kGradSynthetic) cap = n >= 24 ? 24 : 0;
+        else if (grad_mode == rps::kGradNone) cap = n >= 48 ? 8 : (n >= 24 ? 12 : 24);
+        else cap = n >= 24 ? 12 : (n >= 12 ? 20 : 0);
+        return rps::LaunchTuning{4, 1, cap};
+    }
     return default_tuning(ctx->n, ctx->dtype, grad_mode);
 }
 

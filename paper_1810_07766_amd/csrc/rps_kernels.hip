@@ -588,13 +588,14 @@ __device__ __forceinline__ void store_seg(ST *p, int64_t c0, int64_t lo, int64_t
     }
 }
 
-template <typename ST, int GRAD, int LPR, bool FULL>
+template <typename ST, int GRAD, int LPR, int CP, bool FULL>
 struct NarrowTile {
     using S = Storage<ST>;
     using Raw = typename S::Raw;
     static constexpr int VEC = S::VEC;
     static constexpr int GROUPS = 64 / LPR;   // lane groups = rows per wavefront instruction
-    static constexpr int CP = 2;              // row pairs per lane and load chunk (4 rows in flight per chunk)
+    // CP = row pairs per lane and load chunk (2 * CP rows in flight per chunk): 1 up to 16 workers
+    // (a lane then has a single pair), else 2
     static constexpr int CG = GRAD == kGradBuffer ? 2 * CP : 1;
 
     const RoundParams &prm;
@@ -639,13 +640,17 @@ struct NarrowTile {
     }
 
     __device__ __forceinline__ void process_chunk(int k0, const Raw x[2 * CP], const Raw g[CG], double acc[VEC]) const {
+        // the noise does not depend on the loaded values: all of it first, under the loads' latency
+        float za[CP][VEC], zb[CP][VEC];
+        if (GRAD == kGradSynthetic) {
+#pragma unroll
+            for (int q = 0; q < CP; ++q) noise_rows<VEC>(prm, row_a(k0 + q) >> 1, c0, za[q], zb[q]);
+        }
 #pragma unroll
         for (int q = 0; q < CP; ++q) {
             const int ia = row_a(k0 + q);
-            float za[VEC], zb[VEC];
-            if (GRAD == kGradSynthetic) noise_rows<VEC>(prm, ia >> 1, c0, za, zb);
-            row(ia, x[2 * q], g[GRAD == kGradBuffer ? 2 * q : 0], za, acc);
-            row(ia + 1, x[2 * q + 1], g[GRAD == kGradBuffer ? 2 * q + 1 : 0], zb, acc);
+            row(ia, x[2 * q], g[GRAD == kGradBuffer ? 2 * q : 0], za[q], acc);
+            row(ia + 1, x[2 * q + 1], g[GRAD == kGradBuffer ? 2 * q + 1 : 0], zb[q], acc);
         }
 #pragma unroll
         for (int q = 0; q < 2 * CP; ++q) asm volatile("" ::"v"(x[q]));   // see process_chunk of the wide kernel
@@ -696,7 +701,7 @@ struct NarrowTile {
     }
 };
 
-template <typename ST, int GRAD, int LPR>
+template <typename ST, int GRAD, int LPR, int CP>
 __global__ __launch_bounds__(64) void round_kernel_narrow(ST *__restrict__ X, const ST *__restrict__ G,
                                                           const RoundTable *__restrict__ tab, const RoundParams prm) {
     constexpr int VEC = Storage<ST>::VEC;
@@ -710,11 +715,11 @@ __global__ __launch_bounds__(64) void round_kernel_narrow(ST *__restrict__ X, co
     const int64_t lane_off = tile_base(prm, tile0) + sub * VEC;
     const bool full = prm.vec_ok && tile0 >= lo && tile0 + TILE <= hi;   // wave-uniform
     if (full) {
-        const NarrowTile<ST, GRAD, LPR, true> t{prm, X + lane_off, G ? G + lane_off : nullptr, tile0 + sub * VEC, lo, hi,
+        const NarrowTile<ST, GRAD, LPR, CP, true> t{prm, X + lane_off, G ? G + lane_off : nullptr, tile0 + sub * VEC, lo, hi,
                                                 tab->ucol[j], tab->dcol[j], lane / LPR};
         t.run(tab->inv_cnt[j]);
     } else {
-        const NarrowTile<ST, GRAD, LPR, false> t{prm, X + lane_off, G ? G + lane_off : nullptr, tile0 + sub * VEC, lo, hi,
+        const NarrowTile<ST, GRAD, LPR, CP, false> t{prm, X + lane_off, G ? G + lane_off : nullptr, tile0 + sub * VEC, lo, hi,
                                                  tab->ucol[j], tab->dcol[j], lane / LPR};
         t.run(tab->inv_cnt[j]);
     }
@@ -836,7 +841,10 @@ hipError_t launch_round_narrow(ST *X, const ST *G, const RoundTable *tab, const 
         lds = ((size_t)kLdsBytesPerCu / max_waves_per_cu) & ~(size_t)255;
         if (lds > 65536) lds = 65536;
     }
-    hipLaunchKernelGGL((round_kernel_narrow<ST, GRAD, LPR>), grid, dim3(64), lds, stream, X, G, tab, prm);
+    if (prm.n <= 2 * (64 / LPR))
+        hipLaunchKernelGGL((round_kernel_narrow<ST, GRAD, LPR, 1>), grid, dim3(64), lds, stream, X, G, tab, prm);
+    else
+        hipLaunchKernelGGL((round_kernel_narrow<ST, GRAD, LPR, 2>), grid, dim3(64), lds, stream, X, G, tab, prm);
     return hipGetLastError();
 }
 
@@ -1058,14 +1066,26 @@ __device__ __forceinline__ void consensus_tile_tiled(const ST *__restrict__ X, c
     double s1[VEC], s2[VEC];
 #pragma unroll
     for (int e = 0; e < VEC; ++e) s1[e] = s2[e] = 0.0;
-    for (int i = lg; i < n; i += GROUPS) {   // row 0 (group 0) contributes y = 0
-        float v[VEC];
-        S::unpack(load_seg<ST, FULL>(Xl + (int64_t)i * prm.stride, c0, 0, prm.N), v);
+    constexpr int R = 4;   // rows in flight per lane
+    for (int i0 = lg; i0 < n; i0 += R * GROUPS) {   // row 0 (group 0) contributes y = 0
+        typename S::Raw x[R];
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) {
-            const double y = (double)v[e] - (double)p[e];
-            s1[e] += y;
-            s2[e] = __builtin_fma(y, y, s2[e]);
+        for (int r = 0; r < R; ++r) {   // rows past n repeat the lane's last row, unused
+            const int i = i0 + r * GROUPS;
+            x[r] = load_seg<ST, FULL>(Xl + (int64_t)(i < n ? i : i0) * prm.stride, c0, 0, prm.N);
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            if (i0 + r * GROUPS < n) {
+                float v[VEC];
+                S::unpack(x[r], v);
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) {
+                    const double y = (double)v[e] - (double)p[e];
+                    s1[e] += y;
+                    s2[e] = __builtin_fma(y, y, s2[e]);
+                }
+            }
         }
     }
 #pragma unroll

@@ -36,14 +36,23 @@ def _seeded_state(cfg, scale, seed):
     return X
 
 
-def _sampled_trajectory(rps, cfg, p, rounds, init_scale, per_block=40):
+def _sampled_trajectory(rps, cfg, p, rounds, init_scale, per_block=40, tiled=False):
+    """The HIP path on the full state (row-major or tile-major), the oracle on sampled columns."""
     off = workloads.config_offsets(cfg)
     cols = workloads.sample_columns(off, per_block=per_block, seed=11)
     X = _seeded_state(cfg, init_scale, seed=5)
     idx = torch.from_numpy(cols).cuda()
     Xo = to_oracle(X.index_select(1, idx))
+    if tiled:
+        X = workloads.to_tiled(X)
+        T = X.shape[2]
+
+    def sample():
+        return to_oracle(X[idx // T, :, idx % T].t().contiguous() if tiled else X.index_select(1, idx))
+
     ctx = rps.RpsContext(cfg.n, cfg.N, p, cfg.gamma, cfg.seed,
-                         rps.RPS_DTYPE_BF16 if cfg.dtype == "bf16" else rps.RPS_DTYPE_F32, block_offsets=off)
+                         rps.RPS_DTYPE_BF16 if cfg.dtype == "bf16" else rps.RPS_DTYPE_F32, block_offsets=off,
+                         flags=rps.RPS_FLAG_LAYOUT_TILED if tiled else 0)
     ctx.set_synthetic_grad(cfg.sigma, cfg.weight_decay)
     worst = 0.0
     for t in range(rounds):
@@ -52,14 +61,14 @@ def _sampled_trajectory(rps, cfg, p, rounds, init_scale, per_block=40):
                       weight_decay=cfg.weight_decay, cols=cols)
         if t < 3 or t == rounds - 1 or t % 10 == 0:
             masks_equal(ctx, cfg.seed, t, cfg.n, p)
-            got = to_oracle(X.index_select(1, idx))
-            worst = max(worst, assert_close(got, Xo, off, cfg.dtype, cols=cols, what=f"{cfg.name} p={p} round {t}"))
+            worst = max(worst, assert_close(sample(), Xo, off, cfg.dtype, cols=cols, what=f"{cfg.name} p={p} round {t}"))
     # properties that hold at any size, checked on the whole last state: per block, every worker
     # whose reply arrived holds the same bits
     server, U, D = oracle.masks(cfg.seed, rounds - 1, cfg.n, p)
+    Xrm = workloads.from_tiled(X, cfg.N) if tiled else X
     for j in (0, cfg.n // 2, cfg.n - 1):
         recv = np.flatnonzero(D[:, j])
-        blk = X[:, int(off[j]):int(off[j + 1])]
+        blk = Xrm[:, int(off[j]):int(off[j + 1])]
         ref = blk[int(recv[0])]
         for i in recv[1:]:
             assert torch.equal(blk[int(i)], ref)
@@ -136,6 +145,16 @@ def test_config_resnet50_n32_sampled(rps):
 def test_config_resnet50_n32_sampled_random_start(rps):
     cfg = workloads.CONFIGS["resnet50_n32"]
     _sampled_trajectory(rps, cfg, cfg.p, 10, init_scale=0.02)
+
+
+@pytest.mark.parametrize("name,rounds,init", [("resnet50_n32", 50, 0.0), ("resnet50_n32", 10, 0.02),
+                                               ("resnet18_n16", 50, 0.0), ("bert_n64_bf16", 8, 0.0)])
+def test_config_tiled_layout_sampled(rps, name, rounds, init):
+    """The benchmark workloads in the tile-major layout (the launch configuration bench.py times for
+    the fp32 workloads), the oracle on sampled columns; the bf16 workload's width is not a
+    multiple of the tile, so its last tile is padded."""
+    cfg = workloads.CONFIGS[name]
+    _sampled_trajectory(rps, cfg, cfg.p, rounds, init_scale=init, per_block=24 if cfg.n == 64 else 40, tiled=True)
 
 
 def test_config_bert_n64_bf16_sampled(rps):
