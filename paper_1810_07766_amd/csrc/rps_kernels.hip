@@ -593,33 +593,36 @@ struct NarrowTile {
     using S = Storage<ST>;
     using Raw = typename S::Raw;
     static constexpr int VEC = S::VEC;
-    static constexpr int GROUPS = 64 / LPR;   // lane groups = rows per wavefront instruction
+    static constexpr int GROUPS = 64 / LPR;      // lane groups = rows per wavefront instruction
+    static constexpr uint32_t STRIDE = LPR * VEC;   // elements between consecutive rows of a tile (tiled layout)
     // CP = row pairs per lane and load chunk (2 * CP rows in flight per chunk): 1 up to 16 workers
     // (a lane then has a single pair), else 2
     static constexpr int CG = GRAD == kGradBuffer ? 2 * CP : 1;
 
     const RoundParams &prm;
-    ST *Xl;            // (row 0, this lane's columns)
-    const ST *Gl;
+    ST *Xt;            // the tile: wave-uniform base, every access adds a 32-bit lane offset
+    const ST *Gt;
+    uint32_t sub_off;  // this lane's columns inside a row segment
     int64_t c0, lo, hi;
     uint64_t ucol, dcol;
     int lg;
 
     // rows of the lane's k-th pair
     __device__ __forceinline__ int row_a(int k) const { return 2 * (lg + GROUPS * k); }
+    __device__ __forceinline__ uint32_t off(int i) const { return (uint32_t)i * STRIDE + sub_off; }
 
     __device__ __forceinline__ void load_chunk(int k0, Raw x[2 * CP], Raw g[CG]) const {
         const int last = prm.n - 1;
 #pragma unroll
         for (int q = 0; q < CP; ++q) {
             const int ia = row_a(k0 + q);
-            const int64_t oa = (int64_t)(ia < last ? ia : last) * prm.stride;          // rows past n repeat row n-1, unused
-            const int64_t ob = (int64_t)(ia + 1 < last ? ia + 1 : last) * prm.stride;
-            x[2 * q] = load_seg<ST, FULL>(Xl + oa, c0, lo, hi);
-            x[2 * q + 1] = load_seg<ST, FULL>(Xl + ob, c0, lo, hi);
+            const uint32_t oa = off(ia < last ? ia : last);           // rows past n repeat row n-1, unused
+            const uint32_t ob = off(ia + 1 < last ? ia + 1 : last);
+            x[2 * q] = load_seg<ST, FULL>(Xt + oa, c0, lo, hi);
+            x[2 * q + 1] = load_seg<ST, FULL>(Xt + ob, c0, lo, hi);
             if (GRAD == kGradBuffer) {
-                g[GRAD == kGradBuffer ? 2 * q : 0] = load_seg<ST, FULL>(Gl + oa, c0, lo, hi);
-                g[GRAD == kGradBuffer ? 2 * q + 1 : 0] = load_seg<ST, FULL>(Gl + ob, c0, lo, hi);
+                g[GRAD == kGradBuffer ? 2 * q : 0] = load_seg<ST, FULL>(Gt + oa, c0, lo, hi);
+                g[GRAD == kGradBuffer ? 2 * q + 1 : 0] = load_seg<ST, FULL>(Gt + ob, c0, lo, hi);
             }
         }
     }
@@ -636,7 +639,7 @@ struct NarrowTile {
 #pragma unroll
             for (int e = 0; e < VEC; ++e) acc[e] += (double)v[e];
         }
-        if (GRAD != kGradNone && !d) store_seg<ST, FULL>(Xl + (int64_t)i * prm.stride, c0, lo, hi, vr);
+        if (GRAD != kGradNone && !d) store_seg<ST, FULL>(Xt + off(i), c0, lo, hi, vr);
     }
 
     __device__ __forceinline__ void process_chunk(int k0, const Raw x[2 * CP], const Raw g[CG], double acc[VEC]) const {
@@ -694,13 +697,14 @@ struct NarrowTile {
         const Raw vt_raw = S::round_vec(vt);
         for (int q = 0; q < steps; ++q) {
             const int ia = row_a(q);
-            if (ia < n && ((dcol >> ia) & 1)) store_seg<ST, FULL>(Xl + (int64_t)ia * prm.stride, c0, lo, hi, vt_raw);
-            if (ia + 1 < n && ((dcol >> (ia + 1)) & 1))
-                store_seg<ST, FULL>(Xl + (int64_t)(ia + 1) * prm.stride, c0, lo, hi, vt_raw);
+            if (ia < n && ((dcol >> ia) & 1)) store_seg<ST, FULL>(Xt + off(ia), c0, lo, hi, vt_raw);
+            if (ia + 1 < n && ((dcol >> (ia + 1)) & 1)) store_seg<ST, FULL>(Xt + off(ia + 1), c0, lo, hi, vt_raw);
         }
     }
 };
 
+// Tiled layout only: the tile [tile0, tile0 + LPR * VEC) of all n workers is the contiguous run of
+// n * LPR * 16 bytes at element offset tile0 * n.
 template <typename ST, int GRAD, int LPR, int CP>
 __global__ __launch_bounds__(64) void round_kernel_narrow(ST *__restrict__ X, const ST *__restrict__ G,
                                                           const RoundTable *__restrict__ tab, const RoundParams prm) {
@@ -711,16 +715,17 @@ __global__ __launch_bounds__(64) void round_kernel_narrow(ST *__restrict__ X, co
     const int64_t lo = tab->off[j], hi = tab->off[j + 1];
     const int64_t tile0 = (lo / TILE) * TILE + (int64_t)blockIdx.x * TILE;
     if (tile0 >= hi) return;   // wave-uniform
-    const int sub = lane % LPR;
-    const int64_t lane_off = tile_base(prm, tile0) + sub * VEC;
+    const uint32_t sub_off = (uint32_t)(lane % LPR) * VEC;
+    ST *Xt = X + tile0 * prm.n;
+    const ST *Gt = G ? G + tile0 * prm.n : nullptr;
     const bool full = prm.vec_ok && tile0 >= lo && tile0 + TILE <= hi;   // wave-uniform
     if (full) {
-        const NarrowTile<ST, GRAD, LPR, CP, true> t{prm, X + lane_off, G ? G + lane_off : nullptr, tile0 + sub * VEC, lo, hi,
-                                                tab->ucol[j], tab->dcol[j], lane / LPR};
+        const NarrowTile<ST, GRAD, LPR, CP, true> t{prm, Xt, Gt, sub_off, tile0 + sub_off, lo, hi,
+                                                    tab->ucol[j], tab->dcol[j], lane / LPR};
         t.run(tab->inv_cnt[j]);
     } else {
-        const NarrowTile<ST, GRAD, LPR, CP, false> t{prm, X + lane_off, G ? G + lane_off : nullptr, tile0 + sub * VEC, lo, hi,
-                                                 tab->ucol[j], tab->dcol[j], lane / LPR};
+        const NarrowTile<ST, GRAD, LPR, CP, false> t{prm, Xt, Gt, sub_off, tile0 + sub_off, lo, hi,
+                                                     tab->ucol[j], tab->dcol[j], lane / LPR};
         t.run(tab->inv_cnt[j]);
     }
 }
