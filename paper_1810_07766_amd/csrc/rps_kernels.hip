@@ -12,7 +12,10 @@
 //   round_kernel      local SGD step + Reduce-Scatter average + All-Gather write-back in one
 //                     pass; every wavefront owns one tile (64 lanes x 16 bytes) of one block
 //                     and walks all n rows of it, no LDS and no barrier
-//   local_step_kernel the local SGD step alone, one row per wavefront (contiguous streams)
+//   round_kernel_narrow  the same round on the tile-major layout: a wavefront owns the contiguous
+//                     n x 128 bytes of a 128-byte-wide tile, 8 rows per instruction
+//   local_step_kernel the local SGD step alone, one row per wavefront (contiguous streams);
+//                     local_step_tiled_kernel: the same on the tile-major layout
 //   gradavg_kernel    the gradient-averaging comparison of Sec. 6 (same masks applied to G)
 //   consensus_kernel  sum_i ||x_i - xbar||^2 and ||xbar||^2 in one streaming read (Lemma 1's quantity)
 // The path is a streaming reduction with < 0.5 flop per byte: it is bound by HBM bandwidth

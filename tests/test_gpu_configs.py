@@ -163,7 +163,8 @@ def test_config_bert_n64_bf16_sampled(rps):
     _sampled_trajectory(rps, cfg, cfg.p, cfg.rounds, init_scale=0.0, per_block=24)
 
 
-def test_config_mlp_n8_loss_tracks_oracle(rps):
+@pytest.mark.parametrize("tiled", [False, True])
+def test_config_mlp_n8_loss_tracks_oracle(rps, tiled):
     """n=8 workers, 2-layer MLP 1024->2048->1024 (N = 4,194,304), teacher targets, batch 256 per
     worker, p = 0.2, 200 rounds.  Gradients come from PyTorch (GPU side: on the GPU from the GPU
     state; oracle side: on the CPU from the oracle's state), the round from the library / the
@@ -174,13 +175,24 @@ def test_config_mlp_n8_loss_tracks_oracle(rps):
     teacher, X0 = workloads.mlp_problem(cfg, seed=cfg.seed)
     Xg = X0.cuda()
     Xo = X0.numpy().copy()
-    ctx = rps.RpsContext(cfg.n, cfg.N, cfg.p, cfg.gamma, cfg.seed)
+    ctx = rps.RpsContext(cfg.n, cfg.N, cfg.p, cfg.gamma, cfg.seed, flags=rps.RPS_FLAG_LAYOUT_TILED if tiled else 0)
     threads = min(16, oracle.max_threads())
     first = last = None
+
+    def gpu_round(X, G, t):
+        """The library's round on [n, N] tensors; in the tile-major run through re-arranged copies
+        (the model's forward/backward wants each worker's parameters contiguous)."""
+        if not tiled:
+            ctx.round(X, G, t)
+            return
+        Xt = workloads.to_tiled(X)
+        ctx.round(Xt, workloads.to_tiled(G), t)
+        X.copy_(workloads.from_tiled(Xt, cfg.N))
+
     for t in range(cfg.rounds):
         xb, yb = workloads.mlp_batch(cfg, teacher, t, seed=7)
         lg, Gg = workloads.mlp_loss_and_grad(cfg, Xg, xb.cuda(), yb.cuda())
-        ctx.round(Xg, Gg, t)
+        gpu_round(Xg, Gg, t)
         lo, Go = workloads.mlp_loss_and_grad(cfg, torch.from_numpy(Xo), xb, yb)
         oracle.round_(Xo, Go.numpy(), off, p=cfg.p, gamma=cfg.gamma, seed=cfg.seed, step=t, threads=threads)
         lgm, lom = float(lg.mean()), float(lo.mean())
@@ -196,7 +208,7 @@ def test_config_mlp_n8_loss_tracks_oracle(rps):
     assert np.abs(got.mean(axis=0) - ref.mean(axis=0)).max() <= 1e-3 * np.sqrt(np.mean(ref ** 2))
     # the round itself, from the oracle's final state and gradient, still matches element-wise
     Xs = torch.from_numpy(Xo).cuda()
-    ctx.round(Xs, Go.cuda(), cfg.rounds)
+    gpu_round(Xs, Go.cuda(), cfg.rounds)
     oracle.round_(Xo, Go.numpy(), off, p=cfg.p, gamma=cfg.gamma, seed=cfg.seed, step=cfg.rounds, threads=threads)
     torch.cuda.synchronize()
     assert_close(Xs.cpu().numpy(), Xo, off, "f32", what="single round from the oracle state")
