@@ -673,7 +673,11 @@ struct NarrowTile {
 #pragma unroll
         for (int e = 0; e < VEC; ++e) acc[e] = 0.0;
         Raw xa[2 * CP], xb[2 * CP], ga[CG], gb[CG];
+        // a wavefront that is about to issue its loads, or to store its results, goes before the
+        // ones that are busy with arithmetic: the memory queue stays fed
+        __builtin_amdgcn_s_setprio(3);
         load_chunk(0, xa, ga);
+        __builtin_amdgcn_s_setprio(0);
         int k = 0;
         for (; k + 2 * CP < steps; k += 2 * CP) {
             load_chunk(k + CP, xb, gb);
@@ -698,6 +702,7 @@ struct NarrowTile {
 #pragma unroll
         for (int e = 0; e < VEC; ++e) vt[e] = (float)(acc[e] * inv);
         const Raw vt_raw = S::round_vec(vt);
+        __builtin_amdgcn_s_setprio(3);
         for (int q = 0; q < steps; ++q) {
             const int ia = row_a(q);
             if (ia < n && ((dcol >> ia) & 1)) store_seg<ST, FULL>(Xt + off(ia), c0, lo, hi, vt_raw);
