@@ -49,6 +49,15 @@ __device__ __forceinline__ void philox4x32(uint32_t c[4], uint32_t k0, uint32_t 
     }
 }
 
+// A launch dimension holds fewer than 2^32 work-items, so long 1-D ranges of workgroups are folded
+// into (x, z): workgroup index = blockIdx.z * gridDim.x + blockIdx.x.
+constexpr unsigned kMaxGridX = 1u << 20;
+__device__ __forceinline__ int64_t linear_block() { return (int64_t)blockIdx.z * gridDim.x + blockIdx.x; }
+inline dim3 folded_grid(int64_t workgroups, unsigned y) {
+    const int64_t gx = workgroups < (int64_t)kMaxGridX ? (workgroups > 0 ? workgroups : 1) : (int64_t)kMaxGridX;
+    return dim3((unsigned)gx, y, (unsigned)((workgroups + gx - 1) / gx));
+}
+
 constexpr uint32_t kDomainUplink = 0u << 24, kDomainDownlink = 1u << 24, kDomainServer = 2u << 24,
                    kDomainNoise = 3u << 24;
 constexpr int kMaskRounds = 10;   // network outcome: the generator's standard round count
@@ -535,7 +544,7 @@ __global__ __launch_bounds__(WPB * 64) void round_kernel(ST *__restrict__ X, con
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int j = blockIdx.y;
     const int64_t lo = tab->off[j], hi = tab->off[j + 1];
-    const int64_t tile0 = (lo / TILE) * TILE + ((int64_t)blockIdx.x * WPB + wave) * TILE;
+    const int64_t tile0 = (lo / TILE) * TILE + (linear_block() * WPB + wave) * TILE;
     if (tile0 >= hi) return;   // wave-uniform: this block has fewer tiles than the largest one
     const uint64_t ucol = tab->ucol[j], dcol = tab->dcol[j];
     const double inv = tab->inv_cnt[j];
@@ -721,7 +730,7 @@ __global__ __launch_bounds__(64) void round_kernel_narrow(ST *__restrict__ X, co
     const int lane = threadIdx.x;
     const int j = blockIdx.y;
     const int64_t lo = tab->off[j], hi = tab->off[j + 1];
-    const int64_t tile0 = (lo / TILE) * TILE + (int64_t)blockIdx.x * TILE;
+    const int64_t tile0 = (lo / TILE) * TILE + linear_block() * TILE;
     if (tile0 >= hi) return;   // wave-uniform
     const uint32_t sub_off = (uint32_t)(lane % LPR) * VEC;
     ST *Xt = X + tile0 * prm.n;
@@ -768,7 +777,7 @@ __global__ __launch_bounds__(256) void local_step_kernel(ST *__restrict__ X, con
     constexpr int TILE = 64 * VEC;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t tile0 = ((int64_t)blockIdx.x * 4 + wave) * TILE;
+    const int64_t tile0 = (linear_block() * 4 + wave) * TILE;
     const int row = blockIdx.y;
     if (tile0 >= prm.N) return;   // wave-uniform
     LaneCols lc;
@@ -792,7 +801,7 @@ __global__ __launch_bounds__(256) void local_step_tiled_kernel(ST *__restrict__ 
     using S = Storage<ST>;
     constexpr int VEC = S::VEC;
     constexpr int LPR = kTiledLanes, TILE = LPR * VEC;
-    const int64_t q = (int64_t)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t q = linear_block() * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
     const int64_t seg0 = q * (64 / LPR);          // first segment of the wavefront: scalar division
     int64_t tile = seg0 / prm.n;
@@ -831,7 +840,7 @@ hipError_t launch_round_v(ST *X, const ST *G, const RoundTable *tab, const Round
     constexpr int TILE = 64 * Storage<ST>::VEC;
     // tiles sit on absolute multiples of TILE columns: a block may overhang one tile on each side
     const int64_t tiles = (max_block_cols + 2 * TILE - 2) / TILE;
-    const dim3 grid((unsigned)((tiles + WPB - 1) / WPB), (unsigned)prm.blocks, 1);
+    const dim3 grid = folded_grid((tiles + WPB - 1) / WPB, (unsigned)prm.blocks);
     size_t lds = 0;
     if (max_waves_per_cu > 0 && max_waves_per_cu < 32) {
         int wgs = max_waves_per_cu / WPB;
@@ -848,7 +857,7 @@ hipError_t launch_round_narrow(ST *X, const ST *G, const RoundTable *tab, const 
                                int max_waves_per_cu, hipStream_t stream) {
     constexpr int TILE = LPR * Storage<ST>::VEC;
     const int64_t tiles = (max_block_cols + 2 * TILE - 2) / TILE;
-    const dim3 grid((unsigned)tiles, (unsigned)prm.blocks, 1);
+    const dim3 grid = folded_grid(tiles, (unsigned)prm.blocks);
     size_t lds = 0;
     if (max_waves_per_cu > 0 && max_waves_per_cu < 32) {
         lds = ((size_t)kLdsBytesPerCu / max_waves_per_cu) & ~(size_t)255;
@@ -889,7 +898,7 @@ hipError_t launch_local_step_g(int grad_mode, ST *X, const ST *G, const RoundPar
     if (prm.tiled) {
         const int64_t tiles = (prm.N + kTiledLanes * VEC - 1) / (kTiledLanes * VEC);
         const int64_t kb = (tiles * prm.n * kTiledLanes + 63) / 64;   // wavefronts: 1 KB of storage each
-        const dim3 grid((unsigned)((kb + 3) / 4), 1, 1);
+        const dim3 grid = folded_grid((kb + 3) / 4, 1);
         if (grad_mode == kGradBuffer)
             hipLaunchKernelGGL((local_step_tiled_kernel<ST, kGradBuffer>), grid, dim3(256), 0, stream, X, G, prm);
         else
@@ -897,7 +906,7 @@ hipError_t launch_local_step_g(int grad_mode, ST *X, const ST *G, const RoundPar
         return hipGetLastError();
     }
     const int64_t tiles = (prm.N + 64 * VEC - 1) / (64 * VEC);
-    const dim3 grid((unsigned)((tiles + 3) / 4), (unsigned)prm.n, 1);
+    const dim3 grid = folded_grid((tiles + 3) / 4, (unsigned)prm.n);
     if (grad_mode == kGradBuffer)
         hipLaunchKernelGGL((local_step_kernel<ST, kGradBuffer>), grid, dim3(256), 0, stream, X, G, prm);
     else
@@ -988,7 +997,7 @@ __global__ __launch_bounds__(256) void gradavg_kernel(ST *__restrict__ X, const 
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int j = blockIdx.y;
     const int64_t lo = tab->off[j], hi = tab->off[j + 1];
-    const int64_t tile0 = (lo / TILE) * TILE + ((int64_t)blockIdx.x * 4 + wave) * TILE;
+    const int64_t tile0 = (lo / TILE) * TILE + (linear_block() * 4 + wave) * TILE;
     if (tile0 >= hi) return;   // wave-uniform
     LaneCols lc;
     lc.tile0 = tile0;
@@ -1231,7 +1240,7 @@ hipError_t launch_gradavg(int dtype, void *X, const void *G, const RoundTable *t
     const int vec = dtype == 0 ? 4 : 8;
     const int64_t tile = 64 * vec;
     const int64_t tiles = (max_block_cols + 2 * tile - 2) / tile;
-    const dim3 grid((unsigned)((tiles + 3) / 4), (unsigned)prm.blocks, 1);
+    const dim3 grid = folded_grid((tiles + 3) / 4, (unsigned)prm.blocks);
     size_t lds = 0;
     if (max_waves_per_cu > 0 && max_waves_per_cu < 32) {
         int wgs = max_waves_per_cu / 4;

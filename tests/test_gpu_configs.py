@@ -271,32 +271,46 @@ def test_config_lsq_n4_gradient_averaging_drifts(rps):
     ctx.destroy()
 
 
-@pytest.mark.parametrize("n,N,dtype,split", [(2, 1 << 34, "bf16", (1 << 33) + 1288), (1, (1 << 32) + 3, "f32", None)])
-def test_maximum_width(rps, n, N, dtype, split):
+@pytest.mark.parametrize("n,N,dtype,split,tiled", [(2, 1 << 34, "bf16", (1 << 33) + 1288, False),
+                                                   (1, (1 << 32) + 3, "f32", None, False),
+                                                   (1, 1 << 34, "f32", None, False),
+                                                   (2, 1 << 34, "bf16", (1 << 33) + 1288, True),
+                                                   (3, (1 << 32) + 3, "f32", ((1 << 31) + 5, (1 << 31) + 1000008), True)])
+def test_maximum_width(rps, n, N, dtype, split, tiled):
     """The interface's widest model (N = 2^34 columns; column indices, noise counters and byte
     offsets all pass 2^32) and an odd width just past 2^32 (element-wise path, one worker).
     Starts from X = 0 (Alg. 1's identical start); the oracle evolves sampled columns -- both ends,
     both sides of 2^32, of the block boundary and of the last tile -- by itself for three rounds."""
     free, _ = torch.cuda.mem_get_info()
     elem = 2 if dtype == "bf16" else 4
-    if free < n * N * elem + (8 << 30):
+    if free < n * (N + 64) * elem + (8 << 30):
         pytest.skip("not enough free device memory for the maximum-width state")
-    off = np.array([0, N] if split is None else [0, split, N], dtype=np.int64)
-    marks = [0, 1 << 32, N - 600] + ([split] if split else []) + [N - 40]
+    cuts = [] if split is None else (list(split) if isinstance(split, tuple) else [split])
+    off = np.array([0] + cuts + [N], dtype=np.int64)
+    marks = [0, 1 << 32, N - 600] + cuts + [N - 40]
     cols = np.unique(np.concatenate([np.arange(max(m - 20, 0), min(m + 20, N)) for m in marks] +
                                     [workloads.sample_columns(off, per_block=60, seed=3)]))
     idx = torch.from_numpy(cols).cuda()
     p, gamma, seed = 0.3, 0.5, 2024
-    X = torch.zeros(n, N, device="cuda", dtype=torch.bfloat16 if dtype == "bf16" else torch.float32)
-    Xo = to_oracle(X.index_select(1, idx))
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    T = workloads.TILE_BYTES // elem
+    X = torch.zeros(((N + T - 1) // T, n, T) if tiled else (n, N), device="cuda", dtype=tdt)
+
+    def sample():
+        return to_oracle(X[idx // T, :, idx % T].t().contiguous() if tiled else X.index_select(1, idx))
+
+    Xo = sample()
     ctx = rps.RpsContext(n, N, p, gamma, seed, rps.RPS_DTYPE_BF16 if dtype == "bf16" else rps.RPS_DTYPE_F32,
-                         block_offsets=off)
+                         block_offsets=off, flags=rps.RPS_FLAG_LAYOUT_TILED if tiled else 0)
     ctx.set_synthetic_grad(1.0, 0.01)
     for t in range(3):
-        ctx.round(X, None, t)
+        if t == 1:                                               # unfused once: the tiled local step at this width
+            ctx.local_step(X, None, t); ctx.lossy_average(X, t)
+        else:
+            ctx.round(X, None, t)
         oracle.round_(Xo, None, off, p=p, gamma=gamma, seed=seed, step=t, sigma=1.0, weight_decay=0.01, cols=cols)
         masks_equal(ctx, seed, t, n, p)
-        got = to_oracle(X.index_select(1, idx))
+        got = sample()
         assert_close(got, Xo, off, dtype, cols=cols, what=f"N={N} round {t}")
     assert np.abs(as_float(Xo)).max() > 0.1                     # the noise really moved the state
     ctx.destroy()
