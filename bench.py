@@ -29,7 +29,7 @@ HBM_PEAK_GBS = 8000.0     # MI355X published HBM3E bandwidth
 # each scaled by what the same counter reads for a plain 1 GiB device copy; the commands and
 # the raw figures are in profiles/round_kernel_resnet50_n32_hbm_traffic.md).  Counters cannot
 # be read from inside this process, so the measured value is recorded here per workload.
-MEASURED_TRAFFIC_BYTES = {("resnet50_n32", "tiled"): 6.55365e9, ("resnet50_n32", "row-major"): 6.55375e9}
+MEASURED_TRAFFIC_BYTES = {("resnet50_n32", "tiled"): 6.5536e9, ("resnet50_n32", "row-major"): 6.5538e9}
 
 
 def cpu_baseline(cfg, off, budget_cols):
