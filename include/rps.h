@@ -66,8 +66,7 @@ enum {
        them back -- measured 12 % faster than row-major on the benchmark's headline workload.  Results are those of the
        row-major layout up to the summation order of the fp64 column sums (still fixed, and the
        same for every receiver of a block).  Worker i's model is the strided view [:, i, :].
-       rps_round_gradient_averaging is row-major only (RPS_EUNSUPPORTED).  Not available with
-       external servers. */
+       Not available with external servers. */
     RPS_FLAG_LAYOUT_TILED = 2u
 };
 

@@ -307,7 +307,6 @@ int rps_round(rps_ctx *ctx, void *X, const void *G, uint64_t step) {
 
 int rps_round_gradient_averaging(rps_ctx *ctx, void *X, const void *G, uint64_t step) {
     if (!ctx || !X || !G || !step_ok(step)) return RPS_EINVAL;
-    if (ctx->flags & RPS_FLAG_LAYOUT_TILED) return RPS_EUNSUPPORTED;   // the comparison baseline is row-major only
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return RPS_EHIP;
     const RoundParams prm = make_params(ctx, X, G, step);

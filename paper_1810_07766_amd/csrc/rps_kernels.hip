@@ -1011,6 +1011,86 @@ __global__ __launch_bounds__(256) void gradavg_kernel(ST *__restrict__ X, const 
         gradavg_tile<ST, false>(X, G, prm, lc, tab->ucol[j], tab->dcol[j], tab->inv_cnt[j]);
 }
 
+// Gradient averaging on the tiled layout: one wavefront per 128-byte-wide tile, lane groups as in
+// round_kernel_narrow.  A lane has at most 8 rows (n <= 64): its gradient segments stay in
+// registers between the column sums and the update, so G is read once.
+template <typename ST, bool FULL>
+__device__ __forceinline__ void gradavg_tile_narrow(ST *__restrict__ Xt, const ST *__restrict__ Gt, const RoundParams &prm,
+                                                    uint32_t sub_off, int64_t c0, int64_t lo, int64_t hi, uint64_t ucol,
+                                                    uint64_t dcol, double inv, int lg) {
+    using S = Storage<ST>;
+    using Raw = typename S::Raw;
+    constexpr int VEC = S::VEC;
+    constexpr int LPR = kTiledLanes, GROUPS = 64 / LPR;
+    constexpr uint32_t STRIDE = LPR * VEC;
+    constexpr int ROWS = 2 * ((kMaxWorkers / 2 + GROUPS - 1) / GROUPS);   // rows per lane at most: 8
+    const int n = prm.n;
+    Raw g[ROWS], x[ROWS];
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) {   // lane's row r: pair lg + GROUPS * (r / 2); rows past n repeat row n-1, unused
+        const int i = 2 * (lg + GROUPS * (r >> 1)) + (r & 1);
+        const uint32_t o = (uint32_t)(i < n ? i : n - 1) * STRIDE + sub_off;
+        g[r] = load_seg<ST, FULL>(Gt + o, c0, lo, hi);
+        x[r] = load_seg<ST, FULL>(Xt + o, c0, lo, hi);
+    }
+    double acc[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) acc[e] = 0.0;
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) {
+        const int i = 2 * (lg + GROUPS * (r >> 1)) + (r & 1);
+        if (i < n && ((ucol >> i) & 1)) {
+            float v[VEC];
+            S::unpack(g[r], v);
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) acc[e] += (double)v[e];
+        }
+    }
+#pragma unroll
+    for (int o = LPR; o < 64; o <<= 1) {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) acc[e] += __shfl_xor(acc[e], o, 64);
+    }
+    float gt[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) gt[e] = (float)(acc[e] * inv);
+    (void)S::round_vec(gt);   // the average travels in the storage format
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) {
+        const int i = 2 * (lg + GROUPS * (r >> 1)) + (r & 1);
+        if (i < n) {
+            float v[VEC], own[VEC];
+            S::unpack(x[r], v);
+            S::unpack(g[r], own);
+            const bool d = (dcol >> i) & 1;   // reply lost: the worker applies its own gradient
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) v[e] = __builtin_fmaf(-prm.gamma, d ? gt[e] : own[e], v[e]);
+            store_seg<ST, FULL>(Xt + (uint32_t)i * STRIDE + sub_off, c0, lo, hi, S::round_vec(v));
+        }
+    }
+}
+
+template <typename ST>
+__global__ __launch_bounds__(64) void gradavg_kernel_narrow(ST *__restrict__ X, const ST *__restrict__ G,
+                                                            const RoundTable *__restrict__ tab, const RoundParams prm) {
+    constexpr int VEC = Storage<ST>::VEC;
+    constexpr int TILE = kTiledLanes * VEC;
+    const int lane = threadIdx.x;
+    const int j = blockIdx.y;
+    const int64_t lo = tab->off[j], hi = tab->off[j + 1];
+    const int64_t tile0 = (lo / TILE) * TILE + linear_block() * TILE;
+    if (tile0 >= hi) return;   // wave-uniform
+    const uint32_t sub_off = (uint32_t)(lane % kTiledLanes) * VEC;
+    ST *Xt = X + tile0 * prm.n;
+    const ST *Gt = G + tile0 * prm.n;
+    if (prm.vec_ok && tile0 >= lo && tile0 + TILE <= hi)
+        gradavg_tile_narrow<ST, true>(Xt, Gt, prm, sub_off, tile0 + sub_off, lo, hi, tab->ucol[j], tab->dcol[j],
+                                      tab->inv_cnt[j], lane / kTiledLanes);
+    else
+        gradavg_tile_narrow<ST, false>(Xt, Gt, prm, sub_off, tile0 + sub_off, lo, hi, tab->ucol[j], tab->dcol[j],
+                                       tab->inv_cnt[j], lane / kTiledLanes);
+}
+
 // ---------------------------------------------------------------------------------------
 // Consensus statistics (supplement, Lemma 1: the quantity sum_i ||x_i - xbar||^2 =
 // ||X (I - A_n)||_F^2 that the proof bounds) and ||xbar||^2.  One streaming read of X: a
@@ -1238,6 +1318,22 @@ hipError_t launch_local_step(int dtype, int grad_mode, void *X, const void *G, c
 hipError_t launch_gradavg(int dtype, void *X, const void *G, const RoundTable *tab, const RoundParams &prm,
                           int64_t max_block_cols, int max_waves_per_cu, hipStream_t stream) {
     const int vec = dtype == 0 ? 4 : 8;
+    if (prm.tiled) {
+        const int64_t tile = kTiledLanes * vec;
+        const dim3 grid = folded_grid((max_block_cols + 2 * tile - 2) / tile, (unsigned)prm.blocks);
+        size_t lds = 0;
+        if (max_waves_per_cu > 0 && max_waves_per_cu < 32) {
+            lds = ((size_t)kLdsBytesPerCu / max_waves_per_cu) & ~(size_t)255;
+            if (lds > 65536) lds = 65536;
+        }
+        if (dtype == 0)
+            hipLaunchKernelGGL(gradavg_kernel_narrow<float>, grid, dim3(64), lds, stream, (float *)X, (const float *)G, tab,
+                               prm);
+        else
+            hipLaunchKernelGGL(gradavg_kernel_narrow<uint16_t>, grid, dim3(64), lds, stream, (uint16_t *)X,
+                               (const uint16_t *)G, tab, prm);
+        return hipGetLastError();
+    }
     const int64_t tile = 64 * vec;
     const int64_t tiles = (max_block_cols + 2 * tile - 2) / tile;
     const dim3 grid = folded_grid((tiles + 3) / 4, (unsigned)prm.blocks);

@@ -470,7 +470,7 @@ def test_tiled_layout_every_entry_point(rps, n, N, layout, dtype):
     Xt, Gt = tiled(Xr), tiled(Gr)
     Xo = to_oracle(Xr)
     calls = [("round", None), ("round", "G"), ("local_step", None), ("lossy_average", None), ("local_step", "G"),
-             ("round", None), ("lossy_average", None)]
+             ("gradavg", "G"), ("round", None), ("lossy_average", None)]
     for t, (what, g) in enumerate(calls):
         if what == "round":
             unfused = Xt.clone()
@@ -482,10 +482,13 @@ def test_tiled_layout_every_entry_point(rps, n, N, layout, dtype):
         elif what == "local_step":
             rm.local_step(Xr, Gr if g else None, t); tl.local_step(Xt, Gt if g else None, t)
             oracle.local_step(Xo, to_oracle(Gr) if g else None, gamma, sigma=0.5, weight_decay=0.01, seed=seed, step=t)
-        else:
+        elif what == "lossy_average":
             rm.lossy_average(Xr, t); tl.lossy_average(Xt, t)
             _, U, D = oracle.masks(seed, t, n, p)
             oracle.lossy_average(Xo, off, U, D)
+        else:
+            rm.round_gradient_averaging(Xr, Gr, t); tl.round_gradient_averaging(Xt, Gt, t)
+            oracle.round_gradient_averaging(Xo, to_oracle(Gr), off, p=p, gamma=gamma, seed=seed, step=t)
         back = workloads.from_tiled(Xt, N)
         assert_close(to_oracle(back), Xo, off, dtype, what=f"tiled call {t} ({what}) against the oracle")
         if what == "local_step":
@@ -499,9 +502,6 @@ def test_tiled_layout_every_entry_point(rps, n, N, layout, dtype):
     d_t, m_t = tl.consensus(Xt)
     d_r, m_r = rm.consensus(Xr)
     assert abs(d_t - d_r) <= 1e-12 * d_r and abs(m_t - m_r) <= 1e-12 * m_r
-    with pytest.raises(rps.RpsError) as err:
-        tl.round_gradient_averaging(Xt, Gt, 0)
-    assert err.value.code == rps.RPS_EUNSUPPORTED
     rm.destroy(); tl.destroy()
 
 
