@@ -512,3 +512,50 @@ def test_tiled_layout_shape_is_checked(rps):
     ctx.round(torch.zeros(32, 4, 32, device="cuda"), None, 0)
     ctx.destroy()
     assert rps.rps_storage_elems(0, 10, 0, 0) == -1 and rps.rps_storage_elems(4, 1000, 1, 2) == 16 * 4 * 64
+
+
+# ---------------------------------------------------------------------------------------------
+def _random_case(k):
+    rng = np.random.default_rng(1000 + k)
+    n = int(rng.choice([1, 2, 3, 4, 5, 6, 7, 8, 9, 12, 15, 16, 17, 24, 31, 32, 33, 48, 63, 64]))
+    dtype = "bf16" if rng.random() < 0.35 else "f32"
+    per = int(rng.integers(1, 700))
+    N = n * per + int(rng.integers(0, 40))                    # any width: odd pitches, partial last tiles
+    layout = str(rng.choice(["arbitrary", "unequal8", "equal"]))
+    if layout == "equal":
+        N -= N % n
+    if layout == "unequal8" and N < 16 * n:
+        layout = "arbitrary"
+    N = max(N, n)
+    p = float(rng.choice([0.0, 0.02, 0.1, 0.3, 0.6, 1.0]))
+    return n, N, layout, dtype, p, bool(rng.random() < 0.5), bool(rng.random() < 0.25), int(rng.integers(0, 2 ** 40))
+
+
+@pytest.mark.parametrize("k", range(48))
+def test_randomized_cases(rps, k):
+    """Seeded random workloads (workers, width, partition, dtype, drop rate, layout, server rule,
+    starting step): fused rounds with both gradient sources and the unfused pair, against the
+    oracle; fused == unfused bit for bit."""
+    n, N, layout, dtype, p, tiled, identity, step0 = _random_case(k)
+    off = _offsets(n, N, layout, seed=k)
+    gamma, sigma, lam, seed = 0.2, 0.3, 0.02, 900 + k
+    flags = (rps.RPS_FLAG_LAYOUT_TILED if tiled else 0) | (rps.RPS_FLAG_SERVER_IDENTITY if identity else 0)
+    ctx = rps.RpsContext(n, N, p, gamma, seed, _dt(rps, dtype), block_offsets=off, flags=flags)
+    ctx.set_synthetic_grad(sigma, lam)
+    Xr = device_tensor(workloads.gaussian_model(n, N, seed=k), dtype)
+    Gr = device_tensor(workloads.gaussian_model(n, N, seed=k + 500), dtype)
+    Xo, Go = to_oracle(Xr), to_oracle(Gr)
+    X = workloads.to_tiled(Xr) if tiled else Xr
+    G = workloads.to_tiled(Gr) if tiled else Gr
+    for r, g in enumerate((None, "G", None)):
+        t = step0 + r
+        unfused = X.clone()
+        ctx.round(X, G if g else None, t)
+        ctx.local_step(unfused, G if g else None, t); ctx.lossy_average(unfused, t)
+        assert torch.equal(unfused, X), f"case {k} round {r}: fused and unfused differ"
+        oracle.round_(Xo, Go if g else None, off, p=p, gamma=gamma, seed=seed, step=t, sigma=sigma, weight_decay=lam,
+                      identity_server=identity)
+        masks_equal(ctx, seed, t, n, p, identity=identity)
+        got = workloads.from_tiled(X, N) if tiled else X
+        assert_close(to_oracle(got), Xo, off, dtype, what=f"case {k} {(n, N, layout, dtype, p, tiled, identity)} round {r}")
+    ctx.destroy()
