@@ -574,12 +574,23 @@ __global__ __launch_bounds__(WPB * 64) void round_kernel(ST *__restrict__ X, con
 // ---------------------------------------------------------------------------------------
 constexpr int kTiledLanes = 8;   // lanes per row segment of the tiled layout: 8 x 16 B = 128 B (RPS_TILE_BYTES)
 
+// Access to the lane's 16-byte group of one row segment: `base` is wave-uniform, `eoff` the lane's
+// element offset from it.  FULL: one 128-bit access through a raw buffer resource built on `base`
+// (SGPR base + 32-bit VGPR offset: no per-lane 64-bit address arithmetic; loads non-temporal,
+// stores with the sc1 nt streaming policy).  Otherwise element by element inside [lo, hi).
 template <typename ST, bool FULL>
-__device__ __forceinline__ typename Storage<ST>::Raw load_seg(const ST *p, int64_t c0, int64_t lo, int64_t hi) {
+__device__ __forceinline__ typename Storage<ST>::Raw load_seg(const ST *base, uint32_t eoff, int64_t c0, int64_t lo,
+                                                              int64_t hi) {
     using S = Storage<ST>;
     if (FULL) {
-        return __builtin_nontemporal_load(reinterpret_cast<const typename S::Raw *>(p));
+        constexpr int kAuxNt = 1 << 1;
+        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<ST *>(base), 0, 0x7FFFFFFF, 0x00020000);
+        const u32x4 bits = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)(eoff * (uint32_t)sizeof(ST)), 0, kAuxNt);
+        typename S::Raw v;
+        __builtin_memcpy(&v, &bits, sizeof(v));
+        return v;
     } else {
+        const ST *p = base + eoff;
         float x[S::VEC];
 #pragma unroll
         for (int e = 0; e < S::VEC; ++e) x[e] = (c0 + e >= lo && c0 + e < hi) ? S::load1(p + e) : 0.0f;
@@ -587,11 +598,17 @@ __device__ __forceinline__ typename Storage<ST>::Raw load_seg(const ST *p, int64
     }
 }
 template <typename ST, bool FULL>
-__device__ __forceinline__ void store_seg(ST *p, int64_t c0, int64_t lo, int64_t hi, typename Storage<ST>::Raw v) {
+__device__ __forceinline__ void store_seg(ST *base, uint32_t eoff, int64_t c0, int64_t lo, int64_t hi,
+                                          typename Storage<ST>::Raw v) {
     using S = Storage<ST>;
     if (FULL) {
-        __builtin_nontemporal_store(v, reinterpret_cast<typename S::Raw *>(p));
+        constexpr int kAuxSc1Nt = (1 << 4) | (1 << 1);
+        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(base, 0, 0x7FFFFFFF, 0x00020000);
+        u32x4 bits;
+        __builtin_memcpy(&bits, &v, sizeof(bits));
+        __builtin_amdgcn_raw_buffer_store_b128(bits, rsrc, (int)(eoff * (uint32_t)sizeof(ST)), 0, kAuxSc1Nt);
     } else {
+        ST *p = base + eoff;
         float x[S::VEC];
         S::unpack(v, x);
 #pragma unroll
@@ -630,11 +647,11 @@ struct NarrowTile {
             const int ia = row_a(k0 + q);
             const uint32_t oa = off(ia < last ? ia : last);           // rows past n repeat row n-1, unused
             const uint32_t ob = off(ia + 1 < last ? ia + 1 : last);
-            x[2 * q] = load_seg<ST, FULL>(Xt + oa, c0, lo, hi);
-            x[2 * q + 1] = load_seg<ST, FULL>(Xt + ob, c0, lo, hi);
+            x[2 * q] = load_seg<ST, FULL>(Xt, oa, c0, lo, hi);
+            x[2 * q + 1] = load_seg<ST, FULL>(Xt, ob, c0, lo, hi);
             if (GRAD == kGradBuffer) {
-                g[GRAD == kGradBuffer ? 2 * q : 0] = load_seg<ST, FULL>(Gt + oa, c0, lo, hi);
-                g[GRAD == kGradBuffer ? 2 * q + 1 : 0] = load_seg<ST, FULL>(Gt + ob, c0, lo, hi);
+                g[GRAD == kGradBuffer ? 2 * q : 0] = load_seg<ST, FULL>(Gt, oa, c0, lo, hi);
+                g[GRAD == kGradBuffer ? 2 * q + 1 : 0] = load_seg<ST, FULL>(Gt, ob, c0, lo, hi);
             }
         }
     }
@@ -651,7 +668,7 @@ struct NarrowTile {
 #pragma unroll
             for (int e = 0; e < VEC; ++e) acc[e] += (double)v[e];
         }
-        if (GRAD != kGradNone && !d) store_seg<ST, FULL>(Xt + off(i), c0, lo, hi, vr);
+        if (GRAD != kGradNone && !d) store_seg<ST, FULL>(Xt, off(i), c0, lo, hi, vr);
     }
 
     __device__ __forceinline__ void process_chunk(int k0, const Raw x[2 * CP], const Raw g[CG], double acc[VEC]) const {
@@ -714,8 +731,8 @@ struct NarrowTile {
         __builtin_amdgcn_s_setprio(3);
         for (int q = 0; q < steps; ++q) {
             const int ia = row_a(q);
-            if (ia < n && ((dcol >> ia) & 1)) store_seg<ST, FULL>(Xt + off(ia), c0, lo, hi, vt_raw);
-            if (ia + 1 < n && ((dcol >> (ia + 1)) & 1)) store_seg<ST, FULL>(Xt + off(ia + 1), c0, lo, hi, vt_raw);
+            if (ia < n && ((dcol >> ia) & 1)) store_seg<ST, FULL>(Xt, off(ia), c0, lo, hi, vt_raw);
+            if (ia + 1 < n && ((dcol >> (ia + 1)) & 1)) store_seg<ST, FULL>(Xt, off(ia + 1), c0, lo, hi, vt_raw);
         }
     }
 };
@@ -810,25 +827,30 @@ __global__ __launch_bounds__(256) void local_step_tiled_kernel(ST *__restrict__ 
         i -= prm.n;
         ++tile;
     }
-    const int64_t seg = seg0 + lane / LPR;
     const int64_t c0 = tile * TILE + (lane % LPR) * VEC;
     if (c0 >= prm.N) return;   // padding columns of the last tile, or past the last tile
-    const int64_t off = seg * TILE + (lane % LPR) * VEC;
+    ST *px = X + seg0 * TILE + (uint32_t)(lane / LPR) * TILE + (lane % LPR) * VEC;   // plain global accesses:
+    const ST *pg = G ? G + (px - X) : nullptr;   // measured faster here than the buffer form the round kernels use
     float x[VEC], g[VEC], other[VEC];
     const bool full = prm.vec_ok && c0 + VEC <= prm.N;
-    S::unpack(full ? load_seg<ST, true>(X + off, c0, 0, prm.N) : load_seg<ST, false>(X + off, c0, 0, prm.N), x);
-    if (GRAD == kGradBuffer) {
-        S::unpack(full ? load_seg<ST, true>(G + off, c0, 0, prm.N) : load_seg<ST, false>(G + off, c0, 0, prm.N), g);
-    } else if (i & 1) {
-        noise_rows<VEC>(prm, i >> 1, c0, other, g);
+    if (full) {
+        S::unpack(__builtin_nontemporal_load(reinterpret_cast<const typename S::Raw *>(px)), x);
+        if (GRAD == kGradBuffer) S::unpack(__builtin_nontemporal_load(reinterpret_cast<const typename S::Raw *>(pg)), g);
     } else {
-        noise_rows<VEC>(prm, i >> 1, c0, g, other);
+        S::unpack(load_seg<ST, false>(px, 0, c0, 0, prm.N), x);
+        if (GRAD == kGradBuffer) S::unpack(load_seg<ST, false>(pg, 0, c0, 0, prm.N), g);
+    }
+    if (GRAD != kGradBuffer) {
+        if (i & 1)
+            noise_rows<VEC>(prm, i >> 1, c0, other, g);
+        else
+            noise_rows<VEC>(prm, i >> 1, c0, g, other);
     }
     const typename S::Raw v = sgd_step<ST, GRAD>(prm, g, x);
     if (full)
-        store_seg<ST, true>(X + off, c0, 0, prm.N, v);
+        __builtin_nontemporal_store(v, reinterpret_cast<typename S::Raw *>(px));
     else
-        store_seg<ST, false>(X + off, c0, 0, prm.N, v);
+        store_seg<ST, false>(px, 0, c0, 0, prm.N, v);
 }
 
 // Launch shape of the round kernel.  The memory system of this GPU is at its best when the
@@ -1030,8 +1052,8 @@ __device__ __forceinline__ void gradavg_tile_narrow(ST *__restrict__ Xt, const S
     for (int r = 0; r < ROWS; ++r) {   // lane's row r: pair lg + GROUPS * (r / 2); rows past n repeat row n-1, unused
         const int i = 2 * (lg + GROUPS * (r >> 1)) + (r & 1);
         const uint32_t o = (uint32_t)(i < n ? i : n - 1) * STRIDE + sub_off;
-        g[r] = load_seg<ST, FULL>(Gt + o, c0, lo, hi);
-        x[r] = load_seg<ST, FULL>(Xt + o, c0, lo, hi);
+        g[r] = load_seg<ST, FULL>(Gt, o, c0, lo, hi);
+        x[r] = load_seg<ST, FULL>(Xt, o, c0, lo, hi);
     }
     double acc[VEC];
 #pragma unroll
@@ -1065,7 +1087,7 @@ __device__ __forceinline__ void gradavg_tile_narrow(ST *__restrict__ Xt, const S
             const bool d = (dcol >> i) & 1;   // reply lost: the worker applies its own gradient
 #pragma unroll
             for (int e = 0; e < VEC; ++e) v[e] = __builtin_fmaf(-prm.gamma, d ? gt[e] : own[e], v[e]);
-            store_seg<ST, FULL>(Xt + (uint32_t)i * STRIDE + sub_off, c0, lo, hi, S::round_vec(v));
+            store_seg<ST, FULL>(Xt, (uint32_t)i * STRIDE + sub_off, c0, lo, hi, S::round_vec(v));
         }
     }
 }
@@ -1162,9 +1184,9 @@ __device__ __forceinline__ void consensus_tile_tiled(const ST *__restrict__ X, c
     const int n = prm.n;
     const int lg = lane / LPR, sub = lane % LPR;
     const int64_t c0 = tile0 + sub * VEC;
-    const ST *Xl = X + tile0 * n + sub * VEC;
+    const ST *Xt = X + tile0 * n;   // wave-uniform
     float p[VEC];
-    S::unpack(load_seg<ST, FULL>(Xl, c0, 0, prm.N), p);
+    S::unpack(load_seg<ST, FULL>(Xt, sub * VEC, c0, 0, prm.N), p);
     double s1[VEC], s2[VEC];
 #pragma unroll
     for (int e = 0; e < VEC; ++e) s1[e] = s2[e] = 0.0;
@@ -1174,7 +1196,7 @@ __device__ __forceinline__ void consensus_tile_tiled(const ST *__restrict__ X, c
 #pragma unroll
         for (int r = 0; r < R; ++r) {   // rows past n repeat the lane's last row, unused
             const int i = i0 + r * GROUPS;
-            x[r] = load_seg<ST, FULL>(Xl + (int64_t)(i < n ? i : i0) * prm.stride, c0, 0, prm.N);
+            x[r] = load_seg<ST, FULL>(Xt, (uint32_t)(i < n ? i : i0) * (uint32_t)(LPR * VEC) + sub * VEC, c0, 0, prm.N);
         }
 #pragma unroll
         for (int r = 0; r < R; ++r) {
