@@ -74,7 +74,7 @@ rps::LaunchTuning tuning_for(const rps_ctx *ctx, int grad_mode) {
         const int n = ctx->n;                    // (measured at n = 8 / 16 / 32 fp32 and n = 64 bf16)
         int cap;
         if (grad_mode == rps::kGradSynthetic) cap = n >= 24 ? 20 : 0;
-        else if (grad_mode == rps::kGradNone) cap = n >= 48 ? 8 : (n >= 24 ? 12 : 24);
+        else if (grad_mode == rps::kGradNone) cap = n >= 48 ? 8 : (n >= 24 ? 10 : 24);
         else cap = n >= 24 ? 12 : (n >= 12 ? 20 : 0);
         return rps::LaunchTuning{4, 1, cap};
     }

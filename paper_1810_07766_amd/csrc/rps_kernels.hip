@@ -575,16 +575,18 @@ __global__ __launch_bounds__(WPB * 64) void round_kernel(ST *__restrict__ X, con
 constexpr int kTiledLanes = 8;   // lanes per row segment of the tiled layout: 8 x 16 B = 128 B (RPS_TILE_BYTES)
 
 // Access to the lane's 16-byte group of one row segment: `base` is wave-uniform, `eoff` the lane's
-// element offset from it.  FULL: one 128-bit access through a raw buffer resource built on `base`
-// (SGPR base + 32-bit VGPR offset: no per-lane 64-bit address arithmetic; loads non-temporal,
-// stores with the sc1 nt streaming policy).  Otherwise element by element inside [lo, hi).
+// element offset from it.  FULL: one 128-bit access through a raw buffer resource of `limit` bytes
+// built on `base` (SGPR base + 32-bit VGPR offset: no per-lane 64-bit address arithmetic; the
+// hardware drops accesses at or beyond `limit`: loads return 0, stores do nothing; loads
+// non-temporal, stores with the sc1 nt streaming policy).  Otherwise element by element inside
+// [lo, hi).
 template <typename ST, bool FULL>
-__device__ __forceinline__ typename Storage<ST>::Raw load_seg(const ST *base, uint32_t eoff, int64_t c0, int64_t lo,
-                                                              int64_t hi) {
+__device__ __forceinline__ typename Storage<ST>::Raw load_seg(const ST *base, uint32_t eoff, uint32_t limit, int64_t c0,
+                                                              int64_t lo, int64_t hi) {
     using S = Storage<ST>;
     if (FULL) {
         constexpr int kAuxNt = 1 << 1;
-        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<ST *>(base), 0, 0x7FFFFFFF, 0x00020000);
+        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<ST *>(base), 0, (int)limit, 0x00020000);
         const u32x4 bits = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)(eoff * (uint32_t)sizeof(ST)), 0, kAuxNt);
         typename S::Raw v;
         __builtin_memcpy(&v, &bits, sizeof(v));
@@ -598,12 +600,12 @@ __device__ __forceinline__ typename Storage<ST>::Raw load_seg(const ST *base, ui
     }
 }
 template <typename ST, bool FULL>
-__device__ __forceinline__ void store_seg(ST *base, uint32_t eoff, int64_t c0, int64_t lo, int64_t hi,
+__device__ __forceinline__ void store_seg(ST *base, uint32_t eoff, uint32_t limit, int64_t c0, int64_t lo, int64_t hi,
                                           typename Storage<ST>::Raw v) {
     using S = Storage<ST>;
     if (FULL) {
         constexpr int kAuxSc1Nt = (1 << 4) | (1 << 1);
-        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(base, 0, 0x7FFFFFFF, 0x00020000);
+        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(base, 0, (int)limit, 0x00020000);
         u32x4 bits;
         __builtin_memcpy(&bits, &v, sizeof(bits));
         __builtin_amdgcn_raw_buffer_store_b128(bits, rsrc, (int)(eoff * (uint32_t)sizeof(ST)), 0, kAuxSc1Nt);
@@ -633,9 +635,25 @@ struct NarrowTile {
     const ST *Gt;
     uint32_t sub_off;  // this lane's columns inside a row segment
     int64_t c0, lo, hi;
-    uint64_t ucol, dcol;
     int lg;
+    // The lane's rows are 2*lg + 2*GROUPS*k + r (pair k, r = 0, 1): bit 2*GROUPS*k + r of these words
+    // (the masks shifted down by 2*lg) says whether that row's copy reached the server (sum),
+    // whether its reply arrived (gets the average), whether it keeps its own v -- rows >= n: none.
+    uint64_t sum_bits, avg_bits, own_bits;
+    uint32_t limit;    // bytes of the tile: the buffer resource's bound
 
+    __device__ __forceinline__ NarrowTile(const RoundParams &prm_, ST *Xt_, const ST *Gt_, uint32_t sub_off_, int64_t c0_,
+                                          int64_t lo_, int64_t hi_, uint64_t ucol, uint64_t dcol, int lg_)
+        : prm(prm_), Xt(Xt_), Gt(Gt_), sub_off(sub_off_), c0(c0_), lo(lo_), hi(hi_), lg(lg_) {
+        const uint64_t valid = prm.n >= 64 ? ~0ull : ((1ull << prm.n) - 1);
+        sum_bits = (ucol & valid) >> (2 * lg);
+        avg_bits = (dcol & valid) >> (2 * lg);
+        own_bits = (~dcol & valid) >> (2 * lg);
+        limit = (uint32_t)prm.n * STRIDE * (uint32_t)sizeof(ST);
+    }
+
+    // bit of pair k, row r of that pair
+    static __device__ __forceinline__ bool bit(uint64_t w, int k, int r) { return (w >> (2 * GROUPS * k + r)) & 1; }
     // rows of the lane's k-th pair
     __device__ __forceinline__ int row_a(int k) const { return 2 * (lg + GROUPS * k); }
     __device__ __forceinline__ uint32_t off(int i) const { return (uint32_t)i * STRIDE + sub_off; }
@@ -644,22 +662,23 @@ struct NarrowTile {
         const int last = prm.n - 1;
 #pragma unroll
         for (int q = 0; q < CP; ++q) {
-            const int ia = row_a(k0 + q);
-            const uint32_t oa = off(ia < last ? ia : last);           // rows past n repeat row n-1, unused
-            const uint32_t ob = off(ia + 1 < last ? ia + 1 : last);
-            x[2 * q] = load_seg<ST, FULL>(Xt, oa, c0, lo, hi);
-            x[2 * q + 1] = load_seg<ST, FULL>(Xt, ob, c0, lo, hi);
+            int ia = row_a(k0 + q), ib = ia + 1;
+            if (!FULL) {   // rows past n repeat row n-1, unused (FULL: the buffer bound returns zeros)
+                ia = ia < last ? ia : last;
+                ib = ib < last ? ib : last;
+            }
+            x[2 * q] = load_seg<ST, FULL>(Xt, off(ia), limit, c0, lo, hi);
+            x[2 * q + 1] = load_seg<ST, FULL>(Xt, off(ib), limit, c0, lo, hi);
             if (GRAD == kGradBuffer) {
-                g[GRAD == kGradBuffer ? 2 * q : 0] = load_seg<ST, FULL>(Gt, oa, c0, lo, hi);
-                g[GRAD == kGradBuffer ? 2 * q + 1 : 0] = load_seg<ST, FULL>(Gt, ob, c0, lo, hi);
+                g[GRAD == kGradBuffer ? 2 * q : 0] = load_seg<ST, FULL>(Gt, off(ia), limit, c0, lo, hi);
+                g[GRAD == kGradBuffer ? 2 * q + 1 : 0] = load_seg<ST, FULL>(Gt, off(ib), limit, c0, lo, hi);
             }
         }
     }
 
-    __device__ __forceinline__ void row(int i, Raw xr, Raw gr, const float *z, double acc[VEC]) const {
-        if (i >= prm.n) return;
-        const bool u = (ucol >> i) & 1, d = (dcol >> i) & 1;
-        if (!(u || (GRAD != kGradNone && !d))) return;
+    __device__ __forceinline__ void row(int k, int r, Raw xr, Raw gr, const float *z, double acc[VEC]) const {
+        const bool u = bit(sum_bits, k, r), own = GRAD != kGradNone && bit(own_bits, k, r);
+        if (!(u || own)) return;
         float v[VEC], g[VEC];
         S::unpack(xr, v);
         if (GRAD == kGradBuffer) S::unpack(gr, g);
@@ -668,7 +687,7 @@ struct NarrowTile {
 #pragma unroll
             for (int e = 0; e < VEC; ++e) acc[e] += (double)v[e];
         }
-        if (GRAD != kGradNone && !d) store_seg<ST, FULL>(Xt, off(i), c0, lo, hi, vr);
+        if (own) store_seg<ST, FULL>(Xt, off(row_a(k) + r), limit, c0, lo, hi, vr);
     }
 
     __device__ __forceinline__ void process_chunk(int k0, const Raw x[2 * CP], const Raw g[CG], double acc[VEC]) const {
@@ -680,9 +699,8 @@ struct NarrowTile {
         }
 #pragma unroll
         for (int q = 0; q < CP; ++q) {
-            const int ia = row_a(k0 + q);
-            row(ia, x[2 * q], g[GRAD == kGradBuffer ? 2 * q : 0], za[q], acc);
-            row(ia + 1, x[2 * q + 1], g[GRAD == kGradBuffer ? 2 * q + 1 : 0], zb[q], acc);
+            row(k0 + q, 0, x[2 * q], g[GRAD == kGradBuffer ? 2 * q : 0], za[q], acc);
+            row(k0 + q, 1, x[2 * q + 1], g[GRAD == kGradBuffer ? 2 * q + 1 : 0], zb[q], acc);
         }
 #pragma unroll
         for (int q = 0; q < 2 * CP; ++q) asm volatile("" ::"v"(x[q]));   // see process_chunk of the wide kernel
@@ -692,9 +710,30 @@ struct NarrowTile {
         }
     }
 
+    __device__ __forceinline__ void finish(double acc[VEC], double inv, int steps) const {
+        // combine the lane groups: after the butterfly every lane of a column group holds the same sum
+#pragma unroll
+        for (int o = LPR; o < 64; o <<= 1) {
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) acc[e] += __shfl_xor(acc[e], o, 64);
+        }
+        float vt[VEC];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) vt[e] = (float)(acc[e] * inv);
+        const Raw vt_raw = S::round_vec(vt);
+        __builtin_amdgcn_s_setprio(3);
+        for (int q = 0; q < steps; ++q) {
+            if (bit(avg_bits, q, 0)) store_seg<ST, FULL>(Xt, off(row_a(q)), limit, c0, lo, hi, vt_raw);
+            if (bit(avg_bits, q, 1)) store_seg<ST, FULL>(Xt, off(row_a(q) + 1), limit, c0, lo, hi, vt_raw);
+        }
+    }
+
+    // SINGLE: the launcher guarantees n <= 2 * GROUPS * CP, i.e. the lane's rows are one load chunk
+    // and every row index is a compile-time constant (the general loop is then not even compiled
+    // in: having both in one kernel costs registers).
+    template <bool SINGLE>
     __device__ __forceinline__ void run(double inv) const {
-        const int n = prm.n;
-        const int steps = ((n + 1) / 2 + GROUPS - 1) / GROUPS;   // row pairs per lane (wave-uniform)
+        const int steps = ((prm.n + 1) / 2 + GROUPS - 1) / GROUPS;   // row pairs per lane (wave-uniform)
         double acc[VEC];
 #pragma unroll
         for (int e = 0; e < VEC; ++e) acc[e] = 0.0;
@@ -704,6 +743,11 @@ struct NarrowTile {
         __builtin_amdgcn_s_setprio(3);
         load_chunk(0, xa, ga);
         __builtin_amdgcn_s_setprio(0);
+        if constexpr (SINGLE) {
+            process_chunk(0, xa, ga, acc);
+            finish(acc, inv, steps);
+            return;
+        }
         int k = 0;
         for (; k + 2 * CP < steps; k += 2 * CP) {
             load_chunk(k + CP, xb, gb);
@@ -718,28 +762,13 @@ struct NarrowTile {
         } else {
             process_chunk(k, xa, ga, acc);
         }
-        // combine the lane groups: after the butterfly every lane of a column group holds the same sum
-#pragma unroll
-        for (int o = LPR; o < 64; o <<= 1) {
-#pragma unroll
-            for (int e = 0; e < VEC; ++e) acc[e] += __shfl_xor(acc[e], o, 64);
-        }
-        float vt[VEC];
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) vt[e] = (float)(acc[e] * inv);
-        const Raw vt_raw = S::round_vec(vt);
-        __builtin_amdgcn_s_setprio(3);
-        for (int q = 0; q < steps; ++q) {
-            const int ia = row_a(q);
-            if (ia < n && ((dcol >> ia) & 1)) store_seg<ST, FULL>(Xt, off(ia), c0, lo, hi, vt_raw);
-            if (ia + 1 < n && ((dcol >> (ia + 1)) & 1)) store_seg<ST, FULL>(Xt, off(ia + 1), c0, lo, hi, vt_raw);
-        }
+        finish(acc, inv, steps);
     }
 };
 
 // Tiled layout only: the tile [tile0, tile0 + LPR * VEC) of all n workers is the contiguous run of
 // n * LPR * 16 bytes at element offset tile0 * n.
-template <typename ST, int GRAD, int LPR, int CP>
+template <typename ST, int GRAD, int LPR, int CP, bool SINGLE>
 __global__ __launch_bounds__(64) void round_kernel_narrow(ST *__restrict__ X, const ST *__restrict__ G,
                                                           const RoundTable *__restrict__ tab, const RoundParams prm) {
     constexpr int VEC = Storage<ST>::VEC;
@@ -754,13 +783,13 @@ __global__ __launch_bounds__(64) void round_kernel_narrow(ST *__restrict__ X, co
     const ST *Gt = G ? G + tile0 * prm.n : nullptr;
     const bool full = prm.vec_ok && tile0 >= lo && tile0 + TILE <= hi;   // wave-uniform
     if (full) {
-        const NarrowTile<ST, GRAD, LPR, CP, true> t{prm, Xt, Gt, sub_off, tile0 + sub_off, lo, hi,
-                                                    tab->ucol[j], tab->dcol[j], lane / LPR};
-        t.run(tab->inv_cnt[j]);
+        const NarrowTile<ST, GRAD, LPR, CP, true> t(prm, Xt, Gt, sub_off, tile0 + sub_off, lo, hi,
+                                                    tab->ucol[j], tab->dcol[j], lane / LPR);
+        t.template run<SINGLE>(tab->inv_cnt[j]);
     } else {
-        const NarrowTile<ST, GRAD, LPR, CP, false> t{prm, Xt, Gt, sub_off, tile0 + sub_off, lo, hi,
-                                                     tab->ucol[j], tab->dcol[j], lane / LPR};
-        t.run(tab->inv_cnt[j]);
+        const NarrowTile<ST, GRAD, LPR, CP, false> t(prm, Xt, Gt, sub_off, tile0 + sub_off, lo, hi,
+                                                     tab->ucol[j], tab->dcol[j], lane / LPR);
+        t.template run<SINGLE>(tab->inv_cnt[j]);
     }
 }
 
@@ -837,8 +866,8 @@ __global__ __launch_bounds__(256) void local_step_tiled_kernel(ST *__restrict__ 
         S::unpack(__builtin_nontemporal_load(reinterpret_cast<const typename S::Raw *>(px)), x);
         if (GRAD == kGradBuffer) S::unpack(__builtin_nontemporal_load(reinterpret_cast<const typename S::Raw *>(pg)), g);
     } else {
-        S::unpack(load_seg<ST, false>(px, 0, c0, 0, prm.N), x);
-        if (GRAD == kGradBuffer) S::unpack(load_seg<ST, false>(pg, 0, c0, 0, prm.N), g);
+        S::unpack(load_seg<ST, false>(px, 0, 0, c0, 0, prm.N), x);
+        if (GRAD == kGradBuffer) S::unpack(load_seg<ST, false>(pg, 0, 0, c0, 0, prm.N), g);
     }
     if (GRAD != kGradBuffer) {
         if (i & 1)
@@ -850,7 +879,7 @@ __global__ __launch_bounds__(256) void local_step_tiled_kernel(ST *__restrict__ 
     if (full)
         __builtin_nontemporal_store(v, reinterpret_cast<typename S::Raw *>(px));
     else
-        store_seg<ST, false>(px, 0, c0, 0, prm.N, v);
+        store_seg<ST, false>(px, 0, 0, c0, 0, prm.N, v);
 }
 
 // Launch shape of the round kernel.  The memory system of this GPU is at its best when the
@@ -885,10 +914,12 @@ hipError_t launch_round_narrow(ST *X, const ST *G, const RoundTable *tab, const 
         lds = ((size_t)kLdsBytesPerCu / max_waves_per_cu) & ~(size_t)255;
         if (lds > 65536) lds = 65536;
     }
-    if (prm.n <= 2 * (64 / LPR))
-        hipLaunchKernelGGL((round_kernel_narrow<ST, GRAD, LPR, 1>), grid, dim3(64), lds, stream, X, G, tab, prm);
+    if (prm.n <= 2 * (64 / LPR))        // a lane has one row pair
+        hipLaunchKernelGGL((round_kernel_narrow<ST, GRAD, LPR, 1, true>), grid, dim3(64), lds, stream, X, G, tab, prm);
+    else if (prm.n <= 4 * (64 / LPR))   // two pairs: still one load chunk
+        hipLaunchKernelGGL((round_kernel_narrow<ST, GRAD, LPR, 2, true>), grid, dim3(64), lds, stream, X, G, tab, prm);
     else
-        hipLaunchKernelGGL((round_kernel_narrow<ST, GRAD, LPR, 2>), grid, dim3(64), lds, stream, X, G, tab, prm);
+        hipLaunchKernelGGL((round_kernel_narrow<ST, GRAD, LPR, 2, false>), grid, dim3(64), lds, stream, X, G, tab, prm);
     return hipGetLastError();
 }
 
@@ -1047,13 +1078,14 @@ __device__ __forceinline__ void gradavg_tile_narrow(ST *__restrict__ Xt, const S
     constexpr uint32_t STRIDE = LPR * VEC;
     constexpr int ROWS = 2 * ((kMaxWorkers / 2 + GROUPS - 1) / GROUPS);   // rows per lane at most: 8
     const int n = prm.n;
+    const uint32_t limit = (uint32_t)n * STRIDE * (uint32_t)sizeof(ST);
     Raw g[ROWS], x[ROWS];
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) {   // lane's row r: pair lg + GROUPS * (r / 2); rows past n repeat row n-1, unused
         const int i = 2 * (lg + GROUPS * (r >> 1)) + (r & 1);
         const uint32_t o = (uint32_t)(i < n ? i : n - 1) * STRIDE + sub_off;
-        g[r] = load_seg<ST, FULL>(Gt, o, c0, lo, hi);
-        x[r] = load_seg<ST, FULL>(Xt, o, c0, lo, hi);
+        g[r] = load_seg<ST, FULL>(Gt, o, limit, c0, lo, hi);
+        x[r] = load_seg<ST, FULL>(Xt, o, limit, c0, lo, hi);
     }
     double acc[VEC];
 #pragma unroll
@@ -1087,7 +1119,7 @@ __device__ __forceinline__ void gradavg_tile_narrow(ST *__restrict__ Xt, const S
             const bool d = (dcol >> i) & 1;   // reply lost: the worker applies its own gradient
 #pragma unroll
             for (int e = 0; e < VEC; ++e) v[e] = __builtin_fmaf(-prm.gamma, d ? gt[e] : own[e], v[e]);
-            store_seg<ST, FULL>(Xt, (uint32_t)i * STRIDE + sub_off, c0, lo, hi, S::round_vec(v));
+            store_seg<ST, FULL>(Xt, (uint32_t)i * STRIDE + sub_off, limit, c0, lo, hi, S::round_vec(v));
         }
     }
 }
@@ -1186,7 +1218,8 @@ __device__ __forceinline__ void consensus_tile_tiled(const ST *__restrict__ X, c
     const int64_t c0 = tile0 + sub * VEC;
     const ST *Xt = X + tile0 * n;   // wave-uniform
     float p[VEC];
-    S::unpack(load_seg<ST, FULL>(Xt, sub * VEC, c0, 0, prm.N), p);
+    const uint32_t limit = (uint32_t)n * (uint32_t)(LPR * VEC) * (uint32_t)sizeof(ST);
+    S::unpack(load_seg<ST, FULL>(Xt, sub * VEC, limit, c0, 0, prm.N), p);
     double s1[VEC], s2[VEC];
 #pragma unroll
     for (int e = 0; e < VEC; ++e) s1[e] = s2[e] = 0.0;
@@ -1196,7 +1229,7 @@ __device__ __forceinline__ void consensus_tile_tiled(const ST *__restrict__ X, c
 #pragma unroll
         for (int r = 0; r < R; ++r) {   // rows past n repeat the lane's last row, unused
             const int i = i0 + r * GROUPS;
-            x[r] = load_seg<ST, FULL>(Xt, (uint32_t)(i < n ? i : i0) * (uint32_t)(LPR * VEC) + sub * VEC, c0, 0, prm.N);
+            x[r] = load_seg<ST, FULL>(Xt, (uint32_t)(i < n ? i : i0) * (uint32_t)(LPR * VEC) + sub * VEC, limit, c0, 0, prm.N);
         }
 #pragma unroll
         for (int r = 0; r < R; ++r) {
