@@ -156,8 +156,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--config", default=None, help="workload name (default: the headline config)")
     ap.add_argument("--layout", choices=("tiled", "row-major"), default=None,
-                    help="storage layout of X and G (default: tiled for fp32 workloads, row-major for bf16; "
-                         "the other layout is measured too and reported under other_layout)")
+                    help="storage layout of X and G (default: tiled; the other layout is measured too and "
+                         "reported under other_layout)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--other-paths", action="store_true",
                     help="also time the unfused entry points and the gradient-buffer round on the same workload "
@@ -179,7 +179,7 @@ def main():
     cfg = workloads.CONFIGS[args.config or workloads.HEADLINE]
     off = workloads.config_offsets(cfg)
     torch.cuda.set_device(0)
-    layout = args.layout or ("row-major" if cfg.dtype == "bf16" else "tiled")
+    layout = args.layout or "tiled"
     other = "row-major" if layout == "tiled" else "tiled"
 
     m = measure(cfg, off, layout, args, torch, rps, args.other_paths)
