@@ -197,6 +197,15 @@ int rps_consensus(rps_ctx *ctx, const void *X, double *distance, double *mean_sq
 int rps_estimate_mixing(rps_ctx *ctx, uint64_t first_step, int64_t rounds, double *alpha1, double *alpha2);
 
 /*
+ * Copy the state between the two layouts (any context of matching n, N and dtype; its own layout
+ * flag does not matter):  to_tiled != 0: src is row-major [n, N], dst receives the tile-major
+ * arrangement (rps_storage_elems elements; padding columns are written as zeros);  to_tiled == 0:
+ * the reverse.  dst and src are device arrays that must not overlap.  One streaming pass, enqueued
+ * on the context's stream.
+ */
+int rps_convert_layout(rps_ctx *ctx, void *dst, const void *src, int32_t to_tiled);
+
+/*
  * Launch shape of the round kernel, for tuning sweeps; results never depend on it.
  *   rows_in_flight       rows per load chunk (a wavefront keeps two chunks in flight): 2 or 4
  *   waves_per_workgroup  1 or 4 (a workgroup's wavefronts own adjacent tiles)

@@ -413,6 +413,16 @@ int rps_estimate_mixing(rps_ctx *ctx, uint64_t first_step, int64_t rounds, doubl
     return RPS_OK;
 }
 
+int rps_convert_layout(rps_ctx *ctx, void *dst, const void *src, int32_t to_tiled) {
+    if (!ctx || !dst || !src || dst == src) return RPS_EINVAL;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return RPS_EHIP;
+    const int64_t vec = ctx->dtype == RPS_DTYPE_F32 ? 4 : 8;
+    const bool aligned = (uintptr_t)dst % 16 == 0 && (uintptr_t)src % 16 == 0 && ctx->N % vec == 0;
+    RPS_HIP(ctx, rps::launch_convert_layout(ctx->dtype, dst, src, ctx->N, ctx->n, to_tiled != 0, aligned, ctx->stream));
+    return RPS_OK;
+}
+
 int rps_set_launch_tuning(rps_ctx *ctx, int32_t rows_in_flight, int32_t waves_per_workgroup, int32_t max_waves_per_cu) {
     if (!ctx) return RPS_EINVAL;
     if (rows_in_flight != 2 && rows_in_flight != 4) return RPS_EINVAL;

@@ -43,6 +43,7 @@ _lib.rps_set_mask_override.argtypes = [_ctx_p, ctypes.c_void_p, ctypes.c_void_p,
 _lib.rps_consensus.argtypes = [_ctx_p, ctypes.c_void_p, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
 _lib.rps_estimate_mixing.argtypes = [_ctx_p, ctypes.c_uint64, ctypes.c_int64, ctypes.POINTER(ctypes.c_double),
                                      ctypes.POINTER(ctypes.c_double)]
+_lib.rps_convert_layout.argtypes = [_ctx_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32]
 _lib.rps_set_launch_tuning.argtypes = [_ctx_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32]
 _lib.rps_set_profiling.argtypes = [_ctx_p, ctypes.c_int32]
 _lib.rps_get_kernel_time.argtypes = [_ctx_p, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
@@ -51,12 +52,12 @@ _lib.rps_strerror.argtypes = [ctypes.c_int]
 _lib.rps_strerror.restype = ctypes.c_char_p
 for _name in ("rps_create", "rps_create_external", "rps_destroy", "rps_set_synthetic_grad", "rps_set_gamma", "rps_local_step",
               "rps_lossy_average", "rps_round", "rps_round_gradient_averaging", "rps_get_masks", "rps_set_mask_override",
-              "rps_consensus", "rps_estimate_mixing", "rps_set_launch_tuning", "rps_set_profiling", "rps_get_kernel_time", "rps_last_hip_error"):
+              "rps_consensus", "rps_estimate_mixing", "rps_convert_layout", "rps_set_launch_tuning", "rps_set_profiling", "rps_get_kernel_time", "rps_last_hip_error"):
     getattr(_lib, _name).restype = ctypes.c_int
 
 EXPORTS = ("rps_create", "rps_create_external", "rps_storage_elems", "rps_destroy", "rps_set_synthetic_grad", "rps_set_gamma", "rps_local_step",
            "rps_lossy_average", "rps_round", "rps_round_gradient_averaging", "rps_get_masks", "rps_set_mask_override",
-           "rps_consensus", "rps_estimate_mixing", "rps_set_launch_tuning", "rps_set_profiling", "rps_get_kernel_time",
+           "rps_consensus", "rps_estimate_mixing", "rps_convert_layout", "rps_set_launch_tuning", "rps_set_profiling", "rps_get_kernel_time",
            "rps_last_hip_error",
            "rps_strerror")
 
@@ -179,6 +180,29 @@ class RpsContext:
         _check(_lib.rps_estimate_mixing(self._h, first_step, rounds, ctypes.byref(a1), ctypes.byref(a2)), self._h)
         return a1.value, a2.value
 
+    def to_tiled(self, X):
+        """Row-major [n, N] tensor -> new tile-major tensor [tiles, n, T] (device copy by the library)."""
+        import torch
+        want = torch.float32 if self.dtype == RPS_DTYPE_F32 else torch.bfloat16
+        if not (X.is_cuda and X.is_contiguous() and X.dtype == want and tuple(X.shape) == (self.n, self.N)):
+            raise RpsError(RPS_EINVAL)
+        T = RPS_TILE_BYTES // X.element_size()
+        out = torch.empty((self.N + T - 1) // T, self.n, T, device=X.device, dtype=X.dtype)
+        _check(_lib.rps_convert_layout(self._h, out.data_ptr(), X.data_ptr(), 1), self._h)
+        return out
+
+    def from_tiled(self, Xt):
+        """Tile-major tensor -> new row-major [n, N] tensor."""
+        import torch
+        want = torch.float32 if self.dtype == RPS_DTYPE_F32 else torch.bfloat16
+        T = RPS_TILE_BYTES // Xt.element_size()
+        if not (Xt.is_cuda and Xt.is_contiguous() and Xt.dtype == want
+                and tuple(Xt.shape) == ((self.N + T - 1) // T, self.n, T)):
+            raise RpsError(RPS_EINVAL)
+        out = torch.empty(self.n, self.N, device=Xt.device, dtype=Xt.dtype)
+        _check(_lib.rps_convert_layout(self._h, out.data_ptr(), Xt.data_ptr(), 0), self._h)
+        return out
+
     def set_launch_tuning(self, rows_in_flight, waves_per_workgroup, max_waves_per_cu=0):
         _check(_lib.rps_set_launch_tuning(self._h, rows_in_flight, waves_per_workgroup, max_waves_per_cu), self._h)
 
@@ -243,6 +267,10 @@ def rps_consensus(ctx, X):
 
 def rps_estimate_mixing(ctx, first_step, rounds):
     return ctx.estimate_mixing(first_step, rounds)
+
+
+def rps_convert_layout(ctx, X, to_tiled):
+    return ctx.to_tiled(X) if to_tiled else ctx.from_tiled(X)
 
 
 def rps_set_mask_override(ctx, server=None, up=None, down=None):

@@ -559,3 +559,20 @@ def test_randomized_cases(rps, k):
         got = workloads.from_tiled(X, N) if tiled else X
         assert_close(to_oracle(got), Xo, off, dtype, what=f"case {k} {(n, N, layout, dtype, p, tiled, identity)} round {r}")
     ctx.destroy()
+
+
+@pytest.mark.parametrize("n,N,dtype", [(1, 1500, "f32"), (2, 1554, "f32"), (5, 8000, "f32"), (32, 32 * 1544, "f32"),
+                                       (64, 64 * 520 + 3, "f32"), (7, 7001, "bf16"), (64, 64 * 1032, "bf16"), (9, 40, "bf16")])
+def test_layout_conversion(rps, n, N, dtype):
+    """rps_convert_layout against the plain re-arrangement (torch permute) in both directions,
+    bit for bit; padding columns come out as zeros."""
+    ctx = rps.RpsContext(n, N, 0.1, 0.1, 0, _dt(rps, dtype), block_offsets=_offsets(n, N, "arbitrary"))
+    X = device_tensor(workloads.gaussian_model(n, N, seed=n + N), dtype)
+    ref = workloads.to_tiled(X)                                   # zero padding
+    got = ctx.to_tiled(X)
+    assert got.shape == ref.shape and torch.equal(got, ref)
+    back = ctx.from_tiled(got)
+    assert torch.equal(back, X)
+    with pytest.raises(rps.RpsError):
+        ctx.to_tiled(got)                                         # wrong shape
+    ctx.destroy()
