@@ -303,23 +303,16 @@ struct Storage<uint16_t> {
 
 // Where one lane works: VEC columns [c0, c0+VEC) of the column range [lo, hi), c0 = tile0 + loff
 // with tile0 wave-uniform and loff = lane * VEC.  Row pointers handed to load_raw / store_raw
-// already include the tile's storage offset (wave-uniform base + 32-bit lane offset: no per-lane 64-bit address
+// already include tile0 (wave-uniform base + 32-bit lane offset: no per-lane 64-bit address
 // arithmetic).  In a FULL wavefront every lane's vector lies inside the range and is 16-byte
 // aligned: one 128-bit access per row and no per-lane test (keeps all loads of a row chunk in
 // one basic block, in flight together).  Otherwise (block edges, unaligned pitch) lanes touch
 // only their own columns inside the range, element by element.
 struct LaneCols {
     int64_t tile0, lo, hi;
-    int64_t base;    // storage offset of (row 0, column tile0); rows of the tile follow at prm.stride
     uint32_t loff;
     __device__ __forceinline__ int64_t c0() const { return tile0 + loff; }
 };
-
-// Storage offset of (row 0, column tile0), tile0 a multiple of the tile width.  Row-major [n, N]:
-// tile0, rows N apart.  Tiled [tiles][n][tile width]: the n rows of a tile are adjacent.
-__device__ __forceinline__ int64_t tile_base(const RoundParams &prm, int64_t tile0) {
-    return prm.tiled ? tile0 * prm.n : tile0;
-}
 
 template <typename ST, bool FULL>
 __device__ __forceinline__ typename Storage<ST>::Raw load_raw(const ST *tile_row, const LaneCols &lc) {
@@ -496,7 +489,7 @@ __device__ __forceinline__ void round_tile(ST *__restrict__ X, const ST *__restr
     constexpr int VEC = S::VEC;
     constexpr int RG = GRAD == kGradBuffer ? R : 1;
     const int n = prm.n;
-    ST *Xt = X + lc.base;   // row 0 of the tile (wave-uniform)
+    ST *Xt = X + lc.tile0;   // row 0 of the tile (wave-uniform)
 
     double acc[VEC];
 #pragma unroll
@@ -504,7 +497,7 @@ __device__ __forceinline__ void round_tile(ST *__restrict__ X, const ST *__restr
 
     LoadCursor<ST> cur;
     cur.x = Xt;
-    cur.g = GRAD == kGradBuffer ? G + lc.base : nullptr;
+    cur.g = GRAD == kGradBuffer ? G + lc.tile0 : nullptr;
     cur.row = 0;
     Raw xa[R], xb[R], ga[RG], gb[RG];
     load_chunk<ST, GRAD, R, FULL>(cur, prm, lc, xa, ga);
@@ -551,7 +544,6 @@ __global__ __launch_bounds__(WPB * 64) void round_kernel(ST *__restrict__ X, con
 
     LaneCols lc;
     lc.tile0 = tile0;
-    lc.base = tile_base(prm, tile0);
     lc.loff = (uint32_t)lane * VEC;
     lc.lo = lo;
     lc.hi = hi;
@@ -803,11 +795,11 @@ __device__ __forceinline__ void local_step_row(ST *__restrict__ X, const ST *__r
                                                const LaneCols &lc, int i) {
     using S = Storage<ST>;
     constexpr int VEC = S::VEC;
-    ST *row = X + (int64_t)i * prm.stride + lc.base;
+    ST *row = X + (int64_t)i * prm.stride + lc.tile0;
     float x[VEC], g[VEC], other[VEC];
     S::unpack(load_raw<ST, FULL>(row, lc), x);
     if (GRAD == kGradBuffer) {
-        S::unpack(load_raw<ST, FULL>(G + (int64_t)i * prm.stride + lc.base, lc), g);
+        S::unpack(load_raw<ST, FULL>(G + (int64_t)i * prm.stride + lc.tile0, lc), g);
     } else if (i & 1) {
         noise_rows<VEC>(prm, i >> 1, lc.c0(), other, g);
     } else {
@@ -828,7 +820,6 @@ __global__ __launch_bounds__(256) void local_step_kernel(ST *__restrict__ X, con
     if (tile0 >= prm.N) return;   // wave-uniform
     LaneCols lc;
     lc.tile0 = tile0;
-    lc.base = tile_base(prm, tile0);
     lc.loff = (uint32_t)lane * VEC;
     lc.lo = 0;
     lc.hi = prm.N;
@@ -988,7 +979,7 @@ __device__ __forceinline__ void gradavg_tile(ST *__restrict__ X, const ST *__res
     double acc[VEC];
 #pragma unroll
     for (int e = 0; e < VEC; ++e) acc[e] = 0.0;
-    const ST *grow = G + lc.base;
+    const ST *grow = G + lc.tile0;
     for (int i0 = 0; i0 < n; i0 += R) {
         Raw g[R];
 #pragma unroll
@@ -1012,7 +1003,7 @@ __device__ __forceinline__ void gradavg_tile(ST *__restrict__ X, const ST *__res
     for (int e = 0; e < VEC; ++e) gt[e] = (float)(acc[e] * inv);
     (void)S::round_vec(gt);
 
-    ST *xrow = X + lc.base;
+    ST *xrow = X + lc.tile0;
     for (int i0 = 0; i0 < n; i0 += R) {
         Raw x[R];
         const ST *ld = xrow;
@@ -1029,7 +1020,7 @@ __device__ __forceinline__ void gradavg_tile(ST *__restrict__ X, const ST *__res
                 S::unpack(x[r], v);
                 const float *gsrc = gt;
                 if (!((dcol >> i) & 1)) {   // reply lost: the worker applies its own gradient
-                    S::unpack(load_raw<ST, FULL>(G + lc.base + (int64_t)i * prm.stride, lc), own);
+                    S::unpack(load_raw<ST, FULL>(G + lc.tile0 + (int64_t)i * prm.stride, lc), own);
                     gsrc = own;
                 }
 #pragma unroll
@@ -1054,7 +1045,6 @@ __global__ __launch_bounds__(256) void gradavg_kernel(ST *__restrict__ X, const 
     if (tile0 >= hi) return;   // wave-uniform
     LaneCols lc;
     lc.tile0 = tile0;
-    lc.base = tile_base(prm, tile0);
     lc.loff = (uint32_t)lane * VEC;
     lc.lo = lo;
     lc.hi = hi;
@@ -1160,7 +1150,7 @@ __device__ __forceinline__ void consensus_tile(const ST *__restrict__ X, const R
     constexpr int VEC = S::VEC;
     constexpr int R = 4;
     const int n = prm.n;
-    const ST *row = X + lc.base;
+    const ST *row = X + lc.tile0;
     float p[VEC];
     S::unpack(load_raw<ST, FULL>(row, lc), p);
     double s1[VEC], s2[VEC];
@@ -1288,7 +1278,6 @@ __global__ __launch_bounds__(256) void consensus_kernel(const ST *__restrict__ X
         for (int64_t t = (int64_t)blockIdx.x * 4 + wave; t < ntiles; t += (int64_t)gridDim.x * 4) {
             LaneCols lc;
             lc.tile0 = t * TILE;
-            lc.base = lc.tile0;
             lc.loff = (uint32_t)lane * VEC;
             lc.lo = 0;
             lc.hi = prm.N;
