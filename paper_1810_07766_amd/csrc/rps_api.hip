@@ -114,8 +114,15 @@ int timed_launch(rps_ctx *ctx, F launch) {
                 (void)hipEventDestroy(a);
                 return hip_fail(ctx, e);
             }
-            ctx->ev_start.push_back(a);
-            ctx->ev_stop.push_back(b);
+            try {   // no exception may cross the C boundary
+                ctx->ev_start.push_back(a);
+                ctx->ev_stop.push_back(b);
+            } catch (...) {
+                if (ctx->ev_start.size() > ctx->ev_stop.size()) ctx->ev_start.pop_back();
+                (void)hipEventDestroy(a);
+                (void)hipEventDestroy(b);
+                return RPS_ENOMEM;
+            }
         }
         RPS_HIP(ctx, hipEventRecord(ctx->ev_start[ctx->ev_used], ctx->stream));
     }
@@ -167,7 +174,12 @@ static int create_impl(rps_ctx **out, int32_t n, int32_t nb, bool external, int6
 
     rps_ctx *ctx = new (std::nothrow) rps_ctx;
     if (!ctx) return RPS_ENOMEM;
-    ctx->off.resize((size_t)nb + 1);
+    try {   // no exception may cross the C boundary
+        ctx->off.resize((size_t)nb + 1);
+    } catch (...) {
+        delete ctx;
+        return RPS_ENOMEM;
+    }
     if (block_offsets) {
         for (int j = 0; j <= nb; ++j) ctx->off[j] = block_offsets[j];
         bool ok = ctx->off[0] == 0 && ctx->off[nb] == N;
@@ -397,8 +409,8 @@ int rps_estimate_mixing(rps_ctx *ctx, uint64_t first_step, int64_t rounds, doubl
     const int groups = (int)std::min<int64_t>(rounds, rps::kMaxPartials);
     RPS_HIP(ctx, rps::launch_mixing_moments(ctx->partials, groups, rounds, ctx->n, ctx->nb, ctx->seed, first_step,
                                             ctx->threshold, server_mode(ctx), ctx->stream));
-    std::vector<double> host(2 * (size_t)groups);
-    RPS_HIP(ctx, hipMemcpyAsync(host.data(), ctx->partials, host.size() * sizeof(double), hipMemcpyDeviceToHost,
+    double host[2 * rps::kMaxPartials];   // groups <= kMaxPartials
+    RPS_HIP(ctx, hipMemcpyAsync(host, ctx->partials, 2 * (size_t)groups * sizeof(double), hipMemcpyDeviceToHost,
                                 ctx->stream));
     RPS_HIP(ctx, hipStreamSynchronize(ctx->stream));
     double sq = 0.0, sum_sq = 0.0;
