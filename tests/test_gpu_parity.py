@@ -576,3 +576,33 @@ def test_layout_conversion(rps, n, N, dtype):
     with pytest.raises(rps.RpsError):
         ctx.to_tiled(got)                                         # wrong shape
     ctx.destroy()
+
+
+def test_side_stream_and_interleaved_contexts(rps):
+    """Two contexts on two non-default HIP streams of default priority, rounds interleaved from the
+    host: each state evolves as if alone (work is ordered per stream, contexts share nothing)."""
+    n, N, p, gamma = 8, 8 * 4096, 0.2, 0.1
+    off = workloads.block_offsets(n, N)
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    ctxs, Xs, Xo = [], [], []
+    for k, st in enumerate(streams):
+        with torch.cuda.stream(st):
+            X0 = workloads.gaussian_model(n, N, seed=60 + k)
+            Xs.append(torch.from_numpy(X0).cuda())
+            Xo.append(X0.copy())
+            c = rps.RpsContext(n, N, p, gamma, 10 + k, flags=rps.RPS_FLAG_LAYOUT_TILED if k else 0)
+            c.set_synthetic_grad(0.1, 0.0)
+            ctxs.append(c)
+            if k:
+                Xs[k] = c.to_tiled(Xs[k])
+    for t in range(6):
+        for k in (0, 1):
+            ctxs[k].round(Xs[k], None, t)          # enqueued on the context's own stream
+            oracle.round_(Xo[k], None, off, p=p, gamma=gamma, seed=10 + k, step=t, sigma=0.1)
+    for st in streams:
+        st.synchronize()
+    assert_close(to_oracle(Xs[0]), Xo[0], off, "f32", what="context on stream 0")
+    assert_close(to_oracle(ctxs[1].from_tiled(Xs[1])), Xo[1], off, "f32", what="context on stream 1")
+    streams[1].synchronize()
+    for c in ctxs:
+        c.destroy()
