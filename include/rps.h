@@ -23,7 +23,10 @@
  *     the tiled layout) takes the 128-bit load/store path; anything else is handled by a slower
  *     element-wise path with identical results.
  *   - All device work is enqueued on the HIP stream given at creation; no call synchronises
- *     except where stated.  Results are valid in stream order.
+ *     except where stated.  Results are valid in stream order.  rps_local_step, rps_lossy_average,
+ *     rps_round, rps_round_gradient_averaging and rps_convert_layout enqueue kernels only (no
+ *     allocation, no synchronisation, no memset): a caller may capture them in a HIP graph; the
+ *     `step` argument is then part of the captured launch.
  *   - Every function returns RPS_OK (0) or a negative error code; nothing aborts or throws.
  *     An error detected before launch leaves X untouched.
  *   - The round's randomness is a pure function of (seed, step): the caller supplies `step`,

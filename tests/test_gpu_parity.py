@@ -606,3 +606,36 @@ def test_side_stream_and_interleaved_contexts(rps):
     streams[1].synchronize()
     for c in ctxs:
         c.destroy()
+
+
+def test_rounds_can_be_captured_in_a_hip_graph(rps):
+    """The round enqueues kernels only (no allocation, no synchronisation, no memset), so a caller
+    may capture a sequence of rounds in a HIP graph: four rounds captured once, replayed three times
+    from the same start with eager work and synchronisations in between, every replay equal to the
+    eager result bit for bit."""
+    n, N, p, gamma = 16, 16 * 8192, 0.1, 0.1
+    X0 = torch.from_numpy(workloads.gaussian_model(n, N, seed=8)).cuda()
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        ctx = rps.RpsContext(n, N, p, gamma, 21, flags=rps.RPS_FLAG_LAYOUT_TILED)
+        ctx.set_synthetic_grad(0.2, 0.01)
+        start = ctx.to_tiled(X0)
+        eager = start.clone()
+        for t in range(4):
+            ctx.round(eager, None, t)
+        X = start.clone()
+    s.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=s):
+        for t in range(4):
+            ctx.round(X, None, t)
+    for rep in range(3):
+        X.copy_(start)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(X, eager), f"replay {rep} differs from the eager rounds"
+        with torch.cuda.stream(s):                          # eager work between the replays
+            ctx.round(start.clone(), None, 100 + rep)
+        s.synchronize()
+    ctx.destroy()
