@@ -27,8 +27,12 @@ struct rps_ctx {
     int device = 0;
     int64_t max_block_cols = 0;
     std::vector<int64_t> off;
-    RoundTable *tab = nullptr;        // device: table the round kernels read
+    RoundTable *tab_base = nullptr;   // device allocation: three tables + the reduction scratch
+    RoundTable *tab = nullptr;        // device: table the averaging kernels read (outcome of cur_step if cur_valid)
+    RoundTable *tab_other = nullptr;  // device: outcome of next_step if next_valid, prepared by the previous kernel
     RoundTable *tab_query = nullptr;  // device: scratch table for rps_get_masks
+    bool cur_valid = false, next_valid = false;
+    uint64_t cur_step = 0, next_step = 0;
     RoundTable *staging = nullptr;    // pinned host copy (create, override, query)
     double *partials = nullptr;       // device: 2 * kMaxPartials + 2 doubles (consensus reduction scratch + result)
     bool override_on = false;
@@ -98,6 +102,10 @@ RoundParams make_params(const rps_ctx *ctx, const void *X, const void *G, uint64
     prm.seed_hi = (uint32_t)(ctx->seed >> 32);
     prm.step_lo = (uint32_t)step;
     prm.step_hi24 = (uint32_t)((step >> 32) & 0xFFFFFFu);
+    prm.next_tab = nullptr;
+    prm.threshold = ctx->threshold;
+    prm.server_mode = 0;
+    prm.next_step_lo = prm.next_step_hi24 = 0;
     return prm;
 }
 
@@ -138,11 +146,57 @@ int server_mode(const rps_ctx *ctx) {
     return ctx->external ? 2 : ((ctx->flags & RPS_FLAG_SERVER_IDENTITY) ? 1 : 0);
 }
 
-int enqueue_masks(rps_ctx *ctx, uint64_t step) {
+// Makes ctx->tab hold the network outcome of `step` and asks the averaging kernel about to be
+// launched to prepare the outcome of step + 1 in the other table (rounds usually come with
+// consecutive steps; a call whose step is already in one of the two tables needs no mask launch).
+// What a table holds is tracked on the host by step number, so results never depend on this.
+// While the stream is being captured into a graph nothing is assumed or remembered: the captured
+// launches must be self-contained, and they do not execute now.
+int prepare_outcome(rps_ctx *ctx, uint64_t step, RoundParams &prm) {
+    prm.next_tab = nullptr;
+    prm.threshold = ctx->threshold;
+    prm.server_mode = server_mode(ctx);
+    prm.next_step_lo = prm.next_step_hi24 = 0;
     if (ctx->override_on) return RPS_OK;   // the table already holds the forced outcome
-    RPS_HIP(ctx, rps::launch_masks(ctx->tab, ctx->n, ctx->nb, ctx->seed, step, ctx->threshold, server_mode(ctx),
-                                   ctx->stream));
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    bool capturing = true;
+    if (hipStreamIsCapturing(ctx->stream, &cs) == hipSuccess)
+        capturing = cs != hipStreamCaptureStatusNone;
+    else
+        (void)hipGetLastError();
+    if (capturing) {
+        ctx->cur_valid = ctx->next_valid = false;
+        RPS_HIP(ctx, rps::launch_masks(ctx->tab, ctx->n, ctx->nb, ctx->seed, step, ctx->threshold, server_mode(ctx),
+                                       ctx->stream));
+        return RPS_OK;
+    }
+    if (ctx->next_valid && ctx->next_step == step) {
+        std::swap(ctx->tab, ctx->tab_other);
+    } else if (!(ctx->cur_valid && ctx->cur_step == step)) {
+        ctx->cur_valid = false;
+        RPS_HIP(ctx, rps::launch_masks(ctx->tab, ctx->n, ctx->nb, ctx->seed, step, ctx->threshold, server_mode(ctx),
+                                       ctx->stream));
+    }
+    ctx->cur_valid = true;
+    ctx->cur_step = step;
+    ctx->next_valid = false;
+    if (step_ok(step + 1)) {
+        prm.next_tab = ctx->tab_other;
+        prm.next_step_lo = (uint32_t)(step + 1);
+        prm.next_step_hi24 = (uint32_t)(((step + 1) >> 32) & 0xFFFFFFu);
+    }
     return RPS_OK;
+}
+
+// After the averaging kernel was enqueued (rc == RPS_OK) the other table will hold step + 1.
+int commit_outcome(rps_ctx *ctx, uint64_t step, const RoundParams &prm, int rc) {
+    if (rc != RPS_OK) {
+        ctx->cur_valid = ctx->next_valid = false;
+    } else if (prm.next_tab != nullptr) {
+        ctx->next_valid = true;
+        ctx->next_step = step + 1;
+    }
+    return rc;
 }
 
 struct DeviceGuard {   // make the context's device current for the duration of a call
@@ -212,10 +266,12 @@ static int create_impl(rps_ctx **out, int32_t n, int32_t nb, bool external, int6
 
     hipError_t e = hipGetDevice(&ctx->device);
     const size_t scratch_bytes = (2 * (size_t)rps::kMaxPartials + 2) * sizeof(double);
-    if (e == hipSuccess) e = hipMalloc((void **)&ctx->tab, 2 * sizeof(RoundTable) + scratch_bytes);
+    if (e == hipSuccess) e = hipMalloc((void **)&ctx->tab_base, 3 * sizeof(RoundTable) + scratch_bytes);
     if (e == hipSuccess) {
-        ctx->tab_query = ctx->tab + 1;
-        ctx->partials = reinterpret_cast<double *>(ctx->tab + 2);
+        ctx->tab = ctx->tab_base;
+        ctx->tab_other = ctx->tab_base + 1;
+        ctx->tab_query = ctx->tab_base + 2;
+        ctx->partials = reinterpret_cast<double *>(ctx->tab_base + 3);
         e = hipHostMalloc((void **)&ctx->staging, sizeof(RoundTable), hipHostMallocDefault);
     }
     if (e == hipSuccess) {
@@ -223,12 +279,14 @@ static int create_impl(rps_ctx **out, int32_t n, int32_t nb, bool external, int6
         for (int j = 0; j <= nb; ++j) ctx->staging->off[j] = ctx->off[j];
         e = hipMemcpyAsync(ctx->tab, ctx->staging, sizeof(RoundTable), hipMemcpyHostToDevice, ctx->stream);
         if (e == hipSuccess)
+            e = hipMemcpyAsync(ctx->tab_other, ctx->staging, sizeof(RoundTable), hipMemcpyHostToDevice, ctx->stream);
+        if (e == hipSuccess)
             e = hipMemcpyAsync(ctx->tab_query, ctx->staging, sizeof(RoundTable), hipMemcpyHostToDevice, ctx->stream);
         if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
     }
     if (e != hipSuccess) {
         const bool oom = (e == hipErrorOutOfMemory);
-        if (ctx->tab) (void)hipFree(ctx->tab);
+        if (ctx->tab_base) (void)hipFree(ctx->tab_base);
         if (ctx->staging) (void)hipHostFree(ctx->staging);
         delete ctx;
         return oom ? RPS_ENOMEM : RPS_EHIP;
@@ -262,7 +320,7 @@ int rps_destroy(rps_ctx *ctx) {
     if (hipStreamSynchronize(ctx->stream) != hipSuccess) rc = RPS_EHIP;
     for (hipEvent_t ev : ctx->ev_start) (void)hipEventDestroy(ev);
     for (hipEvent_t ev : ctx->ev_stop) (void)hipEventDestroy(ev);
-    if (ctx->tab && hipFree(ctx->tab) != hipSuccess) rc = RPS_EHIP;
+    if (ctx->tab_base && hipFree(ctx->tab_base) != hipSuccess) rc = RPS_EHIP;
     if (ctx->staging && hipHostFree(ctx->staging) != hipSuccess) rc = RPS_EHIP;
     delete ctx;
     return rc;
@@ -294,40 +352,40 @@ int rps_lossy_average(rps_ctx *ctx, void *X, uint64_t step) {
     if (!ctx || !X || !step_ok(step)) return RPS_EINVAL;
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return RPS_EHIP;
-    const RoundParams prm = make_params(ctx, X, nullptr, step);
-    const int rc = enqueue_masks(ctx, step);
+    RoundParams prm = make_params(ctx, X, nullptr, step);
+    const int rc = prepare_outcome(ctx, step, prm);
     if (rc != RPS_OK) return rc;
-    return timed_launch(ctx, [&] {
+    return commit_outcome(ctx, step, prm, timed_launch(ctx, [&] {
         return rps::launch_round(ctx->dtype, rps::kGradNone, X, nullptr, ctx->tab, prm, ctx->max_block_cols,
                                  tuning_for(ctx, rps::kGradNone), ctx->stream);
-    });
+    }));
 }
 
 int rps_round(rps_ctx *ctx, void *X, const void *G, uint64_t step) {
     if (!ctx || !X || !step_ok(step)) return RPS_EINVAL;
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return RPS_EHIP;
-    const RoundParams prm = make_params(ctx, X, G, step);
+    RoundParams prm = make_params(ctx, X, G, step);
     const int mode = G ? rps::kGradBuffer : rps::kGradSynthetic;
-    const int rc = enqueue_masks(ctx, step);
+    const int rc = prepare_outcome(ctx, step, prm);
     if (rc != RPS_OK) return rc;
-    return timed_launch(ctx, [&] {
+    return commit_outcome(ctx, step, prm, timed_launch(ctx, [&] {
         return rps::launch_round(ctx->dtype, mode, X, G, ctx->tab, prm, ctx->max_block_cols, tuning_for(ctx, mode),
                                  ctx->stream);
-    });
+    }));
 }
 
 int rps_round_gradient_averaging(rps_ctx *ctx, void *X, const void *G, uint64_t step) {
     if (!ctx || !X || !G || !step_ok(step)) return RPS_EINVAL;
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return RPS_EHIP;
-    const RoundParams prm = make_params(ctx, X, G, step);
-    const int rc = enqueue_masks(ctx, step);
+    RoundParams prm = make_params(ctx, X, G, step);
+    const int rc = prepare_outcome(ctx, step, prm);
     if (rc != RPS_OK) return rc;
-    return timed_launch(ctx, [&] {
+    return commit_outcome(ctx, step, prm, timed_launch(ctx, [&] {
         return rps::launch_gradavg(ctx->dtype, X, G, ctx->tab, prm, ctx->max_block_cols,
                                    tuning_for(ctx, rps::kGradBuffer).max_waves_per_cu, ctx->stream);
-    });
+    }));
 }
 
 int rps_get_masks(rps_ctx *ctx, uint64_t step, uint8_t *up, uint8_t *down, int32_t *server) {
@@ -356,6 +414,7 @@ int rps_set_mask_override(rps_ctx *ctx, const uint8_t *up, const uint8_t *down, 
     if (!up && !down && !server) {
         RPS_HIP(ctx, hipStreamSynchronize(ctx->stream));
         ctx->override_on = false;
+        ctx->cur_valid = ctx->next_valid = false;
         return RPS_OK;
     }
     if (!up || !down || !server) return RPS_EINVAL;
@@ -383,6 +442,7 @@ int rps_set_mask_override(rps_ctx *ctx, const uint8_t *up, const uint8_t *down, 
     RPS_HIP(ctx, hipMemcpyAsync(ctx->tab, ctx->staging, sizeof(RoundTable), hipMemcpyHostToDevice, ctx->stream));
     RPS_HIP(ctx, hipStreamSynchronize(ctx->stream));
     ctx->override_on = true;
+    ctx->cur_valid = ctx->next_valid = false;
     return RPS_OK;
 }
 

@@ -34,6 +34,11 @@ struct RoundParams {
     float lambda;         // synthetic gradient: weight decay
     uint32_t seed_lo, seed_hi;
     uint32_t step_lo, step_hi24;
+    // Outcome of the following step, prepared by the averaging kernels (nullptr: not wanted)
+    RoundTable *next_tab;
+    uint64_t threshold;     // a message is lost iff its hash word < threshold
+    int32_t server_mode;
+    uint32_t next_step_lo, next_step_hi24;
 };
 
 enum GradMode { kGradNone = 0, kGradBuffer = 1, kGradSynthetic = 2 };

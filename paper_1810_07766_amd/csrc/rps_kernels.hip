@@ -101,12 +101,11 @@ __device__ __forceinline__ void draw_links(int n, int i, int j, int s, uint32_t 
     dcol = __ballot(active && ((uint64_t)cd[0] >= threshold || i == s));
 }
 
-__global__ __launch_bounds__(64) void masks_kernel(RoundTable *__restrict__ tab, int n, uint32_t seed_lo,
-                                                   uint32_t seed_hi, uint32_t step_lo, uint32_t step_hi24,
-                                                   uint64_t threshold, int server_mode) {
-    const int j = blockIdx.x;
-    const int i = threadIdx.x;
-
+// Outcome of block j for one round, computed by one full wavefront (lane i = worker i) and written
+// to `tab` by lane 0.
+__device__ __forceinline__ void write_block_outcome(RoundTable *__restrict__ tab, int n, int j, int i, uint32_t seed_lo,
+                                                    uint32_t seed_hi, uint32_t step_lo, uint32_t step_hi24,
+                                                    uint64_t threshold, int server_mode) {
     // external parameter servers (the paper's Fig. 1) are not workers: no lane is the server
     int s = server_mode == 2 ? -1 : j;
     if (server_mode == 0) s = draw_server(n, i, j, server_key(i, seed_lo, seed_hi, step_lo, step_hi24));
@@ -123,6 +122,22 @@ __global__ __launch_bounds__(64) void masks_kernel(RoundTable *__restrict__ tab,
         tab->inv_cnt[j] = cnt > 0 ? 1.0 / (double)cnt : 0.0;
         tab->server[j] = s;
     }
+}
+
+__global__ __launch_bounds__(64) void masks_kernel(RoundTable *__restrict__ tab, int n, uint32_t seed_lo,
+                                                   uint32_t seed_hi, uint32_t step_lo, uint32_t step_hi24,
+                                                   uint64_t threshold, int server_mode) {
+    write_block_outcome(tab, n, blockIdx.x, threadIdx.x, seed_lo, seed_hi, step_lo, step_hi24, threshold, server_mode);
+}
+
+// The averaging kernels also prepare the NEXT round's outcome (rounds usually come with consecutive
+// steps): the first wavefront of every block's grid row writes block j's outcome for step + 1 into
+// the other table, so that the next call needs no separate mask launch.  prm.next_tab == nullptr:
+// not wanted.  `first` must be wave-uniform and true for exactly one full wavefront per block.
+__device__ __forceinline__ void prepare_next_outcome(const RoundParams &prm, bool first, int j, int lane) {
+    if (prm.next_tab != nullptr && first)
+        write_block_outcome(prm.next_tab, prm.n, j, lane, prm.seed_lo, prm.seed_hi, prm.next_step_lo, prm.next_step_hi24,
+                            prm.threshold, prm.server_mode);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -536,6 +551,7 @@ __global__ __launch_bounds__(WPB * 64) void round_kernel(ST *__restrict__ X, con
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int j = blockIdx.y;
+    prepare_next_outcome(prm, linear_block() == 0 && wave == 0, j, lane);
     const int64_t lo = tab->off[j], hi = tab->off[j + 1];
     const int64_t tile0 = (lo / TILE) * TILE + (linear_block() * WPB + wave) * TILE;
     if (tile0 >= hi) return;   // wave-uniform: this block has fewer tiles than the largest one
@@ -767,6 +783,7 @@ __global__ __launch_bounds__(64) void round_kernel_narrow(ST *__restrict__ X, co
     constexpr int TILE = LPR * VEC;
     const int lane = threadIdx.x;
     const int j = blockIdx.y;
+    prepare_next_outcome(prm, linear_block() == 0, j, lane);
     const int64_t lo = tab->off[j], hi = tab->off[j + 1];
     const int64_t tile0 = (lo / TILE) * TILE + linear_block() * TILE;
     if (tile0 >= hi) return;   // wave-uniform
@@ -1040,6 +1057,7 @@ __global__ __launch_bounds__(256) void gradavg_kernel(ST *__restrict__ X, const 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int j = blockIdx.y;
+    prepare_next_outcome(prm, linear_block() == 0 && wave == 0, j, lane);
     const int64_t lo = tab->off[j], hi = tab->off[j + 1];
     const int64_t tile0 = (lo / TILE) * TILE + (linear_block() * 4 + wave) * TILE;
     if (tile0 >= hi) return;   // wave-uniform
@@ -1121,6 +1139,7 @@ __global__ __launch_bounds__(64) void gradavg_kernel_narrow(ST *__restrict__ X, 
     constexpr int TILE = kTiledLanes * VEC;
     const int lane = threadIdx.x;
     const int j = blockIdx.y;
+    prepare_next_outcome(prm, linear_block() == 0, j, lane);
     const int64_t lo = tab->off[j], hi = tab->off[j + 1];
     const int64_t tile0 = (lo / TILE) * TILE + linear_block() * TILE;
     if (tile0 >= hi) return;   // wave-uniform

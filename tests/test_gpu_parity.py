@@ -639,3 +639,52 @@ def test_rounds_can_be_captured_in_a_hip_graph(rps):
             ctx.round(start.clone(), None, 100 + rep)
         s.synchronize()
     ctx.destroy()
+
+
+@pytest.mark.parametrize("tiled", [False, True])
+def test_any_order_of_steps_and_calls(rps, tiled):
+    """The kernels prepare the next step's network outcome in advance; which outcome a table holds
+    is tracked by step number, so results must not depend on the order of steps or calls: repeated,
+    skipped and decreasing steps, the entry points mixed, a forced outcome set and cleared in
+    between, get_masks in between -- against the oracle after every call."""
+    n, N, p, gamma, seed = 12, 12 * 1000, 0.3, 0.2, 4
+    off = workloads.block_offsets(n, N)
+    ctx = rps.RpsContext(n, N, p, gamma, seed, flags=rps.RPS_FLAG_LAYOUT_TILED if tiled else 0)
+    ctx.set_synthetic_grad(0.2, 0.01)
+    Xr = device_tensor(workloads.gaussian_model(n, N, seed=1), "f32")
+    G = device_tensor(workloads.gaussian_model(n, N, seed=2), "f32")
+    Xo, Go = to_oracle(Xr), to_oracle(G)
+    X = workloads.to_tiled(Xr) if tiled else Xr
+    Gd = workloads.to_tiled(G) if tiled else G
+    rng = np.random.default_rng(0)
+    forced = (rng.permutation(n).astype(np.int32), (rng.random((n, n)) < 0.6).astype(np.uint8),
+              (rng.random((n, n)) < 0.6).astype(np.uint8))
+    for j in range(n):
+        forced[1][forced[0][j], j] = forced[2][forced[0][j], j] = 1
+    script = [("round", 0), ("round", 1), ("round", 2), ("round", 2), ("avg", 3), ("avg", 3), ("round", 7), ("gradavg", 8),
+              ("round", 9), ("masks", 10), ("round", 10), ("round", 5), ("avg", 6), ("force", 0), ("round", 7), ("avg", 8),
+              ("unforce", 0), ("round", 9), ("roundG", 10), ("gradavg", 11), ("avg", 12), ("round", 2 ** 56 - 2),
+              ("round", 2 ** 56 - 1), ("round", 0), ("round", 1)]
+    override = None
+    for k, (what, t) in enumerate(script):
+        if what == "force":
+            ctx.set_mask_override(*forced); override = forced; continue
+        if what == "unforce":
+            ctx.set_mask_override(None, None, None); override = None; continue
+        if what == "masks":
+            masks_equal(ctx, seed, t, n, p); continue
+        if what in ("round", "roundG"):
+            g = what == "roundG"
+            ctx.round(X, Gd if g else None, t)
+            oracle.round_(Xo, Go if g else None, off, p=p, gamma=gamma, seed=seed, step=t, sigma=0.2, weight_decay=0.01,
+                          mask_override=override)
+        elif what == "avg":
+            ctx.lossy_average(X, t)
+            U, D = (override[1], override[2]) if override else oracle.masks(seed, t, n, p)[1:]
+            oracle.lossy_average(Xo, off, U, D)
+        else:
+            ctx.round_gradient_averaging(X, Gd, t)
+            oracle.round_gradient_averaging(Xo, Go, off, p=p, gamma=gamma, seed=seed, step=t, mask_override=override)
+        got = workloads.from_tiled(X, N) if tiled else X
+        assert_close(to_oracle(got), Xo, off, "f32", what=f"call {k}: {what} step {t}")
+    ctx.destroy()
