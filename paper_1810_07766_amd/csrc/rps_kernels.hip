@@ -7,6 +7,7 @@
 // Kernels
 //   masks_kernel      network outcome of one round: server permutation, uplink and downlink
 //                     delivery bits (Sec. 3; Alg. 1 steps 6-7), n workgroups of one wavefront
+//                     (the averaging kernels also prepare the following step's outcome)
 //   mixing_moments_kernel  Monte-Carlo sums for the constants alpha1, alpha2 of the mixing matrix
 //                     (Sec. 4.2), one wavefront per simulated round
 //   round_kernel      local SGD step + Reduce-Scatter average + All-Gather write-back in one
@@ -16,7 +17,9 @@
 //                     n x 128 bytes of a 128-byte-wide tile, 8 rows per instruction
 //   local_step_kernel the local SGD step alone, one row per wavefront (contiguous streams);
 //                     local_step_tiled_kernel: the same on the tile-major layout
-//   gradavg_kernel    the gradient-averaging comparison of Sec. 6 (same masks applied to G)
+//   gradavg_kernel    the gradient-averaging comparison of Sec. 6 (same masks applied to G);
+//                     gradavg_kernel_narrow: the same on the tile-major layout
+//   convert_layout_kernel  copy of a state between the row-major and the tile-major arrangement
 //   consensus_kernel  sum_i ||x_i - xbar||^2 and ||xbar||^2 in one streaming read (Lemma 1's quantity)
 // The path is a streaming reduction with < 0.5 flop per byte: it is bound by HBM bandwidth
 // (and, with the in-register Gaussian generator, by plain vector ALU work), never by a dense
