@@ -630,37 +630,46 @@ __device__ __forceinline__ void store_seg(ST *base, uint32_t eoff, uint32_t limi
     }
 }
 
-template <typename ST, int GRAD, int LPR, int CP, bool FULL>
+// PG = lane groups per tile (8, 4, 2 or 1).  With 16 or more workers a tile takes all 8 lane groups
+// of the wavefront; with fewer, 8 / PG adjacent tiles share the wavefront (lane group lgw serves
+// tile lgw / PG as group lgw % PG), so that no lane group idles and the wavefront still moves 1 KB
+// per instruction.
+template <typename ST, int GRAD, int LPR, int PG, int CP, bool FULL>
 struct NarrowTile {
     using S = Storage<ST>;
     using Raw = typename S::Raw;
     static constexpr int VEC = S::VEC;
-    static constexpr int GROUPS = 64 / LPR;      // lane groups = rows per wavefront instruction
+    static constexpr int GROUPS = PG;            // lane groups of one tile = its rows per wavefront instruction
+    static constexpr int TPW = (64 / LPR) / PG;  // tiles per wavefront
     static constexpr uint32_t STRIDE = LPR * VEC;   // elements between consecutive rows of a tile (tiled layout)
     // CP = row pairs per lane and load chunk (2 * CP rows in flight per chunk): 1 up to 16 workers
     // (a lane then has a single pair), else 2
     static constexpr int CG = GRAD == kGradBuffer ? 2 * CP : 1;
 
     const RoundParams &prm;
-    ST *Xt;            // the tile: wave-uniform base, every access adds a 32-bit lane offset
+    ST *Xt;            // the wavefront's first tile: wave-uniform base, every access adds a 32-bit lane offset
     const ST *Gt;
-    uint32_t sub_off;  // this lane's columns inside a row segment
-    int64_t c0, lo, hi;
-    int lg;
+    uint32_t sub_off;  // this lane's tile inside the wavefront's run + its columns inside a row segment
+    int64_t c0, lo, hi;   // c0: the lane's first column
+    int lg;            // the lane's group inside its tile
     // The lane's rows are 2*lg + 2*GROUPS*k + r (pair k, r = 0, 1): bit 2*GROUPS*k + r of these words
     // (the masks shifted down by 2*lg) says whether that row's copy reached the server (sum),
     // whether its reply arrived (gets the average), whether it keeps its own v -- rows >= n: none.
     uint64_t sum_bits, avg_bits, own_bits;
-    uint32_t limit;    // bytes of the tile: the buffer resource's bound
+    uint32_t limit;    // bytes of the wavefront's tiles: the buffer resource's bound
 
-    __device__ __forceinline__ NarrowTile(const RoundParams &prm_, ST *Xt_, const ST *Gt_, uint32_t sub_off_, int64_t c0_,
-                                          int64_t lo_, int64_t hi_, uint64_t ucol, uint64_t dcol, int lg_)
-        : prm(prm_), Xt(Xt_), Gt(Gt_), sub_off(sub_off_), c0(c0_), lo(lo_), hi(hi_), lg(lg_) {
+    // lgw = lane / LPR, col_off = (lane % LPR) * VEC, first = first column of the wavefront's first tile
+    __device__ __forceinline__ NarrowTile(const RoundParams &prm_, ST *Xt_, const ST *Gt_, uint32_t col_off, int64_t first,
+                                          int64_t lo_, int64_t hi_, uint64_t ucol, uint64_t dcol, int lgw)
+        : prm(prm_), Xt(Xt_), Gt(Gt_), lo(lo_), hi(hi_), lg(lgw % PG) {
+        const int tw = lgw / PG;   // the lane's tile among the wavefront's
+        sub_off = (uint32_t)tw * (uint32_t)prm.n * STRIDE + col_off;
+        c0 = first + (int64_t)tw * (LPR * VEC) + col_off;
         const uint64_t valid = prm.n >= 64 ? ~0ull : ((1ull << prm.n) - 1);
         sum_bits = (ucol & valid) >> (2 * lg);
         avg_bits = (dcol & valid) >> (2 * lg);
         own_bits = (~dcol & valid) >> (2 * lg);
-        limit = (uint32_t)prm.n * STRIDE * (uint32_t)sizeof(ST);
+        limit = (uint32_t)TPW * (uint32_t)prm.n * STRIDE * (uint32_t)sizeof(ST);
     }
 
     // bit of pair k, row r of that pair
@@ -724,7 +733,7 @@ struct NarrowTile {
     __device__ __forceinline__ void finish(double acc[VEC], double inv, int steps) const {
         // combine the lane groups: after the butterfly every lane of a column group holds the same sum
 #pragma unroll
-        for (int o = LPR; o < 64; o <<= 1) {
+        for (int o = LPR; o < LPR * PG; o <<= 1) {
 #pragma unroll
             for (int e = 0; e < VEC; ++e) acc[e] += __shfl_xor(acc[e], o, 64);
         }
@@ -778,29 +787,29 @@ struct NarrowTile {
 };
 
 // Tiled layout only: the tile [tile0, tile0 + LPR * VEC) of all n workers is the contiguous run of
-// n * LPR * 16 bytes at element offset tile0 * n.
-template <typename ST, int GRAD, int LPR, int CP, bool SINGLE>
+// n * LPR * 16 bytes at element offset tile0 * n; a wavefront takes 8 / PG adjacent tiles.
+template <typename ST, int GRAD, int LPR, int PG, int CP, bool SINGLE>
 __global__ __launch_bounds__(64) void round_kernel_narrow(ST *__restrict__ X, const ST *__restrict__ G,
                                                           const RoundTable *__restrict__ tab, const RoundParams prm) {
     constexpr int VEC = Storage<ST>::VEC;
-    constexpr int TILE = LPR * VEC;
+    constexpr int WIDTH = ((64 / LPR) / PG) * LPR * VEC;   // columns per wavefront
     const int lane = threadIdx.x;
     const int j = blockIdx.y;
     prepare_next_outcome(prm, linear_block() == 0, j, lane);
     const int64_t lo = tab->off[j], hi = tab->off[j + 1];
-    const int64_t tile0 = (lo / TILE) * TILE + linear_block() * TILE;
-    if (tile0 >= hi) return;   // wave-uniform
-    const uint32_t sub_off = (uint32_t)(lane % LPR) * VEC;
-    ST *Xt = X + tile0 * prm.n;
-    const ST *Gt = G ? G + tile0 * prm.n : nullptr;
-    const bool full = prm.vec_ok && tile0 >= lo && tile0 + TILE <= hi;   // wave-uniform
+    const int64_t first = (lo / WIDTH) * WIDTH + linear_block() * WIDTH;
+    if (first >= hi) return;   // wave-uniform
+    const uint32_t col_off = (uint32_t)(lane % LPR) * VEC;
+    ST *Xt = X + first * prm.n;
+    const ST *Gt = G ? G + first * prm.n : nullptr;
+    const bool full = prm.vec_ok && first >= lo && first + WIDTH <= hi;   // wave-uniform
     if (full) {
-        const NarrowTile<ST, GRAD, LPR, CP, true> t(prm, Xt, Gt, sub_off, tile0 + sub_off, lo, hi,
-                                                    tab->ucol[j], tab->dcol[j], lane / LPR);
+        const NarrowTile<ST, GRAD, LPR, PG, CP, true> t(prm, Xt, Gt, col_off, first, lo, hi, tab->ucol[j], tab->dcol[j],
+                                                        lane / LPR);
         t.template run<SINGLE>(tab->inv_cnt[j]);
     } else {
-        const NarrowTile<ST, GRAD, LPR, CP, false> t(prm, Xt, Gt, sub_off, tile0 + sub_off, lo, hi,
-                                                     tab->ucol[j], tab->dcol[j], lane / LPR);
+        const NarrowTile<ST, GRAD, LPR, PG, CP, false> t(prm, Xt, Gt, col_off, first, lo, hi, tab->ucol[j], tab->dcol[j],
+                                                         lane / LPR);
         t.template run<SINGLE>(tab->inv_cnt[j]);
     }
 }
@@ -918,19 +927,32 @@ template <typename ST, int GRAD, int LPR>
 hipError_t launch_round_narrow(ST *X, const ST *G, const RoundTable *tab, const RoundParams &prm, int64_t max_block_cols,
                                int max_waves_per_cu, hipStream_t stream) {
     constexpr int TILE = LPR * Storage<ST>::VEC;
-    const int64_t tiles = (max_block_cols + 2 * TILE - 2) / TILE;
-    const dim3 grid = folded_grid(tiles, (unsigned)prm.blocks);
+    constexpr int GROUPS = 64 / LPR;
     size_t lds = 0;
     if (max_waves_per_cu > 0 && max_waves_per_cu < 32) {
         lds = ((size_t)kLdsBytesPerCu / max_waves_per_cu) & ~(size_t)255;
         if (lds > 65536) lds = 65536;
     }
-    if (prm.n <= 2 * (64 / LPR))        // a lane has one row pair
-        hipLaunchKernelGGL((round_kernel_narrow<ST, GRAD, LPR, 1, true>), grid, dim3(64), lds, stream, X, G, tab, prm);
-    else if (prm.n <= 4 * (64 / LPR))   // two pairs: still one load chunk
-        hipLaunchKernelGGL((round_kernel_narrow<ST, GRAD, LPR, 2, true>), grid, dim3(64), lds, stream, X, G, tab, prm);
+    // lane groups per tile: as many as the workers' row pairs need, a power of two
+    const int pairs = (prm.n + 1) / 2;
+    const int pg = pairs > 4 ? 8 : (pairs > 2 ? 4 : (pairs > 1 ? 2 : 1));
+    const int64_t width = (int64_t)(GROUPS / pg) * TILE;   // columns per wavefront
+    const dim3 grid = folded_grid((max_block_cols + 2 * width - 2) / width, (unsigned)prm.blocks);
+#define RPS_N(PG, CP, SINGLE) \
+    hipLaunchKernelGGL((round_kernel_narrow<ST, GRAD, LPR, PG, CP, SINGLE>), grid, dim3(64), lds, stream, X, G, tab, prm)
+    if (pg == 1)
+        RPS_N(1, 1, true);
+    else if (pg == 2)
+        RPS_N(2, 1, true);
+    else if (pg == 4)
+        RPS_N(4, 1, true);
+    else if (prm.n <= 2 * GROUPS)   // a lane has one row pair
+        RPS_N(8, 1, true);
+    else if (prm.n <= 4 * GROUPS)   // two pairs: still one load chunk
+        RPS_N(8, 2, true);
     else
-        hipLaunchKernelGGL((round_kernel_narrow<ST, GRAD, LPR, 2, false>), grid, dim3(64), lds, stream, X, G, tab, prm);
+        RPS_N(8, 2, false);
+#undef RPS_N
     return hipGetLastError();
 }
 
