@@ -74,12 +74,11 @@ rps::LaunchTuning default_tuning(int32_t n, int32_t dtype, int grad_mode) {
 
 rps::LaunchTuning tuning_for(const rps_ctx *ctx, int grad_mode) {
     if (ctx->tune_set) return ctx->tune;
-    if (ctx->flags & RPS_FLAG_LAYOUT_TILED) {   // small tiles, one piece of memory each: more wavefronts resident
-        const int n = ctx->n;                    // (measured at n = 8 / 16 / 32 fp32 and n = 64 bf16)
-        int cap;
-        if (grad_mode == rps::kGradSynthetic) cap = n >= 24 ? 20 : 0;
-        else if (grad_mode == rps::kGradNone) cap = n >= 48 ? 8 : (n >= 24 ? 10 : 24);
-        else cap = n >= 24 ? 12 : (n >= 12 ? 20 : 0);
+    if (ctx->flags & RPS_FLAG_LAYOUT_TILED) {   // a wavefront owns about 4 KB whatever n is: more of them resident
+        int cap;                                 // (measured at n = 8 / 16 / 32 fp32 and n = 64 bf16)
+        if (grad_mode == rps::kGradSynthetic) cap = 20;
+        else if (grad_mode == rps::kGradNone) cap = ctx->n >= 48 ? 8 : 10;
+        else cap = 12;
         return rps::LaunchTuning{4, 1, cap};
     }
     return default_tuning(ctx->n, ctx->dtype, grad_mode);

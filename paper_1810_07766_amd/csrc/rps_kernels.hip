@@ -925,7 +925,7 @@ hipError_t launch_round_v(ST *X, const ST *G, const RoundTable *tab, const Round
 
 template <typename ST, int GRAD, int LPR>
 hipError_t launch_round_narrow(ST *X, const ST *G, const RoundTable *tab, const RoundParams &prm, int64_t max_block_cols,
-                               int max_waves_per_cu, hipStream_t stream) {
+                               int max_waves_per_cu, bool one_pair_per_lane, hipStream_t stream) {
     constexpr int TILE = LPR * Storage<ST>::VEC;
     constexpr int GROUPS = 64 / LPR;
     size_t lds = 0;
@@ -933,19 +933,28 @@ hipError_t launch_round_narrow(ST *X, const ST *G, const RoundTable *tab, const 
         lds = ((size_t)kLdsBytesPerCu / max_waves_per_cu) & ~(size_t)255;
         if (lds > 65536) lds = 65536;
     }
-    // lane groups per tile: as many as the workers' row pairs need, a power of two
+    // lane groups per tile: a power of two such that a lane gets two row pairs where the workers
+    // allow it (tuning knob waves_per_workgroup == 4: one pair per lane, for comparison)
     const int pairs = (prm.n + 1) / 2;
-    const int pg = pairs > 4 ? 8 : (pairs > 2 ? 4 : (pairs > 1 ? 2 : 1));
+    const bool two = !one_pair_per_lane;
+    const int need = two ? (pairs + 1) / 2 : pairs;
+    const int pg = need > 4 ? 8 : (need > 2 ? 4 : (need > 1 ? 2 : 1));
     const int64_t width = (int64_t)(GROUPS / pg) * TILE;   // columns per wavefront
     const dim3 grid = folded_grid((max_block_cols + 2 * width - 2) / width, (unsigned)prm.blocks);
 #define RPS_N(PG, CP, SINGLE) \
     hipLaunchKernelGGL((round_kernel_narrow<ST, GRAD, LPR, PG, CP, SINGLE>), grid, dim3(64), lds, stream, X, G, tab, prm)
-    if (pg == 1)
+    if (pg == 1 && pairs <= 1)
         RPS_N(1, 1, true);
-    else if (pg == 2)
+    else if (pg == 1)
+        RPS_N(1, 2, true);
+    else if (pg == 2 && pairs <= 2)
         RPS_N(2, 1, true);
-    else if (pg == 4)
+    else if (pg == 2)
+        RPS_N(2, 2, true);
+    else if (pg == 4 && pairs <= 4)
         RPS_N(4, 1, true);
+    else if (pg == 4)
+        RPS_N(4, 2, true);
     else if (prm.n <= 2 * GROUPS)   // a lane has one row pair
         RPS_N(8, 1, true);
     else if (prm.n <= 4 * GROUPS)   // two pairs: still one load chunk
@@ -960,7 +969,8 @@ template <typename ST, int GRAD>
 hipError_t launch_round_t(ST *X, const ST *G, const RoundTable *tab, const RoundParams &prm, int64_t max_block_cols,
                           const LaunchTuning &tune, hipStream_t stream) {
     if (prm.tiled)
-        return launch_round_narrow<ST, GRAD, kTiledLanes>(X, G, tab, prm, max_block_cols, tune.max_waves_per_cu, stream);
+        return launch_round_narrow<ST, GRAD, kTiledLanes>(X, G, tab, prm, max_block_cols, tune.max_waves_per_cu,
+                                                          tune.waves_per_workgroup == 4, stream);
 #define RPS_V(R, W) launch_round_v<ST, GRAD, R, W>(X, G, tab, prm, max_block_cols, tune.max_waves_per_cu, stream)
     const int r = tune.rows_in_flight, w = tune.waves_per_workgroup;
     if (w == 1) return r <= 2 ? RPS_V(2, 1) : RPS_V(4, 1);
