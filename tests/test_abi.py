@@ -69,3 +69,23 @@ def test_header_is_plain_c(tmp_path):
     out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split(None, 1)
     assert int(out[0]) == len(names) and out[1].strip() == "invalid argument"
     subprocess.run(["g++", "-std=c++17", "-fsyntax-only", "-x", "c++", "-I", inc, os.path.join(inc, "rps.h")], check=True)
+
+
+def test_tile_major_index_formula():
+    """workloads.to_tiled / from_tiled (the re-arrangement the tests hand to the library) against the
+    index formula of include/rps.h: element (i, c) lives at ((c / T) * n + i) * T + c % T."""
+    import numpy as np
+    import torch
+    import workloads
+    for n, N, dt in ((3, 100, torch.float32), (5, 64, torch.float32), (2, 130, torch.bfloat16)):
+        X = torch.arange(n * N, dtype=torch.float32).reshape(n, N).to(dt)
+        Xt = workloads.to_tiled(X)
+        T = workloads.TILE_BYTES // X.element_size()
+        assert tuple(Xt.shape) == ((N + T - 1) // T, n, T)
+        flat = Xt.reshape(-1)
+        for i, c in ((0, 0), (n - 1, N - 1), (1, T), (n - 1, T - 1), (0, N // 2)):
+            assert flat[((c // T) * n + i) * T + c % T] == X[i, c]
+        assert torch.equal(workloads.from_tiled(Xt, N), X)
+        if N % T:
+            assert float(Xt[-1, :, N % T:].abs().sum()) == 0.0      # zero padding
+    assert workloads.TILE_BYTES == 128
