@@ -89,3 +89,20 @@ def test_tile_major_index_formula():
         if N % T:
             assert float(Xt[-1, :, N % T:].abs().sum()) == 0.0      # zero padding
     assert workloads.TILE_BYTES == 128
+
+
+def test_constants_agree_with_the_header():
+    _ensure_built()
+    import workloads
+    from paper_1810_07766_amd import rps
+    header = open(os.path.join(ROOT, "include", "rps.h")).read()
+    assert int(re.search(r"#define RPS_TILE_BYTES (\d+)", header).group(1)) == rps.RPS_TILE_BYTES == workloads.TILE_BYTES
+    enums = dict(re.findall(r"(RPS_[A-Z0-9_]+)\s*=\s*(-?\d+)u?", header))
+    for name, value in enums.items():
+        assert getattr(rps, name) == int(value), name
+    lib = ctypes.CDLL(LIB)
+    lib.rps_storage_elems.restype = ctypes.c_int64
+    lib.rps_storage_elems.argtypes = [ctypes.c_int32, ctypes.c_int64, ctypes.c_int32, ctypes.c_uint32]
+    assert lib.rps_storage_elems(4, 1000, 0, 0) == 4000
+    assert lib.rps_storage_elems(4, 1000, 0, rps.RPS_FLAG_LAYOUT_TILED) == 32 * 4 * 32
+    assert lib.rps_storage_elems(65, 1000, 0, 0) == -1
