@@ -573,15 +573,16 @@ __global__ __launch_bounds__(WPB * 64) void round_kernel(ST *__restrict__ X, con
 }
 
 // ---------------------------------------------------------------------------------------
-// Narrow tiles: the same round with LPR < 64 lanes per row segment.  A tile is LPR x 16 bytes
-// wide; one wavefront instruction covers 64 / LPR rows of it (lane group lg = lane / LPR), and a
-// lane owns the row pairs lg, lg + 64/LPR, ... of its 16-byte column group, so that the noise
-// hash of a (4 columns x 2 rows) patch still serves one lane.  A wavefront then reads only
-// n x LPR x 16 bytes before it writes them back (8 KB at n = 32, LPR = 16, against 32 KB with
-// 64 lanes per row), which is what the memory system rewards; in the tiled layout these bytes
-// are one contiguous piece of memory.  Column sums: every lane group sums its own rows in
-// ascending order, the groups are then combined by a butterfly over the lanes (a fixed order,
-// the same for every receiver, but not the plain ascending order of the wide kernel).
+// Narrow tiles (the tile-major layout): the same round with LPR = 8 lanes per row segment.  A tile
+// is LPR x 16 = 128 bytes wide and its n rows are adjacent in memory; one wavefront instruction
+// covers 64 / LPR = 8 row segments (lane group = lane / LPR), and a lane owns row pairs of its
+// 16-byte column group, so that the noise hash of a (4 columns x 2 rows) patch still serves one
+// lane.  A wavefront then reads only about 4 KB of consecutive memory before it writes it back
+// (one tile of 32 workers, or several adjacent tiles of fewer), against 32 KB spread over 32 rows
+// in the row-major kernel -- which is what the memory system rewards.  Column sums: every lane
+// group sums its own rows in ascending order, the groups of a tile are then combined by a
+// butterfly over the lanes (a fixed order, the same for every receiver, but not the plain
+// ascending order of the row-major kernel).
 // ---------------------------------------------------------------------------------------
 constexpr int kTiledLanes = 8;   // lanes per row segment of the tiled layout: 8 x 16 B = 128 B (RPS_TILE_BYTES)
 
@@ -642,8 +643,8 @@ struct NarrowTile {
     static constexpr int GROUPS = PG;            // lane groups of one tile = its rows per wavefront instruction
     static constexpr int TPW = (64 / LPR) / PG;  // tiles per wavefront
     static constexpr uint32_t STRIDE = LPR * VEC;   // elements between consecutive rows of a tile (tiled layout)
-    // CP = row pairs per lane and load chunk (2 * CP rows in flight per chunk): 1 up to 16 workers
-    // (a lane then has a single pair), else 2
+    // CP = row pairs per lane and load chunk (2 * CP rows in flight per chunk): 2, or 1 when the
+    // workers give a lane a single pair
     static constexpr int CG = GRAD == kGradBuffer ? 2 * CP : 1;
 
     const RoundParams &prm;
