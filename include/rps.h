@@ -26,7 +26,12 @@
  *     except where stated.  Results are valid in stream order.  rps_local_step, rps_lossy_average,
  *     rps_round, rps_round_gradient_averaging and rps_convert_layout enqueue kernels only (no
  *     allocation, no synchronisation, no memset): a caller may capture them in a HIP graph; the
- *     `step` argument is then part of the captured launch.
+ *     `step` argument is then part of the captured launch.  Launches recorded during capture draw
+ *     the network outcome of their step into a table of their own that no eager call uses, so
+ *     replays and eager calls may be mixed in any order on the context's stream and every call
+ *     still sees the outcome of exactly (seed, its step) (Alg. 1 steps 6-7).  A captured launch
+ *     always uses the generated outcome: capturing while a mask override is in force returns
+ *     RPS_EUNSUPPORTED (nothing is recorded), and an override set later does not reach a graph.
  *   - Every function returns RPS_OK (0) or a negative error code; nothing aborts or throws.
  *     An error detected before launch leaves X untouched.
  *   - The round's randomness is a pure function of (seed, step): the caller supplies `step`,
@@ -49,7 +54,8 @@ enum {
     RPS_EINVAL = -1,        /* bad argument (see each function) */
     RPS_ENOMEM = -2,        /* host or device allocation failed */
     RPS_EHIP = -3,          /* a HIP call failed; see rps_last_hip_error() */
-    RPS_EUNSUPPORTED = -4   /* valid request this build does not implement */
+    RPS_EUNSUPPORTED = -4   /* valid request this build does not implement (a forced network outcome
+                               inside a stream capture) */
 };
 
 enum { RPS_DTYPE_F32 = 0, RPS_DTYPE_BF16 = 1 };

@@ -27,10 +27,14 @@ struct rps_ctx {
     int device = 0;
     int64_t max_block_cols = 0;
     std::vector<int64_t> off;
-    RoundTable *tab_base = nullptr;   // device allocation: three tables + the reduction scratch
+    RoundTable *tab_base = nullptr;   // device allocation: five tables + the reduction scratch
+    // The two tables of the eager calls: only launches that execute at once ever write them, so what
+    // the host believes about them (cur_step / next_step) stays true whatever else happens.
     RoundTable *tab = nullptr;        // device: table the averaging kernels read (outcome of cur_step if cur_valid)
     RoundTable *tab_other = nullptr;  // device: outcome of next_step if next_valid, prepared by the previous kernel
     RoundTable *tab_query = nullptr;  // device: scratch table for rps_get_masks
+    RoundTable *tab_capture = nullptr;   // device: the only table launches recorded during stream capture write and read
+    RoundTable *tab_override = nullptr;  // device: the forced outcome of rps_set_mask_override
     bool cur_valid = false, next_valid = false;
     uint64_t cur_step = 0, next_step = 0;
     RoundTable *staging = nullptr;    // pinned host copy (create, override, query)
@@ -149,14 +153,15 @@ int server_mode(const rps_ctx *ctx) {
 // launched to prepare the outcome of step + 1 in the other table (rounds usually come with
 // consecutive steps; a call whose step is already in one of the two tables needs no mask launch).
 // What a table holds is tracked on the host by step number, so results never depend on this.
-// While the stream is being captured into a graph nothing is assumed or remembered: the captured
-// launches must be self-contained, and they do not execute now.
-int prepare_outcome(rps_ctx *ctx, uint64_t step, RoundParams &prm) {
+// Launches recorded while the stream is being captured into a graph run later, any number of times,
+// between eager calls the host cannot foresee: they are self-contained (their own mask launch) and
+// touch only the capture table, which no eager call reads or writes, so a replay can never change
+// a table whose step the host tracks.  `use` receives the table the averaging kernel must read.
+int prepare_outcome(rps_ctx *ctx, uint64_t step, RoundParams &prm, const RoundTable *&use) {
     prm.next_tab = nullptr;
     prm.threshold = ctx->threshold;
     prm.server_mode = server_mode(ctx);
     prm.next_step_lo = prm.next_step_hi24 = 0;
-    if (ctx->override_on) return RPS_OK;   // the table already holds the forced outcome
     hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
     bool capturing = true;
     if (hipStreamIsCapturing(ctx->stream, &cs) == hipSuccess)
@@ -164,9 +169,16 @@ int prepare_outcome(rps_ctx *ctx, uint64_t step, RoundParams &prm) {
     else
         (void)hipGetLastError();
     if (capturing) {
-        ctx->cur_valid = ctx->next_valid = false;
-        RPS_HIP(ctx, rps::launch_masks(ctx->tab, ctx->n, ctx->nb, ctx->seed, step, ctx->threshold, server_mode(ctx),
-                                       ctx->stream));
+        // a forced outcome lives in host-written memory that a later rps_set_mask_override changes:
+        // a graph cannot pin it
+        if (ctx->override_on) return RPS_EUNSUPPORTED;
+        use = ctx->tab_capture;
+        RPS_HIP(ctx, rps::launch_masks(ctx->tab_capture, ctx->n, ctx->nb, ctx->seed, step, ctx->threshold,
+                                       server_mode(ctx), ctx->stream));
+        return RPS_OK;
+    }
+    if (ctx->override_on) {   // the override table holds the forced outcome
+        use = ctx->tab_override;
         return RPS_OK;
     }
     if (ctx->next_valid && ctx->next_step == step) {
@@ -184,6 +196,7 @@ int prepare_outcome(rps_ctx *ctx, uint64_t step, RoundParams &prm) {
         prm.next_step_lo = (uint32_t)(step + 1);
         prm.next_step_hi24 = (uint32_t)(((step + 1) >> 32) & 0xFFFFFFu);
     }
+    use = ctx->tab;
     return RPS_OK;
 }
 
@@ -265,22 +278,21 @@ static int create_impl(rps_ctx **out, int32_t n, int32_t nb, bool external, int6
 
     hipError_t e = hipGetDevice(&ctx->device);
     const size_t scratch_bytes = (2 * (size_t)rps::kMaxPartials + 2) * sizeof(double);
-    if (e == hipSuccess) e = hipMalloc((void **)&ctx->tab_base, 3 * sizeof(RoundTable) + scratch_bytes);
+    if (e == hipSuccess) e = hipMalloc((void **)&ctx->tab_base, 5 * sizeof(RoundTable) + scratch_bytes);
     if (e == hipSuccess) {
         ctx->tab = ctx->tab_base;
         ctx->tab_other = ctx->tab_base + 1;
         ctx->tab_query = ctx->tab_base + 2;
-        ctx->partials = reinterpret_cast<double *>(ctx->tab_base + 3);
+        ctx->tab_capture = ctx->tab_base + 3;
+        ctx->tab_override = ctx->tab_base + 4;
+        ctx->partials = reinterpret_cast<double *>(ctx->tab_base + 5);
         e = hipHostMalloc((void **)&ctx->staging, sizeof(RoundTable), hipHostMallocDefault);
     }
     if (e == hipSuccess) {
         std::memset(ctx->staging, 0, sizeof(RoundTable));
         for (int j = 0; j <= nb; ++j) ctx->staging->off[j] = ctx->off[j];
-        e = hipMemcpyAsync(ctx->tab, ctx->staging, sizeof(RoundTable), hipMemcpyHostToDevice, ctx->stream);
-        if (e == hipSuccess)
-            e = hipMemcpyAsync(ctx->tab_other, ctx->staging, sizeof(RoundTable), hipMemcpyHostToDevice, ctx->stream);
-        if (e == hipSuccess)
-            e = hipMemcpyAsync(ctx->tab_query, ctx->staging, sizeof(RoundTable), hipMemcpyHostToDevice, ctx->stream);
+        for (int k = 0; k < 5 && e == hipSuccess; ++k)   // every table carries the block offsets
+            e = hipMemcpyAsync(ctx->tab_base + k, ctx->staging, sizeof(RoundTable), hipMemcpyHostToDevice, ctx->stream);
         if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
     }
     if (e != hipSuccess) {
@@ -352,10 +364,11 @@ int rps_lossy_average(rps_ctx *ctx, void *X, uint64_t step) {
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return RPS_EHIP;
     RoundParams prm = make_params(ctx, X, nullptr, step);
-    const int rc = prepare_outcome(ctx, step, prm);
+    const RoundTable *tab = nullptr;
+    const int rc = prepare_outcome(ctx, step, prm, tab);
     if (rc != RPS_OK) return rc;
     return commit_outcome(ctx, step, prm, timed_launch(ctx, [&] {
-        return rps::launch_round(ctx->dtype, rps::kGradNone, X, nullptr, ctx->tab, prm, ctx->max_block_cols,
+        return rps::launch_round(ctx->dtype, rps::kGradNone, X, nullptr, tab, prm, ctx->max_block_cols,
                                  tuning_for(ctx, rps::kGradNone), ctx->stream);
     }));
 }
@@ -366,10 +379,11 @@ int rps_round(rps_ctx *ctx, void *X, const void *G, uint64_t step) {
     if (!guard.ok) return RPS_EHIP;
     RoundParams prm = make_params(ctx, X, G, step);
     const int mode = G ? rps::kGradBuffer : rps::kGradSynthetic;
-    const int rc = prepare_outcome(ctx, step, prm);
+    const RoundTable *tab = nullptr;
+    const int rc = prepare_outcome(ctx, step, prm, tab);
     if (rc != RPS_OK) return rc;
     return commit_outcome(ctx, step, prm, timed_launch(ctx, [&] {
-        return rps::launch_round(ctx->dtype, mode, X, G, ctx->tab, prm, ctx->max_block_cols, tuning_for(ctx, mode),
+        return rps::launch_round(ctx->dtype, mode, X, G, tab, prm, ctx->max_block_cols, tuning_for(ctx, mode),
                                  ctx->stream);
     }));
 }
@@ -379,10 +393,11 @@ int rps_round_gradient_averaging(rps_ctx *ctx, void *X, const void *G, uint64_t 
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return RPS_EHIP;
     RoundParams prm = make_params(ctx, X, G, step);
-    const int rc = prepare_outcome(ctx, step, prm);
+    const RoundTable *tab = nullptr;
+    const int rc = prepare_outcome(ctx, step, prm, tab);
     if (rc != RPS_OK) return rc;
     return commit_outcome(ctx, step, prm, timed_launch(ctx, [&] {
-        return rps::launch_gradavg(ctx->dtype, X, G, ctx->tab, prm, ctx->max_block_cols,
+        return rps::launch_gradavg(ctx->dtype, X, G, tab, prm, ctx->max_block_cols,
                                    tuning_for(ctx, rps::kGradBuffer).max_waves_per_cu, ctx->stream);
     }));
 }
@@ -410,10 +425,9 @@ int rps_set_mask_override(rps_ctx *ctx, const uint8_t *up, const uint8_t *down, 
     if (!ctx) return RPS_EINVAL;
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return RPS_EHIP;
-    if (!up && !down && !server) {
+    if (!up && !down && !server) {   // the eager tables were not touched: what the host tracks still holds
         RPS_HIP(ctx, hipStreamSynchronize(ctx->stream));
         ctx->override_on = false;
-        ctx->cur_valid = ctx->next_valid = false;
         return RPS_OK;
     }
     if (!up || !down || !server) return RPS_EINVAL;
@@ -438,10 +452,9 @@ int rps_set_mask_override(rps_ctx *ctx, const uint8_t *up, const uint8_t *down, 
     }
     RPS_HIP(ctx, hipStreamSynchronize(ctx->stream));   // staging may still be in flight
     *ctx->staging = t;
-    RPS_HIP(ctx, hipMemcpyAsync(ctx->tab, ctx->staging, sizeof(RoundTable), hipMemcpyHostToDevice, ctx->stream));
+    RPS_HIP(ctx, hipMemcpyAsync(ctx->tab_override, ctx->staging, sizeof(RoundTable), hipMemcpyHostToDevice, ctx->stream));
     RPS_HIP(ctx, hipStreamSynchronize(ctx->stream));
     ctx->override_on = true;
-    ctx->cur_valid = ctx->next_valid = false;
     return RPS_OK;
 }
 

@@ -608,36 +608,91 @@ def test_side_stream_and_interleaved_contexts(rps):
         c.destroy()
 
 
-def test_rounds_can_be_captured_in_a_hip_graph(rps):
+@pytest.mark.parametrize("tiled", [False, True])
+def test_rounds_can_be_captured_in_a_hip_graph(rps, tiled):
     """The round enqueues kernels only (no allocation, no synchronisation, no memset), so a caller
     may capture a sequence of rounds in a HIP graph: four rounds captured once, replayed three times
-    from the same start with eager work and synchronisations in between, every replay equal to the
-    eager result bit for bit."""
-    n, N, p, gamma = 16, 16 * 8192, 0.1, 0.1
-    X0 = torch.from_numpy(workloads.gaussian_model(n, N, seed=8)).cuda()
+    from the same start, every replay equal to the eager result bit for bit.  Between the replays
+    the context does eager work whose RESULTS are checked against the oracle: the step the previous
+    eager call prepared in advance, a repeated step, the unfused average -- a replay must never
+    change the outcome an eager call sees (Alg. 1 steps 6-7: a function of (seed, step) only)."""
+    n, N, p, gamma, seed = 16, 16 * 8192, 0.1, 0.1, 21
+    off = workloads.block_offsets(n, N)
+    X0 = workloads.gaussian_model(n, N, seed=8)
+    flags = rps.RPS_FLAG_LAYOUT_TILED if tiled else 0
+    pack = (lambda t: workloads.to_tiled(t)) if tiled else (lambda t: t.clone())
+    unpack = (lambda t: workloads.from_tiled(t, N)) if tiled else (lambda t: t)
     s = torch.cuda.Stream()
     with torch.cuda.stream(s):
-        ctx = rps.RpsContext(n, N, p, gamma, 21, flags=rps.RPS_FLAG_LAYOUT_TILED)
+        ctx = rps.RpsContext(n, N, p, gamma, seed, flags=flags)
         ctx.set_synthetic_grad(0.2, 0.01)
-        start = ctx.to_tiled(X0)
+        start = pack(torch.from_numpy(X0).cuda())
         eager = start.clone()
         for t in range(4):
             ctx.round(eager, None, t)
         X = start.clone()
+        E = start.clone()                                   # state of the eager work between replays
     s.synchronize()
+    Eo = X0.copy()
+    ref4 = X0.copy()
+    for t in range(4):
+        oracle.round_(ref4, None, off, p=p, gamma=gamma, seed=seed, step=t, sigma=0.2, weight_decay=0.01)
+    assert_close(to_oracle(unpack(eager)), ref4, off, "f32", what="eager rounds 0..3")
     g = torch.cuda.CUDAGraph()
     with torch.cuda.graph(g, stream=s):
         for t in range(4):
             ctx.round(X, None, t)
+
+    def eager_round(t):
+        with torch.cuda.stream(s):
+            ctx.round(E, None, t)
+        oracle.round_(Eo, None, off, p=p, gamma=gamma, seed=seed, step=t, sigma=0.2, weight_decay=0.01)
+        s.synchronize()
+        assert_close(to_oracle(unpack(E)), Eo, off, "f32", what=f"eager round at step {t} between replays")
+
+    def eager_average(t):
+        with torch.cuda.stream(s):
+            ctx.lossy_average(E, t)
+        _, U, D = oracle.masks(seed, t, n, p)
+        oracle.lossy_average(Eo, off, U, D)
+        s.synchronize()
+        assert_close(to_oracle(unpack(E)), Eo, off, "f32", what=f"eager average at step {t} between replays")
+
+    eager_round(100)                                        # prepares the outcome of step 101 in advance
     for rep in range(3):
         X.copy_(start)
         torch.cuda.synchronize()
         g.replay()
         torch.cuda.synchronize()
         assert torch.equal(X, eager), f"replay {rep} differs from the eager rounds"
-        with torch.cuda.stream(s):                          # eager work between the replays
-            ctx.round(start.clone(), None, 100 + rep)
-        s.synchronize()
+        eager_round(101 + 2 * rep)                          # the step the last eager call prepared
+        eager_round(101 + 2 * rep)                          # the same step again
+        eager_average(101 + 2 * rep)
+        eager_round(102 + 2 * rep)
+    # a forced outcome set after the capture does not reach the graph, and the graph does not disturb it
+    forced = (np.arange(n, dtype=np.int32), np.ones((n, n), dtype=np.uint8), np.eye(n, dtype=np.uint8))
+    ctx.set_mask_override(*forced)
+    X.copy_(start)
+    torch.cuda.synchronize()
+    g.replay()
+    torch.cuda.synchronize()
+    assert torch.equal(X, eager), "replay under a later override differs"
+    with torch.cuda.stream(s):
+        ctx.lossy_average(E, 7)
+    oracle.lossy_average(Eo, off, forced[1], forced[2])
+    s.synchronize()
+    assert_close(to_oracle(unpack(E)), Eo, off, "f32", what="forced outcome after a replay")
+    # capturing under a forced outcome is refused: nothing is recorded for that call
+    g2 = torch.cuda.CUDAGraph()
+    Y = start.clone()
+    torch.cuda.synchronize()
+    with torch.cuda.graph(g2, stream=s):
+        with pytest.raises(rps.RpsError) as err:
+            ctx.round(Y, None, 0)
+        Y.mul_(1.0)
+    assert err.value.code == rps.RPS_EUNSUPPORTED
+    ctx.set_mask_override()
+    eager_round(200)
     ctx.destroy()
 
 
