@@ -54,8 +54,9 @@ enum {
     RPS_EINVAL = -1,        /* bad argument (see each function) */
     RPS_ENOMEM = -2,        /* host or device allocation failed */
     RPS_EHIP = -3,          /* a HIP call failed; see rps_last_hip_error() */
-    RPS_EUNSUPPORTED = -4   /* valid request this build does not implement (a forced network outcome
+    RPS_EUNSUPPORTED = -4,  /* valid request this build does not implement (a forced network outcome
                                inside a stream capture) */
+    RPS_ETOOBIG = -5        /* rps_consensus_static: n or N beyond the maximum its fixed scratch serves */
 };
 
 enum { RPS_DTYPE_F32 = 0, RPS_DTYPE_BF16 = 1 };
@@ -190,6 +191,29 @@ int rps_set_mask_override(rps_ctx *ctx, const uint8_t *up, const uint8_t *down, 
  * allocated by rps_create.  Synchronises the stream.
  */
 int rps_consensus(rps_ctx *ctx, const void *X, double *distance, double *mean_sq);
+
+/*
+ * rps_consensus for callers that cannot allocate or synchronise: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Needs no context; calls no hipMalloc / hipFree or
+ * any allocating routine, does not synchronise, and only enqueues kernels on `hip_stream`.
+ *   X           device array of n workers x N columns, dtype and layout (flags: 0 or
+ *               RPS_FLAG_LAYOUT_TILED) as for rps_consensus; caller-owned, read only
+ *   out         DEVICE array of 2 doubles, caller-owned: out[0] receives sum_i ||x_i - xbar||^2,
+ *               out[1] receives ||xbar||^2, valid in stream order.  Same kernels, same fixed
+ *               reduction order and therefore the same bits as rps_consensus.
+ *   hip_stream  hipStream_t to enqueue on (NULL = the default stream)
+ * The per-workgroup partial sums go to a reduction scratch that is part of the library's code
+ * object: a fixed 32 KB (2 x 2048 doubles) on every GPU the library runs on, held until the process
+ * ends.  It serves 1 <= n <= 64 and 1 <= N <= 2^34; anything larger is rejected with RPS_ETOOBIG
+ * before anything is enqueued.  Every call on a GPU shares that GPU's scratch (each call overwrites
+ * all the entries it later reads, so nothing needs clearing): calls whose kernels may overlap on one
+ * GPU -- different streams, concurrent graph launches -- race and must be ordered by the caller.
+ * The first call on a GPU (or rps_create on it) looks up the scratch's device address; do that once
+ * outside a capture.  Errors: RPS_EINVAL (NULL or non-device X, bad dtype / flags / sizes),
+ * RPS_ETOOBIG, RPS_EHIP.
+ */
+int rps_consensus_static(const void *X, int32_t n, int64_t N, int32_t dtype, uint32_t flags, double *out,
+                         void *hip_stream);
 
 /*
  * Monte-Carlo estimate of the constants alpha1 and alpha2 of the mixing matrix W_t of

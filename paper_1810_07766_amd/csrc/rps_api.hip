@@ -277,6 +277,10 @@ static int create_impl(rps_ctx **out, int32_t n, int32_t nb, bool external, int6
     ctx->stream = (hipStream_t)hip_stream;
 
     hipError_t e = hipGetDevice(&ctx->device);
+    if (e == hipSuccess) {   // set-up is the place to resolve this GPU's static scratch (rps_consensus_static)
+        double *unused = nullptr;
+        e = rps::static_scratch(ctx->device, &unused);
+    }
     const size_t scratch_bytes = (2 * (size_t)rps::kMaxPartials + 2) * sizeof(double);
     if (e == hipSuccess) e = hipMalloc((void **)&ctx->tab_base, 5 * sizeof(RoundTable) + scratch_bytes);
     if (e == hipSuccess) {
@@ -473,6 +477,37 @@ int rps_consensus(rps_ctx *ctx, const void *X, double *distance, double *mean_sq
     return RPS_OK;
 }
 
+int rps_consensus_static(const void *X, int32_t n, int64_t N, int32_t dtype, uint32_t flags, double *out,
+                         void *hip_stream) {
+    if (!X || !out) return RPS_EINVAL;
+    if (dtype != RPS_DTYPE_F32 && dtype != RPS_DTYPE_BF16) return RPS_EINVAL;
+    if (flags & ~(uint32_t)RPS_FLAG_LAYOUT_TILED) return RPS_EINVAL;
+    if (n < 1 || N < 1) return RPS_EINVAL;
+    if (n > rps::kMaxWorkers || N > (1ll << 34)) return RPS_ETOOBIG;   // beyond what the fixed scratch is laid out for
+    // the GPU that holds X: its copy of the scratch is the one to use
+    hipPointerAttribute_t attr;
+    if (hipPointerGetAttributes(&attr, X) != hipSuccess) {
+        (void)hipGetLastError();
+        return RPS_EINVAL;
+    }
+    if (attr.type != hipMemoryTypeDevice) return RPS_EINVAL;
+    DeviceGuard guard(attr.device);
+    if (!guard.ok) return RPS_EHIP;
+    double *partials = nullptr;
+    if (rps::static_scratch(attr.device, &partials) != hipSuccess) return RPS_EHIP;
+    RoundParams prm{};
+    prm.N = N;
+    prm.n = n;
+    prm.blocks = n;
+    const int64_t vec = dtype == RPS_DTYPE_F32 ? 4 : 8;
+    prm.tiled = (flags & RPS_FLAG_LAYOUT_TILED) ? 1 : 0;
+    prm.stride = prm.tiled ? (RPS_TILE_BYTES / 16) * vec : N;
+    prm.vec_ok = ((uintptr_t)X % 16 == 0 && (prm.tiled || N % vec == 0)) ? 1 : 0;
+    if (rps::launch_consensus(dtype, X, prm, partials, rps::kMaxPartials, out, (hipStream_t)hip_stream) != hipSuccess)
+        return RPS_EHIP;
+    return RPS_OK;
+}
+
 int rps_estimate_mixing(rps_ctx *ctx, uint64_t first_step, int64_t rounds, double *alpha1, double *alpha2) {
     if (!ctx || rounds < 1 || rounds > (1ll << 24) || ctx->n < 2) return RPS_EINVAL;
     if (!step_ok(first_step) || !step_ok(first_step + (uint64_t)rounds - 1)) return RPS_EINVAL;
@@ -553,6 +588,7 @@ const char *rps_strerror(int code) {
         case RPS_ENOMEM: return "out of memory";
         case RPS_EHIP: return "HIP runtime error (see rps_last_hip_error)";
         case RPS_EUNSUPPORTED: return "not supported";
+        case RPS_ETOOBIG: return "size beyond the maximum of the allocation-free entry point";
         default: return "unknown error code";
     }
 }

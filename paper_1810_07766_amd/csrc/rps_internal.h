@@ -79,5 +79,8 @@ hipError_t launch_convert_layout(int dtype, void *dst, const void *src, int64_t 
 constexpr int kMaxPartials = 2048;
 hipError_t launch_consensus(int dtype, const void *X, const RoundParams &prm, double *partials, int max_partials,
                             double *out, hipStream_t stream);
+// Device address, on GPU `device` (which must be current), of the library's statically allocated
+// reduction scratch of 2*kMaxPartials doubles; resolved once per GPU, no allocation.
+hipError_t static_scratch(int device, double **out);
 
 }  // namespace rps

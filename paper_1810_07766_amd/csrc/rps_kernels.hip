@@ -26,6 +26,8 @@
 // contraction, so there is no MFMA here.
 #include "rps_internal.h"
 
+#include <atomic>
+
 namespace rps {
 namespace {
 
@@ -1510,6 +1512,38 @@ hipError_t launch_convert_layout(int dtype, void *dst, const void *src, int64_t 
             hipLaunchKernelGGL((convert_layout_kernel<2, false>), grid, dim3(256), 0, stream, dst, src, N, n, (int)aligned);
     }
     return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
+// Reduction scratch for callers that cannot allocate: one array per GPU, living in the code
+// object's global segment, as large as the scratch a context allocates (the consensus kernels
+// are launched with at most kMaxPartials workgroups, so it serves every width the interface
+// accepts).  `scratch` below is a host-side stand-in for the symbol, NOT a device address:
+// host code must go through the pointer resolved per device by static_scratch().
+// ---------------------------------------------------------------------------------------
+namespace {
+static __device__ __align__(256) double scratch[2 * kMaxPartials];
+constexpr int kMaxDevices = 64;
+std::atomic<double *> g_scratch_ptr[kMaxDevices];   // device address of `scratch` on each GPU, resolved on first use
+}  // namespace
+
+hipError_t static_scratch(int device, double **out) {
+    if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+    double *p = g_scratch_ptr[device].load(std::memory_order_acquire);
+    if (p == nullptr) {   // `device` is current (the caller's guard); every GPU has its own copy at its own address
+        int cur = -1;
+        hipError_t e = hipGetDevice(&cur);
+        if (e != hipSuccess) return e;
+        if (cur != device) return hipErrorInvalidDevice;
+        void *addr = nullptr;
+        e = hipGetSymbolAddress(&addr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (addr == nullptr) return hipErrorInvalidSymbol;
+        p = static_cast<double *>(addr);
+        g_scratch_ptr[device].store(p, std::memory_order_release);   // racing first calls resolve the same address
+    }
+    *out = p;
+    return hipSuccess;
 }
 
 hipError_t launch_consensus(int dtype, const void *X, const RoundParams &prm, double *partials, int max_partials,

@@ -10,7 +10,7 @@ import os
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "librps.so")
 
-RPS_OK, RPS_EINVAL, RPS_ENOMEM, RPS_EHIP, RPS_EUNSUPPORTED = 0, -1, -2, -3, -4
+RPS_OK, RPS_EINVAL, RPS_ENOMEM, RPS_EHIP, RPS_EUNSUPPORTED, RPS_ETOOBIG = 0, -1, -2, -3, -4, -5
 RPS_DTYPE_F32, RPS_DTYPE_BF16 = 0, 1
 RPS_FLAG_SERVER_IDENTITY = 1
 RPS_FLAG_LAYOUT_TILED = 2
@@ -41,6 +41,8 @@ _lib.rps_round_gradient_averaging.argtypes = [_ctx_p, ctypes.c_void_p, ctypes.c_
 _lib.rps_get_masks.argtypes = [_ctx_p, ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
 _lib.rps_set_mask_override.argtypes = [_ctx_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
 _lib.rps_consensus.argtypes = [_ctx_p, ctypes.c_void_p, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
+_lib.rps_consensus_static.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_int32, ctypes.c_uint32,
+                                      ctypes.c_void_p, ctypes.c_void_p]
 _lib.rps_estimate_mixing.argtypes = [_ctx_p, ctypes.c_uint64, ctypes.c_int64, ctypes.POINTER(ctypes.c_double),
                                      ctypes.POINTER(ctypes.c_double)]
 _lib.rps_convert_layout.argtypes = [_ctx_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32]
@@ -52,12 +54,12 @@ _lib.rps_strerror.argtypes = [ctypes.c_int]
 _lib.rps_strerror.restype = ctypes.c_char_p
 for _name in ("rps_create", "rps_create_external", "rps_destroy", "rps_set_synthetic_grad", "rps_set_gamma", "rps_local_step",
               "rps_lossy_average", "rps_round", "rps_round_gradient_averaging", "rps_get_masks", "rps_set_mask_override",
-              "rps_consensus", "rps_estimate_mixing", "rps_convert_layout", "rps_set_launch_tuning", "rps_set_profiling", "rps_get_kernel_time", "rps_last_hip_error"):
+              "rps_consensus", "rps_consensus_static", "rps_estimate_mixing", "rps_convert_layout", "rps_set_launch_tuning", "rps_set_profiling", "rps_get_kernel_time", "rps_last_hip_error"):
     getattr(_lib, _name).restype = ctypes.c_int
 
 EXPORTS = ("rps_create", "rps_create_external", "rps_storage_elems", "rps_destroy", "rps_set_synthetic_grad", "rps_set_gamma", "rps_local_step",
            "rps_lossy_average", "rps_round", "rps_round_gradient_averaging", "rps_get_masks", "rps_set_mask_override",
-           "rps_consensus", "rps_estimate_mixing", "rps_convert_layout", "rps_set_launch_tuning", "rps_set_profiling", "rps_get_kernel_time",
+           "rps_consensus", "rps_consensus_static", "rps_estimate_mixing", "rps_convert_layout", "rps_set_launch_tuning", "rps_set_profiling", "rps_get_kernel_time",
            "rps_last_hip_error",
            "rps_strerror")
 
@@ -263,6 +265,19 @@ def rps_get_masks(ctx, step):
 
 def rps_consensus(ctx, X):
     return ctx.consensus(X)
+
+
+def rps_consensus_static(X, n, N, out, dtype=RPS_DTYPE_F32, flags=0, stream=None):
+    """Allocation-free consensus statistics: X a device tensor holding the state, out a device
+    tensor of 2 float64 that receives (distance, ||xbar||^2) in stream order."""
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream().cuda_stream
+    if not (out.is_cuda and out.is_contiguous() and out.dtype == torch.float64 and out.numel() == 2
+            and X.is_cuda and X.is_contiguous()):
+        raise RpsError(RPS_EINVAL)
+    _check(_lib.rps_consensus_static(ctypes.c_void_p(X.data_ptr()), n, N, dtype, flags, ctypes.c_void_p(out.data_ptr()),
+                                     ctypes.c_void_p(stream)))
 
 
 def rps_estimate_mixing(ctx, first_step, rounds):
