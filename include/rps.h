@@ -241,13 +241,24 @@ int rps_convert_layout(rps_ctx *ctx, void *dst, const void *src, int32_t to_tile
 /*
  * Launch shape of the round kernel, for tuning sweeps; results never depend on it.
  *   rows_in_flight       rows per load chunk (a wavefront keeps two chunks in flight): 2 or 4
- *   waves_per_workgroup  1 or 4 (a workgroup's wavefronts own adjacent tiles)
+ *   waves_per_workgroup  1, 2, 4, 8 or 16 (a workgroup's wavefronts own adjacent tiles and, with the
+ *                        in-register gradient, share one LDS copy of the noise cells); rounded to
+ *                        the nearest width the kernel in question is built for
  *   max_waves_per_cu     cap on resident wavefronts per compute unit (0 = no cap)
+ *   tiles_per_wave       tiles a wavefront works through with the in-register gradient, 1..64
+ *                        (0 = chosen per launch)
  * Until this is called every launch takes the measured best shape for its worker count, dtype
  * and gradient source (none / buffer / in-register).  RPS_EINVAL for other values.
  */
 int rps_set_launch_tuning(rps_ctx *ctx, int32_t rows_in_flight, int32_t waves_per_workgroup,
-                          int32_t max_waves_per_cu);
+                          int32_t max_waves_per_cu, int32_t tiles_per_wave);
+
+/*
+ * Test hook: the cell values of the synthetic gradient noise as the library computes them on the
+ * host (no GPU needed): radius[4096] = sqrt(-2 ln((k + 1/2)/4096)), cos_sin[2 * 4096] = the
+ * interleaved (cos, sin) of 2 pi (a + 1/2)/4096, each the nearest fp32.  HOST arrays.
+ */
+int rps_noise_cells(float *radius, float *cos_sin);
 
 /*
  * Kernel timing for benchmarks: while enabled, every rps_round / rps_lossy_average /

@@ -35,6 +35,10 @@ _lib.rps_oracle_noise_patch.argtypes = [ctypes.c_uint64, ctypes.c_uint64, ctypes
 _lib.rps_oracle_noise_patch.restype = None
 _lib.rps_oracle_noise.argtypes = [ctypes.c_uint64, ctypes.c_uint64, ctypes.c_int32, ctypes.c_int64, ctypes.c_float]
 _lib.rps_oracle_noise.restype = ctypes.c_float
+_lib.rps_oracle_noise_radius.argtypes = [ctypes.c_uint32]
+_lib.rps_oracle_noise_radius.restype = ctypes.c_float
+_lib.rps_oracle_noise_direction.argtypes = [ctypes.c_uint32, _f32p, _f32p]
+_lib.rps_oracle_noise_direction.restype = None
 _lib.rps_oracle_local_step.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64,
                                        _i64p, ctypes.c_int32, ctypes.c_float, ctypes.c_float,
                                        ctypes.c_float, ctypes.c_uint64, ctypes.c_uint64, ctypes.c_int32]
@@ -82,6 +86,18 @@ def noise_patch(seed: int, step: int, pair: int, quad: int, sigma: float = 1.0) 
     out = np.empty(8, dtype=np.float32)
     _lib.rps_oracle_noise_patch(seed, step, pair, quad, sigma, out.ctypes.data_as(_f32p))
     return out.reshape(2, 4)
+
+
+def noise_grid():
+    """(radius[4096], cos[4096], sin[4096]) float32: the cell values of the noise specification."""
+    r = np.array([_lib.rps_oracle_noise_radius(k) for k in range(4096)], dtype=np.float32)
+    c = np.empty(4096, dtype=np.float32)
+    s = np.empty(4096, dtype=np.float32)
+    cc, ss = ctypes.c_float(), ctypes.c_float()
+    for a in range(4096):
+        _lib.rps_oracle_noise_direction(a, ctypes.byref(cc), ctypes.byref(ss))
+        c[a], s[a] = cc.value, ss.value
+    return r, c, s
 
 
 def noise(seed: int, step: int, worker: int, column: int, sigma: float = 1.0) -> float:

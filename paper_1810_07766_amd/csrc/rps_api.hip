@@ -39,14 +39,30 @@ struct rps_ctx {
     uint64_t cur_step = 0, next_step = 0;
     RoundTable *staging = nullptr;    // pinned host copy (create, override, query)
     double *partials = nullptr;       // device: 2 * kMaxPartials + 2 doubles (consensus reduction scratch + result)
+    float *noise_cells = nullptr;     // device: the 3 * kNoiseGrid cell values of the synthetic gradient noise
     bool override_on = false;
     bool profiling = false;
     std::vector<hipEvent_t> ev_start, ev_stop;
     size_t ev_used = 0;
     int last_hip = 0;
     bool tune_set = false;             // rps_set_launch_tuning was called: `tune` replaces the defaults
-    rps::LaunchTuning tune{2, 1, 8};
+    rps::LaunchTuning tune{2, 1, 8, 0};
 };
+
+// Cell values of the synthetic gradient noise (a Box-Muller pair per hash word on a grid of
+// kNoiseGrid radius cells x kNoiseGrid angle cells): the nearest fp32 to the real values, from
+// 80-bit extended arithmetic (64-bit significand: far below half an fp32 ulp of error, so the
+// rounding is the correct one wherever the real value is not within 1e-18 of a tie).
+void rps::build_noise_cells(float *radius, float *cos_sin) {
+    const long double grid = (long double)rps::kNoiseGrid;
+    const long double two_pi = 6.283185307179586476925286766559005768L;
+    for (int k = 0; k < rps::kNoiseGrid; ++k) {
+        radius[k] = (float)sqrtl(-2.0L * logl(((long double)k + 0.5L) / grid));
+        const long double phi = two_pi * (((long double)k + 0.5L) / grid);
+        cos_sin[2 * k] = (float)cosl(phi);
+        cos_sin[2 * k + 1] = (float)sinl(phi);
+    }
+}
 
 namespace {
 
@@ -69,21 +85,23 @@ bool step_ok(uint64_t step) { return step < (1ull << 56); }
 // update mixes n read streams with n write streams; the memory system handles that best with few
 // wavefronts resident -- fewer still when a gradient buffer doubles the loads in flight.
 rps::LaunchTuning default_tuning(int32_t n, int32_t dtype, int grad_mode) {
-    if (grad_mode == rps::kGradNone) return rps::LaunchTuning{4, 1, 5};
-    if (grad_mode == rps::kGradBuffer) return n >= 12 ? rps::LaunchTuning{2, 1, 5} : rps::LaunchTuning{4, 1, 6};
-    if (dtype == RPS_DTYPE_BF16) return rps::LaunchTuning{2, 1, 0};   // close to ALU-bound: full occupancy
-    if (n >= 24) return rps::LaunchTuning{4, 1, 6};
-    return rps::LaunchTuning{4, 1, 8};
+    if (grad_mode == rps::kGradNone) return rps::LaunchTuning{4, 1, 5, 0};
+    if (grad_mode == rps::kGradBuffer) return n >= 12 ? rps::LaunchTuning{2, 1, 5, 0} : rps::LaunchTuning{4, 1, 6, 0};
+    // in-register gradient: the workgroup's wavefronts share the LDS copy of the noise cells
+    if (dtype == RPS_DTYPE_BF16) return rps::LaunchTuning{2, 4, 0, 0};
+    return rps::LaunchTuning{2, 4, 12, 0};
 }
 
 rps::LaunchTuning tuning_for(const rps_ctx *ctx, int grad_mode) {
     if (ctx->tune_set) return ctx->tune;
     if (ctx->flags & RPS_FLAG_LAYOUT_TILED) {   // a wavefront owns about 4 KB whatever n is: more of them resident
         int cap;                                 // (measured at n = 8 / 16 / 32 fp32 and n = 64 bf16)
-        if (grad_mode == rps::kGradSynthetic) cap = 20;
+        // 16 wavefronts share the LDS copy of the noise cells; with more than 32 workers a lane walks its
+        // rows in chunks, and one row pair per chunk keeps the registers at four wavefronts per SIMD
+        if (grad_mode == rps::kGradSynthetic) return rps::LaunchTuning{ctx->n > 32 ? 2 : 4, 16, 0, 0};
         else if (grad_mode == rps::kGradNone) cap = ctx->n >= 48 ? 8 : 10;
         else cap = 12;
-        return rps::LaunchTuning{4, 1, cap};
+        return rps::LaunchTuning{4, 1, cap, 0};
     }
     return default_tuning(ctx->n, ctx->dtype, grad_mode);
 }
@@ -109,6 +127,8 @@ RoundParams make_params(const rps_ctx *ctx, const void *X, const void *G, uint64
     prm.threshold = ctx->threshold;
     prm.server_mode = 0;
     prm.next_step_lo = prm.next_step_hi24 = 0;
+    prm.noise_cells = ctx->noise_cells;
+    prm.tiles_per_wave = 1;
     return prm;
 }
 
@@ -211,6 +231,16 @@ int commit_outcome(rps_ctx *ctx, uint64_t step, const RoundParams &prm, int rc) 
     return rc;
 }
 
+// The cell values of the synthetic gradient noise, computed once per process.
+const float *noise_cells_host() {
+    static const std::vector<float> cells = [] {
+        std::vector<float> v(3 * (size_t)rps::kNoiseGrid);
+        rps::build_noise_cells(v.data(), v.data() + rps::kNoiseGrid);
+        return v;
+    }();
+    return cells.data();
+}
+
 struct DeviceGuard {   // make the context's device current for the duration of a call
     int prev = -1;
     bool ok = false;
@@ -282,7 +312,13 @@ static int create_impl(rps_ctx **out, int32_t n, int32_t nb, bool external, int6
         e = rps::static_scratch(ctx->device, &unused);
     }
     const size_t scratch_bytes = (2 * (size_t)rps::kMaxPartials + 2) * sizeof(double);
-    if (e == hipSuccess) e = hipMalloc((void **)&ctx->tab_base, 5 * sizeof(RoundTable) + scratch_bytes);
+    const size_t cells_at = (5 * sizeof(RoundTable) + scratch_bytes + 255) & ~(size_t)255;
+    const size_t cells_bytes = 3 * (size_t)rps::kNoiseGrid * sizeof(float);
+    if (e == hipSuccess) e = hipMalloc((void **)&ctx->tab_base, cells_at + cells_bytes);
+    if (e == hipSuccess) {
+        ctx->noise_cells = reinterpret_cast<float *>(reinterpret_cast<char *>(ctx->tab_base) + cells_at);
+        e = hipMemcpyAsync(ctx->noise_cells, noise_cells_host(), cells_bytes, hipMemcpyHostToDevice, ctx->stream);
+    }
     if (e == hipSuccess) {
         ctx->tab = ctx->tab_base;
         ctx->tab_other = ctx->tab_base + 1;
@@ -542,12 +578,15 @@ int rps_convert_layout(rps_ctx *ctx, void *dst, const void *src, int32_t to_tile
     return RPS_OK;
 }
 
-int rps_set_launch_tuning(rps_ctx *ctx, int32_t rows_in_flight, int32_t waves_per_workgroup, int32_t max_waves_per_cu) {
+int rps_set_launch_tuning(rps_ctx *ctx, int32_t rows_in_flight, int32_t waves_per_workgroup, int32_t max_waves_per_cu,
+                          int32_t tiles_per_wave) {
     if (!ctx) return RPS_EINVAL;
     if (rows_in_flight != 2 && rows_in_flight != 4) return RPS_EINVAL;
-    if (waves_per_workgroup != 1 && waves_per_workgroup != 4) return RPS_EINVAL;
-    if (max_waves_per_cu < 0) return RPS_EINVAL;
-    ctx->tune = rps::LaunchTuning{rows_in_flight, waves_per_workgroup, max_waves_per_cu};
+    if (waves_per_workgroup != 1 && waves_per_workgroup != 2 && waves_per_workgroup != 4 && waves_per_workgroup != 8 &&
+        waves_per_workgroup != 16)
+        return RPS_EINVAL;
+    if (max_waves_per_cu < 0 || tiles_per_wave < 0 || tiles_per_wave > 64) return RPS_EINVAL;
+    ctx->tune = rps::LaunchTuning{rows_in_flight, waves_per_workgroup, max_waves_per_cu, tiles_per_wave};
     ctx->tune_set = true;
     return RPS_OK;
 }
@@ -576,6 +615,14 @@ int rps_get_kernel_time(rps_ctx *ctx, double *total_ms, int64_t *launches) {
     *total_ms = sum;
     *launches = (int64_t)ctx->ev_used;
     ctx->ev_used = 0;
+    return RPS_OK;
+}
+
+int rps_noise_cells(float *radius, float *cos_sin) {
+    if (!radius || !cos_sin) return RPS_EINVAL;
+    const float *cells = noise_cells_host();
+    std::memcpy(radius, cells, (size_t)rps::kNoiseGrid * sizeof(float));
+    std::memcpy(cos_sin, cells + rps::kNoiseGrid, 2 * (size_t)rps::kNoiseGrid * sizeof(float));
     return RPS_OK;
 }
 

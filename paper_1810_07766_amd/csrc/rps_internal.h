@@ -8,6 +8,7 @@
 namespace rps {
 
 constexpr int kMaxWorkers = 64;          // one 64-bit lane mask per block and direction
+constexpr int kNoiseGrid = 4096;         // radius cells = angle cells of the synthetic gradient noise
 
 // Device-resident description of one round's network outcome plus the block partition.
 // Written by the mask kernel (or copied from the host for a mask override), read by the
@@ -39,6 +40,11 @@ struct RoundParams {
     uint64_t threshold;     // a message is lost iff its hash word < threshold
     int32_t server_mode;
     uint32_t next_step_lo, next_step_hi24;
+    // Synthetic gradient noise: the cell values radius[kNoiseGrid], then (cos, sin) of the angle
+    // cells (the kernels use the kNoiseGrid / 2 below pi; device memory owned by the context), and
+    // how many steps a wavefront takes (set by the launchers)
+    const float *noise_cells;
+    int32_t tiles_per_wave;
 };
 
 enum GradMode { kGradNone = 0, kGradBuffer = 1, kGradSynthetic = 2 };
@@ -48,9 +54,14 @@ constexpr int kLdsBytesPerCu = 160 * 1024;
 // Launch shape of the round kernel (see rps_set_launch_tuning in rps.h).
 struct LaunchTuning {
     int rows_in_flight;        // rows per load chunk (two chunks are in flight): 2 or 4
-    int waves_per_workgroup;   // 1 or 4 (adjacent tiles)
+    int waves_per_workgroup;   // wavefronts per workgroup (adjacent tiles): 1, 2, 4, 8 or 16 (rounded to what the kernel offers)
     int max_waves_per_cu;      // occupancy cap; 0 or >= 32: none
+    int tiles_per_wave;        // steps per wavefront in kernels that generate noise; 0: chosen by the launcher
 };
+
+// Host side of the synthetic gradient noise: the kNoiseGrid radius values sqrt(-2 ln((k + 1/2)/kNoiseGrid))
+// and the kNoiseGrid (cos, sin) pairs of 2 pi (a + 1/2)/kNoiseGrid, each the nearest fp32.
+void build_noise_cells(float *radius, float *cos_sin);
 
 // Launchers (rps_kernels.hip).  All enqueue on `stream` and return the launch status.
 // server_mode: 0 = per-round random permutation of the workers, 1 = worker j serves block j,

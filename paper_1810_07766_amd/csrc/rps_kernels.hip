@@ -58,10 +58,27 @@ __device__ __forceinline__ void philox4x32(uint32_t c[4], uint32_t k0, uint32_t 
 // into (x, z): workgroup index = blockIdx.z * gridDim.x + blockIdx.x.
 constexpr unsigned kMaxGridX = 1u << 20;
 __device__ __forceinline__ int64_t linear_block() { return (int64_t)blockIdx.z * gridDim.x + blockIdx.x; }
+__device__ __forceinline__ int64_t linear_blocks() { return (int64_t)gridDim.z * gridDim.x; }
+// Index of the unit of work (tile, chunk) that wavefront `wave` of a workgroup of `wpb` wavefronts
+// takes in its step `it`.  Workgroups are handed to the 8 XCDs of the chip in turn, and the memory
+// system is at its best when CONSECUTIVE units are in flight on DIFFERENT XCDs (measured with an
+// in-place copy of 4 KB units: 6.0 TB/s when unit u runs on XCD u mod 8, 5.0 TB/s when every XCD
+// works on runs of 16 units).  With one wavefront per workgroup that comes by itself; a workgroup
+// of several wavefronts therefore takes units 8 apart -- the units u = 8 q + x of its own XCD x --
+// so that unit u still runs on XCD u mod 8 (the launchers round the grid to a multiple of 8
+// workgroups).  A wavefront's next step lies a whole grid further on: the chip then works on a few
+// compact, forward-moving windows of memory.
+__device__ __forceinline__ int64_t unit_index(int it, int wpb, int wave) {
+    const int64_t lb = (int64_t)it * linear_blocks() + linear_block();
+    return (((lb >> 3) * wpb + wave) << 3) + (lb & 7);
+}
 inline dim3 folded_grid(int64_t workgroups, unsigned y) {
     const int64_t gx = workgroups < (int64_t)kMaxGridX ? (workgroups > 0 ? workgroups : 1) : (int64_t)kMaxGridX;
     return dim3((unsigned)gx, y, (unsigned)((workgroups + gx - 1) / gx));
 }
+
+// For kernels that place their units with unit_index(): a multiple of 8 workgroups.
+inline dim3 folded_grid8(int64_t workgroups, unsigned y) { return folded_grid((workgroups + 7) & ~(int64_t)7, y); }
 
 constexpr uint32_t kDomainUplink = 0u << 24, kDomainDownlink = 1u << 24, kDomainServer = 2u << 24,
                    kDomainNoise = 3u << 24;
@@ -192,54 +209,108 @@ __global__ __launch_bounds__(64) void mixing_moments_kernel(double *__restrict__
 }
 
 // ---------------------------------------------------------------------------------------
-// Synthetic gradient noise.  Each 32-bit hash word gives a Box-Muller pair sigma*z: 16-bit
-// radius index (low half), 16-bit angle index (high half).  Every operation below is an
-// exactly rounded fp32 operation in a fixed order, so the bits do not depend on the machine.
+// Synthetic gradient noise: a Box-Muller pair per 32-bit hash word on a 4096 x 4096 grid of
+// (radius, angle) cells.  The cell values (correctly rounded fp32 of sqrt(-2 ln((k + 1/2)/4096)),
+// cos and sin of 2 pi (a + 1/2)/4096) come from a table the host computes once per context; every
+// workgroup of a kernel that generates noise copies it into LDS, the radii pre-multiplied by sigma,
+// so that a pair costs one mask, one shift-and-mask, two LDS gathers and two multiplies.
+//   word bits 2..13  -> radius cell (byte offset of a 4-byte entry = word & 0x3FFC)
+//   word bits 17..27 -> angle cell within the half turn (byte offset of an 8-byte (cos, sin) entry
+//                       = (word >> 14) & 0x3FF8);  bit 31 adds the half turn, i.e. flips the sign of
+//                       both members: LDS holds only the 2048 cells of the first half turn, and the
+//                       bit is copied into the sign of sigma * r >= 0 by one bit-field insert
 // ---------------------------------------------------------------------------------------
-__device__ __forceinline__ void box_muller_pair(uint32_t word, float sigma, float &even, float &odd) {
-    // u1 = a / 2^17 (a odd);  -log2 u1 = lz + (1 - log2 m),  m in [1,2),  w = 2 - m
-    const uint32_t a = ((word & 0xFFFFu) << 1) | 1u;
-    const int nlz = __builtin_clz(a);   // 15..31
-    const float m = __uint_as_float((a << (nlz - 8)) + 0x3F000000u);
-    const float w = 2.0f - m;
-    const float lzf = (float)(nlz - 15);
-    float q = __builtin_fmaf(w, 0x1.767762p-5f, -0x1.6ad1d8p-8f);
-    q = __builtin_fmaf(w, q, 0x1.9117f8p-4f);
-    q = __builtin_fmaf(w, q, 0x1.fc1588p-3f);
-    q = __builtin_fmaf(w, q, 0x1.000288p+0f);
-    const float t = w * q;                                        // -2 ln(1 - w/2)
-    const float L = __builtin_fmaf(lzf, 0x1.62e430p+0f, t);       // -2 ln u1
-    // r = L * rsqrt(L): bit-trick seed and two Newton steps
-    const float h = 0.5f * L;
-    float y = __uint_as_float(0x5F3759DFu - (__float_as_uint(L) >> 1));
-    y = y * __builtin_fmaf(-h, y * y, 1.5f);
-    y = y * __builtin_fmaf(-h, y * y, 1.5f);
-    const float rs = sigma * (L * y);
-    // angle x = (2f+1) pi/65536 with f the signed 15-bit field [30:16]; bit 31 adds pi
-    const int32_t f = (int32_t)(word << 1) >> 17;
-    const float x = (float)(2 * f + 1) * 0x1.921fb6p-15f;
-    const float x2 = x * x;
-    float sp = __builtin_fmaf(x2, -0x1.8b3e4ep-13f, 0x1.10c46cp-7f);
-    sp = __builtin_fmaf(x2, sp, -0x1.5554aep-3f);
-    const float sn = __builtin_fmaf(x * x2, sp, x);
-    float cp = __builtin_fmaf(x2, -0x1.54c10ap-10f, 0x1.54aa20p-5f);
-    cp = __builtin_fmaf(x2, cp, -0x1.fffd12p-2f);
-    const float cs = __builtin_fmaf(x2, cp, 1.0f);
-    const float rsgn = __uint_as_float(__float_as_uint(rs) | (word & 0x80000000u));
-    even = rsgn * cs;
-    odd = rsgn * sn;
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+struct NoiseLds {
+    float radius[kNoiseGrid];        // sigma * r, rounded once
+    float dir[kNoiseGrid];           // (cos, sin) interleaved, the kNoiseGrid / 2 angle cells below pi
+};
+struct NoNoiseLds {
+    float unused;
+};
+template <int GRAD>
+struct LdsFor {
+    using type = NoNoiseLds;
+};
+template <>
+struct LdsFor<kGradSynthetic> {
+    using type = NoiseLds;
+};
+
+// All `threads` work-items of the workgroup take part; ends with a workgroup barrier.
+__device__ __forceinline__ void fill_noise_lds(NoiseLds &lds, const float *__restrict__ cells, float sigma, int tid,
+                                               int threads) {
+    const f32x4 *src = reinterpret_cast<const f32x4 *>(cells);   // radius[4096], then (cos, sin)[4096]
+    for (int i = tid; i < kNoiseGrid / 4; i += threads) {
+        f32x4 v = src[i];
+        v.x = sigma * v.x; v.y = sigma * v.y; v.z = sigma * v.z; v.w = sigma * v.w;
+        reinterpret_cast<f32x4 *>(lds.radius)[i] = v;
+    }
+    for (int i = tid; i < kNoiseGrid / 4; i += threads) reinterpret_cast<f32x4 *>(lds.dir)[i] = src[kNoiseGrid / 4 + i];
+    __syncthreads();
+}
+__device__ __forceinline__ void fill_noise_lds(NoNoiseLds &, const float *, float, int, int) {}
+
+// The same copy in two halves, for workgroups of 8 or 16 wavefronts: begin() issues the global
+// loads of the cells, end() writes them to LDS and ends with the workgroup barrier.  What a
+// wavefront issues in between (the loads of its first tile) is in flight during the copy.
+template <int GRAD, int WPB>
+struct NoiseFill {
+    __device__ __forceinline__ void begin(const float *, int) {}
+    __device__ __forceinline__ void end(NoNoiseLds &, float, int) {}
+};
+template <int WPB>
+struct NoiseFill<kGradSynthetic, WPB> {
+    static constexpr int THREADS = WPB * 64;
+    static constexpr int NR = (kNoiseGrid / 4 + THREADS - 1) / THREADS, ND = NR;   // 16-byte pieces per work-item
+    f32x4 r[NR], d[ND];
+    __device__ __forceinline__ void begin(const float *__restrict__ cells, int tid) {
+        const f32x4 *src = reinterpret_cast<const f32x4 *>(cells);
+#pragma unroll
+        for (int k = 0; k < NR; ++k) r[k] = src[(tid + k * THREADS) % (kNoiseGrid / 4)];
+#pragma unroll
+        for (int k = 0; k < ND; ++k) d[k] = src[kNoiseGrid / 4 + (tid + k * THREADS) % (kNoiseGrid / 4)];
+    }
+    __device__ __forceinline__ void end(NoiseLds &lds, float sigma, int tid) {
+#pragma unroll
+        for (int k = 0; k < NR; ++k) {
+            f32x4 v = r[k];
+            v.x = sigma * v.x; v.y = sigma * v.y; v.z = sigma * v.z; v.w = sigma * v.w;
+            reinterpret_cast<f32x4 *>(lds.radius)[(tid + k * THREADS) % (kNoiseGrid / 4)] = v;
+        }
+#pragma unroll
+        for (int k = 0; k < ND; ++k) reinterpret_cast<f32x4 *>(lds.dir)[(tid + k * THREADS) % (kNoiseGrid / 4)] = d[k];
+        __syncthreads();
+    }
+};
+
+__device__ __forceinline__ void box_muller_pair(uint32_t word, const NoiseLds &lds, float &even, float &odd) {
+    const float r = *reinterpret_cast<const float *>(reinterpret_cast<const char *>(lds.radius) + (word & 0x3FFCu));
+    const float2 d = *reinterpret_cast<const float2 *>(reinterpret_cast<const char *>(lds.dir) + ((word >> 14) & 0x3FF8u));
+    // sign bit from the word, the rest from r (v_bfi_b32): -(r * c) is the rounded r * -c exactly
+    const float rs = __uint_as_float((__float_as_uint(r) & 0x7FFFFFFFu) | (word & 0x80000000u));
+    even = rs * d.x;
+    odd = rs * d.y;
 }
 
 // One hash call serves a 4-column x 2-worker patch: words 0,1 -> worker 2*pair, words 2,3 ->
-// worker 2*pair+1, columns 4*quad..4*quad+3 (16 bytes of fp32 per row: one lane's vector).
-__device__ __forceinline__ void noise_patch(const RoundParams &prm, int pair, int64_t quad, float za[4], float zb[4]) {
-    uint32_t c[4] = {(uint32_t)quad, (uint32_t)pair, prm.step_lo, kDomainNoise | prm.step_hi24};
+// worker 2*pair+1, columns 4*quad..4*quad+3 (16 bytes of fp32 per row: one lane's vector).  The
+// counter is (quad >> 7, (quad & 127) | pair << 7, step, domain): the callers pass quad >> 7 as
+// quad_hi -- wave-uniform wherever a wavefront's columns lie inside one aligned run of 512, so
+// that the first hash rounds are partly scalar work -- and the low seven bits as quad_lo.
+__device__ __forceinline__ void noise_patch(const RoundParams &prm, const NoiseLds &lds, int pair, uint32_t quad_hi,
+                                            uint32_t quad_lo, float za[4], float zb[4]) {
+    uint32_t c[4] = {quad_hi, quad_lo | ((uint32_t)pair << 7), prm.step_lo, kDomainNoise | prm.step_hi24};
     philox4x32<kNoiseRounds>(c, prm.seed_lo, prm.seed_hi);
-    box_muller_pair(c[0], prm.sigma, za[0], za[1]);
-    box_muller_pair(c[1], prm.sigma, za[2], za[3]);
-    box_muller_pair(c[2], prm.sigma, zb[0], zb[1]);
-    box_muller_pair(c[3], prm.sigma, zb[2], zb[3]);
+    box_muller_pair(c[0], lds, za[0], za[1]);
+    box_muller_pair(c[1], lds, za[2], za[3]);
+    box_muller_pair(c[2], lds, zb[0], zb[1]);
+    box_muller_pair(c[3], lds, zb[2], zb[3]);
 }
+__device__ __forceinline__ void noise_patch(const RoundParams &, const NoNoiseLds &, int, uint32_t, uint32_t, float *,
+                                            float *) {}
 
 // ---------------------------------------------------------------------------------------
 // Storage formats: fp32, or bf16 bit patterns with round-to-nearest-even on every store.
@@ -254,9 +325,6 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
 
 // 128-bit accesses carry the non-temporal hint: the state is far larger than the caches and
 // every element is touched once per round, so nothing is gained by keeping lines resident.
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
 // One lane's vector is 16 bytes (Raw): 4 fp32 columns or 8 bf16 columns.  Rows wait in
 // registers in Raw form and are unpacked to fp32 only when they are processed.
 template <typename ST>
@@ -332,6 +400,10 @@ struct LaneCols {
     int64_t tile0, lo, hi;
     uint32_t loff;
     __device__ __forceinline__ int64_t c0() const { return tile0 + loff; }
+    // noise counter of the lane's first quad: tile0 is a multiple of the wavefront's tile width (at
+    // most 512 columns, a divisor of 512), so the high part is wave-uniform
+    __device__ __forceinline__ uint32_t quad_hi() const { return (uint32_t)(tile0 >> 9); }
+    __device__ __forceinline__ uint32_t quad_lo() const { return ((uint32_t)(tile0 >> 2) & 127u) + (loff >> 2); }
 };
 
 template <typename ST, bool FULL>
@@ -375,10 +447,11 @@ __device__ __forceinline__ void store_raw(ST *tile_row, const LaneCols &lc, type
 }
 
 // Noise of the lane's VEC columns for the worker pair (2*pair, 2*pair+1).
-template <int VEC>
-__device__ __forceinline__ void noise_rows(const RoundParams &prm, int pair, int64_t c0, float za[VEC], float zb[VEC]) {
+template <int VEC, typename LDS>
+__device__ __forceinline__ void noise_rows(const RoundParams &prm, const LDS &lds, int pair, uint32_t quad_hi,
+                                           uint32_t quad_lo, float za[VEC], float zb[VEC]) {
 #pragma unroll
-    for (int q = 0; q < VEC / 4; ++q) noise_patch(prm, pair, (c0 >> 2) + q, za + 4 * q, zb + 4 * q);
+    for (int q = 0; q < VEC / 4; ++q) noise_patch(prm, lds, pair, quad_hi, quad_lo + q, za + 4 * q, zb + 4 * q);
 }
 
 // v = x - gamma * g, rounded to storage (Alg. 1 step 5); g = the caller's gradient or
@@ -440,9 +513,9 @@ __device__ __forceinline__ void load_chunk(LoadCursor<ST> &cur, const RoundParam
 
 // Pass 1 for the chunk of rows i0..i0+R-1: v for every row that needs it, column sums, and
 // the final value of the rows that will not receive the reply.
-template <typename ST, int GRAD, int R, bool FULL>
-__device__ __forceinline__ void process_chunk(ST *__restrict__ Xt, const RoundParams &prm, const LaneCols &lc,
-                                              uint64_t ucol, uint64_t dcol, int i0,
+template <typename ST, int GRAD, int R, bool FULL, typename LDS>
+__device__ __forceinline__ void process_chunk(ST *__restrict__ Xt, const RoundParams &prm, const LDS &lds,
+                                              const LaneCols &lc, uint64_t ucol, uint64_t dcol, int i0,
                                               const typename Storage<ST>::Raw xr[R],
                                               const typename Storage<ST>::Raw gr[GRAD == kGradBuffer ? R : 1],
                                               double acc[Storage<ST>::VEC]) {
@@ -460,7 +533,7 @@ __device__ __forceinline__ void process_chunk(ST *__restrict__ Xt, const RoundPa
             const bool need_b = ub || (GRAD != kGradNone && !db);
             if (need_a || need_b) {
                 float za[VEC], zb[VEC];
-                if (GRAD == kGradSynthetic) noise_rows<VEC>(prm, ia >> 1, lc.c0(), za, zb);
+                if (GRAD == kGradSynthetic) noise_rows<VEC>(prm, lds, ia >> 1, lc.quad_hi(), lc.quad_lo(), za, zb);
                 if (need_a) {
                     float v[VEC];
                     S::unpack(xr[r], v);
@@ -501,9 +574,9 @@ __device__ __forceinline__ void process_chunk(ST *__restrict__ Xt, const RoundPa
 // One tile, all n rows.  The row loop is software-pipelined by hand: the loads of chunk k+1
 // are issued before chunk k is processed, so a wavefront overlaps its own memory latency with
 // its own arithmetic and few resident wavefronts suffice.
-template <typename ST, int GRAD, int R, bool FULL>
+template <typename ST, int GRAD, int R, bool FULL, typename LDS>
 __device__ __forceinline__ void round_tile(ST *__restrict__ X, const ST *__restrict__ G, const RoundParams &prm,
-                                           const LaneCols &lc, uint64_t ucol, uint64_t dcol, double inv) {
+                                           const LDS &lds, const LaneCols &lc, uint64_t ucol, uint64_t dcol, double inv) {
     using S = Storage<ST>;
     using Raw = typename S::Raw;
     constexpr int VEC = S::VEC;
@@ -526,16 +599,16 @@ __device__ __forceinline__ void round_tile(ST *__restrict__ X, const ST *__restr
     // point is static and the waits inserted by the compiler leave the prefetch outstanding
     for (; i0 + 2 * R < n; i0 += 2 * R) {
         load_chunk<ST, GRAD, R, FULL>(cur, prm, lc, xb, gb);
-        process_chunk<ST, GRAD, R, FULL>(Xt, prm, lc, ucol, dcol, i0, xa, ga, acc);
+        process_chunk<ST, GRAD, R, FULL>(Xt, prm, lds, lc, ucol, dcol, i0, xa, ga, acc);
         load_chunk<ST, GRAD, R, FULL>(cur, prm, lc, xa, ga);
-        process_chunk<ST, GRAD, R, FULL>(Xt, prm, lc, ucol, dcol, i0 + R, xb, gb, acc);
+        process_chunk<ST, GRAD, R, FULL>(Xt, prm, lds, lc, ucol, dcol, i0 + R, xb, gb, acc);
     }
     if (i0 + R < n) {   // two chunks left
         load_chunk<ST, GRAD, R, FULL>(cur, prm, lc, xb, gb);
-        process_chunk<ST, GRAD, R, FULL>(Xt, prm, lc, ucol, dcol, i0, xa, ga, acc);
-        process_chunk<ST, GRAD, R, FULL>(Xt, prm, lc, ucol, dcol, i0 + R, xb, gb, acc);
+        process_chunk<ST, GRAD, R, FULL>(Xt, prm, lds, lc, ucol, dcol, i0, xa, ga, acc);
+        process_chunk<ST, GRAD, R, FULL>(Xt, prm, lds, lc, ucol, dcol, i0 + R, xb, gb, acc);
     } else {            // one chunk left
-        process_chunk<ST, GRAD, R, FULL>(Xt, prm, lc, ucol, dcol, i0, xa, ga, acc);
+        process_chunk<ST, GRAD, R, FULL>(Xt, prm, lds, lc, ucol, dcol, i0, xa, ga, acc);
     }
 
     float vt[VEC];
@@ -552,26 +625,31 @@ __global__ __launch_bounds__(WPB * 64) void round_kernel(ST *__restrict__ X, con
                                                          const RoundTable *__restrict__ tab, const RoundParams prm) {
     constexpr int VEC = Storage<ST>::VEC;
     constexpr int TILE = 64 * VEC;
+    __shared__ typename LdsFor<GRAD>::type lds;
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int j = blockIdx.y;
+    fill_noise_lds(lds, prm.noise_cells, prm.sigma, (int)threadIdx.x, WPB * 64);   // every wavefront, before any exit
     prepare_next_outcome(prm, linear_block() == 0 && wave == 0, j, lane);
     const int64_t lo = tab->off[j], hi = tab->off[j + 1];
-    const int64_t tile0 = (lo / TILE) * TILE + (linear_block() * WPB + wave) * TILE;
-    if (tile0 >= hi) return;   // wave-uniform: this block has fewer tiles than the largest one
     const uint64_t ucol = tab->ucol[j], dcol = tab->dcol[j];
     const double inv = tab->inv_cnt[j];
-
-    LaneCols lc;
-    lc.tile0 = tile0;
-    lc.loff = (uint32_t)lane * VEC;
-    lc.lo = lo;
-    lc.hi = hi;
-    if (prm.vec_ok && tile0 >= lo && tile0 + TILE <= hi)   // wave-uniform
-        round_tile<ST, GRAD, R, true>(X, G, prm, lc, ucol, dcol, inv);
-    else
-        round_tile<ST, GRAD, 2, false>(X, G, prm, lc, ucol, dcol, inv);
+    // a wavefront takes tiles_per_wave tiles, a whole grid apart (the workgroup's wavefronts stay on
+    // adjacent tiles): the LDS copy of the noise cells is paid once per WPB * tiles_per_wave tiles
+    for (int it = 0; it < prm.tiles_per_wave; ++it) {
+        const int64_t tile0 = (lo / TILE) * TILE + unit_index(it, WPB, wave) * TILE;
+        if (tile0 >= hi) break;   // wave-uniform: this block has fewer tiles than the largest one
+        LaneCols lc;
+        lc.tile0 = tile0;
+        lc.loff = (uint32_t)lane * VEC;
+        lc.lo = lo;
+        lc.hi = hi;
+        if (prm.vec_ok && tile0 >= lo && tile0 + TILE <= hi)   // wave-uniform
+            round_tile<ST, GRAD, R, true>(X, G, prm, lds, lc, ucol, dcol, inv);
+        else
+            round_tile<ST, GRAD, 2, false>(X, G, prm, lds, lc, ucol, dcol, inv);
+    }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -640,6 +718,7 @@ __device__ __forceinline__ void store_seg(ST *base, uint32_t eoff, uint32_t limi
 template <typename ST, int GRAD, int LPR, int PG, int CP, bool FULL>
 struct NarrowTile {
     using S = Storage<ST>;
+    using LDS = typename LdsFor<GRAD>::type;
     using Raw = typename S::Raw;
     static constexpr int VEC = S::VEC;
     static constexpr int GROUPS = PG;            // lane groups of one tile = its rows per wavefront instruction
@@ -650,6 +729,8 @@ struct NarrowTile {
     static constexpr int CG = GRAD == kGradBuffer ? 2 * CP : 1;
 
     const RoundParams &prm;
+    const LDS &lds;
+    uint32_t quad_hi, quad_lo;   // noise counter of the lane's first quad; quad_hi is wave-uniform
     ST *Xt;            // the wavefront's first tile: wave-uniform base, every access adds a 32-bit lane offset
     const ST *Gt;
     uint32_t sub_off;  // this lane's tile inside the wavefront's run + its columns inside a row segment
@@ -662,12 +743,16 @@ struct NarrowTile {
     uint32_t limit;    // bytes of the wavefront's tiles: the buffer resource's bound
 
     // lgw = lane / LPR, col_off = (lane % LPR) * VEC, first = first column of the wavefront's first tile
-    __device__ __forceinline__ NarrowTile(const RoundParams &prm_, ST *Xt_, const ST *Gt_, uint32_t col_off, int64_t first,
-                                          int64_t lo_, int64_t hi_, uint64_t ucol, uint64_t dcol, int lgw)
-        : prm(prm_), Xt(Xt_), Gt(Gt_), lo(lo_), hi(hi_), lg(lgw % PG) {
+    __device__ __forceinline__ NarrowTile(const RoundParams &prm_, const LDS &lds_, ST *Xt_, const ST *Gt_,
+                                          uint32_t col_off, int64_t first, int64_t lo_, int64_t hi_, uint64_t ucol,
+                                          uint64_t dcol, int lgw)
+        : prm(prm_), lds(lds_), Xt(Xt_), Gt(Gt_), lo(lo_), hi(hi_), lg(lgw % PG) {
         const int tw = lgw / PG;   // the lane's tile among the wavefront's
         sub_off = (uint32_t)tw * (uint32_t)prm.n * STRIDE + col_off;
         c0 = first + (int64_t)tw * (LPR * VEC) + col_off;
+        // `first` is a multiple of the wavefront's width, which divides 512 columns
+        quad_hi = (uint32_t)(first >> 9);
+        quad_lo = ((uint32_t)(first >> 2) & 127u) + (((uint32_t)tw * (LPR * VEC) + col_off) >> 2);
         const uint64_t valid = prm.n >= 64 ? ~0ull : ((1ull << prm.n) - 1);
         sum_bits = (ucol & valid) >> (2 * lg);
         avg_bits = (dcol & valid) >> (2 * lg);
@@ -718,7 +803,7 @@ struct NarrowTile {
         float za[CP][VEC], zb[CP][VEC];
         if (GRAD == kGradSynthetic) {
 #pragma unroll
-            for (int q = 0; q < CP; ++q) noise_rows<VEC>(prm, row_a(k0 + q) >> 1, c0, za[q], zb[q]);
+            for (int q = 0; q < CP; ++q) noise_rows<VEC>(prm, lds, row_a(k0 + q) >> 1, quad_hi, quad_lo, za[q], zb[q]);
         }
 #pragma unroll
         for (int q = 0; q < CP; ++q) {
@@ -754,8 +839,9 @@ struct NarrowTile {
     // SINGLE: the launcher guarantees n <= 2 * GROUPS * CP, i.e. the lane's rows are one load chunk
     // and every row index is a compile-time constant (the general loop is then not even compiled
     // in: having both in one kernel costs registers).
-    template <bool SINGLE>
-    __device__ __forceinline__ void run(double inv) const {
+    // after_first_loads() is called once the first chunk's loads are issued (see NoiseFill)
+    template <bool SINGLE, typename F>
+    __device__ __forceinline__ void run(double inv, const F &after_first_loads) const {
         const int steps = ((prm.n + 1) / 2 + GROUPS - 1) / GROUPS;   // row pairs per lane (wave-uniform)
         double acc[VEC];
 #pragma unroll
@@ -766,6 +852,7 @@ struct NarrowTile {
         __builtin_amdgcn_s_setprio(3);
         load_chunk(0, xa, ga);
         __builtin_amdgcn_s_setprio(0);
+        after_first_loads();
         if constexpr (SINGLE) {
             process_chunk(0, xa, ga, acc);
             finish(acc, inv, steps);
@@ -790,41 +877,57 @@ struct NarrowTile {
 };
 
 // Tiled layout only: the tile [tile0, tile0 + LPR * VEC) of all n workers is the contiguous run of
-// n * LPR * 16 bytes at element offset tile0 * n; a wavefront takes 8 / PG adjacent tiles.
-template <typename ST, int GRAD, int LPR, int PG, int CP, bool SINGLE>
-__global__ __launch_bounds__(64) void round_kernel_narrow(ST *__restrict__ X, const ST *__restrict__ G,
-                                                          const RoundTable *__restrict__ tab, const RoundParams prm) {
+// n * LPR * 16 bytes at element offset tile0 * n; a wavefront takes 8 / PG adjacent tiles at a time,
+// tiles_per_wave times, WPB such runs apart (the wavefronts of a workgroup stay next to each other).
+template <typename ST, int GRAD, int LPR, int PG, int CP, bool SINGLE, int WPB>
+__global__ __launch_bounds__(WPB * 64) void round_kernel_narrow(ST *__restrict__ X, const ST *__restrict__ G,
+                                                                const RoundTable *__restrict__ tab, const RoundParams prm) {
     constexpr int VEC = Storage<ST>::VEC;
-    constexpr int WIDTH = ((64 / LPR) / PG) * LPR * VEC;   // columns per wavefront
-    const int lane = threadIdx.x;
+    constexpr int WIDTH = ((64 / LPR) / PG) * LPR * VEC;   // columns per wavefront and step
+    __shared__ typename LdsFor<GRAD>::type lds;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int j = blockIdx.y;
-    prepare_next_outcome(prm, linear_block() == 0, j, lane);
+    // the noise cells travel to LDS while the first tile's loads are in flight: their global loads
+    // are issued here, the LDS writes and the workgroup barrier follow the first tile's loads --
+    // or the loop, for a wavefront that has no tile: every wavefront passes the barrier exactly once
+    NoiseFill<GRAD, WPB> fill;
+    fill.begin(prm.noise_cells, (int)threadIdx.x);
+    bool fill_pending = true;
+    const auto finish_fill = [&] {
+        if (fill_pending) fill.end(lds, prm.sigma, (int)threadIdx.x);
+        fill_pending = false;
+    };
     const int64_t lo = tab->off[j], hi = tab->off[j + 1];
-    const int64_t first = (lo / WIDTH) * WIDTH + linear_block() * WIDTH;
-    if (first >= hi) return;   // wave-uniform
+    const uint64_t ucol = tab->ucol[j], dcol = tab->dcol[j];
+    const double inv = tab->inv_cnt[j];
     const uint32_t col_off = (uint32_t)(lane % LPR) * VEC;
-    ST *Xt = X + first * prm.n;
-    const ST *Gt = G ? G + first * prm.n : nullptr;
-    const bool full = prm.vec_ok && first >= lo && first + WIDTH <= hi;   // wave-uniform
-    if (full) {
-        const NarrowTile<ST, GRAD, LPR, PG, CP, true> t(prm, Xt, Gt, col_off, first, lo, hi, tab->ucol[j], tab->dcol[j],
-                                                        lane / LPR);
-        t.template run<SINGLE>(tab->inv_cnt[j]);
-    } else {
-        const NarrowTile<ST, GRAD, LPR, PG, CP, false> t(prm, Xt, Gt, col_off, first, lo, hi, tab->ucol[j], tab->dcol[j],
-                                                         lane / LPR);
-        t.template run<SINGLE>(tab->inv_cnt[j]);
+    for (int it = 0; it < prm.tiles_per_wave; ++it) {
+        const int64_t first = (lo / WIDTH) * WIDTH + unit_index(it, WPB, wave) * WIDTH;
+        if (first >= hi) break;   // wave-uniform
+        ST *Xt = X + first * prm.n;
+        const ST *Gt = G ? G + first * prm.n : nullptr;
+        const bool full = prm.vec_ok && first >= lo && first + WIDTH <= hi;   // wave-uniform
+        if (full) {
+            const NarrowTile<ST, GRAD, LPR, PG, CP, true> t(prm, lds, Xt, Gt, col_off, first, lo, hi, ucol, dcol, lane / LPR);
+            t.template run<SINGLE>(inv, finish_fill);
+        } else {
+            const NarrowTile<ST, GRAD, LPR, PG, CP, false> t(prm, lds, Xt, Gt, col_off, first, lo, hi, ucol, dcol, lane / LPR);
+            t.template run<SINGLE>(inv, finish_fill);
+        }
     }
+    finish_fill();
+    prepare_next_outcome(prm, linear_block() == 0 && wave == 0, j, lane);
 }
 
-// Local SGD step alone: grid = (vector chunks, workers); a lane owns one 16-byte vector of one
-// row.  One row per wavefront keeps every access stream contiguous (measured 0.80 of the HBM
+// Local SGD step alone: grid = (runs of vector chunks, workers); a lane owns one 16-byte vector of
+// one row.  One row per wavefront keeps every access stream contiguous (measured 0.80 of the HBM
 // peak against 0.74 when a lane served both rows of a worker pair); the price is that the
 // noise hash of a (4 columns x 2 workers) patch is evaluated by both rows' lanes, each keeping
-// its half.
-template <typename ST, int GRAD, bool FULL>
+// its half.  A wavefront takes tiles_per_wave chunks, WPB chunks apart.
+template <typename ST, int GRAD, bool FULL, typename LDS>
 __device__ __forceinline__ void local_step_row(ST *__restrict__ X, const ST *__restrict__ G, const RoundParams &prm,
-                                               const LaneCols &lc, int i) {
+                                               const LDS &lds, const LaneCols &lc, int i) {
     using S = Storage<ST>;
     constexpr int VEC = S::VEC;
     ST *row = X + (int64_t)i * prm.stride + lc.tile0;
@@ -833,119 +936,154 @@ __device__ __forceinline__ void local_step_row(ST *__restrict__ X, const ST *__r
     if (GRAD == kGradBuffer) {
         S::unpack(load_raw<ST, FULL>(G + (int64_t)i * prm.stride + lc.tile0, lc), g);
     } else if (i & 1) {
-        noise_rows<VEC>(prm, i >> 1, lc.c0(), other, g);
+        noise_rows<VEC>(prm, lds, i >> 1, lc.quad_hi(), lc.quad_lo(), other, g);
     } else {
-        noise_rows<VEC>(prm, i >> 1, lc.c0(), g, other);
+        noise_rows<VEC>(prm, lds, i >> 1, lc.quad_hi(), lc.quad_lo(), g, other);
     }
     store_raw<ST, FULL>(row, lc, sgd_step<ST, GRAD>(prm, g, x));
 }
 
-template <typename ST, int GRAD>
-__global__ __launch_bounds__(256) void local_step_kernel(ST *__restrict__ X, const ST *__restrict__ G,
-                                                         const RoundParams prm) {
+template <typename ST, int GRAD, int WPB>
+__global__ __launch_bounds__(WPB * 64) void local_step_kernel(ST *__restrict__ X, const ST *__restrict__ G,
+                                                              const RoundParams prm) {
     constexpr int VEC = Storage<ST>::VEC;
     constexpr int TILE = 64 * VEC;
+    __shared__ typename LdsFor<GRAD>::type lds;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t tile0 = (linear_block() * 4 + wave) * TILE;
     const int row = blockIdx.y;
-    if (tile0 >= prm.N) return;   // wave-uniform
-    LaneCols lc;
-    lc.tile0 = tile0;
-    lc.loff = (uint32_t)lane * VEC;
-    lc.lo = 0;
-    lc.hi = prm.N;
-    if (prm.vec_ok && tile0 + TILE <= prm.N)
-        local_step_row<ST, GRAD, true>(X, G, prm, lc, row);
-    else
-        local_step_row<ST, GRAD, false>(X, G, prm, lc, row);
+    fill_noise_lds(lds, prm.noise_cells, prm.sigma, (int)threadIdx.x, WPB * 64);
+    for (int it = 0; it < prm.tiles_per_wave; ++it) {
+        const int64_t tile0 = unit_index(it, WPB, wave) * TILE;
+        if (tile0 >= prm.N) break;   // wave-uniform
+        LaneCols lc;
+        lc.tile0 = tile0;
+        lc.loff = (uint32_t)lane * VEC;
+        lc.lo = 0;
+        lc.hi = prm.N;
+        if (prm.vec_ok && tile0 + TILE <= prm.N)
+            local_step_row<ST, GRAD, true>(X, G, prm, lds, lc, row);
+        else
+            local_step_row<ST, GRAD, false>(X, G, prm, lds, lc, row);
+    }
 }
 
 // Local step on the tiled layout: the storage is one run of (tile, worker) segments of
 // kTiledLanes x 16 bytes; a wavefront takes 1 KB of it in storage order (8 segments), so the pass is
-// a plain sequential stream.  Lane -> segment s = 8 * wavefront + lane / 8 -> (tile, row) = (s / n, s % n).
-template <typename ST, int GRAD>
-__global__ __launch_bounds__(256) void local_step_tiled_kernel(ST *__restrict__ X, const ST *__restrict__ G,
-                                                               const RoundParams prm) {
+// a plain sequential stream.  Lane -> segment s = 8 * q + lane / 8 -> (tile, row) = (s / n, s % n),
+// q = the wavefront's running index (tiles_per_wave of them per wavefront, WPB apart).
+template <typename ST, int GRAD, int WPB>
+__global__ __launch_bounds__(WPB * 64) void local_step_tiled_kernel(ST *__restrict__ X, const ST *__restrict__ G,
+                                                                    const RoundParams prm) {
     using S = Storage<ST>;
     constexpr int VEC = S::VEC;
     constexpr int LPR = kTiledLanes, TILE = LPR * VEC;
-    const int64_t q = linear_block() * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    __shared__ typename LdsFor<GRAD>::type lds;
     const int lane = threadIdx.x & 63;
-    const int64_t seg0 = q * (64 / LPR);          // first segment of the wavefront: scalar division
-    int64_t tile = seg0 / prm.n;
-    int i = (int)(seg0 % prm.n) + lane / LPR;     // then at most 64 / LPR rows further
-    while (i >= prm.n) {
-        i -= prm.n;
-        ++tile;
-    }
-    const int64_t c0 = tile * TILE + (lane % LPR) * VEC;
-    if (c0 >= prm.N) return;   // padding columns of the last tile, or past the last tile
-    ST *px = X + seg0 * TILE + (uint32_t)(lane / LPR) * TILE + (lane % LPR) * VEC;   // plain global accesses:
-    const ST *pg = G ? G + (px - X) : nullptr;   // measured faster here than the buffer form the round kernels use
-    float x[VEC], g[VEC], other[VEC];
-    const bool full = prm.vec_ok && c0 + VEC <= prm.N;
-    if (full) {
-        S::unpack(__builtin_nontemporal_load(reinterpret_cast<const typename S::Raw *>(px)), x);
-        if (GRAD == kGradBuffer) S::unpack(__builtin_nontemporal_load(reinterpret_cast<const typename S::Raw *>(pg)), g);
-    } else {
-        S::unpack(load_seg<ST, false>(px, 0, 0, c0, 0, prm.N), x);
-        if (GRAD == kGradBuffer) S::unpack(load_seg<ST, false>(pg, 0, 0, c0, 0, prm.N), g);
-    }
-    if (GRAD != kGradBuffer) {
-        if (i & 1)
-            noise_rows<VEC>(prm, i >> 1, c0, other, g);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    fill_noise_lds(lds, prm.noise_cells, prm.sigma, (int)threadIdx.x, WPB * 64);
+    const int64_t tiles = (prm.N + TILE - 1) / TILE;
+    for (int it = 0; it < prm.tiles_per_wave; ++it) {
+        const int64_t q = unit_index(it, WPB, wave);
+        const int64_t seg0 = q * (64 / LPR);          // first segment of the wavefront: scalar division
+        int64_t tile = seg0 / prm.n;
+        if (tile >= tiles) break;                     // wave-uniform: past the last tile
+        int i = (int)(seg0 % prm.n) + lane / LPR;     // then at most 64 / LPR rows further
+        while (i >= prm.n) {
+            i -= prm.n;
+            ++tile;
+        }
+        const int64_t c0 = tile * TILE + (lane % LPR) * VEC;
+        if (c0 >= prm.N) continue;   // padding columns of the last tile, or past the last tile
+        ST *px = X + seg0 * TILE + (uint32_t)(lane / LPR) * TILE + (lane % LPR) * VEC;   // plain global accesses:
+        const ST *pg = G ? G + (px - X) : nullptr;   // measured faster here than the buffer form the round kernels use
+        float x[VEC], g[VEC], other[VEC];
+        const bool full = prm.vec_ok && c0 + VEC <= prm.N;
+        if (full) {
+            S::unpack(__builtin_nontemporal_load(reinterpret_cast<const typename S::Raw *>(px)), x);
+            if (GRAD == kGradBuffer) S::unpack(__builtin_nontemporal_load(reinterpret_cast<const typename S::Raw *>(pg)), g);
+        } else {
+            S::unpack(load_seg<ST, false>(px, 0, 0, c0, 0, prm.N), x);
+            if (GRAD == kGradBuffer) S::unpack(load_seg<ST, false>(pg, 0, 0, c0, 0, prm.N), g);
+        }
+        if (GRAD != kGradBuffer) {   // a wavefront's lanes may sit in different tiles: the counter is per lane
+            const uint32_t quad_hi = (uint32_t)(c0 >> 9), quad_lo = (uint32_t)(c0 >> 2) & 127u;
+            if (i & 1)
+                noise_rows<VEC>(prm, lds, i >> 1, quad_hi, quad_lo, other, g);
+            else
+                noise_rows<VEC>(prm, lds, i >> 1, quad_hi, quad_lo, g, other);
+        }
+        const typename S::Raw v = sgd_step<ST, GRAD>(prm, g, x);
+        if (full)
+            __builtin_nontemporal_store(v, reinterpret_cast<typename S::Raw *>(px));
         else
-            noise_rows<VEC>(prm, i >> 1, c0, g, other);
+            store_seg<ST, false>(px, 0, 0, c0, 0, prm.N, v);
     }
-    const typename S::Raw v = sgd_step<ST, GRAD>(prm, g, x);
-    if (full)
-        __builtin_nontemporal_store(v, reinterpret_cast<typename S::Raw *>(px));
-    else
-        store_seg<ST, false>(px, 0, 0, c0, 0, prm.N, v);
 }
 
-// Launch shape of the round kernel.  The memory system of this GPU is at its best when the
-// chip-wide footprint of requests in flight is a few MB: occupancy is therefore capped by a
-// dynamic LDS allocation that the kernel never touches.
+// Launch shapes.  The memory system of this GPU is at its best when the chip-wide footprint of
+// requests in flight is a few MB: occupancy is therefore capped through the LDS a workgroup holds --
+// the noise cells where a kernel generates noise, plus a dynamic allocation that is never touched.
+// Returns the dynamic LDS bytes that leave room for max_waves_per_cu / wpb workgroups per compute
+// unit (0 or >= 32 waves: no cap), given the kernel's static LDS.
+size_t occupancy_pad(int max_waves_per_cu, int wpb, size_t static_lds) {
+    if (max_waves_per_cu <= 0 || max_waves_per_cu >= 32) return 0;
+    int wgs = max_waves_per_cu / wpb;
+    if (wgs < 1) wgs = 1;
+    size_t per = ((size_t)kLdsBytesPerCu / wgs) & ~(size_t)255;
+    if (per > 65536) per = 65536;   // the default per-workgroup limit
+    return per > static_lds ? per - static_lds : 0;
+}
+
+template <int GRAD>
+constexpr size_t static_lds_bytes() {
+    return sizeof(typename LdsFor<GRAD>::type);
+}
+
+// Steps a wavefront takes in a kernel that generates noise (each workgroup first copies the 32 KB
+// of noise cells into LDS, which has to be spread over enough work -- but every further step of a
+// wavefront costs more than a fresh wavefront would, so few): up to `most`, fewer while the grid
+// would otherwise not fill the chip.  Other kernels: 1.
+int steps_per_wave(int grad_mode, int64_t wave_steps_per_row, int wpb, int64_t rows, int wanted, int most) {
+    if (grad_mode != kGradSynthetic) return 1;
+    if (wanted > 0) return wanted;
+    int t = most;
+    while (t > 1 && ((wave_steps_per_row + (int64_t)wpb * t - 1) / ((int64_t)wpb * t)) * rows < 4096) t >>= 1;
+    return t;
+}
+
 template <typename ST, int GRAD, int R, int WPB>
-hipError_t launch_round_v(ST *X, const ST *G, const RoundTable *tab, const RoundParams &prm, int64_t max_block_cols,
-                          int max_waves_per_cu, hipStream_t stream) {
+hipError_t launch_round_v(ST *X, const ST *G, const RoundTable *tab, RoundParams prm, int64_t max_block_cols,
+                          const LaunchTuning &tune, hipStream_t stream) {
     constexpr int TILE = 64 * Storage<ST>::VEC;
     // tiles sit on absolute multiples of TILE columns: a block may overhang one tile on each side
     const int64_t tiles = (max_block_cols + 2 * TILE - 2) / TILE;
-    const dim3 grid = folded_grid((tiles + WPB - 1) / WPB, (unsigned)prm.blocks);
-    size_t lds = 0;
-    if (max_waves_per_cu > 0 && max_waves_per_cu < 32) {
-        int wgs = max_waves_per_cu / WPB;
-        if (wgs < 1) wgs = 1;
-        lds = ((size_t)kLdsBytesPerCu / wgs) & ~(size_t)255;
-        if (lds > 65536) lds = 65536;   // the default per-workgroup limit
-    }
+    prm.tiles_per_wave = steps_per_wave(GRAD, tiles, WPB, prm.blocks, tune.tiles_per_wave, 1);
+    const int64_t per_wg = (int64_t)WPB * prm.tiles_per_wave;
+    const dim3 grid = folded_grid8((tiles + per_wg - 1) / per_wg, (unsigned)prm.blocks);
+    const size_t lds = occupancy_pad(tune.max_waves_per_cu, WPB, static_lds_bytes<GRAD>());
     hipLaunchKernelGGL((round_kernel<ST, GRAD, R, WPB>), grid, dim3(WPB * 64), lds, stream, X, G, tab, prm);
     return hipGetLastError();
 }
 
-template <typename ST, int GRAD, int LPR>
-hipError_t launch_round_narrow(ST *X, const ST *G, const RoundTable *tab, const RoundParams &prm, int64_t max_block_cols,
-                               int max_waves_per_cu, bool one_pair_per_lane, hipStream_t stream) {
+template <typename ST, int GRAD, int LPR, int WPB>
+hipError_t launch_round_narrow(ST *X, const ST *G, const RoundTable *tab, RoundParams prm, int64_t max_block_cols,
+                               const LaunchTuning &tune, hipStream_t stream) {
     constexpr int TILE = LPR * Storage<ST>::VEC;
     constexpr int GROUPS = 64 / LPR;
-    size_t lds = 0;
-    if (max_waves_per_cu > 0 && max_waves_per_cu < 32) {
-        lds = ((size_t)kLdsBytesPerCu / max_waves_per_cu) & ~(size_t)255;
-        if (lds > 65536) lds = 65536;
-    }
-    // lane groups per tile: a power of two such that a lane gets two row pairs where the workers
-    // allow it (tuning knob waves_per_workgroup == 4: one pair per lane, for comparison)
+    // lane groups per tile: a power of two such that a lane gets two row pairs where the workers allow it
     const int pairs = (prm.n + 1) / 2;
-    const bool two = !one_pair_per_lane;
-    const int need = two ? (pairs + 1) / 2 : pairs;
+    const int need = (pairs + 1) / 2;
     const int pg = need > 4 ? 8 : (need > 2 ? 4 : (need > 1 ? 2 : 1));
-    const int64_t width = (int64_t)(GROUPS / pg) * TILE;   // columns per wavefront
-    const dim3 grid = folded_grid((max_block_cols + 2 * width - 2) / width, (unsigned)prm.blocks);
-#define RPS_N(PG, CP, SINGLE) \
-    hipLaunchKernelGGL((round_kernel_narrow<ST, GRAD, LPR, PG, CP, SINGLE>), grid, dim3(64), lds, stream, X, G, tab, prm)
+    const int64_t width = (int64_t)(GROUPS / pg) * TILE;   // columns per wavefront and step
+    const int64_t steps = (max_block_cols + 2 * width - 2) / width;
+    prm.tiles_per_wave = steps_per_wave(GRAD, steps, WPB, prm.blocks, tune.tiles_per_wave, 2);
+    const int64_t per_wg = (int64_t)WPB * prm.tiles_per_wave;
+    const dim3 grid = folded_grid8((steps + per_wg - 1) / per_wg, (unsigned)prm.blocks);
+    const size_t lds = occupancy_pad(tune.max_waves_per_cu, WPB, static_lds_bytes<GRAD>());
+#define RPS_N(PG, CP, SINGLE)                                                                                       \
+    hipLaunchKernelGGL((round_kernel_narrow<ST, GRAD, LPR, PG, CP, SINGLE, WPB>), grid, dim3(WPB * 64), lds, stream, X, G, \
+                       tab, prm)
     if (pg == 1 && pairs <= 1)
         RPS_N(1, 1, true);
     else if (pg == 1)
@@ -962,20 +1100,33 @@ hipError_t launch_round_narrow(ST *X, const ST *G, const RoundTable *tab, const 
         RPS_N(8, 1, true);
     else if (prm.n <= 4 * GROUPS)   // two pairs: still one load chunk
         RPS_N(8, 2, true);
+    else if (tune.rows_in_flight <= 2)
+        RPS_N(8, 1, false);
     else
         RPS_N(8, 2, false);
 #undef RPS_N
     return hipGetLastError();
 }
 
+// Workgroup widths: kernels that generate noise share the LDS copy of the noise cells among 4, 8 or
+// 16 wavefronts (tile-major) or 2 or 4 (row-major, where a tile is n KB); the others keep one
+// wavefront per workgroup (or 4, a tuning option of the row-major kernel).
 template <typename ST, int GRAD>
 hipError_t launch_round_t(ST *X, const ST *G, const RoundTable *tab, const RoundParams &prm, int64_t max_block_cols,
                           const LaunchTuning &tune, hipStream_t stream) {
-    if (prm.tiled)
-        return launch_round_narrow<ST, GRAD, kTiledLanes>(X, G, tab, prm, max_block_cols, tune.max_waves_per_cu,
-                                                          tune.waves_per_workgroup == 4, stream);
-#define RPS_V(R, W) launch_round_v<ST, GRAD, R, W>(X, G, tab, prm, max_block_cols, tune.max_waves_per_cu, stream)
     const int r = tune.rows_in_flight, w = tune.waves_per_workgroup;
+    if (prm.tiled) {
+#define RPS_T(W) launch_round_narrow<ST, GRAD, kTiledLanes, W>(X, G, tab, prm, max_block_cols, tune, stream)
+        if (GRAD != kGradSynthetic) return RPS_T(1);
+        return w <= 4 ? RPS_T(4) : (w <= 8 ? RPS_T(8) : RPS_T(16));
+#undef RPS_T
+    }
+#define RPS_V(R, W) launch_round_v<ST, GRAD, R, W>(X, G, tab, prm, max_block_cols, tune, stream)
+    if (GRAD == kGradSynthetic) {
+        if (w <= 2) return r <= 2 ? RPS_V(2, 2) : RPS_V(4, 2);
+        if (w <= 4) return r <= 2 ? RPS_V(2, 4) : RPS_V(4, 4);
+        return r <= 2 ? RPS_V(2, 8) : RPS_V(4, 8);
+    }
     if (w == 1) return r <= 2 ? RPS_V(2, 1) : RPS_V(4, 1);
     return r <= 2 ? RPS_V(2, 4) : RPS_V(4, 4);
 #undef RPS_V
@@ -992,24 +1143,35 @@ hipError_t launch_round_g(int grad_mode, ST *X, const ST *G, const RoundTable *t
 }
 
 template <typename ST>
-hipError_t launch_local_step_g(int grad_mode, ST *X, const ST *G, const RoundParams &prm, hipStream_t stream) {
+hipError_t launch_local_step_g(int grad_mode, ST *X, const ST *G, RoundParams prm, hipStream_t stream) {
     constexpr int VEC = Storage<ST>::VEC;
+    constexpr int WS = 8;   // wavefronts per workgroup where noise is generated (they share the LDS cells)
     if (prm.tiled) {
         const int64_t tiles = (prm.N + kTiledLanes * VEC - 1) / (kTiledLanes * VEC);
-        const int64_t kb = (tiles * prm.n * kTiledLanes + 63) / 64;   // wavefronts: 1 KB of storage each
-        const dim3 grid = folded_grid((kb + 3) / 4, 1);
-        if (grad_mode == kGradBuffer)
-            hipLaunchKernelGGL((local_step_tiled_kernel<ST, kGradBuffer>), grid, dim3(256), 0, stream, X, G, prm);
-        else
-            hipLaunchKernelGGL((local_step_tiled_kernel<ST, kGradSynthetic>), grid, dim3(256), 0, stream, X, G, prm);
+        const int64_t kb = (tiles * prm.n * kTiledLanes + 63) / 64;   // wavefront steps: 1 KB of storage each
+        if (grad_mode == kGradBuffer) {
+            prm.tiles_per_wave = 1;
+            hipLaunchKernelGGL((local_step_tiled_kernel<ST, kGradBuffer, 4>), folded_grid8((kb + 3) / 4, 1), dim3(256), 0,
+                               stream, X, G, prm);
+        } else {
+            prm.tiles_per_wave = steps_per_wave(kGradSynthetic, kb, WS, 1, 0, 32);   // a step is only 1 KB here
+            const int64_t per_wg = (int64_t)WS * prm.tiles_per_wave;
+            hipLaunchKernelGGL((local_step_tiled_kernel<ST, kGradSynthetic, WS>), folded_grid8((kb + per_wg - 1) / per_wg, 1),
+                               dim3(WS * 64), 0, stream, X, G, prm);
+        }
         return hipGetLastError();
     }
     const int64_t tiles = (prm.N + 64 * VEC - 1) / (64 * VEC);
-    const dim3 grid = folded_grid((tiles + 3) / 4, (unsigned)prm.n);
-    if (grad_mode == kGradBuffer)
-        hipLaunchKernelGGL((local_step_kernel<ST, kGradBuffer>), grid, dim3(256), 0, stream, X, G, prm);
-    else
-        hipLaunchKernelGGL((local_step_kernel<ST, kGradSynthetic>), grid, dim3(256), 0, stream, X, G, prm);
+    if (grad_mode == kGradBuffer) {
+        prm.tiles_per_wave = 1;
+        hipLaunchKernelGGL((local_step_kernel<ST, kGradBuffer, 4>), folded_grid8((tiles + 3) / 4, (unsigned)prm.n), dim3(256),
+                           0, stream, X, G, prm);
+    } else {
+        prm.tiles_per_wave = steps_per_wave(kGradSynthetic, tiles, WS, prm.n, 0, 32);   // a step is only 1 KB here
+        const int64_t per_wg = (int64_t)WS * prm.tiles_per_wave;
+        hipLaunchKernelGGL((local_step_kernel<ST, kGradSynthetic, WS>),
+                           folded_grid8((tiles + per_wg - 1) / per_wg, (unsigned)prm.n), dim3(WS * 64), 0, stream, X, G, prm);
+    }
     return hipGetLastError();
 }
 

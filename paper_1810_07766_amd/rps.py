@@ -46,7 +46,8 @@ _lib.rps_consensus_static.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_
 _lib.rps_estimate_mixing.argtypes = [_ctx_p, ctypes.c_uint64, ctypes.c_int64, ctypes.POINTER(ctypes.c_double),
                                      ctypes.POINTER(ctypes.c_double)]
 _lib.rps_convert_layout.argtypes = [_ctx_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32]
-_lib.rps_set_launch_tuning.argtypes = [_ctx_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32]
+_lib.rps_set_launch_tuning.argtypes = [_ctx_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32]
+_lib.rps_noise_cells.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
 _lib.rps_set_profiling.argtypes = [_ctx_p, ctypes.c_int32]
 _lib.rps_get_kernel_time.argtypes = [_ctx_p, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
 _lib.rps_last_hip_error.argtypes = [_ctx_p]
@@ -54,12 +55,12 @@ _lib.rps_strerror.argtypes = [ctypes.c_int]
 _lib.rps_strerror.restype = ctypes.c_char_p
 for _name in ("rps_create", "rps_create_external", "rps_destroy", "rps_set_synthetic_grad", "rps_set_gamma", "rps_local_step",
               "rps_lossy_average", "rps_round", "rps_round_gradient_averaging", "rps_get_masks", "rps_set_mask_override",
-              "rps_consensus", "rps_consensus_static", "rps_estimate_mixing", "rps_convert_layout", "rps_set_launch_tuning", "rps_set_profiling", "rps_get_kernel_time", "rps_last_hip_error"):
+              "rps_consensus", "rps_consensus_static", "rps_estimate_mixing", "rps_convert_layout", "rps_set_launch_tuning", "rps_noise_cells", "rps_set_profiling", "rps_get_kernel_time", "rps_last_hip_error"):
     getattr(_lib, _name).restype = ctypes.c_int
 
 EXPORTS = ("rps_create", "rps_create_external", "rps_storage_elems", "rps_destroy", "rps_set_synthetic_grad", "rps_set_gamma", "rps_local_step",
            "rps_lossy_average", "rps_round", "rps_round_gradient_averaging", "rps_get_masks", "rps_set_mask_override",
-           "rps_consensus", "rps_consensus_static", "rps_estimate_mixing", "rps_convert_layout", "rps_set_launch_tuning", "rps_set_profiling", "rps_get_kernel_time",
+           "rps_consensus", "rps_consensus_static", "rps_estimate_mixing", "rps_convert_layout", "rps_set_launch_tuning", "rps_noise_cells", "rps_set_profiling", "rps_get_kernel_time",
            "rps_last_hip_error",
            "rps_strerror")
 
@@ -205,8 +206,9 @@ class RpsContext:
         _check(_lib.rps_convert_layout(self._h, out.data_ptr(), Xt.data_ptr(), 0), self._h)
         return out
 
-    def set_launch_tuning(self, rows_in_flight, waves_per_workgroup, max_waves_per_cu=0):
-        _check(_lib.rps_set_launch_tuning(self._h, rows_in_flight, waves_per_workgroup, max_waves_per_cu), self._h)
+    def set_launch_tuning(self, rows_in_flight, waves_per_workgroup, max_waves_per_cu=0, tiles_per_wave=0):
+        _check(_lib.rps_set_launch_tuning(self._h, rows_in_flight, waves_per_workgroup, max_waves_per_cu, tiles_per_wave),
+               self._h)
 
     def set_profiling(self, enable):
         _check(_lib.rps_set_profiling(self._h, 1 if enable else 0), self._h)
@@ -278,6 +280,15 @@ def rps_consensus_static(X, n, N, out, dtype=RPS_DTYPE_F32, flags=0, stream=None
         raise RpsError(RPS_EINVAL)
     _check(_lib.rps_consensus_static(ctypes.c_void_p(X.data_ptr()), n, N, dtype, flags, ctypes.c_void_p(out.data_ptr()),
                                      ctypes.c_void_p(stream)))
+
+
+def rps_noise_cells():
+    """(radius[4096], cos_sin[4096, 2]) float32 as the library computes them on the host."""
+    import numpy as np
+    radius = np.empty(4096, dtype=np.float32)
+    cos_sin = np.empty((4096, 2), dtype=np.float32)
+    _check(_lib.rps_noise_cells(radius.ctypes.data, cos_sin.ctypes.data))
+    return radius, cos_sin
 
 
 def rps_estimate_mixing(ctx, first_step, rounds):

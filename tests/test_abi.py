@@ -106,3 +106,18 @@ def test_constants_agree_with_the_header():
     assert lib.rps_storage_elems(4, 1000, 0, 0) == 4000
     assert lib.rps_storage_elems(4, 1000, 0, rps.RPS_FLAG_LAYOUT_TILED) == 32 * 4 * 32
     assert lib.rps_storage_elems(65, 1000, 0, 0) == -1
+
+
+def test_noise_cells_of_the_library_equal_the_oracle():
+    """The library computes the cell values of the synthetic gradient noise on the host in 80-bit
+    arithmetic, the oracle evaluates the same real values in double: both must land on the same
+    (correctly rounded) fp32 bits, or the device's noise could not match the oracle's."""
+    _ensure_built()
+    import numpy as np
+    from oracle import rps_oracle as oracle
+    from paper_1810_07766_amd import rps
+    radius, cos_sin = rps.rps_noise_cells()
+    r, c, s = oracle.noise_grid()
+    assert (radius.view(np.uint32) == r.view(np.uint32)).all()
+    assert (cos_sin[:, 0].view(np.uint32) == c.view(np.uint32)).all()
+    assert (cos_sin[:, 1].view(np.uint32) == s.view(np.uint32)).all()

@@ -138,21 +138,18 @@ def test_external_server_masks():
 # Gaussian noise
 # ---------------------------------------------------------------------------------------------
 def _noise_reference(seed, step, pair, quad, sigma):
-    """The textbook Box-Muller transform in double precision on the same hash words:
-    u1 = (2k+1)/2^17 from the low 16 bits, angle (2f+1) pi / 65536 from the signed 15-bit
-    field above them, bit 31 adds pi.  Words 0,1 -> worker 2*pair, words 2,3 -> worker 2*pair+1,
-    columns 4*quad..4*quad+3."""
-    ctr = [quad & 0xFFFFFFFF, pair, step & 0xFFFFFFFF, (3 << 24) | ((step >> 32) & 0xFFFFFF)]
+    """The textbook Box-Muller transform in double precision on the same hash words (counter
+    (quad >> 7, (quad & 127) | pair << 7, step low, 3 << 24 | step high)): u1 = (kr + 1/2)/4096 from
+    bits 2..13, angle 2 pi (ka + 1/2)/4096 with ka = bit 31 (the half turn) above bits 17..27.  Words 0,1 -> worker 2*pair,
+    words 2,3 -> worker 2*pair+1, columns 4*quad..4*quad+3."""
+    ctr = [(quad >> 7) & 0xFFFFFFFF, (quad & 127) | (pair << 7), step & 0xFFFFFFFF, (3 << 24) | ((step >> 32) & 0xFFFFFF)]
     key = [seed & 0xFFFFFFFF, seed >> 32]
     words = oracle.philox4x32(ctr, key, rounds=7)      # the noise stream uses 7 rounds
     out = []
     for w in words:
         w = int(w)
-        u1 = (2 * (w & 0xFFFF) + 1) / 2.0 ** 17
-        f = (w >> 16) & 0x7FFF
-        if f >= 0x4000:
-            f -= 0x8000
-        phi = (2 * f + 1) * np.pi / 65536 + (np.pi if w >> 31 else 0.0)
+        u1 = (((w >> 2) & 0xFFF) + 0.5) / 4096.0
+        phi = 2.0 * np.pi * (((w >> 17) & 0x7FF) + 0.5) / 4096.0 + (np.pi if w >> 31 else 0.0)
         r = np.sqrt(-2.0 * np.log(u1))
         out += [sigma * r * np.cos(phi), sigma * r * np.sin(phi)]
     return np.array(out).reshape(2, 4)
@@ -161,12 +158,54 @@ def _noise_reference(seed, step, pair, quad, sigma):
 def test_noise_matches_textbook_box_muller():
     worst = 0.0
     for (seed, step, pair, quad) in [(0, 0, 0, 0), (5, 3, 15, 123456), (2 ** 40 + 1, 2 ** 33, 31, 2 ** 31 + 5)]:
-        for q in range(quad, quad + 300):
-            z = oracle.noise_patch(seed, step, pair, q, 1.0).astype(np.float64)
-            ref = _noise_reference(seed, step, pair, q, 1.0)
-            worst = max(worst, np.abs(z - ref).max())
-            assert np.abs(z - ref).max() < 2e-4     # polynomial approximation error of the spec
-    assert worst > 0.0                               # (it is an approximation, not libm)
+        for sigma in (1.0, 0.1, float(np.float32(np.sqrt(1e-3)))):
+            for q in range(quad, quad + 150):
+                z = oracle.noise_patch(seed, step, pair, q, sigma).astype(np.float64)
+                ref = _noise_reference(seed, step, pair, q, sigma)
+                err = np.abs(z - ref).max() / sigma
+                worst = max(worst, err)
+                assert err < 1e-6                        # three fp32 roundings of values below 4.25
+    assert worst > 0.0                                   # (fp32 roundings, not the double result)
+
+
+def test_noise_cells_are_the_correctly_rounded_values():
+    """Every cell value of the specification -- sqrt(-2 ln((k + 1/2)/4096)), cos and sin of
+    2 pi (a + 1/2)/4096 -- is the fp32 number nearest to the exact real value (50-digit
+    arithmetic), so any implementation that rounds correctly produces the same bits."""
+    import mpmath
+    mpmath.mp.dps = 50
+    r, c, s = oracle.noise_grid()
+
+    def nearest_f32(x):
+        f = np.float32(float(x))                         # double rounding could miss a tie by one ulp:
+        cands = [f, np.nextafter(f, np.float32(np.inf)), np.nextafter(f, np.float32(-np.inf))]
+        return min(cands, key=lambda v: abs(mpmath.mpf(float(v)) - x))
+
+    for k in range(4096):
+        exact = mpmath.sqrt(-2 * mpmath.log((mpmath.mpf(k) + mpmath.mpf(1) / 2) / 4096))
+        assert r[k] == nearest_f32(exact), k
+        phi = 2 * mpmath.pi * (mpmath.mpf(k) + mpmath.mpf(1) / 2) / 4096
+        assert c[k] == nearest_f32(mpmath.cos(phi)), k
+        assert s[k] == nearest_f32(mpmath.sin(phi)), k
+    assert (np.diff(r) < 0).all() and r[0] < 4.2453 and r[-1] > 0.0156
+    assert (c == -c[::-1][np.r_[2048:4096, 0:2048]]).all()   # cos(phi + pi) = -cos(phi) on the half-shifted grid
+    assert (s == -s[::-1]).all() and (c == c[::-1]).all()        # phi -> 2 pi - phi
+    assert (c[2048:] == -c[:2048]).all() and (s[2048:] == -s[:2048]).all()   # the half turn only flips signs
+
+
+def test_noise_law_over_all_cells():
+    """The law of z is the uniform law over the 2^24 (radius, angle) cells: enumerate it exactly.
+    Symmetric; variance, fourth moment and the sup-distance to the normal cdf as documented."""
+    r, c, s = oracle.noise_grid()
+    for trig in (c, s):
+        z = np.outer(r.astype(np.float32), trig.astype(np.float32)).astype(np.float32).astype(np.float64).reshape(-1)
+        assert abs(z.mean()) < 1e-9
+        assert abs(z.var() - 0.999915) < 2e-6
+        assert abs((z ** 4).mean() - 2.99733) < 2e-5
+        assert abs(np.abs(z).max() - 4.2452) < 1e-3
+        z.sort()
+        F = (np.arange(z.size) + 0.5) / z.size
+        assert np.abs(stats.norm.cdf(z) - F).max() < 1e-4
 
 
 def test_noise_indexing_by_worker_and_column():
@@ -207,5 +246,5 @@ def test_noise_is_standard_normal():
     assert corr(z[:, :-1, :, 3], z[:, 1:, :, 0]) < 5 / np.sqrt(m / 2)
     assert corr(z[..., 0] ** 2, z[..., 1] ** 2) < 5 / np.sqrt(m)
     assert corr(z[:, :, 0, :] ** 2, z[:, :, 1, :] ** 2) < 5 / np.sqrt(2 * m)
-    # 16-bit radius index: |z| <= sqrt(2 ln 2^17)
-    assert np.abs(flat).max() <= np.sqrt(2 * np.log(2.0 ** 17)) * (1 + 1e-4)
+    # 12-bit radius index: |z| <= sqrt(2 ln 2^13)
+    assert np.abs(flat).max() <= np.sqrt(2 * np.log(2.0 ** 13)) * (1 + 1e-6)
