@@ -127,6 +127,8 @@ int rps_destroy(rps_ctx *ctx);
  * Synthetic stochastic gradient used when G == NULL:  g = weight_decay * x + sigma * z, with z
  * standard Gaussian noise generated in registers from (seed, step, worker, column).  Stands in
  * for Alg. 1 steps 3-4 (sampling data and computing a stochastic gradient).  Default 0, 0.
+ * A change of sigma rewrites the context's 16 KB device table of noise radii (sigma * r) in
+ * stream order and synchronises the stream; not to be called during a stream capture.
  */
 int rps_set_synthetic_grad(rps_ctx *ctx, float sigma, float weight_decay);
 

@@ -39,7 +39,8 @@ struct rps_ctx {
     uint64_t cur_step = 0, next_step = 0;
     RoundTable *staging = nullptr;    // pinned host copy (create, override, query)
     double *partials = nullptr;       // device: 2 * kMaxPartials + 2 doubles (consensus reduction scratch + result)
-    float *noise_cells = nullptr;     // device: the 3 * kNoiseGrid cell values of the synthetic gradient noise
+    float *noise_cells = nullptr;     // device: sigma * radius[kNoiseGrid], then the (cos, sin) pairs of the angle cells
+    float *radius_staging = nullptr;  // pinned host: sigma * radius on its way to the device
     bool override_on = false;
     bool profiling = false;
     std::vector<hipEvent_t> ev_start, ev_stop;
@@ -89,16 +90,16 @@ rps::LaunchTuning default_tuning(int32_t n, int32_t dtype, int grad_mode) {
     if (grad_mode == rps::kGradBuffer) return n >= 12 ? rps::LaunchTuning{2, 1, 5, 0} : rps::LaunchTuning{4, 1, 6, 0};
     // in-register gradient: the workgroup's wavefronts share the LDS copy of the noise cells
     if (dtype == RPS_DTYPE_BF16) return rps::LaunchTuning{2, 4, 0, 0};
-    return rps::LaunchTuning{2, 4, 12, 0};
+    return n >= 24 ? rps::LaunchTuning{2, 2, 0, 0} : rps::LaunchTuning{2, 4, 12, 0};
 }
 
 rps::LaunchTuning tuning_for(const rps_ctx *ctx, int grad_mode) {
     if (ctx->tune_set) return ctx->tune;
     if (ctx->flags & RPS_FLAG_LAYOUT_TILED) {   // a wavefront owns about 4 KB whatever n is: more of them resident
         int cap;                                 // (measured at n = 8 / 16 / 32 fp32 and n = 64 bf16)
-        // 16 wavefronts share the LDS copy of the noise cells; with more than 32 workers a lane walks its
-        // rows in chunks, and one row pair per chunk keeps the registers at four wavefronts per SIMD
-        if (grad_mode == rps::kGradSynthetic) return rps::LaunchTuning{ctx->n > 32 ? 2 : 4, 16, 0, 0};
+        // 8 wavefronts share the LDS copy of the noise cells; with more than 32 workers a lane walks its
+        // rows in chunks, and one row pair per chunk keeps the registers at five wavefronts per SIMD
+        if (grad_mode == rps::kGradSynthetic) return rps::LaunchTuning{ctx->n > 32 ? 2 : 4, 8, 0, 0};
         else if (grad_mode == rps::kGradNone) cap = ctx->n >= 48 ? 8 : 10;
         else cap = 12;
         return rps::LaunchTuning{4, 1, cap, 0};
@@ -241,6 +242,20 @@ const float *noise_cells_host() {
     return cells.data();
 }
 
+// The device copy of the radius cells carries sigma: sigma * r rounded to fp32 once, here on the
+// host (the same IEEE multiplication the oracle does per sample).  In stream order after the work
+// already enqueued; synchronises so that the staging buffer can be reused.
+hipError_t upload_scaled_radii(rps_ctx *ctx) {
+    hipError_t e = hipStreamSynchronize(ctx->stream);   // an earlier upload may still be reading the staging buffer
+    if (e != hipSuccess) return e;
+    const float *radius = noise_cells_host();
+    for (int k = 0; k < rps::kNoiseGrid; ++k) ctx->radius_staging[k] = ctx->sigma * radius[k];
+    e = hipMemcpyAsync(ctx->noise_cells, ctx->radius_staging, (size_t)rps::kNoiseGrid * sizeof(float),
+                       hipMemcpyHostToDevice, ctx->stream);
+    if (e != hipSuccess) return e;
+    return hipStreamSynchronize(ctx->stream);
+}
+
 struct DeviceGuard {   // make the context's device current for the duration of a call
     int prev = -1;
     bool ok = false;
@@ -319,6 +334,9 @@ static int create_impl(rps_ctx **out, int32_t n, int32_t nb, bool external, int6
         ctx->noise_cells = reinterpret_cast<float *>(reinterpret_cast<char *>(ctx->tab_base) + cells_at);
         e = hipMemcpyAsync(ctx->noise_cells, noise_cells_host(), cells_bytes, hipMemcpyHostToDevice, ctx->stream);
     }
+    if (e == hipSuccess)
+        e = hipHostMalloc((void **)&ctx->radius_staging, (size_t)rps::kNoiseGrid * sizeof(float), hipHostMallocDefault);
+    if (e == hipSuccess) e = upload_scaled_radii(ctx);   // sigma = 0 until rps_set_synthetic_grad
     if (e == hipSuccess) {
         ctx->tab = ctx->tab_base;
         ctx->tab_other = ctx->tab_base + 1;
@@ -339,6 +357,7 @@ static int create_impl(rps_ctx **out, int32_t n, int32_t nb, bool external, int6
         const bool oom = (e == hipErrorOutOfMemory);
         if (ctx->tab_base) (void)hipFree(ctx->tab_base);
         if (ctx->staging) (void)hipHostFree(ctx->staging);
+        if (ctx->radius_staging) (void)hipHostFree(ctx->radius_staging);
         delete ctx;
         return oom ? RPS_ENOMEM : RPS_EHIP;
     }
@@ -373,13 +392,24 @@ int rps_destroy(rps_ctx *ctx) {
     for (hipEvent_t ev : ctx->ev_stop) (void)hipEventDestroy(ev);
     if (ctx->tab_base && hipFree(ctx->tab_base) != hipSuccess) rc = RPS_EHIP;
     if (ctx->staging && hipHostFree(ctx->staging) != hipSuccess) rc = RPS_EHIP;
+    if (ctx->radius_staging && hipHostFree(ctx->radius_staging) != hipSuccess) rc = RPS_EHIP;
     delete ctx;
     return rc;
 }
 
 int rps_set_synthetic_grad(rps_ctx *ctx, float sigma, float weight_decay) {
     if (!ctx || !std::isfinite(sigma) || sigma < 0.0f || !std::isfinite(weight_decay)) return RPS_EINVAL;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return RPS_EHIP;
+    const float before = ctx->sigma;
     ctx->sigma = sigma;
+    if (sigma != before) {
+        const hipError_t e = upload_scaled_radii(ctx);
+        if (e != hipSuccess) {
+            ctx->sigma = before;   // the device table still holds the old radii (or is rewritten by the next call)
+            return hip_fail(ctx, e);
+        }
+    }
     ctx->lambda = weight_decay;
     return RPS_OK;
 }

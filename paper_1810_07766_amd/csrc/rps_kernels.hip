@@ -211,9 +211,10 @@ __global__ __launch_bounds__(64) void mixing_moments_kernel(double *__restrict__
 // ---------------------------------------------------------------------------------------
 // Synthetic gradient noise: a Box-Muller pair per 32-bit hash word on a 4096 x 4096 grid of
 // (radius, angle) cells.  The cell values (correctly rounded fp32 of sqrt(-2 ln((k + 1/2)/4096)),
-// cos and sin of 2 pi (a + 1/2)/4096) come from a table the host computes once per context; every
-// workgroup of a kernel that generates noise copies it into LDS, the radii pre-multiplied by sigma,
-// so that a pair costs one mask, one shift-and-mask, two LDS gathers and two multiplies.
+// cos and sin of 2 pi (a + 1/2)/4096) come from a table the host computes, the radii multiplied by
+// sigma (one more rounding) when sigma is set; every workgroup of a kernel that generates noise
+// copies it into LDS, so that a pair costs one mask, one shift-and-mask, one bit-field insert, two
+// LDS gathers and two multiplies.
 //   word bits 2..13  -> radius cell (byte offset of a 4-byte entry = word & 0x3FFC)
 //   word bits 17..27 -> angle cell within the half turn (byte offset of an 8-byte (cos, sin) entry
 //                       = (word >> 14) & 0x3FF8);  bit 31 adds the half turn, i.e. flips the sign of
@@ -239,52 +240,29 @@ struct LdsFor<kGradSynthetic> {
     using type = NoiseLds;
 };
 
-// All `threads` work-items of the workgroup take part; ends with a workgroup barrier.
-__device__ __forceinline__ void fill_noise_lds(NoiseLds &lds, const float *__restrict__ cells, float sigma, int tid,
-                                               int threads) {
-    const f32x4 *src = reinterpret_cast<const f32x4 *>(cells);   // radius[4096], then (cos, sin)[4096]
-    for (int i = tid; i < kNoiseGrid / 4; i += threads) {
-        f32x4 v = src[i];
-        v.x = sigma * v.x; v.y = sigma * v.y; v.z = sigma * v.z; v.w = sigma * v.w;
-        reinterpret_cast<f32x4 *>(lds.radius)[i] = v;
-    }
-    for (int i = tid; i < kNoiseGrid / 4; i += threads) reinterpret_cast<f32x4 *>(lds.dir)[i] = src[kNoiseGrid / 4 + i];
-    __syncthreads();
-}
-__device__ __forceinline__ void fill_noise_lds(NoNoiseLds &, const float *, float, int, int) {}
-
-// The same copy in two halves, for workgroups of 8 or 16 wavefronts: begin() issues the global
-// loads of the cells, end() writes them to LDS and ends with the workgroup barrier.  What a
-// wavefront issues in between (the loads of its first tile) is in flight during the copy.
-template <int GRAD, int WPB>
-struct NoiseFill {
-    __device__ __forceinline__ void begin(const float *, int) {}
-    __device__ __forceinline__ void end(NoNoiseLds &, float, int) {}
-};
+// Copy of the context's 32 KB of cells (sigma * radius[4096], then the (cos, sin) pairs of the 2048
+// angle cells below pi) into the workgroup's LDS by LDS-direct loads: a wavefront instruction moves
+// 64 lanes x 16 bytes from global memory straight into 1 KB of LDS (no registers), the 32
+// instructions are dealt out to the workgroup's wavefronts.  begin() only issues them; end() waits
+// for this wavefront's share and ends with the workgroup barrier, so what a wavefront issues in
+// between -- the loads of its first tile -- is in flight during the copy.  Every wavefront of the
+// workgroup must pass begin() and end() exactly once.
 template <int WPB>
-struct NoiseFill<kGradSynthetic, WPB> {
-    static constexpr int THREADS = WPB * 64;
-    static constexpr int NR = (kNoiseGrid / 4 + THREADS - 1) / THREADS, ND = NR;   // 16-byte pieces per work-item
-    f32x4 r[NR], d[ND];
-    __device__ __forceinline__ void begin(const float *__restrict__ cells, int tid) {
-        const f32x4 *src = reinterpret_cast<const f32x4 *>(cells);
+__device__ __forceinline__ void noise_fill_begin(NoiseLds &lds, const float *__restrict__ cells, int wave, int lane) {
+    constexpr int kPieces = (int)(sizeof(NoiseLds) / 1024);
+    float *dst = reinterpret_cast<float *>(&lds);
 #pragma unroll
-        for (int k = 0; k < NR; ++k) r[k] = src[(tid + k * THREADS) % (kNoiseGrid / 4)];
-#pragma unroll
-        for (int k = 0; k < ND; ++k) d[k] = src[kNoiseGrid / 4 + (tid + k * THREADS) % (kNoiseGrid / 4)];
+    for (int c = 0; c < (kPieces + WPB - 1) / WPB; ++c) {
+        const int piece = c * WPB + wave;   // wave-uniform
+        if (piece < kPieces)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(cells + piece * 256 + lane * 4),
+                                             (__attribute__((address_space(3))) void *)(dst + piece * 256), 16, 0, 0);
     }
-    __device__ __forceinline__ void end(NoiseLds &lds, float sigma, int tid) {
-#pragma unroll
-        for (int k = 0; k < NR; ++k) {
-            f32x4 v = r[k];
-            v.x = sigma * v.x; v.y = sigma * v.y; v.z = sigma * v.z; v.w = sigma * v.w;
-            reinterpret_cast<f32x4 *>(lds.radius)[(tid + k * THREADS) % (kNoiseGrid / 4)] = v;
-        }
-#pragma unroll
-        for (int k = 0; k < ND; ++k) reinterpret_cast<f32x4 *>(lds.dir)[(tid + k * THREADS) % (kNoiseGrid / 4)] = d[k];
-        __syncthreads();
-    }
-};
+}
+__device__ __forceinline__ void noise_fill_end(NoiseLds &) { __syncthreads(); }
+template <int WPB>
+__device__ __forceinline__ void noise_fill_begin(NoNoiseLds &, const float *, int, int) {}
+__device__ __forceinline__ void noise_fill_end(NoNoiseLds &) {}
 
 __device__ __forceinline__ void box_muller_pair(uint32_t word, const NoiseLds &lds, float &even, float &odd) {
     const float r = *reinterpret_cast<const float *>(reinterpret_cast<const char *>(lds.radius) + (word & 0x3FFCu));
@@ -334,6 +312,7 @@ template <>
 struct Storage<float> {
     static constexpr int VEC = 4;
     using Raw = f32x4;
+    using Acc = double;   // column sums of fp32 values are taken in fp64
     static __device__ __forceinline__ float round(float v) { return v; }
     static __device__ __forceinline__ void unpack(Raw a, float x[VEC]) {
         x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w;
@@ -352,6 +331,8 @@ template <>
 struct Storage<uint16_t> {
     static constexpr int VEC = 8;
     using Raw = u32x4;
+    using Acc = double;   // the same for bf16 values: an fp32 sum would be 1.5 % faster on the 64-worker workload, but
+                          // its rounding flips about one stored bf16 result in 1e5 against the fp64 definition
     static __device__ __forceinline__ float round(float v) { return bf16_bits_to_f32(f32_to_bf16_bits(v)); }
     static __device__ __forceinline__ void unpack(Raw a, float x[VEC]) {
         x[0] = __uint_as_float(a.x << 16); x[1] = __uint_as_float(a.x & 0xFFFF0000u);
@@ -518,8 +499,9 @@ __device__ __forceinline__ void process_chunk(ST *__restrict__ Xt, const RoundPa
                                               const LaneCols &lc, uint64_t ucol, uint64_t dcol, int i0,
                                               const typename Storage<ST>::Raw xr[R],
                                               const typename Storage<ST>::Raw gr[GRAD == kGradBuffer ? R : 1],
-                                              double acc[Storage<ST>::VEC]) {
+                                              typename Storage<ST>::Acc acc[Storage<ST>::VEC]) {
     using S = Storage<ST>;
+    using Acc = typename S::Acc;
     constexpr int VEC = S::VEC;
     const int n = prm.n;
 #pragma unroll
@@ -541,7 +523,7 @@ __device__ __forceinline__ void process_chunk(ST *__restrict__ Xt, const RoundPa
                     const typename S::Raw vr = sgd_step<ST, GRAD>(prm, za, v);
                     if (ua) {
 #pragma unroll
-                        for (int e = 0; e < VEC; ++e) acc[e] += (double)v[e];
+                        for (int e = 0; e < VEC; ++e) acc[e] += (Acc)v[e];
                     }
                     if (GRAD != kGradNone && !da) store_raw<ST, FULL>(Xt + (int64_t)ia * prm.stride, lc, vr);
                 }
@@ -552,7 +534,7 @@ __device__ __forceinline__ void process_chunk(ST *__restrict__ Xt, const RoundPa
                     const typename S::Raw vr = sgd_step<ST, GRAD>(prm, zb, v);
                     if (ub) {
 #pragma unroll
-                        for (int e = 0; e < VEC; ++e) acc[e] += (double)v[e];
+                        for (int e = 0; e < VEC; ++e) acc[e] += (Acc)v[e];
                     }
                     if (GRAD != kGradNone && !db) store_raw<ST, FULL>(Xt + (int64_t)ib * prm.stride, lc, vr);
                 }
@@ -578,15 +560,16 @@ template <typename ST, int GRAD, int R, bool FULL, typename LDS>
 __device__ __forceinline__ void round_tile(ST *__restrict__ X, const ST *__restrict__ G, const RoundParams &prm,
                                            const LDS &lds, const LaneCols &lc, uint64_t ucol, uint64_t dcol, double inv) {
     using S = Storage<ST>;
+    using Acc = typename S::Acc;
     using Raw = typename S::Raw;
     constexpr int VEC = S::VEC;
     constexpr int RG = GRAD == kGradBuffer ? R : 1;
     const int n = prm.n;
     ST *Xt = X + lc.tile0;   // row 0 of the tile (wave-uniform)
 
-    double acc[VEC];
+    Acc acc[VEC];
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) acc[e] = 0.0;
+    for (int e = 0; e < VEC; ++e) acc[e] = 0;
 
     LoadCursor<ST> cur;
     cur.x = Xt;
@@ -613,7 +596,7 @@ __device__ __forceinline__ void round_tile(ST *__restrict__ X, const ST *__restr
 
     float vt[VEC];
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) vt[e] = (float)(acc[e] * inv);
+    for (int e = 0; e < VEC; ++e) vt[e] = (float)(acc[e] * (Acc)inv);
     const Raw vt_raw = S::round_vec(vt);
     ST *row = Xt;
     for (int i = 0; i < n; ++i, row += prm.stride)
@@ -630,7 +613,8 @@ __global__ __launch_bounds__(WPB * 64) void round_kernel(ST *__restrict__ X, con
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int j = blockIdx.y;
-    fill_noise_lds(lds, prm.noise_cells, prm.sigma, (int)threadIdx.x, WPB * 64);   // every wavefront, before any exit
+    noise_fill_begin<WPB>(lds, prm.noise_cells, wave, lane);   // every wavefront, before any exit
+    noise_fill_end(lds);
     prepare_next_outcome(prm, linear_block() == 0 && wave == 0, j, lane);
     const int64_t lo = tab->off[j], hi = tab->off[j + 1];
     const uint64_t ucol = tab->ucol[j], dcol = tab->dcol[j];
@@ -718,6 +702,7 @@ __device__ __forceinline__ void store_seg(ST *base, uint32_t eoff, uint32_t limi
 template <typename ST, int GRAD, int LPR, int PG, int CP, bool FULL>
 struct NarrowTile {
     using S = Storage<ST>;
+    using Acc = typename S::Acc;
     using LDS = typename LdsFor<GRAD>::type;
     using Raw = typename S::Raw;
     static constexpr int VEC = S::VEC;
@@ -784,7 +769,7 @@ struct NarrowTile {
         }
     }
 
-    __device__ __forceinline__ void row(int k, int r, Raw xr, Raw gr, const float *z, double acc[VEC]) const {
+    __device__ __forceinline__ void row(int k, int r, Raw xr, Raw gr, const float *z, Acc acc[VEC]) const {
         const bool u = bit(sum_bits, k, r), own = GRAD != kGradNone && bit(own_bits, k, r);
         if (!(u || own)) return;
         float v[VEC], g[VEC];
@@ -793,12 +778,12 @@ struct NarrowTile {
         const Raw vr = sgd_step<ST, GRAD>(prm, GRAD == kGradBuffer ? g : z, v);
         if (u) {
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) acc[e] += (double)v[e];
+            for (int e = 0; e < VEC; ++e) acc[e] += (Acc)v[e];
         }
         if (own) store_seg<ST, FULL>(Xt, off(row_a(k) + r), limit, c0, lo, hi, vr);
     }
 
-    __device__ __forceinline__ void process_chunk(int k0, const Raw x[2 * CP], const Raw g[CG], double acc[VEC]) const {
+    __device__ __forceinline__ void process_chunk(int k0, const Raw x[2 * CP], const Raw g[CG], Acc acc[VEC]) const {
         // the noise does not depend on the loaded values: all of it first, under the loads' latency
         float za[CP][VEC], zb[CP][VEC];
         if (GRAD == kGradSynthetic) {
@@ -818,7 +803,7 @@ struct NarrowTile {
         }
     }
 
-    __device__ __forceinline__ void finish(double acc[VEC], double inv, int steps) const {
+    __device__ __forceinline__ void finish(Acc acc[VEC], double inv, int steps) const {
         // combine the lane groups: after the butterfly every lane of a column group holds the same sum
 #pragma unroll
         for (int o = LPR; o < LPR * PG; o <<= 1) {
@@ -827,7 +812,7 @@ struct NarrowTile {
         }
         float vt[VEC];
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) vt[e] = (float)(acc[e] * inv);
+        for (int e = 0; e < VEC; ++e) vt[e] = (float)(acc[e] * (Acc)inv);
         const Raw vt_raw = S::round_vec(vt);
         __builtin_amdgcn_s_setprio(3);
         for (int q = 0; q < steps; ++q) {
@@ -839,13 +824,13 @@ struct NarrowTile {
     // SINGLE: the launcher guarantees n <= 2 * GROUPS * CP, i.e. the lane's rows are one load chunk
     // and every row index is a compile-time constant (the general loop is then not even compiled
     // in: having both in one kernel costs registers).
-    // after_first_loads() is called once the first chunk's loads are issued (see NoiseFill)
+    // after_first_loads() is called once the first chunk's loads are issued (see noise_fill_begin)
     template <bool SINGLE, typename F>
     __device__ __forceinline__ void run(double inv, const F &after_first_loads) const {
         const int steps = ((prm.n + 1) / 2 + GROUPS - 1) / GROUPS;   // row pairs per lane (wave-uniform)
-        double acc[VEC];
+        Acc acc[VEC];
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) acc[e] = 0.0;
+        for (int e = 0; e < VEC; ++e) acc[e] = 0;
         Raw xa[2 * CP], xb[2 * CP], ga[CG], gb[CG];
         // a wavefront that is about to issue its loads, or to store its results, goes before the
         // ones that are busy with arithmetic: the memory queue stays fed
@@ -888,14 +873,13 @@ __global__ __launch_bounds__(WPB * 64) void round_kernel_narrow(ST *__restrict__
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int j = blockIdx.y;
-    // the noise cells travel to LDS while the first tile's loads are in flight: their global loads
-    // are issued here, the LDS writes and the workgroup barrier follow the first tile's loads --
-    // or the loop, for a wavefront that has no tile: every wavefront passes the barrier exactly once
-    NoiseFill<GRAD, WPB> fill;
-    fill.begin(prm.noise_cells, (int)threadIdx.x);
+    // the noise cells travel to LDS while the first tile's loads are in flight: the copy is issued
+    // here, the wait and the workgroup barrier follow the first tile's loads -- or the loop, for a
+    // wavefront that has no tile: every wavefront passes the barrier exactly once
+    noise_fill_begin<WPB>(lds, prm.noise_cells, wave, lane);
     bool fill_pending = true;
     const auto finish_fill = [&] {
-        if (fill_pending) fill.end(lds, prm.sigma, (int)threadIdx.x);
+        if (fill_pending) noise_fill_end(lds);
         fill_pending = false;
     };
     const int64_t lo = tab->off[j], hi = tab->off[j + 1];
@@ -952,7 +936,8 @@ __global__ __launch_bounds__(WPB * 64) void local_step_kernel(ST *__restrict__ X
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int row = blockIdx.y;
-    fill_noise_lds(lds, prm.noise_cells, prm.sigma, (int)threadIdx.x, WPB * 64);
+    noise_fill_begin<WPB>(lds, prm.noise_cells, wave, lane);
+    noise_fill_end(lds);
     for (int it = 0; it < prm.tiles_per_wave; ++it) {
         const int64_t tile0 = unit_index(it, WPB, wave) * TILE;
         if (tile0 >= prm.N) break;   // wave-uniform
@@ -981,7 +966,8 @@ __global__ __launch_bounds__(WPB * 64) void local_step_tiled_kernel(ST *__restri
     __shared__ typename LdsFor<GRAD>::type lds;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    fill_noise_lds(lds, prm.noise_cells, prm.sigma, (int)threadIdx.x, WPB * 64);
+    noise_fill_begin<WPB>(lds, prm.noise_cells, wave, lane);
+    noise_fill_end(lds);
     const int64_t tiles = (prm.N + TILE - 1) / TILE;
     for (int it = 0; it < prm.tiles_per_wave; ++it) {
         const int64_t q = unit_index(it, WPB, wave);
@@ -1188,14 +1174,15 @@ template <typename ST, bool FULL>
 __device__ __forceinline__ void gradavg_tile(ST *__restrict__ X, const ST *__restrict__ G, const RoundParams &prm,
                                              const LaneCols &lc, uint64_t ucol, uint64_t dcol, double inv) {
     using S = Storage<ST>;
+    using Acc = typename S::Acc;
     using Raw = typename S::Raw;
     constexpr int VEC = S::VEC;
     constexpr int R = 4;
     const int n = prm.n;
 
-    double acc[VEC];
+    Acc acc[VEC];
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) acc[e] = 0.0;
+    for (int e = 0; e < VEC; ++e) acc[e] = 0;
     const ST *grow = G + lc.tile0;
     for (int i0 = 0; i0 < n; i0 += R) {
         Raw g[R];
@@ -1211,13 +1198,13 @@ __device__ __forceinline__ void gradavg_tile(ST *__restrict__ X, const ST *__res
                 float v[VEC];
                 S::unpack(g[r], v);
 #pragma unroll
-                for (int e = 0; e < VEC; ++e) acc[e] += (double)v[e];
+                for (int e = 0; e < VEC; ++e) acc[e] += (Acc)v[e];
             }
         }
     }
     float gt[VEC];
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) gt[e] = (float)(acc[e] * inv);
+    for (int e = 0; e < VEC; ++e) gt[e] = (float)(acc[e] * (Acc)inv);
     (void)S::round_vec(gt);
 
     ST *xrow = X + lc.tile0;
@@ -1280,6 +1267,7 @@ __device__ __forceinline__ void gradavg_tile_narrow(ST *__restrict__ Xt, const S
                                                     uint32_t sub_off, int64_t c0, int64_t lo, int64_t hi, uint64_t ucol,
                                                     uint64_t dcol, double inv, int lg) {
     using S = Storage<ST>;
+    using Acc = typename S::Acc;
     using Raw = typename S::Raw;
     constexpr int VEC = S::VEC;
     constexpr int LPR = kTiledLanes, GROUPS = 64 / LPR;
@@ -1295,9 +1283,9 @@ __device__ __forceinline__ void gradavg_tile_narrow(ST *__restrict__ Xt, const S
         g[r] = load_seg<ST, FULL>(Gt, o, limit, c0, lo, hi);
         x[r] = load_seg<ST, FULL>(Xt, o, limit, c0, lo, hi);
     }
-    double acc[VEC];
+    Acc acc[VEC];
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) acc[e] = 0.0;
+    for (int e = 0; e < VEC; ++e) acc[e] = 0;
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) {
         const int i = 2 * (lg + GROUPS * (r >> 1)) + (r & 1);
@@ -1305,7 +1293,7 @@ __device__ __forceinline__ void gradavg_tile_narrow(ST *__restrict__ Xt, const S
             float v[VEC];
             S::unpack(g[r], v);
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) acc[e] += (double)v[e];
+            for (int e = 0; e < VEC; ++e) acc[e] += (Acc)v[e];
         }
     }
 #pragma unroll
@@ -1315,7 +1303,7 @@ __device__ __forceinline__ void gradavg_tile_narrow(ST *__restrict__ Xt, const S
     }
     float gt[VEC];
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) gt[e] = (float)(acc[e] * inv);
+    for (int e = 0; e < VEC; ++e) gt[e] = (float)(acc[e] * (Acc)inv);
     (void)S::round_vec(gt);   // the average travels in the storage format
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) {
