@@ -132,6 +132,22 @@ int rps_destroy(rps_ctx *ctx);
  */
 int rps_set_synthetic_grad(rps_ctx *ctx, float sigma, float weight_decay);
 
+/*
+ * Row-major layout only: the rows of X and G (one worker's model each, Sec. 4.1) are `pitch` elements
+ * apart instead of N (N <= pitch <= 2^35), i.e. element (worker i, column c) lives at i * pitch + c and
+ * the pitch - N elements after every row are padding that is never read or written.  Applies to every
+ * following call.  Why one would: a wavefront reads the same columns of all n rows at once, and when
+ * the row size is a multiple of 32 KB those n addresses fall on the same memory channel (measured at
+ * n = 8, N = 2^22 fp32 with a gradient buffer: 0.60-0.65 of the HBM peak at pitch = N, 0.72 at
+ * rps_recommended_row_pitch).  A pitch that is a multiple of 16 bytes keeps the 128-bit path.
+ * RPS_EINVAL for a tiled context or a pitch out of range.
+ */
+int rps_set_row_pitch(rps_ctx *ctx, int64_t pitch);
+
+/* Smallest pitch >= N (in elements) whose size in bytes is 4 KB past a multiple of 64 KB; -1 for
+   invalid arguments. */
+int64_t rps_recommended_row_pitch(int64_t N, int32_t dtype);
+
 /* Change the step size (the paper notes a decayed step size reaches a critical point, Sec. 5). */
 int rps_set_gamma(rps_ctx *ctx, float gamma);
 
@@ -235,7 +251,7 @@ int rps_estimate_mixing(rps_ctx *ctx, uint64_t first_step, int64_t rounds, doubl
  * Copy the state between the two layouts (any context of matching n, N and dtype; its own layout
  * flag does not matter):  to_tiled != 0: src is row-major [n, N], dst receives the tile-major
  * arrangement (rps_storage_elems elements; padding columns are written as zeros);  to_tiled == 0:
- * the reverse.  dst and src are device arrays that must not overlap.  One streaming pass, enqueued
+ * the reverse.  The row-major side has the context's row pitch (rps_set_row_pitch; N by default).  dst and src are device arrays that must not overlap.  One streaming pass, enqueued
  * on the context's stream.
  */
 int rps_convert_layout(rps_ctx *ctx, void *dst, const void *src, int32_t to_tiled);

@@ -17,6 +17,7 @@ struct rps_ctx {
     int32_t nb = 0;                   // blocks: n, or the number of external servers
     bool external = false;
     int64_t N = 0;
+    int64_t pitch = 0;                // row-major: elements between consecutive workers' rows (>= N)
     double p = 0.0;
     uint64_t threshold = 0;     // a message is lost iff its hash word < threshold = floor(p 2^32)
     float gamma = 0.0f, sigma = 0.0f, lambda = 0.0f;
@@ -115,8 +116,8 @@ RoundParams make_params(const rps_ctx *ctx, const void *X, const void *G, uint64
     const int64_t vec = ctx->dtype == RPS_DTYPE_F32 ? 4 : 8;   // elements per 16 bytes
     const bool aligned = ((uintptr_t)X % 16 == 0) && (G == nullptr || (uintptr_t)G % 16 == 0);
     prm.tiled = (ctx->flags & RPS_FLAG_LAYOUT_TILED) ? 1 : 0;
-    prm.stride = prm.tiled ? (RPS_TILE_BYTES / 16) * vec : ctx->N;   // tiled: every tile row is one short segment, whatever N is
-    prm.vec_ok = (aligned && (prm.tiled || ctx->N % vec == 0)) ? 1 : 0;
+    prm.stride = prm.tiled ? (RPS_TILE_BYTES / 16) * vec : ctx->pitch;   // tiled: every tile row is one short segment, whatever N is
+    prm.vec_ok = (aligned && (prm.tiled || ctx->pitch % vec == 0)) ? 1 : 0;  // every row starts on a 16-byte boundary
     prm.gamma = ctx->gamma;
     prm.sigma = ctx->sigma;
     prm.lambda = ctx->lambda;
@@ -313,6 +314,7 @@ static int create_impl(rps_ctx **out, int32_t n, int32_t nb, bool external, int6
     ctx->nb = nb;
     ctx->external = external;
     ctx->N = N;
+    ctx->pitch = N;
     ctx->p = p;
     ctx->threshold = (uint64_t)std::floor(p * 4294967296.0);
     ctx->gamma = gamma;
@@ -412,6 +414,23 @@ int rps_set_synthetic_grad(rps_ctx *ctx, float sigma, float weight_decay) {
     }
     ctx->lambda = weight_decay;
     return RPS_OK;
+}
+
+int rps_set_row_pitch(rps_ctx *ctx, int64_t pitch) {
+    if (!ctx || (ctx->flags & RPS_FLAG_LAYOUT_TILED)) return RPS_EINVAL;
+    if (pitch < ctx->N || pitch > (1ll << 35)) return RPS_EINVAL;
+    ctx->pitch = pitch;
+    return RPS_OK;
+}
+
+int64_t rps_recommended_row_pitch(int64_t N, int32_t dtype) {
+    if (N < 1 || N > (1ll << 34) || (dtype != RPS_DTYPE_F32 && dtype != RPS_DTYPE_BF16)) return -1;
+    const int64_t elem = dtype == RPS_DTYPE_F32 ? 4 : 2;
+    // smallest pitch >= N whose byte size is 4 KB past a multiple of 64 KB
+    const int64_t bytes = N * elem;
+    int64_t base = (bytes / 65536) * 65536 + 4096;
+    if (base < bytes) base += 65536;
+    return base / elem;
 }
 
 int rps_set_gamma(rps_ctx *ctx, float gamma) {
@@ -603,8 +622,9 @@ int rps_convert_layout(rps_ctx *ctx, void *dst, const void *src, int32_t to_tile
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return RPS_EHIP;
     const int64_t vec = ctx->dtype == RPS_DTYPE_F32 ? 4 : 8;
-    const bool aligned = (uintptr_t)dst % 16 == 0 && (uintptr_t)src % 16 == 0 && ctx->N % vec == 0;
-    RPS_HIP(ctx, rps::launch_convert_layout(ctx->dtype, dst, src, ctx->N, ctx->n, to_tiled != 0, aligned, ctx->stream));
+    const bool aligned = (uintptr_t)dst % 16 == 0 && (uintptr_t)src % 16 == 0 && ctx->pitch % vec == 0;
+    RPS_HIP(ctx, rps::launch_convert_layout(ctx->dtype, dst, src, ctx->N, ctx->pitch, ctx->n, to_tiled != 0, aligned,
+                                            ctx->stream));
     return RPS_OK;
 }
 

@@ -81,10 +81,11 @@ hipError_t launch_local_step(int dtype, int grad_mode, void *X, const void *G,
 hipError_t launch_gradavg(int dtype, void *X, const void *G, const RoundTable *tab, const RoundParams &prm,
                           int64_t max_block_cols, int max_waves_per_cu, hipStream_t stream);
 
-// Copy between the row-major [n, N] and the tile-major arrangement of the same state (aligned: both
-// bases 16-byte aligned and N a multiple of the 16-byte group, so whole groups move at once).
-hipError_t launch_convert_layout(int dtype, void *dst, const void *src, int64_t N, int n, bool to_tiled, bool aligned,
-                                 hipStream_t stream);
+// Copy between the row-major [n, N] (rows `pitch` elements apart) and the tile-major arrangement of the
+// same state (aligned: both bases 16-byte aligned and the pitch a multiple of the 16-byte group, so whole
+// groups move at once).
+hipError_t launch_convert_layout(int dtype, void *dst, const void *src, int64_t N, int64_t pitch, int n, bool to_tiled,
+                                 bool aligned, hipStream_t stream);
 
 // Consensus statistics: partials = device scratch of 2*max_partials doubles, out = 2 device doubles.
 constexpr int kMaxPartials = 2048;

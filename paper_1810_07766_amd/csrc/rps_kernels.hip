@@ -1609,7 +1609,7 @@ hipError_t launch_gradavg(int dtype, void *X, const void *G, const RoundTable *t
 // tile are written as zeros.  Byte-wise copy: ELEM is the element size.
 template <int ELEM, bool TO_TILED>
 __global__ __launch_bounds__(256) void convert_layout_kernel(void *__restrict__ dst, const void *__restrict__ src, int64_t N,
-                                                             int n, int aligned) {
+                                                             int64_t pitch, int n, int aligned) {
     constexpr int LPR = kTiledLanes, VEC = 16 / ELEM, TILE = LPR * VEC;
     const int64_t q = linear_block() * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
@@ -1623,7 +1623,7 @@ __global__ __launch_bounds__(256) void convert_layout_kernel(void *__restrict__ 
     const int64_t c0 = tile * TILE + (lane % LPR) * VEC;
     if (tile * TILE >= N) return;   // past the last tile
     const int64_t t_off = ((seg0 + lane / LPR) * TILE + (lane % LPR) * VEC) * ELEM;   // bytes, tile-major array
-    const int64_t r_off = ((int64_t)i * N + c0) * ELEM;                               // bytes, row-major array
+    const int64_t r_off = ((int64_t)i * pitch + c0) * ELEM;                           // bytes, row-major array
     char *d = (char *)dst;
     const char *sp = (const char *)src;
     if (aligned && c0 + VEC <= N) {
@@ -1643,8 +1643,8 @@ __global__ __launch_bounds__(256) void convert_layout_kernel(void *__restrict__ 
     }
 }
 
-hipError_t launch_convert_layout(int dtype, void *dst, const void *src, int64_t N, int n, bool to_tiled, bool aligned,
-                                 hipStream_t stream) {
+hipError_t launch_convert_layout(int dtype, void *dst, const void *src, int64_t N, int64_t pitch, int n, bool to_tiled,
+                                 bool aligned, hipStream_t stream) {
     const int elem = dtype == 0 ? 4 : 2;
     const int64_t T = kTiledLanes * (16 / elem);
     const int64_t tiles = (N + T - 1) / T;
@@ -1652,14 +1652,14 @@ hipError_t launch_convert_layout(int dtype, void *dst, const void *src, int64_t 
     const dim3 grid = folded_grid((kb + 3) / 4, 1);
     if (dtype == 0) {
         if (to_tiled)
-            hipLaunchKernelGGL((convert_layout_kernel<4, true>), grid, dim3(256), 0, stream, dst, src, N, n, (int)aligned);
+            hipLaunchKernelGGL((convert_layout_kernel<4, true>), grid, dim3(256), 0, stream, dst, src, N, pitch, n, (int)aligned);
         else
-            hipLaunchKernelGGL((convert_layout_kernel<4, false>), grid, dim3(256), 0, stream, dst, src, N, n, (int)aligned);
+            hipLaunchKernelGGL((convert_layout_kernel<4, false>), grid, dim3(256), 0, stream, dst, src, N, pitch, n, (int)aligned);
     } else {
         if (to_tiled)
-            hipLaunchKernelGGL((convert_layout_kernel<2, true>), grid, dim3(256), 0, stream, dst, src, N, n, (int)aligned);
+            hipLaunchKernelGGL((convert_layout_kernel<2, true>), grid, dim3(256), 0, stream, dst, src, N, pitch, n, (int)aligned);
         else
-            hipLaunchKernelGGL((convert_layout_kernel<2, false>), grid, dim3(256), 0, stream, dst, src, N, n, (int)aligned);
+            hipLaunchKernelGGL((convert_layout_kernel<2, false>), grid, dim3(256), 0, stream, dst, src, N, pitch, n, (int)aligned);
     }
     return hipGetLastError();
 }

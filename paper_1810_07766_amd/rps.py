@@ -34,6 +34,9 @@ _lib.rps_storage_elems.restype = ctypes.c_int64
 _lib.rps_destroy.argtypes = [_ctx_p]
 _lib.rps_set_synthetic_grad.argtypes = [_ctx_p, ctypes.c_float, ctypes.c_float]
 _lib.rps_set_gamma.argtypes = [_ctx_p, ctypes.c_float]
+_lib.rps_set_row_pitch.argtypes = [_ctx_p, ctypes.c_int64]
+_lib.rps_recommended_row_pitch.argtypes = [ctypes.c_int64, ctypes.c_int32]
+_lib.rps_recommended_row_pitch.restype = ctypes.c_int64
 _lib.rps_local_step.argtypes = [_ctx_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64]
 _lib.rps_lossy_average.argtypes = [_ctx_p, ctypes.c_void_p, ctypes.c_uint64]
 _lib.rps_round.argtypes = [_ctx_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64]
@@ -53,12 +56,13 @@ _lib.rps_get_kernel_time.argtypes = [_ctx_p, ctypes.POINTER(ctypes.c_double), ct
 _lib.rps_last_hip_error.argtypes = [_ctx_p]
 _lib.rps_strerror.argtypes = [ctypes.c_int]
 _lib.rps_strerror.restype = ctypes.c_char_p
-for _name in ("rps_create", "rps_create_external", "rps_destroy", "rps_set_synthetic_grad", "rps_set_gamma", "rps_local_step",
+for _name in ("rps_create", "rps_create_external", "rps_destroy", "rps_set_synthetic_grad", "rps_set_gamma", "rps_set_row_pitch", "rps_local_step",
               "rps_lossy_average", "rps_round", "rps_round_gradient_averaging", "rps_get_masks", "rps_set_mask_override",
               "rps_consensus", "rps_consensus_static", "rps_estimate_mixing", "rps_convert_layout", "rps_set_launch_tuning", "rps_noise_cells", "rps_set_profiling", "rps_get_kernel_time", "rps_last_hip_error"):
     getattr(_lib, _name).restype = ctypes.c_int
 
-EXPORTS = ("rps_create", "rps_create_external", "rps_storage_elems", "rps_destroy", "rps_set_synthetic_grad", "rps_set_gamma", "rps_local_step",
+EXPORTS = ("rps_create", "rps_create_external", "rps_storage_elems", "rps_destroy", "rps_set_synthetic_grad", "rps_set_gamma",
+           "rps_set_row_pitch", "rps_recommended_row_pitch", "rps_local_step",
            "rps_lossy_average", "rps_round", "rps_round_gradient_averaging", "rps_get_masks", "rps_set_mask_override",
            "rps_consensus", "rps_consensus_static", "rps_estimate_mixing", "rps_convert_layout", "rps_set_launch_tuning", "rps_noise_cells", "rps_set_profiling", "rps_get_kernel_time",
            "rps_last_hip_error",
@@ -87,14 +91,15 @@ def _ptr(t, ctx):
     if t is None:
         return None
     want = torch.float32 if ctx.dtype == RPS_DTYPE_F32 else torch.bfloat16
-    if not (t.is_cuda and t.is_contiguous() and t.dtype == want):
+    if not (t.is_cuda and t.dtype == want):
         raise RpsError(RPS_EINVAL)
     if ctx.flags & RPS_FLAG_LAYOUT_TILED:      # [tiles, n, tile width], see rps.h
         T = RPS_TILE_BYTES // t.element_size()
-        if tuple(t.shape) != ((ctx.N + T - 1) // T, ctx.n, T):
+        if not t.is_contiguous() or tuple(t.shape) != ((ctx.N + T - 1) // T, ctx.n, T):
             raise RpsError(RPS_EINVAL)
-    elif tuple(t.shape) != (ctx.n, ctx.N):
-        raise RpsError(RPS_EINVAL)
+    else:                                      # [n, N] with the context's row pitch
+        if tuple(t.shape) != (ctx.n, ctx.N) or (ctx.N > 1 and t.stride(1) != 1) or (ctx.n > 1 and t.stride(0) != ctx.pitch):
+            raise RpsError(RPS_EINVAL)
     return ctypes.c_void_p(t.data_ptr())
 
 
@@ -121,7 +126,7 @@ class RpsContext:
             _check(_lib.rps_create(ctypes.byref(handle), n, N, off, p, gamma, seed, dtype, flags,
                                    ctypes.c_void_p(stream)))
         self._h = handle
-        self.n, self.N, self.dtype, self.blocks, self.flags = n, N, dtype, nb, flags
+        self.n, self.N, self.dtype, self.blocks, self.flags, self.pitch = n, N, dtype, nb, flags, N
 
     def destroy(self):
         if getattr(self, "_h", None) and _lib is not None:   # (_lib is None at interpreter shutdown)
@@ -135,6 +140,19 @@ class RpsContext:
 
     def set_gamma(self, gamma):
         _check(_lib.rps_set_gamma(self._h, gamma), self._h)
+
+    def set_row_pitch(self, pitch):
+        """Row-major: X and G are views [n, N] of arrays whose rows are `pitch` elements apart."""
+        _check(_lib.rps_set_row_pitch(self._h, pitch), self._h)
+        self.pitch = pitch
+
+    def empty_state(self, fill=None):
+        """New row-major state tensor [n, N] with the context's row pitch (a view of [n, pitch])."""
+        import torch
+        dt = torch.float32 if self.dtype == RPS_DTYPE_F32 else torch.bfloat16
+        buf = torch.empty(self.n, self.pitch, device="cuda", dtype=dt) if fill is None else \
+            torch.full((self.n, self.pitch), fill, device="cuda", dtype=dt)
+        return buf[:, : self.N]
 
     def local_step(self, X, G, step):
         _check(_lib.rps_local_step(self._h, _ptr(X, self), _ptr(G, self), step), self._h)
@@ -187,7 +205,8 @@ class RpsContext:
         """Row-major [n, N] tensor -> new tile-major tensor [tiles, n, T] (device copy by the library)."""
         import torch
         want = torch.float32 if self.dtype == RPS_DTYPE_F32 else torch.bfloat16
-        if not (X.is_cuda and X.is_contiguous() and X.dtype == want and tuple(X.shape) == (self.n, self.N)):
+        if not (X.is_cuda and X.dtype == want and tuple(X.shape) == (self.n, self.N)
+                and (self.N == 1 or X.stride(1) == 1) and (self.n == 1 or X.stride(0) == self.pitch)):
             raise RpsError(RPS_EINVAL)
         T = RPS_TILE_BYTES // X.element_size()
         out = torch.empty((self.N + T - 1) // T, self.n, T, device=X.device, dtype=X.dtype)
@@ -202,7 +221,7 @@ class RpsContext:
         if not (Xt.is_cuda and Xt.is_contiguous() and Xt.dtype == want
                 and tuple(Xt.shape) == ((self.N + T - 1) // T, self.n, T)):
             raise RpsError(RPS_EINVAL)
-        out = torch.empty(self.n, self.N, device=Xt.device, dtype=Xt.dtype)
+        out = torch.empty(self.n, self.pitch, device=Xt.device, dtype=Xt.dtype)[:, : self.N]
         _check(_lib.rps_convert_layout(self._h, out.data_ptr(), Xt.data_ptr(), 0), self._h)
         return out
 
@@ -243,6 +262,14 @@ def rps_set_synthetic_grad(ctx, sigma, weight_decay=0.0):
 
 def rps_set_gamma(ctx, gamma):
     ctx.set_gamma(gamma)
+
+
+def rps_set_row_pitch(ctx, pitch):
+    ctx.set_row_pitch(pitch)
+
+
+def rps_recommended_row_pitch(N, dtype=RPS_DTYPE_F32):
+    return _lib.rps_recommended_row_pitch(N, dtype)
 
 
 def rps_local_step(ctx, X, G, step):

@@ -173,9 +173,16 @@ def test_config_mlp_n8_loss_tracks_oracle(rps, tiled):
     cfg = workloads.CONFIGS["mlp_n8"]
     off = workloads.config_offsets(cfg)
     teacher, X0 = workloads.mlp_problem(cfg, seed=cfg.seed)
-    Xg = X0.cuda()
     Xo = X0.numpy().copy()
     ctx = rps.RpsContext(cfg.n, cfg.N, cfg.p, cfg.gamma, cfg.seed, flags=rps.RPS_FLAG_LAYOUT_TILED if tiled else 0)
+    if tiled:
+        Xg = X0.cuda()
+    else:
+        # row-major: every worker's parameters stay one contiguous row; N * 4 bytes = 2^24 would put the
+        # same columns of all rows on one memory channel, so the rows are held a little further apart
+        ctx.set_row_pitch(rps.rps_recommended_row_pitch(cfg.N))
+        Xg = ctx.empty_state(); Xg.copy_(X0.cuda())
+        Gp = ctx.empty_state()
     threads = min(16, oracle.max_threads())
     first = last = None
 
@@ -183,7 +190,8 @@ def test_config_mlp_n8_loss_tracks_oracle(rps, tiled):
         """The library's round on [n, N] tensors; in the tile-major run through re-arranged copies
         (the model's forward/backward wants each worker's parameters contiguous)."""
         if not tiled:
-            ctx.round(X, G, t)
+            Gp.copy_(G)                                  # autograd hands back a dense [n, N] gradient
+            ctx.round(X, Gp, t)
             return
         Xt = workloads.to_tiled(X)
         ctx.round(Xt, workloads.to_tiled(G), t)
@@ -208,6 +216,8 @@ def test_config_mlp_n8_loss_tracks_oracle(rps, tiled):
     assert np.abs(got.mean(axis=0) - ref.mean(axis=0)).max() <= 1e-3 * np.sqrt(np.mean(ref ** 2))
     # the round itself, from the oracle's final state and gradient, still matches element-wise
     Xs = torch.from_numpy(Xo).cuda()
+    if not tiled:
+        Xs = ctx.empty_state().copy_(Xs)
     gpu_round(Xs, Go.cuda(), cfg.rounds)
     oracle.round_(Xo, Go.numpy(), off, p=cfg.p, gamma=cfg.gamma, seed=cfg.seed, step=cfg.rounds, threads=threads)
     torch.cuda.synchronize()

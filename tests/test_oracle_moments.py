@@ -324,3 +324,31 @@ def test_monte_carlo_estimator_converges_to_the_table(n, p, identity):
     est = batches.mean(axis=0); se = batches.std(axis=0, ddof=1) / np.sqrt(len(batches))
     assert abs(est[0] - a1_ref) < 5 * se[0] and se[0] < 0.05 * a1_ref
     assert abs(est[1] - a2_ref) < 5 * se[1] and se[1] < 0.05 * a2_ref
+
+
+def test_alpha_grid_file():
+    """tests/golden/alpha_grid.txt (the (n, p) grid of the paper's Fig. 2 / Fig. 3 at the benchmark
+    worker counts, written by tests/golden/make_alpha_grid.py): its exact columns against this file's
+    own typing of the Lemma 7 / Lemma 8 sums (pinned above to full enumeration for small n), its
+    oracle Monte-Carlo columns within 5 standard errors of them, and the figures' trends."""
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "alpha_grid.txt")
+    rows = [line.split() for line in open(path) if not line.startswith("#")]
+    assert len(rows) == 20
+    table = {}
+    for v in rows:
+        n, p = int(v[0]), float(v[1])
+        a1, a2, beta, m1, s1, m2, s2 = (float(x) for x in v[2:9])
+        assert abs(a1 - alpha1_exact(n, p)) < 1e-10 and abs(a2 - alpha2_exact(n, p)) < 1e-10
+        assert abs(beta - (a1 - a2)) < 1e-12
+        assert abs(m1 - a1) < 5 * s1 and abs(m2 - a2) < 5 * s2, (n, p)
+        assert 0 < a2 < a1 < 1
+        table[(n, p)] = (a1, a2, beta)
+    for p in (0.01, 0.05, 0.1, 0.2):
+        a2s = [table[(n, p)][1] for n in (4, 8, 16, 32, 64)]
+        assert all(x > y for x, y in zip(a2s, a2s[1:]))
+    for n in (4, 8, 16, 32, 64):
+        betas = [table[(n, p)][2] for p in (0.01, 0.05, 0.1, 0.2)]
+        assert all(x < y for x, y in zip(betas, betas[1:]))
+    # the survey's reference values
+    assert abs(table[(32, 0.05)][0] - 0.050053) < 1e-6 and abs(table[(64, 0.1)][1] - 0.002818) < 1e-6
