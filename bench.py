@@ -8,10 +8,17 @@ write-back, for all n workers and all N parameters, in place in HBM.
 The state is held in the library's tile-major layout by default (row-major with --layout
 row-major; the other layout is measured as well and reported under "other_layout").
 
+Order of a measurement: an untimed settling phase of its own (rounds are launched until ten
+consecutive kernel durations agree within 1 %: the first launches after start-up run at ramping
+clocks), then the --warmup rounds, then the timed region of exactly --steps rounds (wall clock
+between two device synchronisations: `value`, `ms_per_step`), then the same number of rounds with
+every kernel bracketed by HIP events on the library's own stream (`roofline`).
+
 Prints ONE JSON line: worker-params averaged per second (n*N per round), the HBM roofline of
 the round kernel (algorithmic bytes = 2*sizeof(dtype) per worker-param, i.e. one read and one
-write of the state, divided by the kernel's mean duration measured with HIP events on the
-library's own stream), and the CPU oracle timed on the host cores on a bounded sample.
+write of the state -- 3 with a gradient buffer -- divided by the kernel's mean duration), the same
+fraction from the timed region, a measured device-copy ceiling on arrays of the state's size, and
+the CPU oracle timed on the host cores on a bounded sample.
 """
 import argparse
 import json
@@ -26,10 +33,13 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0     # MI355X published HBM3E bandwidth
 
 # HBM bytes per launch of the round kernel from rocprofv3 counters (FETCH_SIZE and WRITE_SIZE,
-# each scaled by what the same counter reads for a plain 1 GiB device copy; the commands and
-# the raw figures are in profiles/round_kernel_resnet50_n32_hbm_traffic.md).  Counters cannot
-# be read from inside this process, so the measured value is recorded here per workload.
-MEASURED_TRAFFIC_BYTES = {("resnet50_n32", "tiled"): 6.5536e9, ("resnet50_n32", "row-major"): 6.5538e9}
+# each scaled by what the same counter reads for a plain 1 GiB device copy).  Counters cannot be
+# read from inside this process, so the measured value is recorded here per workload and layout,
+# with the profile it comes from; workloads without a counter run report null.
+MEASURED_TRAFFIC = {
+    ("resnet50_n32", "tiled"): (6.5536e9, "profiles/round_kernel_resnet50_n32_hbm_traffic.md"),
+    ("resnet50_n32", "row-major"): (6.5538e9, "profiles/round_kernel_resnet50_n32_hbm_traffic.md"),
+}
 
 
 def cpu_baseline(cfg, off, budget_cols):
@@ -67,19 +77,54 @@ def cpu_baseline(cfg, off, budget_cols):
                       f"{dt:.1f} s on {threads} threads (+ {reps1} rounds, {dt1:.1f} s, on one)"}
 
 
-def other_paths(ctx, cfg, X, G, step, torch, launches=30):
+def settle(ctx, launch, step, most=300):
+    """Untimed: launch until ten consecutive kernel durations lie within 1 % of each other (3 % for
+    kernels shorter than 0.3 ms, whose launch-to-launch jitter is larger; at most `most` launches).
+    Returns (next step, launches used, whether they settled)."""
+    used = 0
+    window = []
+    while used < most:
+        ctx.set_profiling(True)
+        for _ in range(10):
+            launch(step); step += 1
+        window = list(ctx.get_kernel_times())
+        ctx.set_profiling(False)
+        used += 10
+        band = 1.01 if min(window) >= 0.3 else 1.03
+        if used >= 20 and max(window) <= band * min(window):
+            return step, used, True
+    return step, used, False
+
+
+def other_paths(ctx, cfg, X, G, step, torch, rps, tiled, launches=30):
     """Kernel time (HIP events on the launch stream) of the other entry points on the same state:
     each against the bytes it has to move -- per worker-param, in units of the element size:
     local step 2 (3 with a gradient buffer), averaging alone 2 - p(1 - 1/n) (rows whose reply is
-    lost are not written), fused round on a gradient buffer 3."""
+    lost are not written), fused round on a gradient buffer 3, gradient averaging 3, consensus 1
+    (one read; its time includes the small final reduction), layout conversion 2."""
     elem = 2 if cfg.dtype == "bf16" else 4
     wp = cfg.n * cfg.N
-    Gb = G if G is not None else torch.zeros_like(X).normal_(0.0, 1e-3)
+    if G is not None:
+        Gb = G
+    else:
+        Gb = torch.empty_like(X) if tiled else ctx.empty_state()
+        Gb.normal_(0.0, 1e-3)
     lost = cfg.p * (1.0 - 1.0 / cfg.n)
+    scratch = {}
+
+    def convert(t):
+        if tiled:
+            scratch["o"] = ctx.from_tiled(X)
+        else:
+            scratch["o"] = ctx.to_tiled(X)
+
     cases = (("local_step, in-register gradient", lambda t: ctx.local_step(X, None, t), 2.0),
              ("local_step, gradient buffer", lambda t: ctx.local_step(X, Gb, t), 3.0),
              ("lossy_average alone", lambda t: ctx.lossy_average(X, t), 2.0 - lost),
-             ("round, gradient buffer", lambda t: ctx.round(X, Gb, t), 3.0))
+             ("round, gradient buffer", lambda t: ctx.round(X, Gb, t), 3.0),
+             ("round_gradient_averaging", lambda t: ctx.round_gradient_averaging(X, Gb, t), 3.0),
+             ("consensus", lambda t: ctx.consensus(X), 1.0),
+             ("convert_layout (to the other layout)", convert, 2.0))
     res = {}
     for name, fn, units in cases:
         for t in range(5):
@@ -87,62 +132,106 @@ def other_paths(ctx, cfg, X, G, step, torch, launches=30):
         ctx.set_profiling(True)
         for t in range(launches):
             fn(step + t)
-        ms, cnt = ctx.get_kernel_time()
+        ms = ctx.get_kernel_times()
         ctx.set_profiling(False)
-        ms /= cnt
-        gbs = units * elem * wp / (ms * 1e-3) / 1e9
-        res[name] = {"kernel_ms": ms, "bytes_per_worker_param": units * elem, "achieved": gbs, "unit": "GB/s",
-                     "frac": gbs / HBM_PEAK_GBS}
+        mean = float(ms.mean())
+        gbs = units * elem * wp / (mean * 1e-3) / 1e9
+        res[name] = {"kernel_ms": mean, "kernel_ms_min": float(ms.min()), "bytes_per_worker_param": units * elem,
+                     "achieved": gbs, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS}
+        scratch.clear()
     return res
 
 
-def measure(cfg, off, layout, args, torch, rps, want_other_paths):
-    """Warm-up, the timed region, then the event-bracketed pass of the round kernel, for one storage layout."""
+def copy_ceiling(X, torch, reps=10):
+    """The simplest streaming jobs on the same buffer, timed with events on the current stream, as a
+    measured ceiling next to the published peak: an in-place pass (torch's elementwise x *= 1: every
+    element read once and written once, like the round) and a plain copy into a second array."""
+    flat = torch.empty(0, dtype=X.dtype, device="cuda").set_(X.untyped_storage())
+    nbytes = flat.numel() * flat.element_size()
+
+    def timed(fn):
+        for _ in range(3):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        e1.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    ms_inplace = timed(lambda: flat.mul_(1.0))
+    other = torch.empty_like(flat)
+    ms_copy = timed(lambda: other.copy_(flat))
+    del other
+    torch.cuda.empty_cache()
+    gbs = 2.0 * nbytes / (ms_inplace * 1e-3) / 1e9
+    gbs_copy = 2.0 * nbytes / (ms_copy * 1e-3) / 1e9
+    return {"achieved": gbs, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS, "ms": ms_inplace, "bytes_each_way": nbytes,
+            "what": "torch in-place elementwise pass (x *= 1) over the state buffer",
+            "copy_to_second_array": {"achieved": gbs_copy, "frac": gbs_copy / HBM_PEAK_GBS, "ms": ms_copy}}
+
+
+def measure(cfg, off, layout, args, torch, rps, want_other_paths, want_copy):
+    """Settling, warm-up, the timed region, then the event-bracketed pass of the round kernel, for one storage layout."""
     tiled = layout == "tiled"
     tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
     elem = 2 if cfg.dtype == "bf16" else 4
-    if tiled:
-        T = rps.RPS_TILE_BYTES // elem
-        shape = ((cfg.N + T - 1) // T, cfg.n, T)
-    else:
-        shape = (cfg.n, cfg.N)
-    X = torch.zeros(shape, device="cuda", dtype=tdt)              # Alg. 1: identical start, X_1 = 0
     ctx = rps.RpsContext(cfg.n, cfg.N, cfg.p, cfg.gamma, cfg.seed,
                          rps.RPS_DTYPE_BF16 if cfg.dtype == "bf16" else rps.RPS_DTYPE_F32, block_offsets=off,
                          flags=rps.RPS_FLAG_LAYOUT_TILED if tiled else 0)
     ctx.set_synthetic_grad(cfg.sigma, cfg.weight_decay)
+    pitch = None
+    if tiled:
+        T = rps.RPS_TILE_BYTES // elem
+        X = torch.zeros(((cfg.N + T - 1) // T, cfg.n, T), device="cuda", dtype=tdt)   # Alg. 1: identical start, X_1 = 0
+    else:
+        # rows a little further apart than N where the row size would otherwise be a multiple of 32 KB
+        # (all n rows of a tile on one memory channel); the padding is never touched
+        if (cfg.N * elem) % 32768 == 0:
+            pitch = rps.rps_recommended_row_pitch(cfg.N, ctx.dtype)
+            ctx.set_row_pitch(pitch)
+        X = ctx.empty_state(fill=0.0)
     # workloads whose gradient comes from a model (least squares, MLP): the library's part of a
     # step is the fused round on a caller-supplied gradient buffer; a fixed seeded buffer stands
     # in for it here (3 arrays of traffic instead of 2)
     G = None
     if cfg.gradient != "synthetic":
         gen = torch.Generator(device="cuda"); gen.manual_seed(1)
-        G = (torch.randn(shape, device="cuda", generator=gen) * 1e-3).to(tdt)
+        G = torch.zeros_like(X) if tiled else ctx.empty_state(fill=0.0)
+        G.copy_((torch.randn(tuple(G.shape), device="cuda", generator=gen) * 1e-3).to(tdt))
 
-    step = 0
+    def launch(t):
+        ctx.round(X, G, t)
+
+    step, settle_launches, settled = settle(ctx, launch, 0)
     for _ in range(args.warmup):
-        ctx.round(X, G, step); step += 1
+        launch(step); step += 1
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        ctx.round(X, G, step); step += 1
+        launch(step); step += 1
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
 
     # the round kernel alone, bracketed by HIP events on the stream it is launched on
     ctx.set_profiling(True)
     for _ in range(args.steps):
-        ctx.round(X, G, step); step += 1
-    kernel_ms, launches = ctx.get_kernel_time()
+        launch(step); step += 1
+    times = ctx.get_kernel_times(max(4096, args.steps))
     ctx.set_profiling(False)
-    assert launches == args.steps
-    kernel_ms /= launches
+    assert len(times) == min(args.steps, 4096)
+    kernel_ms = float(times.mean())
 
     alg_bytes = (3.0 if G is not None else 2.0) * elem * cfg.n * cfg.N   # read x (and g) once, write x' once
     res = {"value": cfg.n * cfg.N * args.steps / dt, "ms_per_step": dt / args.steps * 1e3, "kernel_ms": kernel_ms,
-           "alg_bytes": alg_bytes, "achieved": alg_bytes / (kernel_ms * 1e-3) / 1e9, "has_G": G is not None}
+           "kernel_ms_median": float(sorted(times)[len(times) // 2]), "kernel_ms_min": float(times.min()),
+           "alg_bytes": alg_bytes, "achieved": alg_bytes / (kernel_ms * 1e-3) / 1e9, "has_G": G is not None,
+           "settle_launches": settle_launches, "settled": settled, "row_pitch": pitch}
     if want_other_paths:
-        res["other_paths"] = other_paths(ctx, cfg, X, G, step, torch)
+        res["other_paths"] = other_paths(ctx, cfg, X, G, step, torch, rps, tiled)
+    if want_copy:
+        res["copy_ceiling"] = copy_ceiling(X, torch)
     ctx.destroy()
     del X, G
     torch.cuda.empty_cache()
@@ -160,8 +249,9 @@ def main():
                          "reported under other_layout)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--other-paths", action="store_true",
-                    help="also time the unfused entry points and the gradient-buffer round on the same workload "
-                         "(needs a second array of the state's size) and report each against its own algorithmic bytes")
+                    help="also time the unfused entry points, the gradient-buffer round, gradient averaging, consensus "
+                         "and the layout conversion on the same workload (needs further arrays of the state's size) "
+                         "and report each against its own algorithmic bytes, for both layouts")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run three plain 1 GiB device copies (a kernel of known traffic) so that one "
                          "rocprofv3 --pmc run holds both the round kernel and the reference for its counters; "
@@ -182,8 +272,9 @@ def main():
     layout = args.layout or "tiled"
     other = "row-major" if layout == "tiled" else "tiled"
 
-    m = measure(cfg, off, layout, args, torch, rps, args.other_paths)
+    m = measure(cfg, off, layout, args, torch, rps, args.other_paths, want_copy=not args.pmc_calibration)
     kernel = "round_kernel_narrow" if layout == "tiled" else "round_kernel"
+    traffic, traffic_source = MEASURED_TRAFFIC.get((cfg.name, layout), (None, "no rocprofv3 counter run for this workload and layout"))
     out = {
         "metric": "worker-params averaged/sec (n*N per round)",
         "value": m["value"],
@@ -197,18 +288,29 @@ def main():
                    "gradient": (f"in-register N(0,{cfg.sigma ** 2:.3g}) + {cfg.weight_decay}*x" if not m["has_G"]
                                 else "caller-supplied buffer G[n,N] (seeded stand-in)"),
                    "blocks": "unequal" if cfg.unequal_blocks else "equal",
-                   "layout": ("tile-major [N/T][n][T], T = 128 bytes" if layout == "tiled" else "row-major [n][N]")},
+                   "layout": ("tile-major [N/T][n][T], T = 128 bytes" if layout == "tiled" else "row-major [n][N]"),
+                   "row_pitch": m["row_pitch"],
+                   "settling": f"{m['settle_launches']} untimed launches before the warm-up"
+                               + ("" if m["settled"] else " (durations had not settled within 1 %)")},
         "roofline": {"bound": "hbm", "achieved": m["achieved"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": m["achieved"] / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.name, layout)),
-                     "kernel": kernel, "kernel_ms": m["kernel_ms"], "algorithmic_bytes": m["alg_bytes"]},
+                     "frac": m["achieved"] / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_source,
+                     "kernel": kernel, "kernel_ms": m["kernel_ms"], "kernel_ms_median": m["kernel_ms_median"],
+                     "kernel_ms_min": m["kernel_ms_min"], "algorithmic_bytes": m["alg_bytes"],
+                     "frac_timed_region": m["alg_bytes"] / (m["ms_per_step"] * 1e-3) / 1e9 / HBM_PEAK_GBS},
     }
+    if "copy_ceiling" in m:
+        out["copy_ceiling"] = m["copy_ceiling"]
     if "other_paths" in m:
         out["other_paths"] = m["other_paths"]
     if not args.pmc_calibration:
-        o = measure(cfg, off, other, args, torch, rps, False)
+        o = measure(cfg, off, other, args, torch, rps, args.other_paths, want_copy=False)
         out["other_layout"] = {"layout": other, "value": o["value"], "ms_per_step": o["ms_per_step"],
-                               "kernel_ms": o["kernel_ms"], "achieved": o["achieved"], "unit": "GB/s",
-                               "frac": o["achieved"] / HBM_PEAK_GBS}
+                               "kernel_ms": o["kernel_ms"], "kernel_ms_median": o["kernel_ms_median"],
+                               "kernel_ms_min": o["kernel_ms_min"], "achieved": o["achieved"], "unit": "GB/s",
+                               "frac": o["achieved"] / HBM_PEAK_GBS, "row_pitch": o["row_pitch"],
+                               "frac_timed_region": o["alg_bytes"] / (o["ms_per_step"] * 1e-3) / 1e9 / HBM_PEAK_GBS}
+        if "other_paths" in o:
+            out["other_layout"]["other_paths"] = o["other_paths"]
     if args.pmc_calibration:
         src = torch.ones(1 << 28, device="cuda")          # 1 GiB of fp32
         dst = torch.empty_like(src)

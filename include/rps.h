@@ -280,13 +280,16 @@ int rps_noise_cells(float *radius, float *cos_sin);
 
 /*
  * Kernel timing for benchmarks: while enabled, every rps_round / rps_lossy_average /
- * rps_local_step brackets its main kernel (not the small mask kernel) with HIP events on the
- * context's stream.  rps_get_kernel_time synchronises the stream, returns the accumulated
+ * rps_local_step / rps_round_gradient_averaging / rps_consensus / rps_convert_layout brackets its
+ * kernel(s) (not the small mask kernel) with HIP events on the context's stream.  rps_get_kernel_time synchronises the stream, returns the accumulated
  * kernel milliseconds and launch count since enabling, and resets both.  At most 4096
  * launches are recorded between two reads.
  */
 int rps_set_profiling(rps_ctx *ctx, int32_t enable);
 int rps_get_kernel_time(rps_ctx *ctx, double *total_ms, int64_t *launches);
+/* Same, per launch: ms[k] receives the duration of the k-th recorded launch (HOST array of `capacity`
+   doubles; launches beyond it are counted in *launches but not stored). */
+int rps_get_kernel_times(rps_ctx *ctx, double *ms, int64_t capacity, int64_t *launches);
 
 /* hipError_t of the last failing HIP call in this context (0 = none). */
 int rps_last_hip_error(const rps_ctx *ctx);

@@ -445,7 +445,7 @@ int rps_local_step(rps_ctx *ctx, void *X, const void *G, uint64_t step) {
     if (!guard.ok) return RPS_EHIP;
     const RoundParams prm = make_params(ctx, X, G, step);
     const int mode = G ? rps::kGradBuffer : rps::kGradSynthetic;
-    return timed_launch(ctx, [&] { return rps::launch_local_step(ctx->dtype, mode, X, G, prm, ctx->stream); });
+    return timed_launch(ctx, [&] { return rps::launch_local_step(ctx->dtype, mode, X, G, prm, ctx->tune_set ? ctx->tune.tiles_per_wave : 0, ctx->stream); });
 }
 
 int rps_lossy_average(rps_ctx *ctx, void *X, uint64_t step) {
@@ -553,7 +553,10 @@ int rps_consensus(rps_ctx *ctx, const void *X, double *distance, double *mean_sq
     if (!guard.ok) return RPS_EHIP;
     const RoundParams prm = make_params(ctx, X, nullptr, 0);
     double *out = ctx->partials + 2 * rps::kMaxPartials;
-    RPS_HIP(ctx, rps::launch_consensus(ctx->dtype, X, prm, ctx->partials, rps::kMaxPartials, out, ctx->stream));
+    const int rc = timed_launch(ctx, [&] {
+        return rps::launch_consensus(ctx->dtype, X, prm, ctx->partials, rps::kMaxPartials, out, ctx->stream);
+    });
+    if (rc != RPS_OK) return rc;
     double host[2] = {0.0, 0.0};
     RPS_HIP(ctx, hipMemcpyAsync(host, out, sizeof(host), hipMemcpyDeviceToHost, ctx->stream));
     RPS_HIP(ctx, hipStreamSynchronize(ctx->stream));
@@ -623,9 +626,10 @@ int rps_convert_layout(rps_ctx *ctx, void *dst, const void *src, int32_t to_tile
     if (!guard.ok) return RPS_EHIP;
     const int64_t vec = ctx->dtype == RPS_DTYPE_F32 ? 4 : 8;
     const bool aligned = (uintptr_t)dst % 16 == 0 && (uintptr_t)src % 16 == 0 && ctx->pitch % vec == 0;
-    RPS_HIP(ctx, rps::launch_convert_layout(ctx->dtype, dst, src, ctx->N, ctx->pitch, ctx->n, to_tiled != 0, aligned,
-                                            ctx->stream));
-    return RPS_OK;
+    return timed_launch(ctx, [&] {
+        return rps::launch_convert_layout(ctx->dtype, dst, src, ctx->N, ctx->pitch, ctx->n, to_tiled != 0, aligned,
+                                          ctx->stream);
+    });
 }
 
 int rps_set_launch_tuning(rps_ctx *ctx, int32_t rows_in_flight, int32_t waves_per_workgroup, int32_t max_waves_per_cu,
@@ -647,6 +651,22 @@ int rps_set_profiling(rps_ctx *ctx, int32_t enable) {
     if (!guard.ok) return RPS_EHIP;
     RPS_HIP(ctx, hipStreamSynchronize(ctx->stream));
     ctx->profiling = enable != 0;
+    ctx->ev_used = 0;
+    return RPS_OK;
+}
+
+int rps_get_kernel_times(rps_ctx *ctx, double *ms, int64_t capacity, int64_t *launches) {
+    if (!ctx || !launches || capacity < 0 || (capacity > 0 && !ms)) return RPS_EINVAL;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return RPS_EHIP;
+    RPS_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    const size_t count = std::min<size_t>(ctx->ev_used, (size_t)capacity);
+    for (size_t k = 0; k < count; ++k) {
+        float t = 0.0f;
+        RPS_HIP(ctx, hipEventElapsedTime(&t, ctx->ev_start[k], ctx->ev_stop[k]));
+        ms[k] = (double)t;
+    }
+    *launches = (int64_t)ctx->ev_used;
     ctx->ev_used = 0;
     return RPS_OK;
 }

@@ -75,8 +75,9 @@ hipError_t launch_mixing_moments(double *out, int workgroups, int64_t rounds, in
                                  uint64_t first_step, uint64_t threshold, int server_mode, hipStream_t stream);
 hipError_t launch_round(int dtype, int grad_mode, void *X, const void *G, const RoundTable *tab,
                         const RoundParams &prm, int64_t max_block_cols, const LaunchTuning &tune, hipStream_t stream);
+// tiles_per_wave: 1 KB steps per wavefront with the in-register gradient; 0: chosen by the launcher
 hipError_t launch_local_step(int dtype, int grad_mode, void *X, const void *G,
-                             const RoundParams &prm, hipStream_t stream);
+                             const RoundParams &prm, int tiles_per_wave, hipStream_t stream);
 
 hipError_t launch_gradavg(int dtype, void *X, const void *G, const RoundTable *tab, const RoundParams &prm,
                           int64_t max_block_cols, int max_waves_per_cu, hipStream_t stream);

@@ -905,26 +905,45 @@ __global__ __launch_bounds__(WPB * 64) void round_kernel_narrow(ST *__restrict__
 }
 
 // Local SGD step alone: grid = (runs of vector chunks, workers); a lane owns one 16-byte vector of
-// one row.  One row per wavefront keeps every access stream contiguous (measured 0.80 of the HBM
-// peak against 0.74 when a lane served both rows of a worker pair); the price is that the
+// one row per chunk.  One row per wavefront keeps every access stream contiguous (measured 0.80 of
+// the HBM peak against 0.74 when a lane served both rows of a worker pair); the price is that the
 // noise hash of a (4 columns x 2 workers) patch is evaluated by both rows' lanes, each keeping
-// its half.  A wavefront takes tiles_per_wave chunks, WPB chunks apart.
-template <typename ST, int GRAD, bool FULL, typename LDS>
-__device__ __forceinline__ void local_step_row(ST *__restrict__ X, const ST *__restrict__ G, const RoundParams &prm,
-                                               const LDS &lds, const LaneCols &lc, int i) {
+// its half.  A wavefront step covers U adjacent chunks of 1 KB (all loads first, then the
+// arithmetic and the stores); it takes tiles_per_wave steps.
+template <typename ST, int GRAD, bool FULL, int U, typename LDS>
+__device__ __forceinline__ void local_step_chunks(ST *__restrict__ X, const ST *__restrict__ G, const RoundParams &prm,
+                                                  const LDS &lds, LaneCols lc, int i, int chunks) {
     using S = Storage<ST>;
     constexpr int VEC = S::VEC;
+    constexpr int TILE = 64 * VEC;
     ST *row = X + (int64_t)i * prm.stride + lc.tile0;
-    float x[VEC], g[VEC], other[VEC];
-    S::unpack(load_raw<ST, FULL>(row, lc), x);
-    if (GRAD == kGradBuffer) {
-        S::unpack(load_raw<ST, FULL>(G + (int64_t)i * prm.stride + lc.tile0, lc), g);
-    } else if (i & 1) {
-        noise_rows<VEC>(prm, lds, i >> 1, lc.quad_hi(), lc.quad_lo(), other, g);
-    } else {
-        noise_rows<VEC>(prm, lds, i >> 1, lc.quad_hi(), lc.quad_lo(), g, other);
+    const ST *grow = GRAD == kGradBuffer ? G + (int64_t)i * prm.stride + lc.tile0 : nullptr;
+    typename S::Raw xr[U], gr[GRAD == kGradBuffer ? U : 1];
+    const int64_t tile0 = lc.tile0;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        if (u < chunks) {   // wave-uniform
+            lc.tile0 = tile0 + u * TILE;
+            xr[u] = load_raw<ST, FULL>(row + u * TILE, lc);
+            if (GRAD == kGradBuffer) gr[GRAD == kGradBuffer ? u : 0] = load_raw<ST, FULL>(grow + u * TILE, lc);
+        }
     }
-    store_raw<ST, FULL>(row, lc, sgd_step<ST, GRAD>(prm, g, x));
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        if (u < chunks) {
+            lc.tile0 = tile0 + u * TILE;
+            float x[VEC], g[VEC], other[VEC];
+            S::unpack(xr[u], x);
+            if (GRAD == kGradBuffer) {
+                S::unpack(gr[GRAD == kGradBuffer ? u : 0], g);
+            } else if (i & 1) {
+                noise_rows<VEC>(prm, lds, i >> 1, lc.quad_hi(), lc.quad_lo(), other, g);
+            } else {
+                noise_rows<VEC>(prm, lds, i >> 1, lc.quad_hi(), lc.quad_lo(), g, other);
+            }
+            store_raw<ST, FULL>(row + u * TILE, lc, sgd_step<ST, GRAD>(prm, g, x));
+        }
+    }
 }
 
 template <typename ST, int GRAD, int WPB>
@@ -932,6 +951,7 @@ __global__ __launch_bounds__(WPB * 64) void local_step_kernel(ST *__restrict__ X
                                                               const RoundParams prm) {
     constexpr int VEC = Storage<ST>::VEC;
     constexpr int TILE = 64 * VEC;
+    constexpr int U = GRAD == kGradSynthetic ? 4 : 1;
     __shared__ typename LdsFor<GRAD>::type lds;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -939,30 +959,34 @@ __global__ __launch_bounds__(WPB * 64) void local_step_kernel(ST *__restrict__ X
     noise_fill_begin<WPB>(lds, prm.noise_cells, wave, lane);
     noise_fill_end(lds);
     for (int it = 0; it < prm.tiles_per_wave; ++it) {
-        const int64_t tile0 = unit_index(it, WPB, wave) * TILE;
+        const int64_t tile0 = unit_index(it, WPB, wave) * (U * TILE);
         if (tile0 >= prm.N) break;   // wave-uniform
         LaneCols lc;
         lc.tile0 = tile0;
         lc.loff = (uint32_t)lane * VEC;
         lc.lo = 0;
         lc.hi = prm.N;
-        if (prm.vec_ok && tile0 + TILE <= prm.N)
-            local_step_row<ST, GRAD, true>(X, G, prm, lds, lc, row);
+        const int64_t left = (prm.N - tile0 + TILE - 1) / TILE;
+        const int chunks = (int)(left < U ? left : U);
+        if (prm.vec_ok && tile0 + U * TILE <= prm.N)
+            local_step_chunks<ST, GRAD, true, U>(X, G, prm, lds, lc, row, U);
         else
-            local_step_row<ST, GRAD, false>(X, G, prm, lds, lc, row);
+            local_step_chunks<ST, GRAD, false, U>(X, G, prm, lds, lc, row, chunks);
     }
 }
 
 // Local step on the tiled layout: the storage is one run of (tile, worker) segments of
-// kTiledLanes x 16 bytes; a wavefront takes 1 KB of it in storage order (8 segments), so the pass is
-// a plain sequential stream.  Lane -> segment s = 8 * q + lane / 8 -> (tile, row) = (s / n, s % n),
-// q = the wavefront's running index (tiles_per_wave of them per wavefront, WPB apart).
+// kTiledLanes x 16 bytes; a wavefront step takes U adjacent KB of it in storage order (8 segments
+// each), so the pass is a plain sequential stream.  Lane -> segment s = 8 * k + lane / 8 of KB k
+// -> (tile, row) = (s / n, s % n); all U loads are issued before the arithmetic.
 template <typename ST, int GRAD, int WPB>
 __global__ __launch_bounds__(WPB * 64) void local_step_tiled_kernel(ST *__restrict__ X, const ST *__restrict__ G,
                                                                     const RoundParams prm) {
     using S = Storage<ST>;
+    using Raw = typename S::Raw;
     constexpr int VEC = S::VEC;
-    constexpr int LPR = kTiledLanes, TILE = LPR * VEC;
+    constexpr int LPR = kTiledLanes, TILE = LPR * VEC, SEGS = 64 / LPR;
+    constexpr int U = GRAD == kGradSynthetic ? 4 : 1;
     __shared__ typename LdsFor<GRAD>::type lds;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -970,40 +994,60 @@ __global__ __launch_bounds__(WPB * 64) void local_step_tiled_kernel(ST *__restri
     noise_fill_end(lds);
     const int64_t tiles = (prm.N + TILE - 1) / TILE;
     for (int it = 0; it < prm.tiles_per_wave; ++it) {
-        const int64_t q = unit_index(it, WPB, wave);
-        const int64_t seg0 = q * (64 / LPR);          // first segment of the wavefront: scalar division
-        int64_t tile = seg0 / prm.n;
-        if (tile >= tiles) break;                     // wave-uniform: past the last tile
-        int i = (int)(seg0 % prm.n) + lane / LPR;     // then at most 64 / LPR rows further
-        while (i >= prm.n) {
-            i -= prm.n;
-            ++tile;
+        const int64_t kb0 = unit_index(it, WPB, wave) * U;
+        if ((kb0 * SEGS) / prm.n >= tiles) break;         // wave-uniform: past the last tile
+        Raw xr[U], gr[GRAD == kGradBuffer ? U : 1];
+        int64_t c0s[U];
+        int rows[U];
+        bool fulls[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t seg0 = (kb0 + u) * SEGS;        // first segment of this KB: scalar division
+            int64_t tile = seg0 / prm.n;
+            int i = (int)(seg0 % prm.n) + lane / LPR;     // then at most 64 / LPR rows further
+            while (i >= prm.n) {
+                i -= prm.n;
+                ++tile;
+            }
+            const int64_t c0 = tile * TILE + (lane % LPR) * VEC;
+            c0s[u] = c0;
+            rows[u] = i;
+            fulls[u] = prm.vec_ok && c0 + VEC <= prm.N;
+            const ST *px = X + seg0 * TILE + (uint32_t)(lane / LPR) * TILE + (lane % LPR) * VEC;   // plain global accesses:
+            const ST *pg = G ? G + (px - X) : nullptr;   // measured faster here than the buffer form the round kernels use
+            if (c0 >= prm.N) {                            // padding columns of the last tile, or past the last tile
+                xr[u] = Raw{};
+            } else if (fulls[u]) {
+                xr[u] = __builtin_nontemporal_load(reinterpret_cast<const Raw *>(px));
+                if (GRAD == kGradBuffer) gr[GRAD == kGradBuffer ? u : 0] = __builtin_nontemporal_load(reinterpret_cast<const Raw *>(pg));
+            } else {
+                xr[u] = load_seg<ST, false>(px, 0, 0, c0, 0, prm.N);
+                if (GRAD == kGradBuffer) gr[GRAD == kGradBuffer ? u : 0] = load_seg<ST, false>(pg, 0, 0, c0, 0, prm.N);
+            }
         }
-        const int64_t c0 = tile * TILE + (lane % LPR) * VEC;
-        if (c0 >= prm.N) continue;   // padding columns of the last tile, or past the last tile
-        ST *px = X + seg0 * TILE + (uint32_t)(lane / LPR) * TILE + (lane % LPR) * VEC;   // plain global accesses:
-        const ST *pg = G ? G + (px - X) : nullptr;   // measured faster here than the buffer form the round kernels use
-        float x[VEC], g[VEC], other[VEC];
-        const bool full = prm.vec_ok && c0 + VEC <= prm.N;
-        if (full) {
-            S::unpack(__builtin_nontemporal_load(reinterpret_cast<const typename S::Raw *>(px)), x);
-            if (GRAD == kGradBuffer) S::unpack(__builtin_nontemporal_load(reinterpret_cast<const typename S::Raw *>(pg)), g);
-        } else {
-            S::unpack(load_seg<ST, false>(px, 0, 0, c0, 0, prm.N), x);
-            if (GRAD == kGradBuffer) S::unpack(load_seg<ST, false>(pg, 0, 0, c0, 0, prm.N), g);
-        }
-        if (GRAD != kGradBuffer) {   // a wavefront's lanes may sit in different tiles: the counter is per lane
-            const uint32_t quad_hi = (uint32_t)(c0 >> 9), quad_lo = (uint32_t)(c0 >> 2) & 127u;
-            if (i & 1)
-                noise_rows<VEC>(prm, lds, i >> 1, quad_hi, quad_lo, other, g);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t c0 = c0s[u];
+            if (c0 >= prm.N) continue;
+            const int i = rows[u];
+            ST *px = X + (kb0 + u) * SEGS * TILE + (uint32_t)(lane / LPR) * TILE + (lane % LPR) * VEC;
+            float x[VEC], g[VEC], other[VEC];
+            S::unpack(xr[u], x);
+            if (GRAD == kGradBuffer) {
+                S::unpack(gr[GRAD == kGradBuffer ? u : 0], g);
+            } else {   // a wavefront's lanes may sit in different tiles: the counter is per lane
+                const uint32_t quad_hi = (uint32_t)(c0 >> 9), quad_lo = (uint32_t)(c0 >> 2) & 127u;
+                if (i & 1)
+                    noise_rows<VEC>(prm, lds, i >> 1, quad_hi, quad_lo, other, g);
+                else
+                    noise_rows<VEC>(prm, lds, i >> 1, quad_hi, quad_lo, g, other);
+            }
+            const Raw v = sgd_step<ST, GRAD>(prm, g, x);
+            if (fulls[u])
+                __builtin_nontemporal_store(v, reinterpret_cast<Raw *>(px));
             else
-                noise_rows<VEC>(prm, lds, i >> 1, quad_hi, quad_lo, g, other);
+                store_seg<ST, false>(px, 0, 0, c0, 0, prm.N, v);
         }
-        const typename S::Raw v = sgd_step<ST, GRAD>(prm, g, x);
-        if (full)
-            __builtin_nontemporal_store(v, reinterpret_cast<typename S::Raw *>(px));
-        else
-            store_seg<ST, false>(px, 0, 0, c0, 0, prm.N, v);
     }
 }
 
@@ -1129,7 +1173,7 @@ hipError_t launch_round_g(int grad_mode, ST *X, const ST *G, const RoundTable *t
 }
 
 template <typename ST>
-hipError_t launch_local_step_g(int grad_mode, ST *X, const ST *G, RoundParams prm, hipStream_t stream) {
+hipError_t launch_local_step_g(int grad_mode, ST *X, const ST *G, RoundParams prm, int wanted_steps, hipStream_t stream) {
     constexpr int VEC = Storage<ST>::VEC;
     constexpr int WS = 8;   // wavefronts per workgroup where noise is generated (they share the LDS cells)
     if (prm.tiled) {
@@ -1140,9 +1184,10 @@ hipError_t launch_local_step_g(int grad_mode, ST *X, const ST *G, RoundParams pr
             hipLaunchKernelGGL((local_step_tiled_kernel<ST, kGradBuffer, 4>), folded_grid8((kb + 3) / 4, 1), dim3(256), 0,
                                stream, X, G, prm);
         } else {
-            prm.tiles_per_wave = steps_per_wave(kGradSynthetic, kb, WS, 1, 0, 32);   // a step is only 1 KB here
+            const int64_t units = (kb + 3) / 4;   // a wavefront step is 4 KB here
+            prm.tiles_per_wave = steps_per_wave(kGradSynthetic, units, WS, 1, wanted_steps, 2);
             const int64_t per_wg = (int64_t)WS * prm.tiles_per_wave;
-            hipLaunchKernelGGL((local_step_tiled_kernel<ST, kGradSynthetic, WS>), folded_grid8((kb + per_wg - 1) / per_wg, 1),
+            hipLaunchKernelGGL((local_step_tiled_kernel<ST, kGradSynthetic, WS>), folded_grid8((units + per_wg - 1) / per_wg, 1),
                                dim3(WS * 64), 0, stream, X, G, prm);
         }
         return hipGetLastError();
@@ -1153,10 +1198,11 @@ hipError_t launch_local_step_g(int grad_mode, ST *X, const ST *G, RoundParams pr
         hipLaunchKernelGGL((local_step_kernel<ST, kGradBuffer, 4>), folded_grid8((tiles + 3) / 4, (unsigned)prm.n), dim3(256),
                            0, stream, X, G, prm);
     } else {
-        prm.tiles_per_wave = steps_per_wave(kGradSynthetic, tiles, WS, prm.n, 0, 32);   // a step is only 1 KB here
+        const int64_t units = (tiles + 3) / 4;   // a wavefront step is 4 chunks here
+        prm.tiles_per_wave = steps_per_wave(kGradSynthetic, units, WS, prm.n, wanted_steps, 1);
         const int64_t per_wg = (int64_t)WS * prm.tiles_per_wave;
         hipLaunchKernelGGL((local_step_kernel<ST, kGradSynthetic, WS>),
-                           folded_grid8((tiles + per_wg - 1) / per_wg, (unsigned)prm.n), dim3(WS * 64), 0, stream, X, G, prm);
+                           folded_grid8((units + per_wg - 1) / per_wg, (unsigned)prm.n), dim3(WS * 64), 0, stream, X, G, prm);
     }
     return hipGetLastError();
 }
@@ -1401,64 +1447,98 @@ __device__ __forceinline__ void consensus_tile(const ST *__restrict__ X, const R
     }
 }
 
-// The same statistics on the tiled layout: lane group lg takes rows lg, lg + 8, ... of its 16-byte
-// column group (every lane also loads the pivot row 0), the groups are combined by a butterfly,
-// and the lanes of group 0 carry the tile's contribution.
-template <typename ST, bool FULL>
-__device__ __forceinline__ void consensus_tile_tiled(const ST *__restrict__ X, const RoundParams &prm, int64_t tile0,
-                                                     int lane, double &dist, double &msq) {
+// The same statistics on the tiled layout.  A wavefront takes U adjacent tiles at a time; lane group
+// lg = lane / 8 holds rows lg, lg + 8, ... (ROWS of them) of its 16-byte column group in each tile,
+// all U * ROWS loads are issued up front (4 or 8 KB in flight per wavefront: U = 4 tiles of up to
+// 8 workers, 2 of up to 16, one of more).  The pivot row 0 is what lane group 0 loaded: the other
+// groups get it by a lane shuffle.  Per column, sum_i y_i^2 needs no exchange (every lane adds its own
+// rows' share to its running total), sum_i y_i is combined over the lane groups by a butterfly and
+// the lanes of group 0 carry the column's -(sum y)^2 / n and mean^2.
+template <typename ST, bool FULL, int ROWS, int U>
+__device__ __forceinline__ void consensus_tiles_tiled(const ST *__restrict__ X, const RoundParams &prm, int64_t tile_index,
+                                                      int lane, double &dist, double &msq) {
     using S = Storage<ST>;
+    using Raw = typename S::Raw;
     constexpr int VEC = S::VEC;
-    constexpr int LPR = kTiledLanes, GROUPS = 64 / LPR;
+    constexpr int LPR = kTiledLanes, GROUPS = 64 / LPR, TILE = LPR * VEC;
     const int n = prm.n;
     const int lg = lane / LPR, sub = lane % LPR;
-    const int64_t c0 = tile0 + sub * VEC;
-    const ST *Xt = X + tile0 * n;   // wave-uniform
-    float p[VEC];
-    const uint32_t limit = (uint32_t)n * (uint32_t)(LPR * VEC) * (uint32_t)sizeof(ST);
-    S::unpack(load_seg<ST, FULL>(Xt, sub * VEC, limit, c0, 0, prm.N), p);
-    double s1[VEC], s2[VEC];
+    const ST *Xt = X + tile_index * TILE * n;   // wave-uniform: first tile of the unit
+    const uint32_t tile_elems = (uint32_t)n * TILE;
+    const int64_t ntiles = (prm.N + TILE - 1) / TILE;
+    int tiles = (int)(ntiles - tile_index < U ? ntiles - tile_index : U);   // wave-uniform
+    const uint32_t limit = (uint32_t)tiles * tile_elems * (uint32_t)sizeof(ST);
+    Raw x[U][ROWS];
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) s1[e] = s2[e] = 0.0;
-    constexpr int R = 4;   // rows in flight per lane
-    for (int i0 = lg; i0 < n; i0 += R * GROUPS) {   // row 0 (group 0) contributes y = 0
-        typename S::Raw x[R];
+    for (int u = 0; u < U; ++u) {
+        const int64_t c0 = (tile_index + u) * TILE + sub * VEC;
 #pragma unroll
-        for (int r = 0; r < R; ++r) {   // rows past n repeat the lane's last row, unused
-            const int i = i0 + r * GROUPS;
-            x[r] = load_seg<ST, FULL>(Xt, (uint32_t)(i < n ? i : i0) * (uint32_t)(LPR * VEC) + sub * VEC, limit, c0, 0, prm.N);
+        for (int k = 0; k < ROWS; ++k) {
+            const int i = lg + GROUPS * k;
+            // rows past n and tiles past the last one: an offset at the buffer's bound (FULL: the
+            // hardware returns zeros without touching memory) / an empty column range (element-wise)
+            const bool live = i < n && u < tiles;
+            const uint32_t off = live ? (uint32_t)u * tile_elems + (uint32_t)i * TILE + sub * VEC : limit / (uint32_t)sizeof(ST);
+            x[u][k] = load_seg<ST, FULL>(Xt, FULL || live ? off : 0u, limit, c0, 0, live ? prm.N : 0);
         }
+    }
+    const double inv_n = 1.0 / (double)n;
 #pragma unroll
-        for (int r = 0; r < R; ++r) {
-            if (i0 + r * GROUPS < n) {
-                float v[VEC];
-                S::unpack(x[r], v);
+    for (int u = 0; u < U; ++u) {
+        if (u < tiles) {   // wave-uniform
+            float p[VEC], v[VEC];
+            u32x4 bits;
+            __builtin_memcpy(&bits, &x[u][0], sizeof(bits));
+            bits.x = __shfl(bits.x, sub, 64); bits.y = __shfl(bits.y, sub, 64);
+            bits.z = __shfl(bits.z, sub, 64); bits.w = __shfl(bits.w, sub, 64);
+            Raw praw;
+            __builtin_memcpy(&praw, &bits, sizeof(praw));
+            S::unpack(praw, p);                 // row 0 of this lane's column group
+            double s1[VEC];
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) s1[e] = 0.0;
+#pragma unroll
+            for (int k = 0; k < ROWS; ++k) {
+                if (lg + GROUPS * k < n) {
+                    S::unpack(x[u][k], v);
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) {   // columns outside [0, N) were loaded as 0, their pivot too
+                        const double y = (double)v[e] - (double)p[e];
+                        s1[e] += y;
+                        dist = __builtin_fma(y, y, dist);
+                    }
+                }
+            }
+#pragma unroll
+            for (int o = LPR; o < 64; o <<= 1) {
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) s1[e] += __shfl_xor(s1[e], o, 64);
+            }
+            if (lg == 0) {
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) {
-                    const double y = (double)v[e] - (double)p[e];
-                    s1[e] += y;
-                    s2[e] = __builtin_fma(y, y, s2[e]);
+                    const double m = s1[e] * inv_n;
+                    dist = __builtin_fma(-s1[e], m, dist);
+                    const double mean = (double)p[e] + m;
+                    msq = __builtin_fma(mean, mean, msq);
                 }
             }
         }
     }
-#pragma unroll
-    for (int o = LPR; o < 64; o <<= 1) {
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) {
-            s1[e] += __shfl_xor(s1[e], o, 64);
-            s2[e] += __shfl_xor(s2[e], o, 64);
-        }
-    }
-    if (lg == 0) {
-        const double inv_n = 1.0 / (double)n;
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) {   // columns outside [0, N) were loaded as 0 and add 0
-            const double m = s1[e] * inv_n;
-            dist += s2[e] - s1[e] * m;
-            const double mean = (double)p[e] + m;
-            msq = __builtin_fma(mean, mean, msq);
-        }
+}
+
+template <typename ST, int ROWS, int U>
+__device__ __forceinline__ void consensus_walk_tiled(const ST *__restrict__ X, const RoundParams &prm, int wave, int lane,
+                                                     double &dist, double &msq) {
+    constexpr int TILE = kTiledLanes * Storage<ST>::VEC;
+    const int64_t ntiles = (prm.N + TILE - 1) / TILE;
+    for (int it = 0;; ++it) {
+        const int64_t t = unit_index(it, 4, wave) * U;
+        if (t >= ntiles) break;   // wave-uniform; later steps lie further on
+        if (prm.vec_ok && (t + U) * TILE <= prm.N)
+            consensus_tiles_tiled<ST, true, ROWS, U>(X, prm, t, lane, dist, msq);
+        else
+            consensus_tiles_tiled<ST, false, ROWS, U>(X, prm, t, lane, dist, msq);
     }
 }
 
@@ -1471,18 +1551,20 @@ __global__ __launch_bounds__(256) void consensus_kernel(const ST *__restrict__ X
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     double dist = 0.0, msq = 0.0;
     if (prm.tiled) {
-        constexpr int TILE = kTiledLanes * VEC;
-        const int64_t ntiles = (prm.N + TILE - 1) / TILE;
-        for (int64_t t = (int64_t)blockIdx.x * 4 + wave; t < ntiles; t += (int64_t)gridDim.x * 4) {
-            if (prm.vec_ok && (t + 1) * TILE <= prm.N)
-                consensus_tile_tiled<ST, true>(X, prm, t * TILE, lane, dist, msq);
-            else
-                consensus_tile_tiled<ST, false>(X, prm, t * TILE, lane, dist, msq);
-        }
+        if (prm.n <= 8)
+            consensus_walk_tiled<ST, 1, 4>(X, prm, wave, lane, dist, msq);
+        else if (prm.n <= 16)
+            consensus_walk_tiled<ST, 2, 2>(X, prm, wave, lane, dist, msq);
+        else if (prm.n <= 32)
+            consensus_walk_tiled<ST, 4, 1>(X, prm, wave, lane, dist, msq);
+        else
+            consensus_walk_tiled<ST, 8, 1>(X, prm, wave, lane, dist, msq);
     } else {
         constexpr int TILE = 64 * VEC;
         const int64_t ntiles = (prm.N + TILE - 1) / TILE;
-        for (int64_t t = (int64_t)blockIdx.x * 4 + wave; t < ntiles; t += (int64_t)gridDim.x * 4) {
+        for (int it = 0;; ++it) {
+            const int64_t t = unit_index(it, 4, wave);
+            if (t >= ntiles) break;   // wave-uniform
             LaneCols lc;
             lc.tile0 = t * TILE;
             lc.loff = (uint32_t)lane * VEC;
@@ -1561,9 +1643,9 @@ hipError_t launch_round(int dtype, int grad_mode, void *X, const void *G, const 
 }
 
 hipError_t launch_local_step(int dtype, int grad_mode, void *X, const void *G, const RoundParams &prm,
-                             hipStream_t stream) {
-    if (dtype == 0) return launch_local_step_g<float>(grad_mode, (float *)X, (const float *)G, prm, stream);
-    return launch_local_step_g<uint16_t>(grad_mode, (uint16_t *)X, (const uint16_t *)G, prm, stream);
+                             int tiles_per_wave, hipStream_t stream) {
+    if (dtype == 0) return launch_local_step_g<float>(grad_mode, (float *)X, (const float *)G, prm, tiles_per_wave, stream);
+    return launch_local_step_g<uint16_t>(grad_mode, (uint16_t *)X, (const uint16_t *)G, prm, tiles_per_wave, stream);
 }
 
 hipError_t launch_gradavg(int dtype, void *X, const void *G, const RoundTable *tab, const RoundParams &prm,
@@ -1698,9 +1780,11 @@ hipError_t static_scratch(int device, double **out) {
 
 hipError_t launch_consensus(int dtype, const void *X, const RoundParams &prm, double *partials, int max_partials,
                             double *out, hipStream_t stream) {
-    const int64_t tile = dtype == 0 ? 256 : 512;
+    // units of one wavefront step: a tile of 64 lanes x 16 bytes (row-major), or 4 / 2 / 1 tiles of 128 bytes (tiled)
+    int64_t tile = dtype == 0 ? 256 : 512;
+    if (prm.tiled) tile = (tile / 8) * (prm.n <= 8 ? 4 : (prm.n <= 16 ? 2 : 1));
     const int64_t ntiles = (prm.N + tile - 1) / tile;
-    int64_t wgs = (ntiles + 3) / 4;
+    int64_t wgs = ((ntiles + 3) / 4 + 7) & ~(int64_t)7;   // unit_index(): a multiple of 8 workgroups
     if (wgs > max_partials) wgs = max_partials;
     if (dtype == 0)
         hipLaunchKernelGGL(consensus_kernel<float>, dim3((unsigned)wgs), dim3(256), 0, stream, (const float *)X, prm,

@@ -53,18 +53,19 @@ _lib.rps_set_launch_tuning.argtypes = [_ctx_p, ctypes.c_int32, ctypes.c_int32, c
 _lib.rps_noise_cells.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
 _lib.rps_set_profiling.argtypes = [_ctx_p, ctypes.c_int32]
 _lib.rps_get_kernel_time.argtypes = [_ctx_p, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
+_lib.rps_get_kernel_times.argtypes = [_ctx_p, ctypes.c_void_p, ctypes.c_int64, ctypes.POINTER(ctypes.c_int64)]
 _lib.rps_last_hip_error.argtypes = [_ctx_p]
 _lib.rps_strerror.argtypes = [ctypes.c_int]
 _lib.rps_strerror.restype = ctypes.c_char_p
 for _name in ("rps_create", "rps_create_external", "rps_destroy", "rps_set_synthetic_grad", "rps_set_gamma", "rps_set_row_pitch", "rps_local_step",
               "rps_lossy_average", "rps_round", "rps_round_gradient_averaging", "rps_get_masks", "rps_set_mask_override",
-              "rps_consensus", "rps_consensus_static", "rps_estimate_mixing", "rps_convert_layout", "rps_set_launch_tuning", "rps_noise_cells", "rps_set_profiling", "rps_get_kernel_time", "rps_last_hip_error"):
+              "rps_consensus", "rps_consensus_static", "rps_estimate_mixing", "rps_convert_layout", "rps_set_launch_tuning", "rps_noise_cells", "rps_set_profiling", "rps_get_kernel_time", "rps_get_kernel_times", "rps_last_hip_error"):
     getattr(_lib, _name).restype = ctypes.c_int
 
 EXPORTS = ("rps_create", "rps_create_external", "rps_storage_elems", "rps_destroy", "rps_set_synthetic_grad", "rps_set_gamma",
            "rps_set_row_pitch", "rps_recommended_row_pitch", "rps_local_step",
            "rps_lossy_average", "rps_round", "rps_round_gradient_averaging", "rps_get_masks", "rps_set_mask_override",
-           "rps_consensus", "rps_consensus_static", "rps_estimate_mixing", "rps_convert_layout", "rps_set_launch_tuning", "rps_noise_cells", "rps_set_profiling", "rps_get_kernel_time",
+           "rps_consensus", "rps_consensus_static", "rps_estimate_mixing", "rps_convert_layout", "rps_set_launch_tuning", "rps_noise_cells", "rps_set_profiling", "rps_get_kernel_time", "rps_get_kernel_times",
            "rps_last_hip_error",
            "rps_strerror")
 
@@ -231,6 +232,14 @@ class RpsContext:
 
     def set_profiling(self, enable):
         _check(_lib.rps_set_profiling(self._h, 1 if enable else 0), self._h)
+
+    def get_kernel_times(self, capacity=4096):
+        """Per-launch kernel milliseconds (numpy array) since profiling was enabled / last read."""
+        import numpy as np
+        ms = np.zeros(capacity, dtype=np.float64)
+        cnt = ctypes.c_int64()
+        _check(_lib.rps_get_kernel_times(self._h, ms.ctypes.data, capacity, ctypes.byref(cnt)), self._h)
+        return ms[: min(cnt.value, capacity)]
 
     def get_kernel_time(self):
         """(total kernel milliseconds, launches) since profiling was enabled / last read."""
