@@ -102,8 +102,11 @@ int64_t rps_storage_elems(int32_t n, int64_t N, int32_t dtype, uint32_t flags);
  *   dtype          RPS_DTYPE_F32 or RPS_DTYPE_BF16 (storage; arithmetic is fp32, sums fp64)
  *   flags          RPS_FLAG_* (server assignment, storage layout)
  *   hip_stream     hipStream_t on which all work is enqueued (NULL = the default stream)
- * Allocates a fixed ~40 KB of device memory (per-round tables, reduction scratch) and a pinned
- * host staging buffer of a few KB; nothing proportional to N.  Errors: RPS_EINVAL, RPS_ENOMEM, RPS_EHIP.
+ * Allocates a fixed ~96 KB of device memory -- five tables of the O(n^2) delivery bits packed as one
+ * 64-bit word per block and direction (3 KB each: two for eager calls, one each for queries, stream
+ * capture and a forced outcome), 32 KB of reduction scratch for rps_consensus / rps_estimate_mixing,
+ * 48 KB of noise cells for the synthetic gradient -- and two pinned host staging buffers (3 KB,
+ * 16 KB); nothing proportional to N.  Errors: RPS_EINVAL, RPS_ENOMEM, RPS_EHIP.
  */
 int rps_create(rps_ctx **out, int32_t n, int64_t N, const int64_t *block_offsets, double p,
                float gamma, uint64_t seed, int32_t dtype, uint32_t flags, void *hip_stream);
@@ -120,7 +123,8 @@ int rps_create(rps_ctx **out, int32_t n, int64_t N, const int64_t *block_offsets
 int rps_create_external(rps_ctx **out, int32_t n, int32_t servers, int64_t N, const int64_t *block_offsets,
                         double p, float gamma, uint64_t seed, int32_t dtype, void *hip_stream);
 
-/* Free the context's tables.  Synchronises the stream first.  NULL is a no-op. */
+/* End of a run (Alg. 1's output is the workers' models, which stay in the caller's X): frees the
+   context's tables.  Synchronises the stream first.  NULL is a no-op. */
 int rps_destroy(rps_ctx *ctx);
 
 /*
@@ -167,8 +171,10 @@ int rps_local_step(rps_ctx *ctx, void *X, const void *G, uint64_t step);
 int rps_lossy_average(rps_ctx *ctx, void *X, uint64_t step);
 
 /*
- * Fused round: same result, bit for bit, as rps_local_step followed by rps_lossy_average, in
- * one pass over X (each element read at most once and written once).
+ * Fused round -- one iteration of Alg. 1 (steps 3-8; Sec. 4.1: local step, Reduce-Scatter and
+ * All-Gather with drops) for all n workers: same result, bit for bit, as rps_local_step followed by
+ * rps_lossy_average, in one pass over X (each element read at most once and written once).
+ * Arguments as for those two calls.
  */
 int rps_round(rps_ctx *ctx, void *X, const void *G, uint64_t step);
 
@@ -185,7 +191,9 @@ int rps_round(rps_ctx *ctx, void *X, const void *G, uint64_t step);
 int rps_round_gradient_averaging(rps_ctx *ctx, void *X, const void *G, uint64_t step);
 
 /*
- * Test hook: the network outcome the DEVICE generates for `step`, copied to HOST arrays.
+ * Test hook: the network outcome (Sec. 3: every message between a worker and a server is lost
+ * independently with probability p; Alg. 1 step 6: the servers are a fresh uniform permutation of
+ * the workers) that the DEVICE generates for `step`, copied to HOST arrays.
  *   up, down   n*B bytes each (B = number of blocks), index [worker * B + block]; 1 = delivered
  *   server     B int32, server[j] = worker that averages block j (-1: external server)
  * Any pointer may be NULL.  Ignores a mask override.  Synchronises the stream.
@@ -193,7 +201,19 @@ int rps_round_gradient_averaging(rps_ctx *ctx, void *X, const void *G, uint64_t 
 int rps_get_masks(rps_ctx *ctx, uint64_t step, uint8_t *up, uint8_t *down, int32_t *server);
 
 /*
- * Test hook: force the network outcome of every following round (HOST arrays, layout as in
+ * The same outcome computed on the HOST by the library's own host copy of the generator (no GPU, no
+ * context; same specification as the device kernel, separate code): what rps_get_masks must return
+ * for a context created with these n, p, seed and flags -- or, with servers > 0, for an
+ * rps_create_external context with that many servers (flags must then be 0; servers = 0 means the
+ * workers are the servers).  Output arrays as in rps_get_masks; any may be NULL.
+ * Errors: RPS_EINVAL (n or servers outside 1..64, p outside [0, 1], step >= 2^56, unknown flags).
+ */
+int rps_masks_host(int32_t n, int32_t servers, double p, uint64_t seed, uint32_t flags, uint64_t step, uint8_t *up,
+                   uint8_t *down, int32_t *server);
+
+/*
+ * Test hook: force the network outcome of every following round -- any pattern of lost messages the
+ * network model of Sec. 3 allows, e.g. every uplink lost, or one worker cut off (HOST arrays, layout as in
  * rps_get_masks; copied).  Every block must have at least one delivered uplink (a server
  * always holds its own copy).  Passing all three NULL restores the generated masks.
  * Synchronises the stream.

@@ -7,6 +7,7 @@
 #include <cmath>
 #include <cstring>
 #include <new>
+#include <utility>
 #include <vector>
 
 using rps::RoundParams;
@@ -257,6 +258,67 @@ hipError_t upload_scaled_radii(rps_ctx *ctx) {
     return hipStreamSynchronize(ctx->stream);
 }
 
+// ---------------------------------------------------------------------------------------
+// Host copy of the network-outcome generator (Sec. 3; Alg. 1 steps 6-7), written on its own: the
+// same specification the mask kernel implements on the device -- Philox4x32-10 keyed by the seed,
+// counter (worker, block, step low word, domain << 24 | step high 24 bits); domains 0 uplink,
+// 1 downlink, 2 server sort key -- evaluated here with plain 64-bit integer arithmetic, so that
+// the device table can be checked against something that never ran on the GPU.
+// ---------------------------------------------------------------------------------------
+uint32_t host_hash_word0(uint64_t seed, uint64_t step, uint32_t a, uint32_t b, uint32_t domain) {
+    uint32_t x0 = a, x1 = b, x2 = (uint32_t)step, x3 = (domain << 24) | (uint32_t)((step >> 32) & 0xFFFFFFu);
+    uint32_t ka = (uint32_t)seed, kb = (uint32_t)(seed >> 32);
+    for (int round = 0; round < 10; ++round) {
+        const uint64_t left = 0xD2511F53ull * x0, right = 0xCD9E8D57ull * x2;
+        const uint32_t y0 = (uint32_t)(right >> 32) ^ x1 ^ ka, y2 = (uint32_t)(left >> 32) ^ x3 ^ kb;
+        x1 = (uint32_t)right;
+        x3 = (uint32_t)left;
+        x0 = y0;
+        x2 = y2;
+        ka += 0x9E3779B9u;
+        kb += 0xBB67AE85u;
+    }
+    return x0;
+}
+
+// Fills a RoundTable's outcome fields (not the offsets) for `step`.
+void host_outcome(RoundTable &t, int n, int nb, uint64_t seed, uint64_t step, uint64_t threshold, int mode) {
+    int32_t server_of[rps::kMaxWorkers];
+    if (mode == 0) {
+        // block j goes to the worker whose sort key has rank j among (key, worker index)
+        std::pair<uint32_t, int> keyed[rps::kMaxWorkers];
+        for (int i = 0; i < n; ++i) keyed[i] = {host_hash_word0(seed, step, (uint32_t)i, 0u, 2u), i};
+        std::sort(keyed, keyed + n);
+        for (int j = 0; j < nb; ++j) server_of[j] = keyed[j].second;
+    } else {
+        for (int j = 0; j < nb; ++j) server_of[j] = mode == 1 ? j : -1;
+    }
+    for (int j = 0; j < nb; ++j) {
+        uint64_t u = 0, d = 0;
+        for (int i = 0; i < n; ++i) {
+            const bool self = i == server_of[j];   // not a network message
+            if (self || (uint64_t)host_hash_word0(seed, step, (uint32_t)i, (uint32_t)j, 0u) >= threshold) u |= 1ull << i;
+            if (self || (uint64_t)host_hash_word0(seed, step, (uint32_t)i, (uint32_t)j, 1u) >= threshold) d |= 1ull << i;
+        }
+        t.ucol[j] = u;
+        t.dcol_drawn[j] = d;
+        t.dcol[j] = u ? d : 0;
+        t.cnt[j] = __builtin_popcountll(u);
+        t.inv_cnt[j] = u ? 1.0 / (double)t.cnt[j] : 0.0;
+        t.server[j] = server_of[j];
+    }
+}
+
+void unpack_outcome(const RoundTable &t, int n, int nb, uint8_t *up, uint8_t *down, int32_t *server) {
+    for (int i = 0; i < n; ++i)
+        for (int j = 0; j < nb; ++j) {
+            if (up) up[i * nb + j] = (uint8_t)((t.ucol[j] >> i) & 1);
+            if (down) down[i * nb + j] = (uint8_t)((t.dcol_drawn[j] >> i) & 1);
+        }
+    if (server)
+        for (int j = 0; j < nb; ++j) server[j] = t.server[j];
+}
+
 struct DeviceGuard {   // make the context's device current for the duration of a call
     int prev = -1;
     bool ok = false;
@@ -499,14 +561,22 @@ int rps_get_masks(rps_ctx *ctx, uint64_t step, uint8_t *up, uint8_t *down, int32
                                    ctx->stream));
     RPS_HIP(ctx, hipMemcpyAsync(ctx->staging, ctx->tab_query, sizeof(RoundTable), hipMemcpyDeviceToHost, ctx->stream));
     RPS_HIP(ctx, hipStreamSynchronize(ctx->stream));
-    const int n = ctx->n, nb = ctx->nb;
-    for (int i = 0; i < n; ++i)
-        for (int j = 0; j < nb; ++j) {
-            if (up) up[i * nb + j] = (uint8_t)((ctx->staging->ucol[j] >> i) & 1);
-            if (down) down[i * nb + j] = (uint8_t)((ctx->staging->dcol_drawn[j] >> i) & 1);
-        }
-    if (server)
-        for (int j = 0; j < nb; ++j) server[j] = ctx->staging->server[j];
+    unpack_outcome(*ctx->staging, ctx->n, ctx->nb, up, down, server);
+    return RPS_OK;
+}
+
+int rps_masks_host(int32_t n, int32_t servers, double p, uint64_t seed, uint32_t flags, uint64_t step, uint8_t *up,
+                   uint8_t *down, int32_t *server) {
+    if (n < 1 || n > rps::kMaxWorkers || servers < 0 || servers > rps::kMaxWorkers) return RPS_EINVAL;
+    if (!(p >= 0.0 && p <= 1.0) || !step_ok(step)) return RPS_EINVAL;
+    if (flags & ~(uint32_t)(RPS_FLAG_SERVER_IDENTITY | RPS_FLAG_LAYOUT_TILED)) return RPS_EINVAL;
+    if (servers > 0 && flags != 0) return RPS_EINVAL;   // as rps_create_external: no flags
+    const int nb = servers > 0 ? servers : n;
+    const int mode = servers > 0 ? 2 : ((flags & RPS_FLAG_SERVER_IDENTITY) ? 1 : 0);
+    RoundTable t;
+    std::memset(&t, 0, sizeof(t));
+    host_outcome(t, n, nb, seed, step, (uint64_t)std::floor(p * 4294967296.0), mode);
+    unpack_outcome(t, n, nb, up, down, server);
     return RPS_OK;
 }
 

@@ -27,6 +27,7 @@
 #include "rps_internal.h"
 
 #include <atomic>
+#include <type_traits>
 
 namespace rps {
 namespace {
@@ -259,9 +260,20 @@ __device__ __forceinline__ void noise_fill_begin(NoiseLds &lds, const float *__r
                                              (__attribute__((address_space(3))) void *)(dst + piece * 256), 16, 0, 0);
     }
 }
-__device__ __forceinline__ void noise_fill_end(NoiseLds &) { __syncthreads(); }
+// PENDING = vector memory instructions this wavefront has issued since noise_fill_begin() (its first
+// tile's loads): the memory counter retires in order, so waiting until only PENDING operations are
+// outstanding waits for the copy and leaves those loads in flight -- the workgroup barrier then
+// does not line the wavefronts up on their tile loads, and the noise of the first tile is computed
+// under their latency like that of every later one.  (A __syncthreads() here makes the compiler
+// drain the whole memory queue first.)
+template <int PENDING>
+__device__ __forceinline__ void noise_fill_end(NoiseLds &) {
+    static_assert(PENDING >= 0 && PENDING < 64, "the counter holds 6 bits");
+    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(PENDING) : "memory");
+}
 template <int WPB>
 __device__ __forceinline__ void noise_fill_begin(NoNoiseLds &, const float *, int, int) {}
+template <int PENDING>
 __device__ __forceinline__ void noise_fill_end(NoNoiseLds &) {}
 
 __device__ __forceinline__ void box_muller_pair(uint32_t word, const NoiseLds &lds, float &even, float &odd) {
@@ -556,9 +568,12 @@ __device__ __forceinline__ void process_chunk(ST *__restrict__ Xt, const RoundPa
 // One tile, all n rows.  The row loop is software-pipelined by hand: the loads of chunk k+1
 // are issued before chunk k is processed, so a wavefront overlaps its own memory latency with
 // its own arithmetic and few resident wavefronts suffice.
-template <typename ST, int GRAD, int R, bool FULL, typename LDS>
+// after_first_loads(count) is called once the first chunk's loads are issued, with their number
+// (see noise_fill_end).
+template <typename ST, int GRAD, int R, bool FULL, typename LDS, typename F>
 __device__ __forceinline__ void round_tile(ST *__restrict__ X, const ST *__restrict__ G, const RoundParams &prm,
-                                           const LDS &lds, const LaneCols &lc, uint64_t ucol, uint64_t dcol, double inv) {
+                                           const LDS &lds, const LaneCols &lc, uint64_t ucol, uint64_t dcol, double inv,
+                                           const F &after_first_loads) {
     using S = Storage<ST>;
     using Acc = typename S::Acc;
     using Raw = typename S::Raw;
@@ -577,6 +592,7 @@ __device__ __forceinline__ void round_tile(ST *__restrict__ X, const ST *__restr
     cur.row = 0;
     Raw xa[R], xb[R], ga[RG], gb[RG];
     load_chunk<ST, GRAD, R, FULL>(cur, prm, lc, xa, ga);
+    after_first_loads(std::integral_constant<int, FULL ? (GRAD == kGradBuffer ? 2 : 1) * R : 0>{});
     int i0 = 0;
     // steady state: every load is unconditional, so the number of requests in flight at each
     // point is static and the waits inserted by the compiler leave the prefetch outstanding
@@ -613,9 +629,14 @@ __global__ __launch_bounds__(WPB * 64) void round_kernel(ST *__restrict__ X, con
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int j = blockIdx.y;
-    noise_fill_begin<WPB>(lds, prm.noise_cells, wave, lane);   // every wavefront, before any exit
-    noise_fill_end(lds);
-    prepare_next_outcome(prm, linear_block() == 0 && wave == 0, j, lane);
+    // the noise cells travel to LDS while the first tile's loads are in flight (as in
+    // round_kernel_narrow): every wavefront passes the copy's barrier exactly once
+    noise_fill_begin<WPB>(lds, prm.noise_cells, wave, lane);
+    bool fill_pending = true;
+    const auto finish_fill = [&](auto pending) {
+        if (fill_pending) noise_fill_end<decltype(pending)::value>(lds);
+        fill_pending = false;
+    };
     const int64_t lo = tab->off[j], hi = tab->off[j + 1];
     const uint64_t ucol = tab->ucol[j], dcol = tab->dcol[j];
     const double inv = tab->inv_cnt[j];
@@ -630,10 +651,12 @@ __global__ __launch_bounds__(WPB * 64) void round_kernel(ST *__restrict__ X, con
         lc.lo = lo;
         lc.hi = hi;
         if (prm.vec_ok && tile0 >= lo && tile0 + TILE <= hi)   // wave-uniform
-            round_tile<ST, GRAD, R, true>(X, G, prm, lds, lc, ucol, dcol, inv);
+            round_tile<ST, GRAD, R, true>(X, G, prm, lds, lc, ucol, dcol, inv, finish_fill);
         else
-            round_tile<ST, GRAD, 2, false>(X, G, prm, lds, lc, ucol, dcol, inv);
+            round_tile<ST, GRAD, 2, false>(X, G, prm, lds, lc, ucol, dcol, inv, finish_fill);
     }
+    finish_fill(std::integral_constant<int, 0>{});
+    prepare_next_outcome(prm, linear_block() == 0 && wave == 0, j, lane);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -693,6 +716,46 @@ __device__ __forceinline__ void store_seg(ST *base, uint32_t eoff, uint32_t limi
         for (int e = 0; e < S::VEC; ++e)
             if (c0 + e >= lo && c0 + e < hi) S::store1(p + e, x[e]);
     }
+}
+
+// Sum of a double over the PG lane groups (of 8 lanes each) that share a tile, left in every one of
+// them -- the same additions in the same order as a butterfly of __shfl_xor steps over lane distances
+// 8, 16 and 32 (a + b for the pair of groups, whichever lane computes it), but through the
+// cross-lane VALU paths instead of three dependent LDS permutes per 32-bit half:
+//   distance 8   DPP row rotate by 8 within each row of 16 lanes
+//   distance 16  v_permlane16_swap(x, x): rows 0,1 <- (row 0, row 1), rows 2,3 <- (row 2, row 3)
+//   distance 32  v_permlane32_swap(x, x): both halves <- (lanes 0-31, lanes 32-63)
+// Used where the kernel also keeps the LDS busy with noise gathers (bf16, 64 workers: +2.5 %; it
+// is not faster where the LDS is otherwise idle).
+__device__ __forceinline__ double pair_to_double(uint32_t lo, uint32_t hi) {
+    const uint64_t b = ((uint64_t)hi << 32) | lo;
+    double d;
+    __builtin_memcpy(&d, &b, 8);
+    return d;
+}
+template <int PG>
+__device__ __forceinline__ double sum_lane_groups(double a) {
+    uint64_t b;
+    if (PG >= 2) {
+        __builtin_memcpy(&b, &a, 8);
+        constexpr int kRowRotate8 = 0x128;
+        const uint32_t lo = __builtin_amdgcn_update_dpp(0u, (uint32_t)b, kRowRotate8, 0xf, 0xf, false);
+        const uint32_t hi = __builtin_amdgcn_update_dpp(0u, (uint32_t)(b >> 32), kRowRotate8, 0xf, 0xf, false);
+        a += pair_to_double(lo, hi);
+    }
+    if (PG >= 4) {
+        __builtin_memcpy(&b, &a, 8);
+        const auto lo = __builtin_amdgcn_permlane16_swap((uint32_t)b, (uint32_t)b, false, false);
+        const auto hi = __builtin_amdgcn_permlane16_swap((uint32_t)(b >> 32), (uint32_t)(b >> 32), false, false);
+        a = pair_to_double(lo[0], hi[0]) + pair_to_double(lo[1], hi[1]);
+    }
+    if (PG >= 8) {
+        __builtin_memcpy(&b, &a, 8);
+        const auto lo = __builtin_amdgcn_permlane32_swap((uint32_t)b, (uint32_t)b, false, false);
+        const auto hi = __builtin_amdgcn_permlane32_swap((uint32_t)(b >> 32), (uint32_t)(b >> 32), false, false);
+        a = pair_to_double(lo[0], hi[0]) + pair_to_double(lo[1], hi[1]);
+    }
+    return a;
 }
 
 // PG = lane groups per tile (8, 4, 2 or 1).  With 16 or more workers a tile takes all 8 lane groups
@@ -805,10 +868,15 @@ struct NarrowTile {
 
     __device__ __forceinline__ void finish(Acc acc[VEC], double inv, int steps) const {
         // combine the lane groups: after the butterfly every lane of a column group holds the same sum
+        if (GRAD == kGradSynthetic && LPR == 8) {
 #pragma unroll
-        for (int o = LPR; o < LPR * PG; o <<= 1) {
+            for (int e = 0; e < VEC; ++e) acc[e] = sum_lane_groups<PG>(acc[e]);
+        } else {
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) acc[e] += __shfl_xor(acc[e], o, 64);
+            for (int o = LPR; o < LPR * PG; o <<= 1) {
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) acc[e] += __shfl_xor(acc[e], o, 64);
+            }
         }
         float vt[VEC];
 #pragma unroll
@@ -837,7 +905,8 @@ struct NarrowTile {
         __builtin_amdgcn_s_setprio(3);
         load_chunk(0, xa, ga);
         __builtin_amdgcn_s_setprio(0);
-        after_first_loads();
+        // vector loads just issued (the element-wise path issues many small ones: it waits for all)
+        after_first_loads(std::integral_constant<int, FULL ? (GRAD == kGradBuffer ? 4 : 2) * CP : 0>{});
         if constexpr (SINGLE) {
             process_chunk(0, xa, ga, acc);
             finish(acc, inv, steps);
@@ -878,8 +947,8 @@ __global__ __launch_bounds__(WPB * 64) void round_kernel_narrow(ST *__restrict__
     // wavefront that has no tile: every wavefront passes the barrier exactly once
     noise_fill_begin<WPB>(lds, prm.noise_cells, wave, lane);
     bool fill_pending = true;
-    const auto finish_fill = [&] {
-        if (fill_pending) noise_fill_end(lds);
+    const auto finish_fill = [&](auto pending) {
+        if (fill_pending) noise_fill_end<decltype(pending)::value>(lds);
         fill_pending = false;
     };
     const int64_t lo = tab->off[j], hi = tab->off[j + 1];
@@ -900,7 +969,7 @@ __global__ __launch_bounds__(WPB * 64) void round_kernel_narrow(ST *__restrict__
             t.template run<SINGLE>(inv, finish_fill);
         }
     }
-    finish_fill();
+    finish_fill(std::integral_constant<int, 0>{});
     prepare_next_outcome(prm, linear_block() == 0 && wave == 0, j, lane);
 }
 
@@ -910,9 +979,9 @@ __global__ __launch_bounds__(WPB * 64) void round_kernel_narrow(ST *__restrict__
 // noise hash of a (4 columns x 2 workers) patch is evaluated by both rows' lanes, each keeping
 // its half.  A wavefront step covers U adjacent chunks of 1 KB (all loads first, then the
 // arithmetic and the stores); it takes tiles_per_wave steps.
-template <typename ST, int GRAD, bool FULL, int U, typename LDS>
+template <typename ST, int GRAD, bool FULL, int U, typename LDS, typename F>
 __device__ __forceinline__ void local_step_chunks(ST *__restrict__ X, const ST *__restrict__ G, const RoundParams &prm,
-                                                  const LDS &lds, LaneCols lc, int i, int chunks) {
+                                                  const LDS &lds, LaneCols lc, int i, int chunks, const F &after_loads) {
     using S = Storage<ST>;
     constexpr int VEC = S::VEC;
     constexpr int TILE = 64 * VEC;
@@ -928,6 +997,7 @@ __device__ __forceinline__ void local_step_chunks(ST *__restrict__ X, const ST *
             if (GRAD == kGradBuffer) gr[GRAD == kGradBuffer ? u : 0] = load_raw<ST, FULL>(grow + u * TILE, lc);
         }
     }
+    after_loads(std::integral_constant<int, FULL ? (GRAD == kGradBuffer ? 2 : 1) * U : 0>{});   // FULL: chunks == U
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         if (u < chunks) {
@@ -957,7 +1027,11 @@ __global__ __launch_bounds__(WPB * 64) void local_step_kernel(ST *__restrict__ X
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int row = blockIdx.y;
     noise_fill_begin<WPB>(lds, prm.noise_cells, wave, lane);
-    noise_fill_end(lds);
+    bool fill_pending = true;
+    const auto finish_fill = [&](auto pending) {
+        if (fill_pending) noise_fill_end<decltype(pending)::value>(lds);
+        fill_pending = false;
+    };
     for (int it = 0; it < prm.tiles_per_wave; ++it) {
         const int64_t tile0 = unit_index(it, WPB, wave) * (U * TILE);
         if (tile0 >= prm.N) break;   // wave-uniform
@@ -969,10 +1043,11 @@ __global__ __launch_bounds__(WPB * 64) void local_step_kernel(ST *__restrict__ X
         const int64_t left = (prm.N - tile0 + TILE - 1) / TILE;
         const int chunks = (int)(left < U ? left : U);
         if (prm.vec_ok && tile0 + U * TILE <= prm.N)
-            local_step_chunks<ST, GRAD, true, U>(X, G, prm, lds, lc, row, U);
+            local_step_chunks<ST, GRAD, true, U>(X, G, prm, lds, lc, row, U, finish_fill);
         else
-            local_step_chunks<ST, GRAD, false, U>(X, G, prm, lds, lc, row, chunks);
+            local_step_chunks<ST, GRAD, false, U>(X, G, prm, lds, lc, row, chunks, finish_fill);
     }
+    finish_fill(std::integral_constant<int, 0>{});
 }
 
 // Local step on the tiled layout: the storage is one run of (tile, worker) segments of
@@ -991,7 +1066,7 @@ __global__ __launch_bounds__(WPB * 64) void local_step_tiled_kernel(ST *__restri
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     noise_fill_begin<WPB>(lds, prm.noise_cells, wave, lane);
-    noise_fill_end(lds);
+    noise_fill_end<0>(lds);
     const int64_t tiles = (prm.N + TILE - 1) / TILE;
     for (int it = 0; it < prm.tiles_per_wave; ++it) {
         const int64_t kb0 = unit_index(it, WPB, wave) * U;
@@ -1107,7 +1182,9 @@ hipError_t launch_round_narrow(ST *X, const ST *G, const RoundTable *tab, RoundP
     const int pg = need > 4 ? 8 : (need > 2 ? 4 : (need > 1 ? 2 : 1));
     const int64_t width = (int64_t)(GROUPS / pg) * TILE;   // columns per wavefront and step
     const int64_t steps = (max_block_cols + 2 * width - 2) / width;
-    prm.tiles_per_wave = steps_per_wave(GRAD, steps, WPB, prm.blocks, tune.tiles_per_wave, 2);
+    // fp32 with 24 or more workers: one tile (4 KB and more) per wavefront is best; otherwise two steps
+    prm.tiles_per_wave = steps_per_wave(GRAD, steps, WPB, prm.blocks, tune.tiles_per_wave,
+                                        sizeof(ST) == 4 && prm.n >= 24 ? 1 : 2);
     const int64_t per_wg = (int64_t)WPB * prm.tiles_per_wave;
     const dim3 grid = folded_grid8((steps + per_wg - 1) / per_wg, (unsigned)prm.blocks);
     const size_t lds = occupancy_pad(tune.max_waves_per_cu, WPB, static_lds_bytes<GRAD>());

@@ -42,6 +42,8 @@ _lib.rps_lossy_average.argtypes = [_ctx_p, ctypes.c_void_p, ctypes.c_uint64]
 _lib.rps_round.argtypes = [_ctx_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64]
 _lib.rps_round_gradient_averaging.argtypes = [_ctx_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64]
 _lib.rps_get_masks.argtypes = [_ctx_p, ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+_lib.rps_masks_host.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_double, ctypes.c_uint64, ctypes.c_uint32,
+                                ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
 _lib.rps_set_mask_override.argtypes = [_ctx_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
 _lib.rps_consensus.argtypes = [_ctx_p, ctypes.c_void_p, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
 _lib.rps_consensus_static.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_int32, ctypes.c_uint32,
@@ -58,13 +60,13 @@ _lib.rps_last_hip_error.argtypes = [_ctx_p]
 _lib.rps_strerror.argtypes = [ctypes.c_int]
 _lib.rps_strerror.restype = ctypes.c_char_p
 for _name in ("rps_create", "rps_create_external", "rps_destroy", "rps_set_synthetic_grad", "rps_set_gamma", "rps_set_row_pitch", "rps_local_step",
-              "rps_lossy_average", "rps_round", "rps_round_gradient_averaging", "rps_get_masks", "rps_set_mask_override",
+              "rps_lossy_average", "rps_round", "rps_round_gradient_averaging", "rps_get_masks", "rps_masks_host", "rps_set_mask_override",
               "rps_consensus", "rps_consensus_static", "rps_estimate_mixing", "rps_convert_layout", "rps_set_launch_tuning", "rps_noise_cells", "rps_set_profiling", "rps_get_kernel_time", "rps_get_kernel_times", "rps_last_hip_error"):
     getattr(_lib, _name).restype = ctypes.c_int
 
 EXPORTS = ("rps_create", "rps_create_external", "rps_storage_elems", "rps_destroy", "rps_set_synthetic_grad", "rps_set_gamma",
            "rps_set_row_pitch", "rps_recommended_row_pitch", "rps_local_step",
-           "rps_lossy_average", "rps_round", "rps_round_gradient_averaging", "rps_get_masks", "rps_set_mask_override",
+           "rps_lossy_average", "rps_round", "rps_round_gradient_averaging", "rps_get_masks", "rps_masks_host", "rps_set_mask_override",
            "rps_consensus", "rps_consensus_static", "rps_estimate_mixing", "rps_convert_layout", "rps_set_launch_tuning", "rps_noise_cells", "rps_set_profiling", "rps_get_kernel_time", "rps_get_kernel_times",
            "rps_last_hip_error",
            "rps_strerror")
@@ -299,6 +301,17 @@ def rps_round_gradient_averaging(ctx, X, G, step):
 
 def rps_get_masks(ctx, step):
     return ctx.get_masks(step)
+
+
+def rps_masks_host(n, p, seed, step, flags=0, servers=0):
+    """(server, up, down) of `step` from the library's host copy of the generator (no GPU)."""
+    import numpy as np
+    nb = servers if servers > 0 else n
+    up = np.empty((max(n, 0), max(nb, 0)), dtype=np.uint8)
+    down = np.empty_like(up)
+    server = np.empty(max(nb, 0), dtype=np.int32)
+    _check(_lib.rps_masks_host(n, servers, p, seed, flags, step, up.ctypes.data, down.ctypes.data, server.ctypes.data))
+    return server, up, down
 
 
 def rps_consensus(ctx, X):

@@ -11,6 +11,7 @@ import torch
 
 import workloads
 from oracle import rps_oracle as oracle
+from paper_1810_07766_amd import rps
 
 RTOL = {"f32": 1e-6, "bf16": 1e-2}
 
@@ -58,6 +59,9 @@ def assert_close(gpu: np.ndarray, ref: np.ndarray, offsets, dtype: str, cols=Non
 def masks_equal(ctx, seed, step, n, p, identity=False):
     s_g, u_g, d_g = ctx.get_masks(step)
     s_o, u_o, d_o = oracle.masks(seed, step, n, p, identity)
+    # the library's host copy of the generator must tell the same story as its device table
+    s_h, u_h, d_h = rps.rps_masks_host(n, p, seed, step, flags=rps.RPS_FLAG_SERVER_IDENTITY if identity else 0)
+    assert (s_g == s_h).all() and (u_g == u_h).all() and (d_g == d_h).all(), f"device and host generator differ at step {step}"
     assert (s_g == s_o).all(), f"server permutation differs at step {step}"
     assert (u_g == u_o).all(), f"uplink mask differs at step {step}"
     assert (d_g == d_o).all(), f"downlink mask differs at step {step}"

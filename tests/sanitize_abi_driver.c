@@ -47,6 +47,21 @@ int main(void)
     for (int k = 0; k < 4096; ++k) sum += (double)cs[2 * k] * cs[2 * k] + (double)cs[2 * k + 1] * cs[2 * k + 1];
     EXPECT(fabs(sum - 4096.0) < 1e-3 && radius[0] > 4.24f && radius[4095] < 0.016f);
     free(radius); free(cs);
+    /* host copy of the network-outcome generator: exact-size buffers at the smallest and largest shapes */
+    for (int n = 1; n <= 64; n += 21) {
+        const int servers[3] = { 0, 1, 64 };
+        for (int k = 0; k < 3; ++k) {
+            const int nb = servers[k] ? servers[k] : n;
+            uint8_t *up = (uint8_t *)malloc((size_t)n * nb), *down = (uint8_t *)malloc((size_t)n * nb);
+            int32_t *srv = (int32_t *)malloc((size_t)nb * sizeof(int32_t));
+            EXPECT(rps_masks_host(n, servers[k], 0.25, 0x123456789abcdefULL, 0, (1ULL << 56) - 1, up, down, srv) == RPS_OK);
+            EXPECT(rps_masks_host(n, servers[k], 1.0, 1, 0, 3, NULL, NULL, NULL) == RPS_OK);
+            for (int j = 0; j < nb; ++j) EXPECT(servers[k] ? srv[j] == -1 : (srv[j] >= 0 && srv[j] < n && up[srv[j] * nb + j] == 1));
+            free(up); free(down); free(srv);
+        }
+    }
+    EXPECT(rps_masks_host(65, 0, 0.1, 0, 0, 0, NULL, NULL, NULL) == RPS_EINVAL);
+    EXPECT(rps_masks_host(4, 0, 0.1, 0, 0, 1ULL << 56, NULL, NULL, NULL) == RPS_EINVAL);
     for (int code = 1; code >= -7; --code) EXPECT(rps_strerror(code) != NULL);
     EXPECT(rps_last_hip_error(NULL) == 0);
     printf("abi host paths ok\n");

@@ -121,3 +121,38 @@ def test_noise_cells_of_the_library_equal_the_oracle():
     assert (radius.view(np.uint32) == r.view(np.uint32)).all()
     assert (cos_sin[:, 0].view(np.uint32) == c.view(np.uint32)).all()
     assert (cos_sin[:, 1].view(np.uint32) == s.view(np.uint32)).all()
+
+
+def test_host_copy_of_the_mask_generator_equals_the_oracle():
+    """rps_masks_host (the library's own host implementation of the network-outcome generator: Sec. 3
+    drops, Alg. 1 step 6 permutation) against the oracle, bit for bit, without a GPU: worker counts
+    1..64, both server rules, external servers, the extreme drop rates and the largest steps."""
+    import numpy as np
+    _ensure_built()
+    from oracle import rps_oracle as oracle
+    from paper_1810_07766_amd import rps
+    rng = np.random.default_rng(7)
+    steps = [0, 1, 2, 2 ** 32 - 1, 2 ** 32, 2 ** 40 + 7, 2 ** 56 - 1]
+    for n in list(range(1, 9)) + [15, 16, 17, 31, 32, 33, 63, 64]:
+        for p in (0.0, 0.01, 0.3, 1.0):
+            seed = int(rng.integers(0, 2 ** 63)) * 2 + int(rng.integers(0, 2))
+            for step in steps + [int(rng.integers(0, 2 ** 56))]:
+                for identity in (False, True):
+                    s_h, u_h, d_h = rps.rps_masks_host(n, p, seed, step, flags=rps.RPS_FLAG_SERVER_IDENTITY if identity else 0)
+                    s_o, u_o, d_o = oracle.masks(seed, step, n, p, identity)
+                    assert (s_h == s_o).all() and (u_h == u_o).all() and (d_h == d_o).all(), (n, p, seed, step, identity)
+            for servers in (1, 3, 64):
+                s_h, u_h, d_h = rps.rps_masks_host(n, p, seed, 5, servers=servers)
+                s_o, u_o, d_o = oracle.masks(seed, 5, n, p, external_servers=servers)
+                assert (s_h == s_o).all() and (u_h == u_o).all() and (d_h == d_o).all(), (n, p, seed, servers)
+    # argument errors
+    for bad in (dict(n=0), dict(n=65), dict(p=-0.1), dict(p=float("nan")), dict(step=2 ** 56), dict(flags=8),
+                dict(servers=65), dict(servers=3, flags=1)):
+        kw = dict(n=4, p=0.1, seed=0, step=0, flags=0, servers=0)
+        kw.update(bad)
+        try:
+            rps.rps_masks_host(**kw)
+        except rps.RpsError as e:
+            assert e.code == rps.RPS_EINVAL
+        else:
+            raise AssertionError(f"accepted {bad}")
