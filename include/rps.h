@@ -282,7 +282,9 @@ int rps_convert_layout(rps_ctx *ctx, void *dst, const void *src, int32_t to_tile
  *   waves_per_workgroup  1, 2, 4, 8 or 16 (a workgroup's wavefronts own adjacent tiles and, with the
  *                        in-register gradient, share one LDS copy of the noise cells); rounded to
  *                        the nearest width the kernel in question is built for
- *   max_waves_per_cu     cap on resident wavefronts per compute unit (0 = no cap)
+ *   max_waves_per_cu     cap on resident wavefronts per compute unit (0 = no cap); rounded down to whole
+ *                        workgroups, and never below two workgroups (a workgroup holds at most 64 KB
+ *                        of the compute unit's 160 KB of LDS); rps_query_occupancy shows the outcome
  *   tiles_per_wave       tiles a wavefront works through with the in-register gradient, 1..64
  *                        (0 = chosen per launch)
  * Until this is called every launch takes the measured best shape for its worker count, dtype
@@ -290,6 +292,17 @@ int rps_convert_layout(rps_ctx *ctx, void *dst, const void *src, int32_t to_tile
  */
 int rps_set_launch_tuning(rps_ctx *ctx, int32_t rows_in_flight, int32_t waves_per_workgroup,
                           int32_t max_waves_per_cu, int32_t tiles_per_wave);
+
+/*
+ * Test hook for the launch shape: how many wavefronts of the round kernel one compute unit can hold
+ * with the launch shape this context would use for the given gradient source (0 = none, i.e.
+ * rps_lossy_average; 1 = gradient buffer; 2 = in-register gradient) -- the answer of the HIP
+ * runtime's occupancy calculator for that kernel, its workgroup size and the LDS it is launched
+ * with.  Nothing is launched.  The library caps occupancy through an LDS allocation it never touches
+ * (max_waves_per_cu of rps_set_launch_tuning and the built-in defaults); this call lets a test
+ * check that the cap arrives.  Errors: RPS_EINVAL, RPS_EHIP.
+ */
+int rps_query_occupancy(rps_ctx *ctx, int32_t gradient_source, int32_t *waves_per_cu);
 
 /*
  * Test hook: the cell values of the synthetic gradient noise as the library computes them on the

@@ -92,7 +92,7 @@ rps::LaunchTuning default_tuning(int32_t n, int32_t dtype, int grad_mode) {
     if (grad_mode == rps::kGradBuffer) return n >= 12 ? rps::LaunchTuning{2, 1, 5, 0} : rps::LaunchTuning{4, 1, 6, 0};
     // in-register gradient: the workgroup's wavefronts share the LDS copy of the noise cells
     if (dtype == RPS_DTYPE_BF16) return rps::LaunchTuning{2, 4, 0, 0};
-    return n >= 24 ? rps::LaunchTuning{2, 2, 0, 0} : rps::LaunchTuning{2, 4, 12, 0};
+    return n >= 24 ? rps::LaunchTuning{2, 2, 0, 0} : rps::LaunchTuning{4, 4, 12, 0};
 }
 
 rps::LaunchTuning tuning_for(const rps_ctx *ctx, int grad_mode) {
@@ -712,6 +712,23 @@ int rps_set_launch_tuning(rps_ctx *ctx, int32_t rows_in_flight, int32_t waves_pe
     if (max_waves_per_cu < 0 || tiles_per_wave < 0 || tiles_per_wave > 64) return RPS_EINVAL;
     ctx->tune = rps::LaunchTuning{rows_in_flight, waves_per_workgroup, max_waves_per_cu, tiles_per_wave};
     ctx->tune_set = true;
+    return RPS_OK;
+}
+
+int rps_query_occupancy(rps_ctx *ctx, int32_t gradient_source, int32_t *waves_per_cu) {
+    if (!ctx || !waves_per_cu) return RPS_EINVAL;
+    if (gradient_source != rps::kGradNone && gradient_source != rps::kGradBuffer && gradient_source != rps::kGradSynthetic)
+        return RPS_EINVAL;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return RPS_EHIP;
+    // no array is touched: any aligned address serves to pick the 128-bit kernels
+    const RoundParams prm = make_params(ctx, nullptr, nullptr, 0);
+    rps::LaunchTuning tune = tuning_for(ctx, gradient_source);
+    int waves = 0;
+    tune.occupancy_query = &waves;
+    RPS_HIP(ctx, rps::launch_round(ctx->dtype, gradient_source, nullptr, nullptr, nullptr, prm, ctx->max_block_cols, tune,
+                                   ctx->stream));
+    *waves_per_cu = waves;
     return RPS_OK;
 }
 

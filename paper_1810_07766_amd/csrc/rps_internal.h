@@ -57,6 +57,8 @@ struct LaunchTuning {
     int waves_per_workgroup;   // wavefronts per workgroup (adjacent tiles): 1, 2, 4, 8 or 16 (rounded to what the kernel offers)
     int max_waves_per_cu;      // occupancy cap; 0 or >= 32: none
     int tiles_per_wave;        // steps per wavefront in kernels that generate noise; 0: chosen by the launcher
+    int *occupancy_query = nullptr;   // non-null: launch_round launches nothing and stores here the wavefronts per compute
+                                      // unit that the chosen kernel and launch shape allow
 };
 
 // Host side of the synthetic gradient noise: the kNoiseGrid radius values sqrt(-2 ln((k + 1/2)/kNoiseGrid))

@@ -1157,6 +1157,23 @@ int steps_per_wave(int grad_mode, int64_t wave_steps_per_row, int wpb, int64_t r
     return t;
 }
 
+// Launches the round kernel `kernel` -- or, when the tuning carries an occupancy query, launches
+// nothing and reports how many wavefronts of this kernel, workgroup size and dynamic LDS size the
+// runtime's occupancy calculator lets one compute unit hold (what the occupancy cap above is meant
+// to control).
+template <typename K, typename ST>
+hipError_t launch_or_query(K kernel, dim3 grid, int wpb, size_t lds, hipStream_t stream, const LaunchTuning &tune, ST *X,
+                           const ST *G, const RoundTable *tab, const RoundParams &prm) {
+    if (tune.occupancy_query != nullptr) {
+        int wgs = 0;
+        const hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&wgs, kernel, wpb * 64, lds);
+        *tune.occupancy_query = wgs * wpb;
+        return e;
+    }
+    hipLaunchKernelGGL(kernel, grid, dim3(wpb * 64), lds, stream, X, G, tab, prm);
+    return hipGetLastError();
+}
+
 template <typename ST, int GRAD, int R, int WPB>
 hipError_t launch_round_v(ST *X, const ST *G, const RoundTable *tab, RoundParams prm, int64_t max_block_cols,
                           const LaunchTuning &tune, hipStream_t stream) {
@@ -1167,8 +1184,7 @@ hipError_t launch_round_v(ST *X, const ST *G, const RoundTable *tab, RoundParams
     const int64_t per_wg = (int64_t)WPB * prm.tiles_per_wave;
     const dim3 grid = folded_grid8((tiles + per_wg - 1) / per_wg, (unsigned)prm.blocks);
     const size_t lds = occupancy_pad(tune.max_waves_per_cu, WPB, static_lds_bytes<GRAD>());
-    hipLaunchKernelGGL((round_kernel<ST, GRAD, R, WPB>), grid, dim3(WPB * 64), lds, stream, X, G, tab, prm);
-    return hipGetLastError();
+    return launch_or_query(round_kernel<ST, GRAD, R, WPB>, grid, WPB, lds, stream, tune, X, G, tab, prm);
 }
 
 template <typename ST, int GRAD, int LPR, int WPB>
@@ -1188,9 +1204,8 @@ hipError_t launch_round_narrow(ST *X, const ST *G, const RoundTable *tab, RoundP
     const int64_t per_wg = (int64_t)WPB * prm.tiles_per_wave;
     const dim3 grid = folded_grid8((steps + per_wg - 1) / per_wg, (unsigned)prm.blocks);
     const size_t lds = occupancy_pad(tune.max_waves_per_cu, WPB, static_lds_bytes<GRAD>());
-#define RPS_N(PG, CP, SINGLE)                                                                                       \
-    hipLaunchKernelGGL((round_kernel_narrow<ST, GRAD, LPR, PG, CP, SINGLE, WPB>), grid, dim3(WPB * 64), lds, stream, X, G, \
-                       tab, prm)
+#define RPS_N(PG, CP, SINGLE) \
+    return launch_or_query(round_kernel_narrow<ST, GRAD, LPR, PG, CP, SINGLE, WPB>, grid, WPB, lds, stream, tune, X, G, tab, prm)
     if (pg == 1 && pairs <= 1)
         RPS_N(1, 1, true);
     else if (pg == 1)
@@ -1212,7 +1227,6 @@ hipError_t launch_round_narrow(ST *X, const ST *G, const RoundTable *tab, RoundP
     else
         RPS_N(8, 2, false);
 #undef RPS_N
-    return hipGetLastError();
 }
 
 // Workgroup widths: kernels that generate noise share the LDS copy of the noise cells among 4, 8 or

@@ -53,6 +53,7 @@ _lib.rps_estimate_mixing.argtypes = [_ctx_p, ctypes.c_uint64, ctypes.c_int64, ct
 _lib.rps_convert_layout.argtypes = [_ctx_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32]
 _lib.rps_set_launch_tuning.argtypes = [_ctx_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32]
 _lib.rps_noise_cells.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+_lib.rps_query_occupancy.argtypes = [_ctx_p, ctypes.c_int32, ctypes.POINTER(ctypes.c_int32)]
 _lib.rps_set_profiling.argtypes = [_ctx_p, ctypes.c_int32]
 _lib.rps_get_kernel_time.argtypes = [_ctx_p, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
 _lib.rps_get_kernel_times.argtypes = [_ctx_p, ctypes.c_void_p, ctypes.c_int64, ctypes.POINTER(ctypes.c_int64)]
@@ -61,13 +62,13 @@ _lib.rps_strerror.argtypes = [ctypes.c_int]
 _lib.rps_strerror.restype = ctypes.c_char_p
 for _name in ("rps_create", "rps_create_external", "rps_destroy", "rps_set_synthetic_grad", "rps_set_gamma", "rps_set_row_pitch", "rps_local_step",
               "rps_lossy_average", "rps_round", "rps_round_gradient_averaging", "rps_get_masks", "rps_masks_host", "rps_set_mask_override",
-              "rps_consensus", "rps_consensus_static", "rps_estimate_mixing", "rps_convert_layout", "rps_set_launch_tuning", "rps_noise_cells", "rps_set_profiling", "rps_get_kernel_time", "rps_get_kernel_times", "rps_last_hip_error"):
+              "rps_consensus", "rps_consensus_static", "rps_estimate_mixing", "rps_convert_layout", "rps_set_launch_tuning", "rps_query_occupancy", "rps_noise_cells", "rps_set_profiling", "rps_get_kernel_time", "rps_get_kernel_times", "rps_last_hip_error"):
     getattr(_lib, _name).restype = ctypes.c_int
 
 EXPORTS = ("rps_create", "rps_create_external", "rps_storage_elems", "rps_destroy", "rps_set_synthetic_grad", "rps_set_gamma",
            "rps_set_row_pitch", "rps_recommended_row_pitch", "rps_local_step",
            "rps_lossy_average", "rps_round", "rps_round_gradient_averaging", "rps_get_masks", "rps_masks_host", "rps_set_mask_override",
-           "rps_consensus", "rps_consensus_static", "rps_estimate_mixing", "rps_convert_layout", "rps_set_launch_tuning", "rps_noise_cells", "rps_set_profiling", "rps_get_kernel_time", "rps_get_kernel_times",
+           "rps_consensus", "rps_consensus_static", "rps_estimate_mixing", "rps_convert_layout", "rps_set_launch_tuning", "rps_query_occupancy", "rps_noise_cells", "rps_set_profiling", "rps_get_kernel_time", "rps_get_kernel_times",
            "rps_last_hip_error",
            "rps_strerror")
 
@@ -231,6 +232,13 @@ class RpsContext:
     def set_launch_tuning(self, rows_in_flight, waves_per_workgroup, max_waves_per_cu=0, tiles_per_wave=0):
         _check(_lib.rps_set_launch_tuning(self._h, rows_in_flight, waves_per_workgroup, max_waves_per_cu, tiles_per_wave),
                self._h)
+
+    def query_occupancy(self, gradient_source):
+        """Wavefronts of the round kernel per compute unit with this context's launch shape
+        (gradient_source: 0 none, 1 buffer, 2 in-register)."""
+        waves = ctypes.c_int32(0)
+        _check(_lib.rps_query_occupancy(self._h, gradient_source, ctypes.byref(waves)), self._h)
+        return waves.value
 
     def set_profiling(self, enable):
         _check(_lib.rps_set_profiling(self._h, 1 if enable else 0), self._h)

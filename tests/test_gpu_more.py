@@ -211,3 +211,41 @@ def test_mixing_constants_over_the_grid_of_fig2_and_fig3(rps):
         betas = [est[(n, p)][2] for p in ps]
         assert all(x < y for x, y in zip(betas, betas[1:])), (n, betas)      # Fig. 3: beta grows with p
         assert all(abs(b - p) < 0.45 * p for b, p in zip(betas, ps)), (n, betas)
+
+
+# ---------------------------------------------------------------------------------------------
+def test_occupancy_cap_reaches_the_launch(rps):
+    """The round kernels limit how many wavefronts a compute unit holds through an LDS allocation
+    they never touch.  rps_query_occupancy reports what the runtime's occupancy calculator makes of
+    the kernel and launch shape a context would use: a requested cap must arrive exactly where it is
+    a whole number of workgroups, the built-in defaults must be what the library documents, and no
+    cap must mean the register-limited occupancy of the kernel."""
+    for tiled in (False, True):
+        flags = rps.RPS_FLAG_LAYOUT_TILED if tiled else 0
+        ctx = rps.RpsContext(32, 32 * 4096, 0.05, 0.1, 0, rps.RPS_DTYPE_F32, flags=flags)
+        ctx.set_synthetic_grad(0.1, 0.0)
+        free = {}
+        for src in (0, 1, 2):
+            ctx.set_launch_tuning(4, 8 if src == 2 else 1, 0, 0)
+            free[src] = ctx.query_occupancy(src)
+            assert 4 <= free[src] <= 32, (tiled, src, free[src])
+        for cap in (2, 3, 5, 6, 8, 10, 12, 16):
+            for src in (0, 1):                       # one wavefront per workgroup: the cap is met exactly
+                ctx.set_launch_tuning(4, 1, cap, 0)
+                assert ctx.query_occupancy(src) == min(cap, free[src]), (tiled, src, cap)
+        # in-register gradient: workgroups of 8 wavefronts that also hold the 32 KB of noise cells; the cap is
+        # rounded down to whole workgroups, and a workgroup cannot hold more than 64 KB of LDS, so two
+        # workgroups always fit
+        for cap in (8, 12, 16, 20, 24):
+            ctx.set_launch_tuning(4, 8, cap, 0)
+            assert ctx.query_occupancy(2) == min(max(2, cap // 8) * 8, free[2]), (tiled, cap)
+        ctx.destroy()
+    # built-in defaults (no tuning call): averaging alone is capped, the in-register round is not
+    ctx = rps.RpsContext(32, 32 * 4096, 0.05, 0.1, 0, rps.RPS_DTYPE_F32, flags=rps.RPS_FLAG_LAYOUT_TILED)
+    assert ctx.query_occupancy(0) == 10 and ctx.query_occupancy(1) == 12
+    assert ctx.query_occupancy(2) == 16              # 81-88 registers per lane: two workgroups of 8 wavefronts (measured
+                                                     # best: three are 1 % slower, four spill)
+    ctx.destroy()
+    ctx = rps.RpsContext(32, 32 * 4096, 0.05, 0.1, 0, rps.RPS_DTYPE_F32)
+    assert ctx.query_occupancy(0) == 5 and ctx.query_occupancy(1) == 5
+    ctx.destroy()
