@@ -102,9 +102,9 @@ int64_t rps_storage_elems(int32_t n, int64_t N, int32_t dtype, uint32_t flags);
  *   dtype          RPS_DTYPE_F32 or RPS_DTYPE_BF16 (storage; arithmetic is fp32, sums fp64)
  *   flags          RPS_FLAG_* (server assignment, storage layout)
  *   hip_stream     hipStream_t on which all work is enqueued (NULL = the default stream)
- * Allocates a fixed ~96 KB of device memory -- five tables of the O(n^2) delivery bits packed as one
+ * Allocates a fixed ~100 KB of device memory -- six tables of the O(n^2) delivery bits packed as one
  * 64-bit word per block and direction (3 KB each: two for eager calls, one each for queries, stream
- * capture and a forced outcome), 32 KB of reduction scratch for rps_consensus / rps_estimate_mixing,
+ * capture, a forced outcome and the outcome "nothing arrives"), 32 KB of reduction scratch for rps_consensus / rps_estimate_mixing,
  * 48 KB of noise cells for the synthetic gradient -- and two pinned host staging buffers (3 KB,
  * 16 KB); nothing proportional to N.  Errors: RPS_EINVAL, RPS_ENOMEM, RPS_EHIP.
  */

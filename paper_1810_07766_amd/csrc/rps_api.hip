@@ -29,7 +29,7 @@ struct rps_ctx {
     int device = 0;
     int64_t max_block_cols = 0;
     std::vector<int64_t> off;
-    RoundTable *tab_base = nullptr;   // device allocation: five tables + the reduction scratch
+    RoundTable *tab_base = nullptr;   // device allocation: six tables + the reduction scratch
     // The two tables of the eager calls: only launches that execute at once ever write them, so what
     // the host believes about them (cur_step / next_step) stays true whatever else happens.
     RoundTable *tab = nullptr;        // device: table the averaging kernels read (outcome of cur_step if cur_valid)
@@ -37,6 +37,8 @@ struct rps_ctx {
     RoundTable *tab_query = nullptr;  // device: scratch table for rps_get_masks
     RoundTable *tab_capture = nullptr;   // device: the only table launches recorded during stream capture write and read
     RoundTable *tab_override = nullptr;  // device: the forced outcome of rps_set_mask_override
+    RoundTable *tab_nothing = nullptr;   // device: the outcome "no message arrives" (all masks zero), never rewritten: with
+                                         // it the round kernel performs exactly the local step
     bool cur_valid = false, next_valid = false;
     uint64_t cur_step = 0, next_step = 0;
     RoundTable *staging = nullptr;    // pinned host copy (create, override, query)
@@ -391,7 +393,7 @@ static int create_impl(rps_ctx **out, int32_t n, int32_t nb, bool external, int6
         e = rps::static_scratch(ctx->device, &unused);
     }
     const size_t scratch_bytes = (2 * (size_t)rps::kMaxPartials + 2) * sizeof(double);
-    const size_t cells_at = (5 * sizeof(RoundTable) + scratch_bytes + 255) & ~(size_t)255;
+    const size_t cells_at = (6 * sizeof(RoundTable) + scratch_bytes + 255) & ~(size_t)255;
     const size_t cells_bytes = 3 * (size_t)rps::kNoiseGrid * sizeof(float);
     if (e == hipSuccess) e = hipMalloc((void **)&ctx->tab_base, cells_at + cells_bytes);
     if (e == hipSuccess) {
@@ -407,13 +409,14 @@ static int create_impl(rps_ctx **out, int32_t n, int32_t nb, bool external, int6
         ctx->tab_query = ctx->tab_base + 2;
         ctx->tab_capture = ctx->tab_base + 3;
         ctx->tab_override = ctx->tab_base + 4;
-        ctx->partials = reinterpret_cast<double *>(ctx->tab_base + 5);
+        ctx->tab_nothing = ctx->tab_base + 5;
+        ctx->partials = reinterpret_cast<double *>(ctx->tab_base + 6);
         e = hipHostMalloc((void **)&ctx->staging, sizeof(RoundTable), hipHostMallocDefault);
     }
     if (e == hipSuccess) {
         std::memset(ctx->staging, 0, sizeof(RoundTable));
         for (int j = 0; j <= nb; ++j) ctx->staging->off[j] = ctx->off[j];
-        for (int k = 0; k < 5 && e == hipSuccess; ++k)   // every table carries the block offsets
+        for (int k = 0; k < 6 && e == hipSuccess; ++k)   // every table carries the block offsets; all masks start at zero
             e = hipMemcpyAsync(ctx->tab_base + k, ctx->staging, sizeof(RoundTable), hipMemcpyHostToDevice, ctx->stream);
         if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
     }
@@ -507,6 +510,14 @@ int rps_local_step(rps_ctx *ctx, void *X, const void *G, uint64_t step) {
     if (!guard.ok) return RPS_EHIP;
     const RoundParams prm = make_params(ctx, X, G, step);
     const int mode = G ? rps::kGradBuffer : rps::kGradSynthetic;
+    // Tile-major layout, in-register gradient: the round kernel under the outcome "no message arrives"
+    // is the local step (no row enters a sum, every row keeps its own v), and its lanes own both rows of
+    // a worker pair, so the noise of a (4 columns x 2 workers) patch is generated once.
+    if ((ctx->flags & RPS_FLAG_LAYOUT_TILED) && mode == rps::kGradSynthetic)
+        return timed_launch(ctx, [&] {
+            return rps::launch_round(ctx->dtype, mode, X, nullptr, ctx->tab_nothing, prm, ctx->max_block_cols,
+                                     tuning_for(ctx, mode), ctx->stream);
+        });
     return timed_launch(ctx, [&] { return rps::launch_local_step(ctx->dtype, mode, X, G, prm, ctx->tune_set ? ctx->tune.tiles_per_wave : 0, ctx->stream); });
 }
 

@@ -16,7 +16,8 @@
 //   round_kernel_narrow  the same round on the tile-major layout: a wavefront owns the contiguous
 //                     n x 128 bytes of a 128-byte-wide tile, 8 rows per instruction
 //   local_step_kernel the local SGD step alone, one row per wavefront (contiguous streams);
-//                     local_step_tiled_kernel: the same on the tile-major layout
+//                     local_step_tiled_kernel: the same on the tile-major layout with a gradient
+//                     buffer (with the in-register gradient: round_kernel_narrow, nothing delivered)
 //   gradavg_kernel    the gradient-averaging comparison of Sec. 6 (same masks applied to G);
 //                     gradavg_kernel_narrow: the same on the tile-major layout
 //   convert_layout_kernel  copy of a state between the row-major and the tile-major arrangement
@@ -343,8 +344,8 @@ template <>
 struct Storage<uint16_t> {
     static constexpr int VEC = 8;
     using Raw = u32x4;
-    using Acc = double;   // the same for bf16 values: an fp32 sum would be 1.5 % faster on the 64-worker workload, but
-                          // its rounding flips about one stored bf16 result in 1e5 against the fp64 definition
+    using Acc = double;   // the same for bf16 values: an fp32 sum is under 1 % faster on the 64-worker workload (measured),
+                          // and its rounding flips about one stored bf16 result in 1e5 against the fp64 definition
     static __device__ __forceinline__ float round(float v) { return bf16_bits_to_f32(f32_to_bf16_bits(v)); }
     static __device__ __forceinline__ void unpack(Raw a, float x[VEC]) {
         x[0] = __uint_as_float(a.x << 16); x[1] = __uint_as_float(a.x & 0xFFFF0000u);
@@ -1050,79 +1051,47 @@ __global__ __launch_bounds__(WPB * 64) void local_step_kernel(ST *__restrict__ X
     finish_fill(std::integral_constant<int, 0>{});
 }
 
-// Local step on the tiled layout: the storage is one run of (tile, worker) segments of
-// kTiledLanes x 16 bytes; a wavefront step takes U adjacent KB of it in storage order (8 segments
-// each), so the pass is a plain sequential stream.  Lane -> segment s = 8 * k + lane / 8 of KB k
-// -> (tile, row) = (s / n, s % n); all U loads are issued before the arithmetic.
-template <typename ST, int GRAD, int WPB>
+// Local step on the tiled layout with a gradient buffer: the storage is one run of (tile, worker)
+// segments of kTiledLanes x 16 bytes, and x - gamma * g needs no coordinates, so a wavefront takes
+// 1 KB of it in storage order (8 segments) and the pass is a plain sequential stream over X and G.
+// Lane -> segment s = 8 * k + lane / 8 of KB k -> tile s / n; only the padding columns of the last
+// tile need care.  (With the in-register gradient the local step runs through round_kernel_narrow
+// under the outcome "no message arrives".)
+template <typename ST, int WPB>
 __global__ __launch_bounds__(WPB * 64) void local_step_tiled_kernel(ST *__restrict__ X, const ST *__restrict__ G,
                                                                     const RoundParams prm) {
     using S = Storage<ST>;
     using Raw = typename S::Raw;
     constexpr int VEC = S::VEC;
     constexpr int LPR = kTiledLanes, TILE = LPR * VEC, SEGS = 64 / LPR;
-    constexpr int U = GRAD == kGradSynthetic ? 4 : 1;
-    __shared__ typename LdsFor<GRAD>::type lds;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    noise_fill_begin<WPB>(lds, prm.noise_cells, wave, lane);
-    noise_fill_end<0>(lds);
     const int64_t tiles = (prm.N + TILE - 1) / TILE;
-    for (int it = 0; it < prm.tiles_per_wave; ++it) {
-        const int64_t kb0 = unit_index(it, WPB, wave) * U;
-        if ((kb0 * SEGS) / prm.n >= tiles) break;         // wave-uniform: past the last tile
-        Raw xr[U], gr[GRAD == kGradBuffer ? U : 1];
-        int64_t c0s[U];
-        int rows[U];
-        bool fulls[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int64_t seg0 = (kb0 + u) * SEGS;        // first segment of this KB: scalar division
-            int64_t tile = seg0 / prm.n;
-            int i = (int)(seg0 % prm.n) + lane / LPR;     // then at most 64 / LPR rows further
-            while (i >= prm.n) {
-                i -= prm.n;
-                ++tile;
-            }
-            const int64_t c0 = tile * TILE + (lane % LPR) * VEC;
-            c0s[u] = c0;
-            rows[u] = i;
-            fulls[u] = prm.vec_ok && c0 + VEC <= prm.N;
-            const ST *px = X + seg0 * TILE + (uint32_t)(lane / LPR) * TILE + (lane % LPR) * VEC;   // plain global accesses:
-            const ST *pg = G ? G + (px - X) : nullptr;   // measured faster here than the buffer form the round kernels use
-            if (c0 >= prm.N) {                            // padding columns of the last tile, or past the last tile
-                xr[u] = Raw{};
-            } else if (fulls[u]) {
-                xr[u] = __builtin_nontemporal_load(reinterpret_cast<const Raw *>(px));
-                if (GRAD == kGradBuffer) gr[GRAD == kGradBuffer ? u : 0] = __builtin_nontemporal_load(reinterpret_cast<const Raw *>(pg));
-            } else {
-                xr[u] = load_seg<ST, false>(px, 0, 0, c0, 0, prm.N);
-                if (GRAD == kGradBuffer) gr[GRAD == kGradBuffer ? u : 0] = load_seg<ST, false>(pg, 0, 0, c0, 0, prm.N);
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int64_t c0 = c0s[u];
-            if (c0 >= prm.N) continue;
-            const int i = rows[u];
-            ST *px = X + (kb0 + u) * SEGS * TILE + (uint32_t)(lane / LPR) * TILE + (lane % LPR) * VEC;
-            float x[VEC], g[VEC], other[VEC];
-            S::unpack(xr[u], x);
-            if (GRAD == kGradBuffer) {
-                S::unpack(gr[GRAD == kGradBuffer ? u : 0], g);
-            } else {   // a wavefront's lanes may sit in different tiles: the counter is per lane
-                const uint32_t quad_hi = (uint32_t)(c0 >> 9), quad_lo = (uint32_t)(c0 >> 2) & 127u;
-                if (i & 1)
-                    noise_rows<VEC>(prm, lds, i >> 1, quad_hi, quad_lo, other, g);
-                else
-                    noise_rows<VEC>(prm, lds, i >> 1, quad_hi, quad_lo, g, other);
-            }
-            const Raw v = sgd_step<ST, GRAD>(prm, g, x);
-            if (fulls[u])
-                __builtin_nontemporal_store(v, reinterpret_cast<Raw *>(px));
-            else
-                store_seg<ST, false>(px, 0, 0, c0, 0, prm.N, v);
-        }
+    const int64_t kb = unit_index(0, WPB, wave);
+    const int64_t seg0 = kb * SEGS;                   // first segment of this KB: scalar division
+    int64_t tile = seg0 / prm.n;
+    int i = (int)(seg0 % prm.n) + lane / LPR;         // the lane's segment lies at most 64 / LPR rows further
+    while (i >= prm.n) {
+        i -= prm.n;
+        ++tile;
+    }
+    const int64_t seg = seg0 + lane / LPR;
+    if (tile >= tiles) return;                        // past the last tile
+    const int64_t c0 = tile * TILE + (lane % LPR) * VEC;
+    if (c0 >= prm.N) return;                          // padding columns of the last tile
+    ST *px = X + seg * TILE + (lane % LPR) * VEC;     // plain global accesses: measured faster here than the
+    const ST *pg = G + (px - X);                      // buffer form the round kernels use
+    float x[VEC], g[VEC];
+    if (prm.vec_ok && c0 + VEC <= prm.N) {
+        const Raw xr = __builtin_nontemporal_load(reinterpret_cast<const Raw *>(px));
+        const Raw gr = __builtin_nontemporal_load(reinterpret_cast<const Raw *>(pg));
+        S::unpack(xr, x);
+        S::unpack(gr, g);
+        __builtin_nontemporal_store(sgd_step<ST, kGradBuffer>(prm, g, x), reinterpret_cast<Raw *>(px));
+    } else {
+        S::unpack(load_seg<ST, false>(px, 0, 0, c0, 0, prm.N), x);
+        S::unpack(load_seg<ST, false>(pg, 0, 0, c0, 0, prm.N), g);
+        store_seg<ST, false>(px, 0, 0, c0, 0, prm.N, sgd_step<ST, kGradBuffer>(prm, g, x));
     }
 }
 
@@ -1268,19 +1237,11 @@ hipError_t launch_local_step_g(int grad_mode, ST *X, const ST *G, RoundParams pr
     constexpr int VEC = Storage<ST>::VEC;
     constexpr int WS = 8;   // wavefronts per workgroup where noise is generated (they share the LDS cells)
     if (prm.tiled) {
+        if (grad_mode != kGradBuffer) return hipErrorInvalidValue;   // the in-register gradient goes through launch_round
         const int64_t tiles = (prm.N + kTiledLanes * VEC - 1) / (kTiledLanes * VEC);
-        const int64_t kb = (tiles * prm.n * kTiledLanes + 63) / 64;   // wavefront steps: 1 KB of storage each
-        if (grad_mode == kGradBuffer) {
-            prm.tiles_per_wave = 1;
-            hipLaunchKernelGGL((local_step_tiled_kernel<ST, kGradBuffer, 4>), folded_grid8((kb + 3) / 4, 1), dim3(256), 0,
-                               stream, X, G, prm);
-        } else {
-            const int64_t units = (kb + 3) / 4;   // a wavefront step is 4 KB here
-            prm.tiles_per_wave = steps_per_wave(kGradSynthetic, units, WS, 1, wanted_steps, 2);
-            const int64_t per_wg = (int64_t)WS * prm.tiles_per_wave;
-            hipLaunchKernelGGL((local_step_tiled_kernel<ST, kGradSynthetic, WS>), folded_grid8((units + per_wg - 1) / per_wg, 1),
-                               dim3(WS * 64), 0, stream, X, G, prm);
-        }
+        const int64_t kb = (tiles * prm.n * kTiledLanes + 63) / 64;   // wavefronts: 1 KB of storage each
+        prm.tiles_per_wave = 1;
+        hipLaunchKernelGGL((local_step_tiled_kernel<ST, 4>), folded_grid8((kb + 3) / 4, 1), dim3(256), 0, stream, X, G, prm);
         return hipGetLastError();
     }
     const int64_t tiles = (prm.N + 64 * VEC - 1) / (64 * VEC);
