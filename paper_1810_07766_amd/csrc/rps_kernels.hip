@@ -1357,26 +1357,31 @@ __global__ __launch_bounds__(256) void gradavg_kernel(ST *__restrict__ X, const 
         gradavg_tile<ST, false>(X, G, prm, lc, tab->ucol[j], tab->dcol[j], tab->inv_cnt[j]);
 }
 
-// Gradient averaging on the tiled layout: one wavefront per 128-byte-wide tile, lane groups as in
-// round_kernel_narrow.  A lane has at most 8 rows (n <= 64): its gradient segments stay in
-// registers between the column sums and the update, so G is read once.
-template <typename ST, bool FULL>
+// Gradient averaging on the tiled layout, lane groups as in round_kernel_narrow: PG lane groups per
+// 128-byte-wide tile (8 with more than 16 workers; with fewer, 8 / PG adjacent tiles share the
+// wavefront so that no lane group idles).  A lane has at most 8 rows (n <= 64), at most 4 below
+// PG = 8: its gradient segments stay in registers between the column sums and the update, so G is
+// read once.
+template <typename ST, int PG, bool FULL>
 __device__ __forceinline__ void gradavg_tile_narrow(ST *__restrict__ Xt, const ST *__restrict__ Gt, const RoundParams &prm,
-                                                    uint32_t sub_off, int64_t c0, int64_t lo, int64_t hi, uint64_t ucol,
-                                                    uint64_t dcol, double inv, int lg) {
+                                                    uint32_t col_off, int64_t first, int64_t lo, int64_t hi, uint64_t ucol,
+                                                    uint64_t dcol, double inv, int lgw) {
     using S = Storage<ST>;
     using Acc = typename S::Acc;
     using Raw = typename S::Raw;
     constexpr int VEC = S::VEC;
-    constexpr int LPR = kTiledLanes, GROUPS = 64 / LPR;
+    constexpr int LPR = kTiledLanes, TPW = (64 / LPR) / PG;
     constexpr uint32_t STRIDE = LPR * VEC;
-    constexpr int ROWS = 2 * ((kMaxWorkers / 2 + GROUPS - 1) / GROUPS);   // rows per lane at most: 8
+    constexpr int ROWS = PG == 8 ? 2 * ((kMaxWorkers / 2 + PG - 1) / PG) : 4;   // rows per lane at most
     const int n = prm.n;
-    const uint32_t limit = (uint32_t)n * STRIDE * (uint32_t)sizeof(ST);
+    const int tw = lgw / PG, lg = lgw % PG;   // the lane's tile among the wavefront's, its group inside that tile
+    const uint32_t sub_off = (uint32_t)tw * (uint32_t)n * STRIDE + col_off;
+    const int64_t c0 = first + (int64_t)tw * (LPR * VEC) + col_off;
+    const uint32_t limit = (uint32_t)TPW * (uint32_t)n * STRIDE * (uint32_t)sizeof(ST);
     Raw g[ROWS], x[ROWS];
 #pragma unroll
-    for (int r = 0; r < ROWS; ++r) {   // lane's row r: pair lg + GROUPS * (r / 2); rows past n repeat row n-1, unused
-        const int i = 2 * (lg + GROUPS * (r >> 1)) + (r & 1);
+    for (int r = 0; r < ROWS; ++r) {   // lane's row r: pair lg + PG * (r / 2); rows past n repeat row n-1, unused
+        const int i = 2 * (lg + PG * (r >> 1)) + (r & 1);
         const uint32_t o = (uint32_t)(i < n ? i : n - 1) * STRIDE + sub_off;
         g[r] = load_seg<ST, FULL>(Gt, o, limit, c0, lo, hi);
         x[r] = load_seg<ST, FULL>(Xt, o, limit, c0, lo, hi);
@@ -1386,7 +1391,7 @@ __device__ __forceinline__ void gradavg_tile_narrow(ST *__restrict__ Xt, const S
     for (int e = 0; e < VEC; ++e) acc[e] = 0;
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) {
-        const int i = 2 * (lg + GROUPS * (r >> 1)) + (r & 1);
+        const int i = 2 * (lg + PG * (r >> 1)) + (r & 1);
         if (i < n && ((ucol >> i) & 1)) {
             float v[VEC];
             S::unpack(g[r], v);
@@ -1395,7 +1400,7 @@ __device__ __forceinline__ void gradavg_tile_narrow(ST *__restrict__ Xt, const S
         }
     }
 #pragma unroll
-    for (int o = LPR; o < 64; o <<= 1) {
+    for (int o = LPR; o < LPR * PG; o <<= 1) {
 #pragma unroll
         for (int e = 0; e < VEC; ++e) acc[e] += __shfl_xor(acc[e], o, 64);
     }
@@ -1405,7 +1410,7 @@ __device__ __forceinline__ void gradavg_tile_narrow(ST *__restrict__ Xt, const S
     (void)S::round_vec(gt);   // the average travels in the storage format
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) {
-        const int i = 2 * (lg + GROUPS * (r >> 1)) + (r & 1);
+        const int i = 2 * (lg + PG * (r >> 1)) + (r & 1);
         if (i < n) {
             float v[VEC], own[VEC];
             S::unpack(x[r], v);
@@ -1418,26 +1423,26 @@ __device__ __forceinline__ void gradavg_tile_narrow(ST *__restrict__ Xt, const S
     }
 }
 
-template <typename ST>
+template <typename ST, int PG>
 __global__ __launch_bounds__(64) void gradavg_kernel_narrow(ST *__restrict__ X, const ST *__restrict__ G,
                                                             const RoundTable *__restrict__ tab, const RoundParams prm) {
     constexpr int VEC = Storage<ST>::VEC;
-    constexpr int TILE = kTiledLanes * VEC;
+    constexpr int WIDTH = ((64 / kTiledLanes) / PG) * kTiledLanes * VEC;   // columns per wavefront
     const int lane = threadIdx.x;
     const int j = blockIdx.y;
     prepare_next_outcome(prm, linear_block() == 0, j, lane);
     const int64_t lo = tab->off[j], hi = tab->off[j + 1];
-    const int64_t tile0 = (lo / TILE) * TILE + linear_block() * TILE;
-    if (tile0 >= hi) return;   // wave-uniform
-    const uint32_t sub_off = (uint32_t)(lane % kTiledLanes) * VEC;
-    ST *Xt = X + tile0 * prm.n;
-    const ST *Gt = G + tile0 * prm.n;
-    if (prm.vec_ok && tile0 >= lo && tile0 + TILE <= hi)
-        gradavg_tile_narrow<ST, true>(Xt, Gt, prm, sub_off, tile0 + sub_off, lo, hi, tab->ucol[j], tab->dcol[j],
-                                      tab->inv_cnt[j], lane / kTiledLanes);
+    const int64_t first = (lo / WIDTH) * WIDTH + linear_block() * WIDTH;
+    if (first >= hi) return;   // wave-uniform
+    const uint32_t col_off = (uint32_t)(lane % kTiledLanes) * VEC;
+    ST *Xt = X + first * prm.n;
+    const ST *Gt = G + first * prm.n;
+    if (prm.vec_ok && first >= lo && first + WIDTH <= hi)
+        gradavg_tile_narrow<ST, PG, true>(Xt, Gt, prm, col_off, first, lo, hi, tab->ucol[j], tab->dcol[j], tab->inv_cnt[j],
+                                          lane / kTiledLanes);
     else
-        gradavg_tile_narrow<ST, false>(Xt, Gt, prm, sub_off, tile0 + sub_off, lo, hi, tab->ucol[j], tab->dcol[j],
-                                       tab->inv_cnt[j], lane / kTiledLanes);
+        gradavg_tile_narrow<ST, PG, false>(Xt, Gt, prm, col_off, first, lo, hi, tab->ucol[j], tab->dcol[j], tab->inv_cnt[j],
+                                           lane / kTiledLanes);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -1704,19 +1709,24 @@ hipError_t launch_gradavg(int dtype, void *X, const void *G, const RoundTable *t
                           int64_t max_block_cols, int max_waves_per_cu, hipStream_t stream) {
     const int vec = dtype == 0 ? 4 : 8;
     if (prm.tiled) {
-        const int64_t tile = kTiledLanes * vec;
-        const dim3 grid = folded_grid((max_block_cols + 2 * tile - 2) / tile, (unsigned)prm.blocks);
+        // lane groups per tile as in launch_round_narrow: a lane gets two row pairs where the workers allow it
+        const int pairs = (prm.n + 1) / 2, need = (pairs + 1) / 2;
+        const int pg = need > 4 ? 8 : (need > 2 ? 4 : (need > 1 ? 2 : 1));
+        const int64_t width = (int64_t)(8 / pg) * kTiledLanes * vec;   // columns per wavefront
+        const dim3 grid = folded_grid((max_block_cols + 2 * width - 2) / width, (unsigned)prm.blocks);
         size_t lds = 0;
         if (max_waves_per_cu > 0 && max_waves_per_cu < 32) {
             lds = ((size_t)kLdsBytesPerCu / max_waves_per_cu) & ~(size_t)255;
             if (lds > 65536) lds = 65536;
         }
-        if (dtype == 0)
-            hipLaunchKernelGGL(gradavg_kernel_narrow<float>, grid, dim3(64), lds, stream, (float *)X, (const float *)G, tab,
-                               prm);
-        else
-            hipLaunchKernelGGL(gradavg_kernel_narrow<uint16_t>, grid, dim3(64), lds, stream, (uint16_t *)X,
-                               (const uint16_t *)G, tab, prm);
+#define RPS_GA(ST, PG) \
+    hipLaunchKernelGGL((gradavg_kernel_narrow<ST, PG>), grid, dim3(64), lds, stream, (ST *)X, (const ST *)G, tab, prm)
+        if (dtype == 0) {
+            if (pg == 8) RPS_GA(float, 8); else if (pg == 4) RPS_GA(float, 4); else if (pg == 2) RPS_GA(float, 2); else RPS_GA(float, 1);
+        } else {
+            if (pg == 8) RPS_GA(uint16_t, 8); else if (pg == 4) RPS_GA(uint16_t, 4); else if (pg == 2) RPS_GA(uint16_t, 2); else RPS_GA(uint16_t, 1);
+        }
+#undef RPS_GA
         return hipGetLastError();
     }
     const int64_t tile = 64 * vec;
