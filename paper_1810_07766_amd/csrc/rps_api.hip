@@ -683,10 +683,15 @@ int rps_estimate_mixing(rps_ctx *ctx, uint64_t first_step, int64_t rounds, doubl
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return RPS_EHIP;
     const int groups = (int)std::min<int64_t>(rounds, rps::kMaxPartials);
+    std::vector<double> host;
+    try {   // no exception may cross the C boundary; nothing is enqueued yet
+        host.resize(2 * (size_t)groups);
+    } catch (...) {
+        return RPS_ENOMEM;
+    }
     RPS_HIP(ctx, rps::launch_mixing_moments(ctx->partials, groups, rounds, ctx->n, ctx->nb, ctx->seed, first_step,
                                             ctx->threshold, server_mode(ctx), ctx->stream));
-    double host[2 * rps::kMaxPartials];   // groups <= kMaxPartials
-    RPS_HIP(ctx, hipMemcpyAsync(host, ctx->partials, 2 * (size_t)groups * sizeof(double), hipMemcpyDeviceToHost,
+    RPS_HIP(ctx, hipMemcpyAsync(host.data(), ctx->partials, 2 * (size_t)groups * sizeof(double), hipMemcpyDeviceToHost,
                                 ctx->stream));
     RPS_HIP(ctx, hipStreamSynchronize(ctx->stream));
     double sq = 0.0, sum_sq = 0.0;
