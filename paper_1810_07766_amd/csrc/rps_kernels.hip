@@ -1169,9 +1169,9 @@ hipError_t launch_round_narrow(ST *X, const ST *G, const RoundTable *tab, RoundP
     const int pg = need > 4 ? 8 : (need > 2 ? 4 : (need > 1 ? 2 : 1));
     const int64_t width = (int64_t)(GROUPS / pg) * TILE;   // columns per wavefront and step
     const int64_t steps = (max_block_cols + 2 * width - 2) / width;
-    // fp32 with 24 or more workers: one tile (4 KB and more) per wavefront is best; otherwise two steps
-    prm.tiles_per_wave = steps_per_wave(GRAD, steps, WPB, prm.blocks, tune.tiles_per_wave,
-                                        sizeof(ST) == 4 && prm.n >= 24 ? 1 : 2);
+    // fp32: one step (about 4 KB) per wavefront is best at every worker count (n = 8 / 16 / 32: +2-3 %
+    // over two); bf16: two
+    prm.tiles_per_wave = steps_per_wave(GRAD, steps, WPB, prm.blocks, tune.tiles_per_wave, sizeof(ST) == 4 ? 1 : 2);
     const int64_t per_wg = (int64_t)WPB * prm.tiles_per_wave;
     const dim3 grid = folded_grid8((steps + per_wg - 1) / per_wg, (unsigned)prm.blocks);
     const size_t lds = occupancy_pad(tune.max_waves_per_cu, WPB, static_lds_bytes<GRAD>());
