@@ -210,6 +210,49 @@ def test_mask_override_forces_outcomes(rps):
     ctx.destroy()
 
 
+@pytest.mark.parametrize("tiled", [False, True])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_local_step_ignores_the_network(rps, tiled, dtype):
+    """Alg. 1 step 5 involves no message: rps_local_step gives the oracle's v bit for bit whatever the
+    drop rate, and a forced network outcome in force changes nothing -- in both layouts (the tile-major
+    one runs the step through the round kernel under the outcome "nothing arrives"), for both gradient
+    sources, on a width with a ragged last tile and unaligned block cuts."""
+    n, N = 7, 7 * 333 + 5
+    off = _offsets(n, N, "arbitrary", seed=3)
+    X0 = workloads.gaussian_model(n, N, seed=41, scale=0.2)
+    G0 = workloads.gaussian_model(n, N, seed=42, scale=0.05)
+    flags = rps.RPS_FLAG_LAYOUT_TILED if tiled else 0
+    code = rps.RPS_DTYPE_BF16 if dtype == "bf16" else rps.RPS_DTYPE_F32
+    outs = []
+    for p, forced in ((0.0, False), (1.0, False), (0.3, True)):
+        ctx = rps.RpsContext(n, N, p, 0.25, 77, code, block_offsets=off, flags=flags)
+        ctx.set_synthetic_grad(0.3, 1e-3)
+        if forced:
+            server = np.arange(n, dtype=np.int32)[::-1].copy()
+            U = np.zeros((n, n), dtype=np.uint8); D = np.ones((n, n), dtype=np.uint8)
+            U[server, np.arange(n)] = 1
+            ctx.set_mask_override(server, U, D)
+        res = []
+        for G in (None, G0):
+            X = device_tensor(X0, dtype)
+            Gd = None if G is None else device_tensor(G, dtype)
+            if tiled:
+                X = workloads.to_tiled(X); Gd = None if Gd is None else workloads.to_tiled(Gd)
+            ctx.local_step(X, Gd, 5)
+            torch.cuda.synchronize()
+            res.append(to_oracle(workloads.from_tiled(X, N) if tiled else X))
+        ctx.destroy()
+        outs.append(res)
+    for res in outs[1:]:
+        assert (res[0] == outs[0][0]).all() and (res[1] == outs[0][1]).all()
+    ref = to_oracle(device_tensor(X0, dtype)).copy()
+    oracle.local_step(ref, None, 0.25, sigma=0.3, weight_decay=1e-3, seed=77, step=5)
+    assert (outs[0][0] == ref).all()
+    ref = to_oracle(device_tensor(X0, dtype)).copy()
+    oracle.local_step(ref, to_oracle(device_tensor(G0, dtype)).copy(), 0.25)
+    assert (outs[0][1] == ref).all()
+
+
 def test_deterministic_and_stateless_resume(rps):
     n, N = 16, 16 * 1100
     X0 = workloads.gaussian_model(n, N, seed=30, scale=0.1)
