@@ -274,3 +274,49 @@ def test_gradient_averaging_variant_special_cases_and_drift():
         dg.append(oracle.consensus(Xg)[0]); dm.append(oracle.consensus(Xm)[0])
     assert dg[-1] > 20 * dm[-1]                     # gradient averaging: disagreement accumulates
     assert max(dm[100:]) < 10 * np.mean(dm[50:100]) # model averaging: bounded steady state
+
+
+def test_gradient_averaging_is_x_minus_gamma_g_times_w():
+    """Sec. 6's gradient averaging in the global view of Sec. 4.2: the network acts on the gradients
+    exactly as it acts on models, G~ = G W per block, and then X' = X - gamma G~.  W is rebuilt here
+    (not by the oracle); checked for random outcomes and, by enumerating every (server, uplink,
+    downlink) outcome of a block for n = 3, in expectation: E[W] = a0 I + (1 - a0) A_n preserves the
+    mean, so E[mean_i x'_i] = xbar - gamma gbar, the same unbiasedness as model averaging
+    (supplement, Lemma 3's first identity) -- what differs is that nothing contracts the spread."""
+    import itertools
+    rng = np.random.default_rng(7)
+    n, N, gamma = 6, 6 * 40, 0.3
+    off = workloads.block_offsets(n, N)
+    X = rng.standard_normal((n, N)).astype(np.float32)
+    G = rng.standard_normal((n, N)).astype(np.float32)
+    for trial in range(5):
+        server, U, D = _random_masks(rng, n, 0.35)
+        Y = X.copy()
+        oracle.round_gradient_averaging(Y, G, off, p=0.0, gamma=gamma, seed=0, step=0, mask_override=(server, U, D))
+        for j in range(n):
+            blk = slice(off[j], off[j + 1])
+            W = _mixing_matrix(U, D, j)
+            # the averaged gradient travels in fp32: one rounding of the column means, then one fused step
+            Gt = (G[:, blk].astype(np.float64).T @ W).T.astype(np.float32)
+            ref = X[:, blk].astype(np.float64) - gamma * Gt.astype(np.float64)
+            assert np.abs(Y[:, blk] - ref).max() < 2e-6
+    # expectation over every outcome of one block, n = 3, p = 0.25
+    n, p, q = 3, 0.25, 0.75
+    X = rng.standard_normal((n, 8)).astype(np.float32)
+    G = rng.standard_normal((n, 8)).astype(np.float32)
+    acc = np.zeros(8); total = 0.0
+    for s in range(n):
+        others = [i for i in range(n) if i != s]
+        for ubits in itertools.product((0, 1), repeat=n - 1):
+            for dbits in itertools.product((0, 1), repeat=n - 1):
+                U = np.zeros((n, 1), dtype=np.uint8); D = np.zeros((n, 1), dtype=np.uint8)
+                U[s, 0] = D[s, 0] = 1
+                for i, u, d in zip(others, ubits, dbits):
+                    U[i, 0], D[i, 0] = u, d
+                prob = (1.0 / n) * np.prod([q if b else p for b in ubits + dbits])
+                W = _mixing_matrix(U, D, 0)
+                Xp = X.astype(np.float64) - gamma * (G.astype(np.float64).T @ W).T
+                acc += prob * Xp.mean(axis=0); total += prob
+    assert abs(total - 1.0) < 1e-12
+    want = X.astype(np.float64).mean(axis=0) - gamma * G.astype(np.float64).mean(axis=0)
+    assert np.abs(acc - want).max() < 1e-12
