@@ -1,8 +1,8 @@
 // HIP kernels (gfx950 / CDNA4, wave64) of the RPS lossy model-averaging round of
 // "Distributed Learning over Unreliable Networks" (arXiv 1810.07766), Sec. 4.1 / Alg. 1.
 //
-// Compile with -ffp-contract=off: the synthetic-gradient noise is specified as an exact
-// sequence of IEEE fp32 operations and every fused multiply-add is written explicitly.
+// Compile with -ffp-contract=off: the local step and the synthetic-gradient noise are specified as
+// exact sequences of IEEE fp32 operations and every fused multiply-add is written explicitly.
 //
 // Kernels
 //   masks_kernel      network outcome of one round: server permutation, uplink and downlink
@@ -12,7 +12,8 @@
 //                     (Sec. 4.2), one wavefront per simulated round
 //   round_kernel      local SGD step + Reduce-Scatter average + All-Gather write-back in one
 //                     pass; every wavefront owns one tile (64 lanes x 16 bytes) of one block
-//                     and walks all n rows of it, no LDS and no barrier
+//                     and walks all n rows of it; no data is staged in LDS (the only LDS use is
+//                     the shared copy of the noise cells, the only barrier the one that ends it)
 //   round_kernel_narrow  the same round on the tile-major layout: a wavefront owns the contiguous
 //                     n x 128 bytes of a 128-byte-wide tile, 8 rows per instruction
 //   local_step_kernel the local SGD step alone, one row per wavefront (contiguous streams);
@@ -23,8 +24,8 @@
 //   convert_layout_kernel  copy of a state between the row-major and the tile-major arrangement
 //   consensus_kernel  sum_i ||x_i - xbar||^2 and ||xbar||^2 in one streaming read (Lemma 1's quantity)
 // The path is a streaming reduction with < 0.5 flop per byte: it is bound by HBM bandwidth
-// (and, with the in-register Gaussian generator, by plain vector ALU work), never by a dense
-// contraction, so there is no MFMA here.
+// (with the in-register Gaussian generator also by the LDS gathers of the noise cells and plain
+// vector ALU work on the bf16 workloads), never by a dense contraction, so there is no MFMA here.
 #include "rps_internal.h"
 
 #include <atomic>
@@ -478,7 +479,8 @@ __device__ __forceinline__ typename Storage<ST>::Raw sgd_step(const RoundParams 
 //           (uplink bit) add it to the fp64 column sums; if the reply will not reach worker i
 //           (downlink bit clear) its final value is v: store it now
 //   pass 2  vt = sum / |N_j| once per column; store vt to every row whose downlink bit is set
-// Every element is read once and written once, nothing is staged in LDS, there is no barrier.
+// Every element is read once and written once; no state data is staged in LDS (only the noise cells
+// live there, and the one barrier of a workgroup is the one that ends their copy).
 // Delivery tests are wave-uniform scalar branches (row index and mask words live in SGPRs).
 // All receivers get the same registers, so they hold identical bits.
 // ---------------------------------------------------------------------------------------
