@@ -249,3 +249,38 @@ def test_occupancy_cap_reaches_the_launch(rps):
     ctx = rps.RpsContext(32, 32 * 4096, 0.05, 0.1, 0, rps.RPS_DTYPE_F32)
     assert ctx.query_occupancy(0) == 5 and ctx.query_occupancy(1) == 5
     ctx.destroy()
+
+
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("k", range(24))
+def test_results_do_not_depend_on_the_launch_shape(rps, k):
+    """rps_set_launch_tuning changes how the work is laid over wavefronts (rows per load chunk,
+    workgroup width, occupancy cap, steps per wavefront), never what is computed: every entry point
+    gives the same bits under three random launch shapes as under the built-in one, on seeded random
+    workloads (workers, width, partition, dtype, drop rate, layout, server rule)."""
+    import test_gpu_parity as P
+    n, N, layout, dtype, p, tiled, identity, step0 = P._random_case(200 + k)
+    off = P._offsets(n, N, layout, seed=k)
+    flags = (rps.RPS_FLAG_LAYOUT_TILED if tiled else 0) | (rps.RPS_FLAG_SERVER_IDENTITY if identity else 0)
+    code = rps.RPS_DTYPE_BF16 if dtype == "bf16" else rps.RPS_DTYPE_F32
+    X0 = device_tensor(workloads.gaussian_model(n, N, seed=k), dtype)
+    G0 = device_tensor(workloads.gaussian_model(n, N, seed=k + 500), dtype)
+    if tiled:
+        X0 = workloads.to_tiled(X0); G0 = workloads.to_tiled(G0)
+    rng = np.random.default_rng(k)
+    outs = []
+    for variant in range(4):
+        ctx = rps.RpsContext(n, N, p, 0.2, 900 + k, code, block_offsets=off, flags=flags)
+        ctx.set_synthetic_grad(0.3, 0.02)
+        if variant:
+            ctx.set_launch_tuning(int(rng.choice([2, 4])), int(rng.choice([1, 2, 4, 8, 16])),
+                                  int(rng.choice([0, 3, 5, 8, 12, 16, 24])), int(rng.choice([0, 1, 2, 3, 5])))
+        X = X0.clone()
+        ctx.round(X, None, step0); ctx.round(X, G0, step0 + 1); ctx.local_step(X, None, step0 + 2)
+        ctx.lossy_average(X, step0 + 2); ctx.local_step(X, G0, step0 + 3); ctx.round_gradient_averaging(X, G0, step0 + 4)
+        torch.cuda.synchronize()
+        outs.append(X.clone())
+        ctx.destroy()
+    as_bits = torch.int16 if dtype == "bf16" else torch.int32
+    for o in outs[1:]:
+        assert torch.equal(o.view(as_bits), outs[0].view(as_bits)), (k, n, N, layout, dtype, p, tiled)
