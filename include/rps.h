@@ -279,9 +279,11 @@ int rps_convert_layout(rps_ctx *ctx, void *dst, const void *src, int32_t to_tile
 /*
  * Launch shape of the round kernel, for tuning sweeps; results never depend on it.
  *   rows_in_flight       rows per load chunk (a wavefront keeps two chunks in flight): 2 or 4
- *   waves_per_workgroup  1, 2, 4, 8 or 16 (a workgroup's wavefronts own adjacent tiles and, with the
- *                        in-register gradient, share one LDS copy of the noise cells); rounded to
- *                        the nearest width the kernel in question is built for
+ *   waves_per_workgroup  1..16 (a workgroup's wavefronts own adjacent tiles and, with the
+ *                        in-register gradient, share one LDS copy of the noise cells); rounded up to
+ *                        the nearest width the kernel in question is built for (in-register
+ *                        gradient: 4, 8, 12, 14 tile-major and 2, 4, 8 row-major; otherwise 1, or
+ *                        4 row-major)
  *   max_waves_per_cu     cap on resident wavefronts per compute unit (0 = no cap); rounded down to whole
  *                        workgroups, and never below two workgroups (a workgroup holds at most 64 KB
  *                        of the compute unit's 160 KB of LDS); rps_query_occupancy shows the outcome

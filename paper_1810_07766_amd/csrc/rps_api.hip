@@ -101,9 +101,13 @@ rps::LaunchTuning tuning_for(const rps_ctx *ctx, int grad_mode) {
     if (ctx->tune_set) return ctx->tune;
     if (ctx->flags & RPS_FLAG_LAYOUT_TILED) {   // a wavefront owns about 4 KB whatever n is: more of them resident
         int cap;                                 // (measured at n = 8 / 16 / 32 fp32 and n = 64 bf16)
-        // 8 wavefronts share the LDS copy of the noise cells; with more than 32 workers a lane walks its
-        // rows in chunks, and one row pair per chunk keeps the registers at five wavefronts per SIMD
-        if (grad_mode == rps::kGradSynthetic) return rps::LaunchTuning{ctx->n > 32 ? 2 : 4, 8, 0, 0};
+        // the workgroup's wavefronts share the LDS copy of the noise cells: one workgroup of 14 (12 below 24
+        // workers) per compute unit for fp32, two of 8 for bf16; with more than 32 workers a lane walks its
+        // rows in chunks, and one row pair per chunk keeps the registers at four wavefronts per SIMD
+        if (grad_mode == rps::kGradSynthetic) {
+            const int wpb = ctx->dtype == RPS_DTYPE_BF16 ? 8 : (ctx->n >= 24 ? 14 : 12);
+            return rps::LaunchTuning{ctx->n > 32 ? 2 : 4, wpb, 0, 0};
+        }
         else if (grad_mode == rps::kGradNone) cap = ctx->n >= 48 ? 8 : 10;
         else cap = 12;
         return rps::LaunchTuning{4, 1, cap, 0};
@@ -722,9 +726,7 @@ int rps_set_launch_tuning(rps_ctx *ctx, int32_t rows_in_flight, int32_t waves_pe
                           int32_t tiles_per_wave) {
     if (!ctx) return RPS_EINVAL;
     if (rows_in_flight != 2 && rows_in_flight != 4) return RPS_EINVAL;
-    if (waves_per_workgroup != 1 && waves_per_workgroup != 2 && waves_per_workgroup != 4 && waves_per_workgroup != 8 &&
-        waves_per_workgroup != 16)
-        return RPS_EINVAL;
+    if (waves_per_workgroup < 1 || waves_per_workgroup > 16) return RPS_EINVAL;
     if (max_waves_per_cu < 0 || tiles_per_wave < 0 || tiles_per_wave > 64) return RPS_EINVAL;
     ctx->tune = rps::LaunchTuning{rows_in_flight, waves_per_workgroup, max_waves_per_cu, tiles_per_wave};
     ctx->tune_set = true;
