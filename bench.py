@@ -8,10 +8,11 @@ write-back, for all n workers and all N parameters, in place in HBM.
 The state is held in the library's tile-major layout by default (row-major with --layout
 row-major; the other layout is measured as well and reported under "other_layout").
 
-Order of a measurement: an untimed settling phase of its own (rounds are launched until ten
-consecutive kernel durations agree within 1 %: the first launches after start-up run at ramping
-clocks), then the --warmup rounds, then the timed region of exactly --steps rounds (wall clock
-between two device synchronisations: `value`, `ms_per_step`), then the same number of rounds with
+Order of a measurement: an untimed settling phase of its own (windows of ten rounds are launched
+until two consecutive windows agree within 1 % in their mean kernel duration: the first launches
+after start-up run at ramping clocks), then the --warmup rounds, then the timed region of exactly
+--steps rounds (wall clock between two device synchronisations: `value`, `ms_per_step`), then the
+same number of rounds with
 every kernel bracketed by HIP events on the library's own stream (`roofline`).
 
 Prints ONE JSON line: worker-params averaged per second (n*N per round), the HBM roofline of
@@ -38,7 +39,7 @@ HBM_PEAK_GBS = 8000.0     # MI355X published HBM3E bandwidth
 # with the profile it comes from; workloads without a counter run report null.
 MEASURED_TRAFFIC = {
     ("resnet50_n32", "tiled"): (6.5539e9, "profiles/round_kernel_resnet50_n32_hbm_traffic.md"),
-    ("resnet50_n32", "row-major"): (6.5540e9, "profiles/round_kernel_resnet50_n32_hbm_traffic.md"),
+    ("resnet50_n32", "row-major"): (6.5539e9, "profiles/round_kernel_resnet50_n32_hbm_traffic.md"),
     ("bert_n64_bf16", "tiled"): (2.81612e10, "profiles/round_kernel_bert_n64_bf16_hbm_traffic.md"),
 }
 
@@ -79,21 +80,23 @@ def cpu_baseline(cfg, off, budget_cols):
 
 
 def settle(ctx, launch, step, most=300):
-    """Untimed: launch until ten consecutive kernel durations lie within 1 % of each other (3 % for
-    kernels shorter than 0.3 ms, whose launch-to-launch jitter is larger; at most `most` launches).
+    """Untimed: launch windows of ten rounds until the mean kernel duration of a window agrees with
+    that of the window before it within 1 % (2 % for kernels shorter than 0.3 ms, whose
+    launch-to-launch jitter is larger; at most `most` launches): the clock ramp after start-up is over.
     Returns (next step, launches used, whether they settled)."""
     used = 0
-    window = []
+    before = None
     while used < most:
         ctx.set_profiling(True)
         for _ in range(10):
             launch(step); step += 1
-        window = list(ctx.get_kernel_times())
+        mean = float(ctx.get_kernel_times().mean())
         ctx.set_profiling(False)
         used += 10
-        band = 1.01 if min(window) >= 0.3 else 1.03
-        if used >= 20 and max(window) <= band * min(window):
+        band = 0.01 if mean >= 0.3 else 0.02
+        if before is not None and abs(mean - before) <= band * mean:
             return step, used, True
+        before = mean
     return step, used, False
 
 
@@ -292,7 +295,7 @@ def main():
                    "layout": ("tile-major [N/T][n][T], T = 128 bytes" if layout == "tiled" else "row-major [n][N]"),
                    "row_pitch": m["row_pitch"],
                    "settling": f"{m['settle_launches']} untimed launches before the warm-up"
-                               + ("" if m["settled"] else " (durations had not settled within 1 %)")},
+                               + ("" if m["settled"] else " (window means had not settled within 1 %)")},
         "roofline": {"bound": "hbm", "achieved": m["achieved"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": m["achieved"] / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_source,
                      "kernel": kernel, "kernel_ms": m["kernel_ms"], "kernel_ms_median": m["kernel_ms_median"],

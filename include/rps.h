@@ -73,7 +73,7 @@ enum {
        (rps_storage_elems); the columns of the last tile beyond N are padding that is never read
        or written.  All n values of a column then sit within n * 128 bytes of each other, and a
        round streams through memory in address order, reading only a few KB before it writes
-       them back -- measured 17 % faster than row-major on the benchmark's headline workload.
+       them back -- measured 19 % faster than row-major on the benchmark's headline workload.
        Results are those of the row-major layout up to the summation order of the fp64 column
        sums (still fixed, and the same for every receiver of a block).  Worker i's model is the
        strided view [:, i, :].  Every entry point accepts either layout; not available with
