@@ -326,7 +326,8 @@ int rps_get_kernel_time(rps_ctx *ctx, double *total_ms, int64_t *launches);
    doubles; launches beyond it are counted in *launches but not stored). */
 int rps_get_kernel_times(rps_ctx *ctx, double *ms, int64_t capacity, int64_t *launches);
 
-/* hipError_t of the last failing HIP call in this context (0 = none). */
+/* hipError_t of the last failing HIP call in this context (0 = none); with ctx == NULL: of the last
+   failing HIP call of this host thread that had no context yet (inside rps_create). */
 int rps_last_hip_error(const rps_ctx *ctx);
 
 /* Static description of an error code. */

@@ -73,8 +73,15 @@ namespace {
 
 constexpr size_t kMaxProfiledLaunches = 4096;
 
+// hipError_t of the last failing HIP call that had no context to record it in (rps_create,
+// rps_consensus_static), per host thread.
+thread_local int g_last_hip_without_ctx = 0;
+
 int hip_fail(rps_ctx *ctx, hipError_t e) {
-    if (ctx) ctx->last_hip = (int)e;
+    if (ctx)
+        ctx->last_hip = (int)e;
+    else
+        g_last_hip_without_ctx = (int)e;
     return RPS_EHIP;
 }
 #define RPS_HIP(ctx, call)                                  \
@@ -100,17 +107,16 @@ rps::LaunchTuning default_tuning(int32_t n, int32_t dtype, int grad_mode) {
 rps::LaunchTuning tuning_for(const rps_ctx *ctx, int grad_mode) {
     if (ctx->tune_set) return ctx->tune;
     if (ctx->flags & RPS_FLAG_LAYOUT_TILED) {   // a wavefront owns about 4 KB whatever n is: more of them resident
-        int cap;                                 // (measured at n = 8 / 16 / 32 fp32 and n = 64 bf16)
-        // the workgroup's wavefronts share the LDS copy of the noise cells: one workgroup of 14 (12 below 24
-        // workers) per compute unit for fp32, two of 8 for bf16; with more than 32 workers a lane walks its
-        // rows in chunks, and one row pair per chunk keeps the registers at four wavefronts per SIMD
-        if (grad_mode == rps::kGradSynthetic) {
-            const int wpb = ctx->dtype == RPS_DTYPE_BF16 ? 8 : (ctx->n >= 24 ? 14 : 12);
-            return rps::LaunchTuning{ctx->n > 32 ? 2 : 4, wpb, 0, 0};
-        }
-        else if (grad_mode == rps::kGradNone) cap = ctx->n >= 48 ? 8 : 10;
-        else cap = 12;
-        return rps::LaunchTuning{4, 1, cap, 0};
+        // (measured at n = 8 / 16 / 32 fp32 and n = 64 bf16)
+        // in-register gradient: the workgroup's wavefronts share the LDS copy of the noise cells: one
+        // workgroup of 14 (12 below 16 workers) per compute unit for fp32, two of 8 for bf16; with more than
+        // 32 workers a lane walks its rows in chunks, and one row pair per chunk keeps the registers at four
+        // wavefronts per SIMD.  Gradient buffer: the same widths (nothing is shared, the wide workgroup is
+        // simply faster); bf16: 8, at most 16 wavefronts per compute unit
+        const int wide = ctx->dtype == RPS_DTYPE_BF16 ? 8 : (ctx->n >= 16 ? 14 : 12);
+        if (grad_mode == rps::kGradSynthetic) return rps::LaunchTuning{ctx->n > 32 ? 2 : 4, wide, 0, 0};
+        if (grad_mode == rps::kGradBuffer) return rps::LaunchTuning{4, wide, ctx->dtype == RPS_DTYPE_BF16 ? 16 : 0, 0};
+        return rps::LaunchTuning{4, 1, ctx->n >= 48 ? 8 : 10, 0};   // averaging alone: single wavefronts, capped
     }
     return default_tuning(ctx->n, ctx->dtype, grad_mode);
 }
@@ -426,6 +432,7 @@ static int create_impl(rps_ctx **out, int32_t n, int32_t nb, bool external, int6
     }
     if (e != hipSuccess) {
         const bool oom = (e == hipErrorOutOfMemory);
+        g_last_hip_without_ctx = (int)e;
         if (ctx->tab_base) (void)hipFree(ctx->tab_base);
         if (ctx->staging) (void)hipHostFree(ctx->staging);
         if (ctx->radius_staging) (void)hipHostFree(ctx->radius_staging);
@@ -563,8 +570,10 @@ int rps_round_gradient_averaging(rps_ctx *ctx, void *X, const void *G, uint64_t 
     const int rc = prepare_outcome(ctx, step, prm, tab);
     if (rc != RPS_OK) return rc;
     return commit_outcome(ctx, step, prm, timed_launch(ctx, [&] {
-        return rps::launch_gradavg(ctx->dtype, X, G, tab, prm, ctx->max_block_cols,
-                                   tuning_for(ctx, rps::kGradBuffer).max_waves_per_cu, ctx->stream);
+        // single-wavefront workgroups under an occupancy cap (measured best: 12 tile-major)
+        const int cap = ctx->tune_set ? ctx->tune.max_waves_per_cu
+                                      : ((ctx->flags & RPS_FLAG_LAYOUT_TILED) ? 12 : default_tuning(ctx->n, ctx->dtype, rps::kGradBuffer).max_waves_per_cu);
+        return rps::launch_gradavg(ctx->dtype, X, G, tab, prm, ctx->max_block_cols, cap, ctx->stream);
     }));
 }
 
@@ -801,7 +810,7 @@ int rps_noise_cells(float *radius, float *cos_sin) {
     return RPS_OK;
 }
 
-int rps_last_hip_error(const rps_ctx *ctx) { return ctx ? ctx->last_hip : 0; }
+int rps_last_hip_error(const rps_ctx *ctx) { return ctx ? ctx->last_hip : g_last_hip_without_ctx; }
 
 const char *rps_strerror(int code) {
     switch (code) {

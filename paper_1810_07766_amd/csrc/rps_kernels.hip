@@ -1202,19 +1202,23 @@ hipError_t launch_round_narrow(ST *X, const ST *G, const RoundTable *tab, RoundP
 #undef RPS_N
 }
 
-// Workgroup widths: kernels that generate noise share the LDS copy of the noise cells among 4, 8, 12
-// or 14 wavefronts (tile-major: with 81-88 registers per lane one workgroup of 12 or 14 is all a
+// Workgroup widths.  Tile-major: kernels that generate noise share the LDS copy of the noise cells
+// among 4, 8, 12 or 14 wavefronts: with 81-88 registers per lane one workgroup of 12 or 14 is all a
 // compute unit holds, which is both the occupancy this memory system likes best for the in-place
-// walk and the fewest copies of the cells: n = 32 fp32 0.823 of the HBM peak with 2 x 8, 0.834 with
-// 12, 0.838 with 14, 0.827 with 16) or 2, 4 or 8 (row-major, where a tile is n KB); the others keep
-// one wavefront per workgroup (or 4, a tuning option of the row-major kernel).
+// walk and the fewest copies of the cells (n = 32 fp32: 0.823 of the HBM peak with 2 x 8, 0.834
+// with 12, 0.838 with 14, 0.827 with 16).  The round on a gradient buffer shares nothing, and is
+// still 3-4 % faster in workgroups of 12 or 14 than in single wavefronts (a workgroup's wavefronts
+// start together on adjacent tiles of their XCD); the averaging alone is fastest in single
+// wavefronts under its occupancy cap.  Row-major, where a tile is n KB: 2, 4 or 8 wavefronts share
+// the cells; the others keep one wavefront per workgroup (or 4, a tuning option).
 template <typename ST, int GRAD>
 hipError_t launch_round_t(ST *X, const ST *G, const RoundTable *tab, const RoundParams &prm, int64_t max_block_cols,
                           const LaunchTuning &tune, hipStream_t stream) {
     const int r = tune.rows_in_flight, w = tune.waves_per_workgroup;
     if (prm.tiled) {
 #define RPS_T(W) launch_round_narrow<ST, GRAD, kTiledLanes, W>(X, G, tab, prm, max_block_cols, tune, stream)
-        if (GRAD != kGradSynthetic) return RPS_T(1);
+        if (GRAD == kGradNone) return RPS_T(1);
+        if (GRAD == kGradBuffer) return w <= 1 ? RPS_T(1) : (w <= 8 ? RPS_T(8) : (w <= 12 ? RPS_T(12) : RPS_T(14)));
         return w <= 4 ? RPS_T(4) : (w <= 8 ? RPS_T(8) : (w <= 12 ? RPS_T(12) : RPS_T(14)));
 #undef RPS_T
     }

@@ -20,6 +20,11 @@ if not os.path.exists(LIB_PATH):
     raise ImportError(
         f"{LIB_PATH} is not built: run `python -m paper_1810_07766_amd.build` (hipcc, gfx950). "
         "There is no fallback path.")
+# The tensors this binding is handed are PyTorch's, and PyTorch ships its own copy of the HIP
+# runtime: it has to be the one already in the process when the library is loaded, so that both
+# talk to the same runtime (loaded the other way round, the library binds to the system copy, the
+# process ends up with two runtimes, and the library's first HIP call reports no device).
+import torch  # noqa: E402,F401
 _lib = ctypes.CDLL(LIB_PATH)
 
 _ctx_p = ctypes.c_void_p
@@ -82,7 +87,7 @@ class RpsError(RuntimeError):
 
 def _check(code, ctx=None):
     if code != RPS_OK:
-        raise RpsError(code, _lib.rps_last_hip_error(ctx) if ctx else 0)
+        raise RpsError(code, _lib.rps_last_hip_error(ctx) if code == RPS_EHIP else 0)
 
 
 def rps_strerror(code: int) -> str:
