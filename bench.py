@@ -39,7 +39,7 @@ HBM_PEAK_GBS = 8000.0     # MI355X published HBM3E bandwidth
 # with the profile it comes from; workloads without a counter run report null.
 MEASURED_TRAFFIC = {
     ("resnet50_n32", "tiled"): (6.5539e9, "profiles/round_kernel_resnet50_n32_hbm_traffic.md"),
-    ("resnet50_n32", "row-major"): (6.5539e9, "profiles/round_kernel_resnet50_n32_hbm_traffic.md"),
+    ("resnet50_n32", "row-major"): (6.5540e9, "profiles/round_kernel_resnet50_n32_hbm_traffic.md"),
     ("bert_n64_bf16", "tiled"): (2.81612e10, "profiles/round_kernel_bert_n64_bf16_hbm_traffic.md"),
 }
 

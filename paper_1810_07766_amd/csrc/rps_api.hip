@@ -570,9 +570,11 @@ int rps_round_gradient_averaging(rps_ctx *ctx, void *X, const void *G, uint64_t 
     const int rc = prepare_outcome(ctx, step, prm, tab);
     if (rc != RPS_OK) return rc;
     return commit_outcome(ctx, step, prm, timed_launch(ctx, [&] {
-        // single-wavefront workgroups under an occupancy cap (measured best: 12 tile-major)
+        // tile-major fp32 with 24 or more workers: no cap (one wide workgroup per compute unit); other tile-major
+        // cases: single wavefronts, at most 12 per compute unit; row-major: the cap of the round on a gradient buffer
         const int cap = ctx->tune_set ? ctx->tune.max_waves_per_cu
-                                      : ((ctx->flags & RPS_FLAG_LAYOUT_TILED) ? 12 : default_tuning(ctx->n, ctx->dtype, rps::kGradBuffer).max_waves_per_cu);
+                        : ((ctx->flags & RPS_FLAG_LAYOUT_TILED) ? (ctx->dtype == RPS_DTYPE_F32 && ctx->n >= 24 ? 0 : 12)
+                                                                : default_tuning(ctx->n, ctx->dtype, rps::kGradBuffer).max_waves_per_cu);
         return rps::launch_gradavg(ctx->dtype, X, G, tab, prm, ctx->max_block_cols, cap, ctx->stream);
     }));
 }

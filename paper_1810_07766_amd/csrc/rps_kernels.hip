@@ -1434,16 +1434,20 @@ __device__ __forceinline__ void gradavg_tile_narrow(ST *__restrict__ Xt, const S
     }
 }
 
-template <typename ST, int PG>
-__global__ __launch_bounds__(64) void gradavg_kernel_narrow(ST *__restrict__ X, const ST *__restrict__ G,
-                                                            const RoundTable *__restrict__ tab, const RoundParams prm) {
+// WPB wavefronts per workgroup, on adjacent units of their XCD (see unit_index): as for the round on a
+// gradient buffer, a workgroup of 14 is a few per cent faster than single wavefronts at 32 workers.
+template <typename ST, int PG, int WPB>
+__global__ __launch_bounds__(WPB * 64) void gradavg_kernel_narrow(ST *__restrict__ X, const ST *__restrict__ G,
+                                                                  const RoundTable *__restrict__ tab,
+                                                                  const RoundParams prm) {
     constexpr int VEC = Storage<ST>::VEC;
     constexpr int WIDTH = ((64 / kTiledLanes) / PG) * kTiledLanes * VEC;   // columns per wavefront
-    const int lane = threadIdx.x;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int j = blockIdx.y;
-    prepare_next_outcome(prm, linear_block() == 0, j, lane);
+    prepare_next_outcome(prm, linear_block() == 0 && wave == 0, j, lane);
     const int64_t lo = tab->off[j], hi = tab->off[j + 1];
-    const int64_t first = (lo / WIDTH) * WIDTH + linear_block() * WIDTH;
+    const int64_t first = (lo / WIDTH) * WIDTH + unit_index(0, WPB, wave) * WIDTH;
     if (first >= hi) return;   // wave-uniform
     const uint32_t col_off = (uint32_t)(lane % kTiledLanes) * VEC;
     ST *Xt = X + first * prm.n;
@@ -1724,14 +1728,25 @@ hipError_t launch_gradavg(int dtype, void *X, const void *G, const RoundTable *t
         const int pairs = (prm.n + 1) / 2, need = (pairs + 1) / 2;
         const int pg = need > 4 ? 8 : (need > 2 ? 4 : (need > 1 ? 2 : 1));
         const int64_t width = (int64_t)(8 / pg) * kTiledLanes * vec;   // columns per wavefront
-        const dim3 grid = folded_grid((max_block_cols + 2 * width - 2) / width, (unsigned)prm.blocks);
+        const int64_t steps = (max_block_cols + 2 * width - 2) / width;
+        // no cap asked for (the default for fp32 with 24 or more workers: +3 % there, nothing or a loss with
+        // fewer): one workgroup of 14 wavefronts; otherwise single wavefronts under the cap
+        const int wpb = (dtype == 0 && max_waves_per_cu == 0) ? 14 : 1;
+        const dim3 grid = folded_grid8((steps + wpb - 1) / wpb, (unsigned)prm.blocks);
         size_t lds = 0;
         if (max_waves_per_cu > 0 && max_waves_per_cu < 32) {
             lds = ((size_t)kLdsBytesPerCu / max_waves_per_cu) & ~(size_t)255;
             if (lds > 65536) lds = 65536;
         }
-#define RPS_GA(ST, PG) \
-    hipLaunchKernelGGL((gradavg_kernel_narrow<ST, PG>), grid, dim3(64), lds, stream, (ST *)X, (const ST *)G, tab, prm)
+#define RPS_GA(ST, PG)                                                                                                  \
+    do {                                                                                                                \
+        if (wpb == 14)                                                                                                  \
+            hipLaunchKernelGGL((gradavg_kernel_narrow<ST, PG, 14>), grid, dim3(14 * 64), lds, stream, (ST *)X, (const ST *)G, \
+                               tab, prm);                                                                               \
+        else                                                                                                            \
+            hipLaunchKernelGGL((gradavg_kernel_narrow<ST, PG, 1>), grid, dim3(64), lds, stream, (ST *)X, (const ST *)G, tab,  \
+                               prm);                                                                                    \
+    } while (0)
         if (dtype == 0) {
             if (pg == 8) RPS_GA(float, 8); else if (pg == 4) RPS_GA(float, 4); else if (pg == 2) RPS_GA(float, 2); else RPS_GA(float, 1);
         } else {
