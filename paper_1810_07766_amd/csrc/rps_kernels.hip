@@ -1168,7 +1168,21 @@ hipError_t launch_round_narrow(ST *X, const ST *G, const RoundTable *tab, RoundP
     // lane groups per tile: a power of two such that a lane gets two row pairs where the workers allow it
     const int pairs = (prm.n + 1) / 2;
     const int need = (pairs + 1) / 2;
-    const int pg = need > 4 ? 8 : (need > 2 ? 4 : (need > 1 ? 2 : 1));
+    int pg = need > 4 ? 8 : (need > 2 ? 4 : (need > 1 ? 2 : 1));
+    // fp32, worker counts well off a power of two (9-10 and 17-22 workers, where two pairs per lane leave
+    // more than 30 % of the row slots idle): three row pairs per lane on half the lane groups.  Measured at
+    // equal state size: n = 10 0.68 -> 0.75 of the HBM peak, n = 18 0.60 -> 0.72, n = 20 0.65 -> 0.74,
+    // n = 22 0.69 -> 0.72 (where the slots are at least 75 % used it does not pay: n = 6, 12: -4 %).
+    bool three = false;
+    if (sizeof(ST) == 4 && pairs <= 2 * GROUPS) {
+        const int slots = pg * (pairs <= pg ? 1 : 2);
+        const int need3 = (pairs + 2) / 3;
+        const int pg3 = need3 > 2 ? 4 : (need3 > 1 ? 2 : 1);
+        if (10 * pairs < 7 * slots && need3 <= 4 && pg3 >= 2 && pg3 * 3 - pairs < slots - pairs) {
+            three = true;
+            pg = pg3;
+        }
+    }
     const int64_t width = (int64_t)(GROUPS / pg) * TILE;   // columns per wavefront and step
     const int64_t steps = (max_block_cols + 2 * width - 2) / width;
     // fp32: one step (about 4 KB) per wavefront is best at every worker count (n = 8 / 16 / 32: +2-3 %
@@ -1179,6 +1193,12 @@ hipError_t launch_round_narrow(ST *X, const ST *G, const RoundTable *tab, RoundP
     const size_t lds = occupancy_pad(tune.max_waves_per_cu, WPB, static_lds_bytes<GRAD>());
 #define RPS_N(PG, CP, SINGLE) \
     return launch_or_query(round_kernel_narrow<ST, GRAD, LPR, PG, CP, SINGLE, WPB>, grid, WPB, lds, stream, tune, X, G, tab, prm)
+    if constexpr (sizeof(ST) == 4) {
+        if (three) {
+            if (pg == 2) RPS_N(2, 3, true);
+            RPS_N(4, 3, true);
+        }
+    }
     if (pg == 1 && pairs <= 1)
         RPS_N(1, 1, true);
     else if (pg == 1)

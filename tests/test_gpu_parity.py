@@ -77,6 +77,10 @@ SHAPES = [
     (16, 16 * 1544, "unequal8", "bf16"),
     (64, 64 * 1032, "unequal8", "bf16"),
     (6, 6 * 999, "equal", "bf16"),           # N % 8 != 0 -> element-wise path
+    (10, 10 * 1304, "arbitrary", "f32"),     # worker counts whose tile-major kernels give a lane three row pairs
+    (18, 18 * 1032, "unequal8", "f32"),
+    (21, 21 * 800, "equal", "f32"),
+    (22, 22 * 1000, "arbitrary", "f32"),
 ]
 
 
@@ -483,7 +487,7 @@ def test_bf16_rounding_edge_cases(rps):
 
 # ---------------------------------------------------------------------------------------------
 # Tile-major storage (RPS_FLAG_LAYOUT_TILED): same arithmetic on a re-arranged array.
-@pytest.mark.parametrize("n,N,layout,dtype", [SHAPES[k] for k in (0, 1, 3, 4, 6, 7, 8, 9, 10, 11, 12, 14, 15, 16)])
+@pytest.mark.parametrize("n,N,layout,dtype", [SHAPES[k] for k in (0, 1, 3, 4, 6, 7, 8, 9, 10, 11, 12, 14, 15, 16, 17, 18, 19, 20)])
 def test_tiled_layout_every_entry_point(rps, n, N, layout, dtype):
     """Each entry point on the tile-major array against the oracle (the library's tolerance) and
     against the row-major run (same values; the fp64 column sums are taken in a different fixed
