@@ -113,9 +113,12 @@ rps::LaunchTuning tuning_for(const rps_ctx *ctx, int grad_mode) {
         // 32 workers a lane walks its rows in chunks, and one row pair per chunk keeps the registers at four
         // wavefronts per SIMD.  Gradient buffer: the same widths (nothing is shared, the wide workgroup is
         // simply faster); bf16: 8, at most 16 wavefronts per compute unit
-        const int wide = ctx->dtype == RPS_DTYPE_BF16 ? 8 : (ctx->n >= 16 ? 14 : 12);
-        if (grad_mode == rps::kGradSynthetic) return rps::LaunchTuning{ctx->n > 32 ? 2 : 4, wide, 0, 0};
-        if (grad_mode == rps::kGradBuffer) return rps::LaunchTuning{4, wide, ctx->dtype == RPS_DTYPE_BF16 ? 16 : 0, 0};
+        const bool bf16 = ctx->dtype == RPS_DTYPE_BF16;
+        const int wide = bf16 ? 8 : (ctx->n >= 16 ? 14 : 12);
+        // bf16 up to 16 workers on one or two row pairs per lane (139 registers): one workgroup of 12 (+2-4 %)
+        const int wide_noise = bf16 && ctx->n <= 16 && rps::narrow_shape(ctx->n, 2).row_pairs < 3 ? 12 : wide;
+        if (grad_mode == rps::kGradSynthetic) return rps::LaunchTuning{ctx->n > 32 ? 2 : 4, wide_noise, 0, 0};
+        if (grad_mode == rps::kGradBuffer) return rps::LaunchTuning{4, wide, bf16 ? 16 : 0, 0};
         return rps::LaunchTuning{4, 1, ctx->n >= 48 ? 8 : 10, 0};   // averaging alone: single wavefronts, capped
     }
     return default_tuning(ctx->n, ctx->dtype, grad_mode);

@@ -61,6 +61,32 @@ struct LaunchTuning {
                                       // unit that the chosen kernel and launch shape allow
 };
 
+// Tile-major round: how the n rows of a 128-byte tile are dealt to a wavefront's 8 lane groups.  A tile
+// takes 1, 2, 4 or 8 of them (8, 4, 2 or 1 tiles share the wavefront); each group's lanes hold 1, 2 or 3
+// row pairs, or walk more in chunks (row_pairs == 0, more than 32 workers).  Two pairs per lane is the
+// rule; three go where the worker count is far enough off a power of two that two would leave row slots
+// (i.e. loads, and for bf16 the noise arithmetic, which every slot pays) idle:
+//   fp32: only where over 30 % were idle (9-10 and 17-22 workers: 0.60-0.69 -> 0.72-0.76 of the HBM peak
+//         at equal state size; it measured 4 % slower at 6 and 12 workers, +-1 % at 24);
+//   bf16: wherever fewer slots result (5-6, 9-12, 17-24 workers: 0.45-0.57 -> 0.62-0.75).
+// Three pairs on all 8 groups (33-48 workers) are not used: 187-200 registers per lane halve the occupancy.
+struct NarrowShape {
+    int lane_groups;
+    int row_pairs;
+};
+inline NarrowShape narrow_shape(int n, int elem_bytes) {
+    const int pairs = (n + 1) / 2;
+    if (pairs > 16) return {8, 0};
+    const int need = (pairs + 1) / 2;
+    const int pg = need > 4 ? 8 : (need > 2 ? 4 : (need > 1 ? 2 : 1));
+    const int cp = pairs <= pg ? 1 : 2;
+    const int need3 = (pairs + 2) / 3;
+    const int pg3 = need3 > 4 ? 8 : (need3 > 2 ? 4 : (need3 > 1 ? 2 : 1));
+    const int slots = pg * cp, slots3 = pg3 * 3;
+    const bool three = pg3 <= 4 && slots3 < slots && (elem_bytes == 2 || (pg3 >= 2 && 10 * pairs < 7 * slots));
+    return three ? NarrowShape{pg3, 3} : NarrowShape{pg, cp};
+}
+
 // Host side of the synthetic gradient noise: the kNoiseGrid radius values sqrt(-2 ln((k + 1/2)/kNoiseGrid))
 // and the kNoiseGrid (cos, sin) pairs of 2 pi (a + 1/2)/kNoiseGrid, each the nearest fp32.
 void build_noise_cells(float *radius, float *cos_sin);

@@ -938,9 +938,20 @@ struct NarrowTile {
 // Tiled layout only: the tile [tile0, tile0 + LPR * VEC) of all n workers is the contiguous run of
 // n * LPR * 16 bytes at element offset tile0 * n; a wavefront takes 8 / PG adjacent tiles at a time,
 // tiles_per_wave times, WPB such runs apart (the wavefronts of a workgroup stay next to each other).
+//
+// Register budget (second launch bound: wavefronts per SIMD the compiler has to leave room for; 0 = its
+// own choice).  bf16, in-register gradient, 17-32 workers on two row pairs: 130 registers per lane by
+// itself, i.e. three wavefronts per SIMD and one workgroup of 8 per compute unit; held to 128 (no
+// spills) two workgroups fit: 0.69 -> 0.78 of the HBM peak at 32 workers.  The variants that need
+// spills for it (two pairs on fewer lane groups: 139 registers; three pairs: 200) are slower with it.
+template <typename ST, int GRAD, int PG, int CP, bool SINGLE>
+constexpr int narrow_min_waves_per_simd() {
+    return sizeof(ST) == 2 && GRAD == kGradSynthetic && SINGLE && PG == 8 && CP == 2 ? 4 : 0;
+}
+
 template <typename ST, int GRAD, int LPR, int PG, int CP, bool SINGLE, int WPB>
-__global__ __launch_bounds__(WPB * 64) void round_kernel_narrow(ST *__restrict__ X, const ST *__restrict__ G,
-                                                                const RoundTable *__restrict__ tab, const RoundParams prm) {
+__global__ __launch_bounds__(WPB * 64, (narrow_min_waves_per_simd<ST, GRAD, PG, CP, SINGLE>())) void round_kernel_narrow(
+    ST *__restrict__ X, const ST *__restrict__ G, const RoundTable *__restrict__ tab, const RoundParams prm) {
     constexpr int VEC = Storage<ST>::VEC;
     constexpr int WIDTH = ((64 / LPR) / PG) * LPR * VEC;   // columns per wavefront and step
     __shared__ typename LdsFor<GRAD>::type lds;
@@ -1165,24 +1176,8 @@ hipError_t launch_round_narrow(ST *X, const ST *G, const RoundTable *tab, RoundP
                                const LaunchTuning &tune, hipStream_t stream) {
     constexpr int TILE = LPR * Storage<ST>::VEC;
     constexpr int GROUPS = 64 / LPR;
-    // lane groups per tile: a power of two such that a lane gets two row pairs where the workers allow it
-    const int pairs = (prm.n + 1) / 2;
-    const int need = (pairs + 1) / 2;
-    int pg = need > 4 ? 8 : (need > 2 ? 4 : (need > 1 ? 2 : 1));
-    // fp32, worker counts well off a power of two (9-10 and 17-22 workers, where two pairs per lane leave
-    // more than 30 % of the row slots idle): three row pairs per lane on half the lane groups.  Measured at
-    // equal state size: n = 10 0.68 -> 0.75 of the HBM peak, n = 18 0.60 -> 0.72, n = 20 0.65 -> 0.74,
-    // n = 22 0.69 -> 0.72 (where the slots are at least 75 % used it does not pay: n = 6, 12: -4 %).
-    bool three = false;
-    if (sizeof(ST) == 4 && pairs <= 2 * GROUPS) {
-        const int slots = pg * (pairs <= pg ? 1 : 2);
-        const int need3 = (pairs + 2) / 3;
-        const int pg3 = need3 > 2 ? 4 : (need3 > 1 ? 2 : 1);
-        if (10 * pairs < 7 * slots && need3 <= 4 && pg3 >= 2 && pg3 * 3 - pairs < slots - pairs) {
-            three = true;
-            pg = pg3;
-        }
-    }
+    const NarrowShape shape = narrow_shape(prm.n, (int)sizeof(ST));
+    const int pg = shape.lane_groups;
     const int64_t width = (int64_t)(GROUPS / pg) * TILE;   // columns per wavefront and step
     const int64_t steps = (max_block_cols + 2 * width - 2) / width;
     // fp32: one step (about 4 KB) per wavefront is best at every worker count (n = 8 / 16 / 32: +2-3 %
@@ -1193,32 +1188,26 @@ hipError_t launch_round_narrow(ST *X, const ST *G, const RoundTable *tab, RoundP
     const size_t lds = occupancy_pad(tune.max_waves_per_cu, WPB, static_lds_bytes<GRAD>());
 #define RPS_N(PG, CP, SINGLE) \
     return launch_or_query(round_kernel_narrow<ST, GRAD, LPR, PG, CP, SINGLE, WPB>, grid, WPB, lds, stream, tune, X, G, tab, prm)
-    if constexpr (sizeof(ST) == 4) {
-        if (three) {
-            if (pg == 2) RPS_N(2, 3, true);
-            RPS_N(4, 3, true);
-        }
+    switch (shape.row_pairs * 8 + pg) {
+        case 1 * 8 + 1: RPS_N(1, 1, true);
+        case 1 * 8 + 2: RPS_N(2, 1, true);
+        case 1 * 8 + 4: RPS_N(4, 1, true);
+        case 1 * 8 + 8: RPS_N(8, 1, true);
+        case 2 * 8 + 1: RPS_N(1, 2, true);
+        case 2 * 8 + 2: RPS_N(2, 2, true);
+        case 2 * 8 + 4: RPS_N(4, 2, true);
+        case 2 * 8 + 8: RPS_N(8, 2, true);
+        case 3 * 8 + 2: RPS_N(2, 3, true);
+        case 3 * 8 + 4: RPS_N(4, 3, true);
+        case 3 * 8 + 1:
+            if constexpr (sizeof(ST) == 2) RPS_N(1, 3, true);
+            return hipErrorInvalidValue;
+        default: break;
     }
-    if (pg == 1 && pairs <= 1)
-        RPS_N(1, 1, true);
-    else if (pg == 1)
-        RPS_N(1, 2, true);
-    else if (pg == 2 && pairs <= 2)
-        RPS_N(2, 1, true);
-    else if (pg == 2)
-        RPS_N(2, 2, true);
-    else if (pg == 4 && pairs <= 4)
-        RPS_N(4, 1, true);
-    else if (pg == 4)
-        RPS_N(4, 2, true);
-    else if (prm.n <= 2 * GROUPS)   // a lane has one row pair
-        RPS_N(8, 1, true);
-    else if (prm.n <= 4 * GROUPS)   // two pairs: still one load chunk
-        RPS_N(8, 2, true);
-    else if (tune.rows_in_flight <= 2)
-        RPS_N(8, 1, false);
-    else
-        RPS_N(8, 2, false);
+    if (shape.row_pairs != 0) return hipErrorInvalidValue;
+    // more than 32 workers: chunks of one or two row pairs
+    if (tune.rows_in_flight <= 2) RPS_N(8, 1, false);
+    RPS_N(8, 2, false);
 #undef RPS_N
 }
 

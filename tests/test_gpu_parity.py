@@ -81,6 +81,10 @@ SHAPES = [
     (18, 18 * 1032, "unequal8", "f32"),
     (21, 21 * 800, "equal", "f32"),
     (22, 22 * 1000, "arbitrary", "f32"),
+    (5, 5 * 1608, "arbitrary", "bf16"),      # the same for bf16 (5-6, 9-12 and 17-24 workers)
+    (12, 12 * 1032, "unequal8", "bf16"),
+    (20, 20 * 1000, "arbitrary", "bf16"),
+    (24, 24 * 1544, "equal", "bf16"),
 ]
 
 
@@ -487,7 +491,7 @@ def test_bf16_rounding_edge_cases(rps):
 
 # ---------------------------------------------------------------------------------------------
 # Tile-major storage (RPS_FLAG_LAYOUT_TILED): same arithmetic on a re-arranged array.
-@pytest.mark.parametrize("n,N,layout,dtype", [SHAPES[k] for k in (0, 1, 3, 4, 6, 7, 8, 9, 10, 11, 12, 14, 15, 16, 17, 18, 19, 20)])
+@pytest.mark.parametrize("n,N,layout,dtype", [SHAPES[k] for k in (0, 1, 3, 4, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15, 16, 17, 18, 19, 20, 21, 22, 23, 24)])
 def test_tiled_layout_every_entry_point(rps, n, N, layout, dtype):
     """Each entry point on the tile-major array against the oracle (the library's tolerance) and
     against the row-major run (same values; the fp64 column sums are taken in a different fixed
