@@ -568,7 +568,7 @@ def test_tiled_layout_shape_is_checked(rps):
 # ---------------------------------------------------------------------------------------------
 def _random_case(k):
     rng = np.random.default_rng(1000 + k)
-    n = int(rng.choice([1, 2, 3, 4, 5, 6, 7, 8, 9, 12, 15, 16, 17, 24, 31, 32, 33, 48, 63, 64]))
+    n = int(rng.choice([1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 15, 16, 17, 18, 20, 21, 22, 23, 24, 31, 32, 33, 48, 63, 64]))
     dtype = "bf16" if rng.random() < 0.35 else "f32"
     per = int(rng.integers(1, 700))
     N = n * per + int(rng.integers(0, 40))                    # any width: odd pitches, partial last tiles
