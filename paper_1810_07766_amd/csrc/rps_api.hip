@@ -116,7 +116,9 @@ rps::LaunchTuning tuning_for(const rps_ctx *ctx, int grad_mode) {
         const bool bf16 = ctx->dtype == RPS_DTYPE_BF16;
         const int wide = bf16 ? 8 : (ctx->n >= 16 ? 14 : 12);
         // bf16 up to 16 workers on one or two row pairs per lane (139 registers): one workgroup of 12 (+2-4 %)
-        const int wide_noise = bf16 && ctx->n <= 16 && rps::narrow_shape(ctx->n, 2).row_pairs < 3 ? 12 : wide;
+        // fp32 above 32 workers (the chunked kernel, 74 registers): two workgroups of 12 (+1-3 % over one of 14)
+        const int wide_noise = bf16 ? (ctx->n <= 16 && rps::narrow_shape(ctx->n, 2).row_pairs < 3 ? 12 : wide)
+                                    : (ctx->n > 32 ? 12 : wide);
         if (grad_mode == rps::kGradSynthetic) return rps::LaunchTuning{ctx->n > 32 ? 2 : 4, wide_noise, 0, 0};
         if (grad_mode == rps::kGradBuffer) return rps::LaunchTuning{4, wide, bf16 ? 16 : 0, 0};
         // averaging alone: single wavefronts, capped so that a compute unit has about 40 KB in flight (a
