@@ -283,7 +283,8 @@ int rps_convert_layout(rps_ctx *ctx, void *dst, const void *src, int32_t to_tile
  *                        in-register gradient, share one LDS copy of the noise cells); rounded up to
  *                        the nearest width the kernel in question is built for (in-register
  *                        gradient: 4, 8, 12, 14 tile-major and 2, 4, 8 row-major; otherwise 1, or
- *                        4 row-major)
+ *                        4 row-major; always 8 for fp32 tile-major with 57 or more workers, where
+ *                        pairs of wavefronts share a tile)
  *   max_waves_per_cu     cap on resident wavefronts per compute unit (0 = no cap); rounded down to whole
  *                        workgroups, and never below two workgroups (a workgroup holds at most 64 KB
  *                        of the compute unit's 160 KB of LDS); rps_query_occupancy shows the outcome

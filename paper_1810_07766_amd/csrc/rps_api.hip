@@ -114,6 +114,8 @@ rps::LaunchTuning tuning_for(const rps_ctx *ctx, int grad_mode) {
         // wavefronts per SIMD.  Gradient buffer: the same widths (nothing is shared, the wide workgroup is
         // simply faster); bf16: 8, at most 16 wavefronts per compute unit
         const bool bf16 = ctx->dtype == RPS_DTYPE_BF16;
+        if (rps::narrow_split(ctx->n, bf16 ? 2 : 4))   // pairs of wavefronts per tile, workgroups of 8: two per compute unit
+            return rps::LaunchTuning{4, 8, grad_mode == rps::kGradSynthetic ? 0 : 16, 0};
         const int wide = bf16 ? 8 : (ctx->n >= 16 ? 14 : 12);
         // bf16 up to 16 workers on one or two row pairs per lane (139 registers): one workgroup of 12 (+2-4 %)
         // fp32 above 32 workers (the chunked kernel, 74 registers): two workgroups of 12 (+1-3 % over one of 14)

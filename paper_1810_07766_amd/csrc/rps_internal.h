@@ -87,6 +87,17 @@ inline NarrowShape narrow_shape(int n, int elem_bytes) {
     return three ? NarrowShape{pg3, 3} : NarrowShape{pg, cp};
 }
 
+// Tile-major round above 32 workers: the chunked kernel (one wavefront per tile of n x 128 bytes), or
+// round_kernel_split (a pair of wavefronts per tile, 32 rows + the rest, column sums exchanged through
+// LDS).  The split pays once the upper half is nearly as tall as the lower one; measured at equal
+// state size, fp32, fraction of the HBM peak, chunked -> split (fused round / averaging alone / round on
+// a gradient buffer): n = 64 0.77 -> 0.80 / 0.82 -> 0.85 / 0.78 -> 0.80, n = 60 0.73 -> 0.76 / 0.79 -> 0.83
+// / 0.71 -> 0.76, n = 56 0.75 -> 0.75 / 0.80 -> 0.78 / 0.74 -> 0.76, n = 48 0.76 -> 0.71 / 0.84 -> 0.83 /
+// 0.76 -> 0.77.  bf16, where the fused round is bound by the noise arithmetic, loses with it (n = 64:
+// 0.75 -> 0.69 fused, 0.79 -> 0.74 on a gradient buffer; only the averaging alone gains, 0.82 -> 0.84),
+// and all entry points of one dtype must share one summation order (fused == unfused bit for bit).
+inline bool narrow_split(int n, int elem_bytes) { return elem_bytes == 4 && n >= 57; }
+
 // Host side of the synthetic gradient noise: the kNoiseGrid radius values sqrt(-2 ln((k + 1/2)/kNoiseGrid))
 // and the kNoiseGrid (cos, sin) pairs of 2 pi (a + 1/2)/kNoiseGrid, each the nearest fp32.
 void build_noise_cells(float *radius, float *cos_sin);

@@ -789,6 +789,8 @@ struct NarrowTile {
     uint32_t sub_off;  // this lane's tile inside the wavefront's run + its columns inside a row segment
     int64_t c0, lo, hi;   // c0: the lane's first column
     int lg;            // the lane's group inside its tile
+    int n;             // rows this wavefront walks: all prm.n workers, or its half of them (round_kernel_split)
+    int pair0;         // worker pair of its first row (0, or 16 for the upper half): the noise counter
     // The lane's rows are 2*lg + 2*GROUPS*k + r (pair k, r = 0, 1): bit 2*GROUPS*k + r of these words
     // (the masks shifted down by 2*lg) says whether that row's copy reached the server (sum),
     // whether its reply arrived (gets the average), whether it keeps its own v -- rows >= n: none.
@@ -798,19 +800,19 @@ struct NarrowTile {
     // lgw = lane / LPR, col_off = (lane % LPR) * VEC, first = first column of the wavefront's first tile
     __device__ __forceinline__ NarrowTile(const RoundParams &prm_, const LDS &lds_, ST *Xt_, const ST *Gt_,
                                           uint32_t col_off, int64_t first, int64_t lo_, int64_t hi_, uint64_t ucol,
-                                          uint64_t dcol, int lgw)
-        : prm(prm_), lds(lds_), Xt(Xt_), Gt(Gt_), lo(lo_), hi(hi_), lg(lgw % PG) {
+                                          uint64_t dcol, int lgw, int rows, int pair0_)
+        : prm(prm_), lds(lds_), Xt(Xt_), Gt(Gt_), lo(lo_), hi(hi_), lg(lgw % PG), n(rows), pair0(pair0_) {
         const int tw = lgw / PG;   // the lane's tile among the wavefront's
         sub_off = (uint32_t)tw * (uint32_t)prm.n * STRIDE + col_off;
         c0 = first + (int64_t)tw * (LPR * VEC) + col_off;
         // `first` is a multiple of the wavefront's width, which divides 512 columns
         quad_hi = (uint32_t)(first >> 9);
         quad_lo = ((uint32_t)(first >> 2) & 127u) + (((uint32_t)tw * (LPR * VEC) + col_off) >> 2);
-        const uint64_t valid = prm.n >= 64 ? ~0ull : ((1ull << prm.n) - 1);
+        const uint64_t valid = n >= 64 ? ~0ull : ((1ull << n) - 1);
         sum_bits = (ucol & valid) >> (2 * lg);
         avg_bits = (dcol & valid) >> (2 * lg);
         own_bits = (~dcol & valid) >> (2 * lg);
-        limit = (uint32_t)TPW * (uint32_t)prm.n * STRIDE * (uint32_t)sizeof(ST);
+        limit = (uint32_t)TPW * (uint32_t)n * STRIDE * (uint32_t)sizeof(ST);
     }
 
     // bit of pair k, row r of that pair
@@ -820,7 +822,7 @@ struct NarrowTile {
     __device__ __forceinline__ uint32_t off(int i) const { return (uint32_t)i * STRIDE + sub_off; }
 
     __device__ __forceinline__ void load_chunk(int k0, Raw x[2 * CP], Raw g[CG]) const {
-        const int last = prm.n - 1;
+        const int last = n - 1;
 #pragma unroll
         for (int q = 0; q < CP; ++q) {
             int ia = row_a(k0 + q), ib = ia + 1;
@@ -856,7 +858,7 @@ struct NarrowTile {
         float za[CP][VEC], zb[CP][VEC];
         if (GRAD == kGradSynthetic) {
 #pragma unroll
-            for (int q = 0; q < CP; ++q) noise_rows<VEC>(prm, lds, row_a(k0 + q) >> 1, quad_hi, quad_lo, za[q], zb[q]);
+            for (int q = 0; q < CP; ++q) noise_rows<VEC>(prm, lds, pair0 + (row_a(k0 + q) >> 1), quad_hi, quad_lo, za[q], zb[q]);
         }
 #pragma unroll
         for (int q = 0; q < CP; ++q) {
@@ -871,7 +873,8 @@ struct NarrowTile {
         }
     }
 
-    __device__ __forceinline__ void finish(Acc acc[VEC], double inv, int steps) const {
+    template <typename C>
+    __device__ __forceinline__ void finish(Acc acc[VEC], double inv, int steps, const C &combine) const {
         // combine the lane groups: after the butterfly every lane of a column group holds the same sum
         if (GRAD == kGradSynthetic && LPR == 8) {
 #pragma unroll
@@ -883,6 +886,7 @@ struct NarrowTile {
                 for (int e = 0; e < VEC; ++e) acc[e] += __shfl_xor(acc[e], o, 64);
             }
         }
+        combine(acc);   // round_kernel_split: plus the other half's sums
         float vt[VEC];
 #pragma unroll
         for (int e = 0; e < VEC; ++e) vt[e] = (float)(acc[e] * (Acc)inv);
@@ -898,9 +902,9 @@ struct NarrowTile {
     // and every row index is a compile-time constant (the general loop is then not even compiled
     // in: having both in one kernel costs registers).
     // after_first_loads() is called once the first chunk's loads are issued (see noise_fill_begin)
-    template <bool SINGLE, typename F>
-    __device__ __forceinline__ void run(double inv, const F &after_first_loads) const {
-        const int steps = ((prm.n + 1) / 2 + GROUPS - 1) / GROUPS;   // row pairs per lane (wave-uniform)
+    template <bool SINGLE, typename F, typename C>
+    __device__ __forceinline__ void run(double inv, const F &after_first_loads, const C &combine) const {
+        const int steps = ((n + 1) / 2 + GROUPS - 1) / GROUPS;   // row pairs per lane (wave-uniform)
         Acc acc[VEC];
 #pragma unroll
         for (int e = 0; e < VEC; ++e) acc[e] = 0;
@@ -914,7 +918,7 @@ struct NarrowTile {
         after_first_loads(std::integral_constant<int, FULL ? (GRAD == kGradBuffer ? 4 : 2) * CP : 0>{});
         if constexpr (SINGLE) {
             process_chunk(0, xa, ga, acc);
-            finish(acc, inv, steps);
+            finish(acc, inv, steps, combine);
             return;
         }
         int k = 0;
@@ -931,7 +935,7 @@ struct NarrowTile {
         } else {
             process_chunk(k, xa, ga, acc);
         }
-        finish(acc, inv, steps);
+        finish(acc, inv, steps, combine);
     }
 };
 
@@ -971,6 +975,7 @@ __global__ __launch_bounds__(WPB * 64, (narrow_min_waves_per_simd<ST, GRAD, PG, 
     const uint64_t ucol = tab->ucol[j], dcol = tab->dcol[j];
     const double inv = tab->inv_cnt[j];
     const uint32_t col_off = (uint32_t)(lane % LPR) * VEC;
+    const auto nothing = [](auto) {};
     for (int it = 0; it < prm.tiles_per_wave; ++it) {
         const int64_t first = (lo / WIDTH) * WIDTH + unit_index(it, WPB, wave) * WIDTH;
         if (first >= hi) break;   // wave-uniform
@@ -978,14 +983,89 @@ __global__ __launch_bounds__(WPB * 64, (narrow_min_waves_per_simd<ST, GRAD, PG, 
         const ST *Gt = G ? G + first * prm.n : nullptr;
         const bool full = prm.vec_ok && first >= lo && first + WIDTH <= hi;   // wave-uniform
         if (full) {
-            const NarrowTile<ST, GRAD, LPR, PG, CP, true> t(prm, lds, Xt, Gt, col_off, first, lo, hi, ucol, dcol, lane / LPR);
-            t.template run<SINGLE>(inv, finish_fill);
+            const NarrowTile<ST, GRAD, LPR, PG, CP, true> t(prm, lds, Xt, Gt, col_off, first, lo, hi, ucol, dcol, lane / LPR,
+                                                            prm.n, 0);
+            t.template run<SINGLE>(inv, finish_fill, nothing);
         } else {
-            const NarrowTile<ST, GRAD, LPR, PG, CP, false> t(prm, lds, Xt, Gt, col_off, first, lo, hi, ucol, dcol, lane / LPR);
-            t.template run<SINGLE>(inv, finish_fill);
+            const NarrowTile<ST, GRAD, LPR, PG, CP, false> t(prm, lds, Xt, Gt, col_off, first, lo, hi, ucol, dcol, lane / LPR,
+                                                             prm.n, 0);
+            t.template run<SINGLE>(inv, finish_fill, nothing);
         }
     }
     finish_fill(std::integral_constant<int, 0>{});
+    prepare_next_outcome(prm, linear_block() == 0 && wave == 0, j, lane);
+}
+
+// More than 32 workers, tiled layout: a tile (n x 128 bytes, up to 8 KB) is shared by a PAIR of
+// wavefronts of the workgroup -- wavefront 2q takes rows 0..31, wavefront 2q+1 the rows from 32 on,
+// each as a single load chunk like a tile of 32 workers -- and the two exchange their column sums
+// through LDS before either writes the average back.  What this buys is the memory behaviour of the
+// 4 KB tile: an in-place walk is the slower the more data lies between a read and its write-back.
+// Used for fp32 from 57 workers on (narrow_split() has the measurements); bf16 is not built.
+// Barriers: every wavefront of the workgroup executes exactly one for the noise-cell copy (at its
+// first step, whether or not it has a tile) and exactly one per step for the exchange (whether or
+// not it has a tile), so their counts agree however the tiles run out; the two wavefronts of a pair
+// always share their tile and hence take the same path.  The exchange slots alternate between two
+// buffers: a wavefront rewrites a slot two steps later, after a barrier that its partner reaches
+// only once it has used the values read from it.
+template <typename ST, int GRAD, int LPR, int WPB>
+__global__ __launch_bounds__(WPB * 64, (narrow_min_waves_per_simd<ST, GRAD, 8, 2, true>())) void round_kernel_split(
+    ST *__restrict__ X, const ST *__restrict__ G, const RoundTable *__restrict__ tab, const RoundParams prm) {
+    static_assert(WPB % 2 == 0 && 64 / LPR == 8, "pairs of wavefronts; a tile takes all 8 lane groups");
+    constexpr int VEC = Storage<ST>::VEC;
+    constexpr int WIDTH = LPR * VEC;   // columns per pair of wavefronts and step: one tile
+    constexpr uint32_t STRIDE = LPR * VEC;
+    constexpr int kHalf = 32;          // rows of the lower half
+    using Acc = typename Storage<ST>::Acc;
+    __shared__ typename LdsFor<GRAD>::type lds;
+    __shared__ Acc exchange[2][WPB][LPR][VEC];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int upper = wave & 1;
+    const int j = blockIdx.y;
+    noise_fill_begin<WPB>(lds, prm.noise_cells, wave, lane);
+    bool fill_pending = true;
+    const auto finish_fill = [&](auto pending) {
+        if (fill_pending) noise_fill_end<decltype(pending)::value>(lds);
+        fill_pending = false;
+    };
+    const int64_t lo = tab->off[j], hi = tab->off[j + 1];
+    const uint64_t ucol = tab->ucol[j] >> (upper * kHalf), dcol = tab->dcol[j] >> (upper * kHalf);
+    const double inv = tab->inv_cnt[j];
+    const int rows = upper ? prm.n - kHalf : kHalf;   // the launcher guarantees n > 32
+    const uint32_t col_off = (uint32_t)(lane % LPR) * VEC;
+    for (int it = 0; it < prm.tiles_per_wave; ++it) {
+        const int64_t first = (lo / WIDTH) * WIDTH + unit_index(it, WPB / 2, wave >> 1) * WIDTH;
+        Acc(*const mine)[VEC] = exchange[it & 1][wave], (*const theirs)[VEC] = exchange[it & 1][wave ^ 1];
+        const auto exchange_barrier = [] { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
+        const auto add_other_half = [&](Acc acc[VEC]) {
+            if (lane < LPR) {
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) mine[lane][e] = acc[e];
+            }
+            exchange_barrier();
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) acc[e] += theirs[lane % LPR][e];
+        };
+        if (first >= hi) {   // wave-uniform, and the same for both wavefronts of a pair
+            finish_fill(std::integral_constant<int, 0>{});
+            exchange_barrier();
+            continue;
+        }
+        ST *Xt = X + first * prm.n + upper * (kHalf * STRIDE);
+        const ST *Gt = G ? G + first * prm.n + upper * (kHalf * STRIDE) : nullptr;
+        const bool full = prm.vec_ok && first >= lo && first + WIDTH <= hi;   // wave-uniform
+        if (full) {
+            const NarrowTile<ST, GRAD, LPR, 8, 2, true> t(prm, lds, Xt, Gt, col_off, first, lo, hi, ucol, dcol, lane / LPR, rows,
+                                                          upper * (kHalf / 2));
+            t.template run<true>(inv, finish_fill, add_other_half);
+        } else {
+            const NarrowTile<ST, GRAD, LPR, 8, 2, false> t(prm, lds, Xt, Gt, col_off, first, lo, hi, ucol, dcol, lane / LPR, rows,
+                                                           upper * (kHalf / 2));
+            t.template run<true>(inv, finish_fill, add_other_half);
+        }
+    }
+    finish_fill(std::integral_constant<int, 0>{});   // only if the loop had no step at all
     prepare_next_outcome(prm, linear_block() == 0 && wave == 0, j, lane);
 }
 
@@ -1211,6 +1291,20 @@ hipError_t launch_round_narrow(ST *X, const ST *G, const RoundTable *tab, RoundP
 #undef RPS_N
 }
 
+template <typename ST, int GRAD, int LPR, int WPB>
+hipError_t launch_round_split(ST *X, const ST *G, const RoundTable *tab, RoundParams prm, int64_t max_block_cols,
+                              const LaunchTuning &tune, hipStream_t stream) {
+    constexpr int TILE = LPR * Storage<ST>::VEC;
+    if (prm.n <= 32 || prm.n > 64) return hipErrorInvalidValue;   // the kernel's two halves are rows 0..31 and 32..n-1
+    const int64_t steps = (max_block_cols + 2 * TILE - 2) / TILE;
+    prm.tiles_per_wave = steps_per_wave(GRAD, steps, WPB / 2, prm.blocks, tune.tiles_per_wave, sizeof(ST) == 4 ? 1 : 2);
+    const int64_t per_wg = (int64_t)(WPB / 2) * prm.tiles_per_wave;
+    const dim3 grid = folded_grid8((steps + per_wg - 1) / per_wg, (unsigned)prm.blocks);
+    const size_t fixed = static_lds_bytes<GRAD>() + sizeof(typename Storage<ST>::Acc) * 2 * WPB * LPR * Storage<ST>::VEC;
+    const size_t lds = occupancy_pad(tune.max_waves_per_cu, WPB, fixed);
+    return launch_or_query(round_kernel_split<ST, GRAD, LPR, WPB>, grid, WPB, lds, stream, tune, X, G, tab, prm);
+}
+
 // Workgroup widths.  Tile-major: kernels that generate noise share the LDS copy of the noise cells
 // among 4, 8, 12 or 14 wavefronts: with 81-88 registers per lane one workgroup of 12 or 14 is all a
 // compute unit holds, which is both the occupancy this memory system likes best for the in-place
@@ -1225,6 +1319,9 @@ hipError_t launch_round_t(ST *X, const ST *G, const RoundTable *tab, const Round
                           const LaunchTuning &tune, hipStream_t stream) {
     const int r = tune.rows_in_flight, w = tune.waves_per_workgroup;
     if (prm.tiled) {
+        if constexpr (sizeof(ST) == 4) {
+            if (narrow_split(prm.n, 4)) return launch_round_split<ST, GRAD, kTiledLanes, 8>(X, G, tab, prm, max_block_cols, tune, stream);
+        }
 #define RPS_T(W) launch_round_narrow<ST, GRAD, kTiledLanes, W>(X, G, tab, prm, max_block_cols, tune, stream)
         if (GRAD == kGradNone) return RPS_T(1);
         if (GRAD == kGradBuffer) return w <= 1 ? RPS_T(1) : (w <= 8 ? RPS_T(8) : (w <= 12 ? RPS_T(12) : RPS_T(14)));

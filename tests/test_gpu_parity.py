@@ -85,6 +85,8 @@ SHAPES = [
     (12, 12 * 1032, "unequal8", "bf16"),
     (20, 20 * 1000, "arbitrary", "bf16"),
     (24, 24 * 1544, "equal", "bf16"),
+    (57, 57 * 1000, "unequal8", "f32"),      # fp32 tile-major from 57 workers on: two wavefronts share a tile
+    (60, 60 * 520, "arbitrary", "f32"),
 ]
 
 
@@ -491,7 +493,7 @@ def test_bf16_rounding_edge_cases(rps):
 
 # ---------------------------------------------------------------------------------------------
 # Tile-major storage (RPS_FLAG_LAYOUT_TILED): same arithmetic on a re-arranged array.
-@pytest.mark.parametrize("n,N,layout,dtype", [SHAPES[k] for k in (0, 1, 3, 4, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15, 16, 17, 18, 19, 20, 21, 22, 23, 24)])
+@pytest.mark.parametrize("n,N,layout,dtype", [SHAPES[k] for k in (0, 1, 3, 4, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15, 16, 17, 18, 19, 20, 21, 22, 23, 24, 25, 26)])
 def test_tiled_layout_every_entry_point(rps, n, N, layout, dtype):
     """Each entry point on the tile-major array against the oracle (the library's tolerance) and
     against the row-major run (same values; the fp64 column sums are taken in a different fixed
