@@ -1323,19 +1323,24 @@ hipError_t launch_round_t(ST *X, const ST *G, const RoundTable *tab, const Round
             if (narrow_split(prm.n, 4)) return launch_round_split<ST, GRAD, kTiledLanes, 8>(X, G, tab, prm, max_block_cols, tune, stream);
         }
 #define RPS_T(W) launch_round_narrow<ST, GRAD, kTiledLanes, W>(X, G, tab, prm, max_block_cols, tune, stream)
-        if (GRAD == kGradNone) return RPS_T(1);
-        if (GRAD == kGradBuffer) return w <= 1 ? RPS_T(1) : (w <= 8 ? RPS_T(8) : (w <= 12 ? RPS_T(12) : RPS_T(14)));
-        return w <= 4 ? RPS_T(4) : (w <= 8 ? RPS_T(8) : (w <= 12 ? RPS_T(12) : RPS_T(14)));
+        // (if constexpr: only the widths a gradient source is launched with are compiled)
+        if constexpr (GRAD == kGradNone)
+            return RPS_T(1);
+        else if constexpr (GRAD == kGradBuffer)
+            return w <= 1 ? RPS_T(1) : (w <= 8 ? RPS_T(8) : (w <= 12 ? RPS_T(12) : RPS_T(14)));
+        else
+            return w <= 4 ? RPS_T(4) : (w <= 8 ? RPS_T(8) : (w <= 12 ? RPS_T(12) : RPS_T(14)));
 #undef RPS_T
     }
 #define RPS_V(R, W) launch_round_v<ST, GRAD, R, W>(X, G, tab, prm, max_block_cols, tune, stream)
-    if (GRAD == kGradSynthetic) {
+    if constexpr (GRAD == kGradSynthetic) {
         if (w <= 2) return r <= 2 ? RPS_V(2, 2) : RPS_V(4, 2);
         if (w <= 4) return r <= 2 ? RPS_V(2, 4) : RPS_V(4, 4);
         return r <= 2 ? RPS_V(2, 8) : RPS_V(4, 8);
+    } else {
+        if (w == 1) return r <= 2 ? RPS_V(2, 1) : RPS_V(4, 1);
+        return r <= 2 ? RPS_V(2, 4) : RPS_V(4, 4);
     }
-    if (w == 1) return r <= 2 ? RPS_V(2, 1) : RPS_V(4, 1);
-    return r <= 2 ? RPS_V(2, 4) : RPS_V(4, 4);
 #undef RPS_V
 }
 
