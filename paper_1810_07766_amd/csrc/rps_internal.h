@@ -88,8 +88,8 @@ inline NarrowShape narrow_shape(int n, int elem_bytes) {
 }
 
 // Tile-major round above 32 workers: the chunked kernel (one wavefront per tile of n x 128 bytes), or
-// round_kernel_split (a pair of wavefronts per tile, 32 rows + the rest, column sums exchanged through
-// LDS).  The split pays once the upper half is nearly as tall as the lower one; measured at equal
+// round_kernel_split (a pair of wavefronts per tile, half the row pairs each, column sums exchanged
+// through LDS).  The split pays once each half nearly fills a wavefront's 32 row slots; measured at equal
 // state size, fp32, fraction of the HBM peak, chunked -> split (fused round / averaging alone / round on
 // a gradient buffer): n = 64 0.77 -> 0.80 / 0.82 -> 0.85 / 0.78 -> 0.80, n = 60 0.73 -> 0.76 / 0.79 -> 0.83
 // / 0.71 -> 0.76, n = 56 0.75 -> 0.75 / 0.80 -> 0.78 / 0.74 -> 0.76, n = 48 0.76 -> 0.71 / 0.84 -> 0.83 /

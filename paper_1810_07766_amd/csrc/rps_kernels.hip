@@ -997,10 +997,11 @@ __global__ __launch_bounds__(WPB * 64, (narrow_min_waves_per_simd<ST, GRAD, PG, 
 }
 
 // More than 32 workers, tiled layout: a tile (n x 128 bytes, up to 8 KB) is shared by a PAIR of
-// wavefronts of the workgroup -- wavefront 2q takes rows 0..31, wavefront 2q+1 the rows from 32 on,
-// each as a single load chunk like a tile of 32 workers -- and the two exchange their column sums
-// through LDS before either writes the average back.  What this buys is the memory behaviour of the
-// 4 KB tile: an in-place walk is the slower the more data lies between a read and its write-back.
+// wavefronts of the workgroup -- wavefront 2q takes the lower half of the row pairs (rounded up),
+// wavefront 2q+1 the rest, each as a single load chunk like a tile of up to 32 workers -- and the two
+// exchange their column sums through LDS before either writes the average back.  What this buys is
+// the memory behaviour of the 4 KB tile: an in-place walk is the slower the more data lies between a
+// read and its write-back.
 // Used for fp32 from 57 workers on (narrow_split() has the measurements); bf16 is not built.
 // Barriers: every wavefront of the workgroup executes exactly one for the noise-cell copy (at its
 // first step, whether or not it has a tile) and exactly one per step for the exchange (whether or
@@ -1015,7 +1016,6 @@ __global__ __launch_bounds__(WPB * 64, (narrow_min_waves_per_simd<ST, GRAD, 8, 2
     constexpr int VEC = Storage<ST>::VEC;
     constexpr int WIDTH = LPR * VEC;   // columns per pair of wavefronts and step: one tile
     constexpr uint32_t STRIDE = LPR * VEC;
-    constexpr int kHalf = 32;          // rows of the lower half
     using Acc = typename Storage<ST>::Acc;
     __shared__ typename LdsFor<GRAD>::type lds;
     __shared__ Acc exchange[2][WPB][LPR][VEC];
@@ -1030,9 +1030,10 @@ __global__ __launch_bounds__(WPB * 64, (narrow_min_waves_per_simd<ST, GRAD, 8, 2
         fill_pending = false;
     };
     const int64_t lo = tab->off[j], hi = tab->off[j + 1];
+    const int kHalf = ((prm.n + 3) / 4) * 2;   // rows of the lower half: half the row pairs, rounded up (wave-uniform)
     const uint64_t ucol = tab->ucol[j] >> (upper * kHalf), dcol = tab->dcol[j] >> (upper * kHalf);
     const double inv = tab->inv_cnt[j];
-    const int rows = upper ? prm.n - kHalf : kHalf;   // the launcher guarantees n > 32
+    const int rows = upper ? prm.n - kHalf : kHalf;   // the launcher guarantees 32 < n <= 64: both halves hold 1..32 rows
     const uint32_t col_off = (uint32_t)(lane % LPR) * VEC;
     for (int it = 0; it < prm.tiles_per_wave; ++it) {
         const int64_t first = (lo / WIDTH) * WIDTH + unit_index(it, WPB / 2, wave >> 1) * WIDTH;
@@ -1295,7 +1296,7 @@ template <typename ST, int GRAD, int LPR, int WPB>
 hipError_t launch_round_split(ST *X, const ST *G, const RoundTable *tab, RoundParams prm, int64_t max_block_cols,
                               const LaunchTuning &tune, hipStream_t stream) {
     constexpr int TILE = LPR * Storage<ST>::VEC;
-    if (prm.n <= 32 || prm.n > 64) return hipErrorInvalidValue;   // the kernel's two halves are rows 0..31 and 32..n-1
+    if (prm.n <= 32 || prm.n > 64) return hipErrorInvalidValue;   // each half must hold 1..32 rows
     const int64_t steps = (max_block_cols + 2 * TILE - 2) / TILE;
     prm.tiles_per_wave = steps_per_wave(GRAD, steps, WPB / 2, prm.blocks, tune.tiles_per_wave, sizeof(ST) == 4 ? 1 : 2);
     const int64_t per_wg = (int64_t)(WPB / 2) * prm.tiles_per_wave;
