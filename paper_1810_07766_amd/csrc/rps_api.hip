@@ -122,7 +122,12 @@ rps::LaunchTuning tuning_for(const rps_ctx *ctx, int grad_mode) {
         const int wide_noise = bf16 ? (ctx->n <= 16 && rps::narrow_shape(ctx->n, 2).row_pairs < 3 ? 12 : wide)
                                     : (ctx->n > 32 ? 12 : wide);
         if (grad_mode == rps::kGradSynthetic) return rps::LaunchTuning{ctx->n > 32 ? 2 : 4, wide_noise, 0, 0};
-        if (grad_mode == rps::kGradBuffer) return rps::LaunchTuning{4, wide, bf16 ? 16 : 0, 0};
+        if (grad_mode == rps::kGradBuffer) {
+            // bf16, 33-61 workers (the chunked kernel at 185 registers): single wavefronts, at most 10 per compute
+            // unit (n = 33 0.66 -> 0.79 of the HBM peak, n = 44 0.73 -> 0.78, n = 56 0.75 -> 0.77; n = 64 0.79 -> 0.77: not there)
+            if (bf16 && ctx->n > 32 && ctx->n < 62) return rps::LaunchTuning{4, 1, 10, 0};
+            return rps::LaunchTuning{4, wide, bf16 ? 16 : 0, 0};
+        }
         // averaging alone: single wavefronts, capped so that a compute unit has about 40 KB in flight (a
         // wavefront step is 4 KB from 3 workers on, 2 KB with 2, 1 KB with 1: n = 2 0.75 -> 0.87 of the HBM peak
         // with 20 instead of 10, n = 1 0.37 -> 0.66 without a cap)
