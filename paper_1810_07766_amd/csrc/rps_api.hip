@@ -104,36 +104,65 @@ rps::LaunchTuning default_tuning(int32_t n, int32_t dtype, int grad_mode) {
     return n >= 24 ? rps::LaunchTuning{2, 2, 0, 0} : rps::LaunchTuning{4, 4, 12, 0};
 }
 
+// Tile-major launch shapes, from sweeps over 1-64 workers in both dtypes at equal state size (fractions of
+// the HBM peak in the comments).  Two things decide: how many bytes a wavefront step covers (a tile is
+// n x 128 bytes and 8 / lane_groups tiles share a wavefront) and how full its row slots are.
+rps::LaunchTuning tiled_tuning(int n, bool bf16, int grad_mode) {
+    const int elem = bf16 ? 2 : 4;
+    const bool noise = grad_mode == rps::kGradSynthetic, buffer = grad_mode == rps::kGradBuffer;
+    if (rps::narrow_split(n, elem))   // pairs of wavefronts per tile, workgroups of 8: two per compute unit
+        return rps::LaunchTuning{4, 8, noise ? 0 : 16, 0};
+    if (n > 32) {   // the chunked kernel
+        // in-register gradient: one row pair per chunk keeps the registers at four or more wavefronts per SIMD;
+        // fp32 (74 registers): two workgroups of 12 (+1-3 % over one of 14), bf16: two of 8
+        // (bf16 below 62 workers: workgroups of 4, n = 40 0.68 -> 0.70, n = 56 0.72 -> 0.74; not at 64)
+        if (noise) return rps::LaunchTuning{2, bf16 ? (n < 62 ? 4 : 8) : 12, 0, 0};
+        // gradient buffer: single wavefronts -- bf16 below 62 workers (185 registers; n = 33 0.66 -> 0.79,
+        // n = 44 0.73 -> 0.78, n = 56 0.75 -> 0.77; n = 64 0.79 -> 0.77: not there), fp32 with one row pair
+        // per chunk (n = 36 0.75 -> 0.78, n = 56 0.73 -> 0.77)
+        if (buffer)
+            return bf16 ? (n < 62 ? rps::LaunchTuning{4, 1, 10, 0} : rps::LaunchTuning{4, 8, 16, 0})
+                        : rps::LaunchTuning{2, 1, n < 40 ? 10 : 8, 0};
+        // averaging alone: from 52 workers on one row pair per chunk (bf16 n = 64 0.81 -> 0.86, fp32 n = 56 0.80 -> 0.83)
+        return rps::LaunchTuning{n >= 52 ? 2 : 4, 1, n >= 48 ? 8 : 10, 0};
+    }
+    const rps::NarrowShape shape = rps::narrow_shape(n, elem);
+    const int slots = 2 * shape.lane_groups * shape.row_pairs;   // rows a tile's lanes can hold
+    const bool three = shape.row_pairs == 3;
+    // Single wavefronts: as many per compute unit as put about 44 KB in flight (4 KB steps: 11; 3 KB,
+    // e.g. 12 or 24 workers: 14, measured 0.80 -> 0.84 and 0.77 -> 0.84 against 10; 2 KB, 2 workers: 22,
+    // 0.75 -> 0.87; 6 KB, bf16 on three row pairs: 8; 1 KB, 1 worker: no cap, 0.37 -> 0.66)
+    const int step_bytes = (8 / shape.lane_groups) * n * RPS_TILE_BYTES;
+    const int fit = 45056 / step_bytes;
+    const rps::LaunchTuning singles{4, 1, fit >= 32 ? 0 : std::max(fit, 8), 0};
+    if (!noise && !buffer) return singles;   // averaging alone
+    if (buffer) {
+        // nothing is shared between wavefronts; a wide workgroup (its wavefronts start together on adjacent
+        // tiles of their XCD) is still 2-4 % faster where the row slots are full, single wavefronts are
+        // where they are not (fp32 n = 12 0.75 -> 0.78, n = 5 0.73 -> 0.76; bf16 n = 10 0.72 -> 0.78,
+        // n = 20 0.72 -> 0.77, n = 28 0.74 -> 0.78)
+        if (bf16) {
+            if (!three && n == slots && n >= 4 && n <= 16) return rps::LaunchTuning{4, 14, 0, 0};   // 4, 8, 16 workers
+            if (three && (shape.lane_groups == 1 || n == slots)) return rps::LaunchTuning{4, 8, 16, 0};   // 5, 6, 12, 24
+            return singles;
+        }
+        if (n > 2 && 100 * n > 85 * slots) return rps::LaunchTuning{4, n >= 16 ? 14 : 12, 0, 0};
+        return singles;
+    }
+    // in-register gradient: the workgroup's wavefronts share one LDS copy of the noise cells.  fp32 (81-90
+    // registers): one workgroup of 14 per compute unit (12 below 16 workers; also 12 at 23-31 workers, whose
+    // tiles leave row slots idle: n = 24 0.73 -> 0.76, n = 28 0.76 -> 0.78); three row pairs (125
+    // registers): two workgroups of 8 (n = 18 0.72 -> 0.77, n = 20 0.74 -> 0.77).  bf16 (128-139 registers,
+    // 200 on three row pairs): two workgroups of 8, one of 12 up to 16 workers, workgroups of 4 on three
+    // row pairs (n = 10 0.61 -> 0.65, n = 12 0.69 -> 0.72, n = 24 0.68 -> 0.70)
+    if (three) return rps::LaunchTuning{4, bf16 ? 4 : 8, 0, 0};
+    if (bf16) return rps::LaunchTuning{4, n > 16 ? 8 : (shape.lane_groups == 4 ? 4 : 12), 0, 0};   // 13-16 workers: 0.70 -> 0.72 in workgroups of 4
+    return rps::LaunchTuning{4, n >= 16 && (n < 23 || n == 32) ? 14 : 12, 0, 0};
+}
+
 rps::LaunchTuning tuning_for(const rps_ctx *ctx, int grad_mode) {
     if (ctx->tune_set) return ctx->tune;
-    if (ctx->flags & RPS_FLAG_LAYOUT_TILED) {   // a wavefront owns about 4 KB whatever n is: more of them resident
-        // (measured at n = 8 / 16 / 32 fp32 and n = 64 bf16)
-        // in-register gradient: the workgroup's wavefronts share the LDS copy of the noise cells: one
-        // workgroup of 14 (12 below 16 workers) per compute unit for fp32, two of 8 for bf16; with more than
-        // 32 workers a lane walks its rows in chunks, and one row pair per chunk keeps the registers at four
-        // wavefronts per SIMD.  Gradient buffer: the same widths (nothing is shared, the wide workgroup is
-        // simply faster); bf16: 8, at most 16 wavefronts per compute unit
-        const bool bf16 = ctx->dtype == RPS_DTYPE_BF16;
-        if (rps::narrow_split(ctx->n, bf16 ? 2 : 4))   // pairs of wavefronts per tile, workgroups of 8: two per compute unit
-            return rps::LaunchTuning{4, 8, grad_mode == rps::kGradSynthetic ? 0 : 16, 0};
-        const int wide = bf16 ? 8 : (ctx->n >= 16 ? 14 : 12);
-        // bf16 up to 16 workers on one or two row pairs per lane (139 registers): one workgroup of 12 (+2-4 %)
-        // fp32 above 32 workers (the chunked kernel, 74 registers): two workgroups of 12 (+1-3 % over one of 14)
-        const int wide_noise = bf16 ? (ctx->n <= 16 && rps::narrow_shape(ctx->n, 2).row_pairs < 3 ? 12 : wide)
-                                    : (ctx->n > 32 ? 12 : wide);
-        if (grad_mode == rps::kGradSynthetic) return rps::LaunchTuning{ctx->n > 32 ? 2 : 4, wide_noise, 0, 0};
-        if (grad_mode == rps::kGradBuffer) {
-            // bf16, 33-61 workers (the chunked kernel at 185 registers): single wavefronts, at most 10 per compute
-            // unit (n = 33 0.66 -> 0.79 of the HBM peak, n = 44 0.73 -> 0.78, n = 56 0.75 -> 0.77; n = 64 0.79 -> 0.77: not there)
-            if (bf16 && ctx->n > 32 && ctx->n < 62) return rps::LaunchTuning{4, 1, 10, 0};
-            return rps::LaunchTuning{4, wide, bf16 ? 16 : 0, 0};
-        }
-        // averaging alone: single wavefronts, capped so that a compute unit has about 40 KB in flight (a
-        // wavefront step is 4 KB from 3 workers on, 2 KB with 2, 1 KB with 1: n = 2 0.75 -> 0.87 of the HBM peak
-        // with 20 instead of 10, n = 1 0.37 -> 0.66 without a cap)
-        const int cap = ctx->n >= 48 ? 8 : (ctx->n >= 3 ? 10 : (ctx->n == 2 ? 20 : 0));
-        return rps::LaunchTuning{4, 1, cap, 0};
-    }
+    if (ctx->flags & RPS_FLAG_LAYOUT_TILED) return tiled_tuning(ctx->n, ctx->dtype == RPS_DTYPE_BF16, grad_mode);
     return default_tuning(ctx->n, ctx->dtype, grad_mode);
 }
 

@@ -242,7 +242,7 @@ def test_occupancy_cap_reaches_the_launch(rps):
         ctx.destroy()
     # built-in defaults (no tuning call): averaging alone is capped, the in-register round is not
     ctx = rps.RpsContext(32, 32 * 4096, 0.05, 0.1, 0, rps.RPS_DTYPE_F32, flags=rps.RPS_FLAG_LAYOUT_TILED)
-    assert ctx.query_occupancy(0) == 10              # single wavefronts under the cap
+    assert ctx.query_occupancy(0) == 11              # single wavefronts under the cap (about 44 KB in flight: 11 steps of 4 KB)
     assert ctx.query_occupancy(1) == 14              # gradient buffer: one workgroup of 14 as well
     assert ctx.query_occupancy(2) == 14              # 81-88 registers per lane: one workgroup of 14 wavefronts (measured best)
     ctx.destroy()
