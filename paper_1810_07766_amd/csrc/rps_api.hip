@@ -92,15 +92,31 @@ int hip_fail(rps_ctx *ctx, hipError_t e) {
 
 bool step_ok(uint64_t step) { return step < (1ull << 56); }
 
-// Measured best launch shapes on MI355X (sweeps over rows per chunk, workgroup width and the
-// occupancy cap at n = 8 / 16 / 32 fp32 and n = 64 bf16, for each gradient source).  The in-place
-// update mixes n read streams with n write streams; the memory system handles that best with few
-// wavefronts resident -- fewer still when a gradient buffer doubles the loads in flight.
+// Row-major launch shapes, from sweeps over rows per chunk, workgroup width and occupancy cap at 2-64
+// workers in both dtypes and for each gradient source (fractions of the HBM peak in the comments).  The
+// in-place update mixes n read streams with n write streams, and a wavefront's tile is n KB: the memory
+// system handles that best with few wavefronts resident -- fewer still when a gradient buffer doubles
+// the loads in flight -- but a compute unit wants some 40-70 KB in flight, so small n takes more of them.
 rps::LaunchTuning default_tuning(int32_t n, int32_t dtype, int grad_mode) {
-    if (grad_mode == rps::kGradNone) return rps::LaunchTuning{4, 1, 5, 0};
-    if (grad_mode == rps::kGradBuffer) return n >= 12 ? rps::LaunchTuning{2, 1, 5, 0} : rps::LaunchTuning{4, 1, 6, 0};
+    const bool bf16 = dtype == RPS_DTYPE_BF16;
+    if (grad_mode == rps::kGradNone) {
+        // averaging alone: single wavefronts under a cap (fixed at 5 this ran at 0.59 instead of 0.86 at 4
+        // workers, 0.71 / 0.85 at 6, 0.78 / 0.84 at 12); bf16 takes more from 32 workers on (n = 64 0.54 -> 0.63)
+        if (n <= 2) return rps::LaunchTuning{2, 4, 0, 0};
+        int cap = n <= 4 ? 12 : (n <= 7 ? 8 : (n <= 12 ? 6 : 5));
+        if (bf16) cap = n >= 48 ? 12 : (n >= 32 ? 8 : std::max(cap, 6));
+        return rps::LaunchTuning{4, 1, cap, 0};
+    }
+    if (grad_mode == rps::kGradBuffer) {
+        if (n <= 2) return bf16 ? rps::LaunchTuning{2, 4, 0, 0} : rps::LaunchTuning{2, 1, 12, 0};   // 0.51-0.55 -> 0.82
+        if (n <= 4) return rps::LaunchTuning{2, 1, n == 3 ? 12 : 8, 0};                             // 0.63-0.78 -> 0.81-0.82
+        if (n < 12) return rps::LaunchTuning{2, 1, 6, 0};                                           // fp32 n = 8 0.72 -> 0.75
+        if (bf16 && n >= 32) return rps::LaunchTuning{2, 4, 0, 0};                                  // n = 64 0.48 -> 0.60
+        return rps::LaunchTuning{2, 1, 5, 0};
+    }
     // in-register gradient: the workgroup's wavefronts share the LDS copy of the noise cells
-    if (dtype == RPS_DTYPE_BF16) return rps::LaunchTuning{2, 4, 0, 0};
+    if (bf16) return n <= 4 ? rps::LaunchTuning{4, 8, 0, 0} : rps::LaunchTuning{2, 4, 0, 0};   // n = 4 0.69 -> 0.73
+    if (n <= 8) return rps::LaunchTuning{2, 8, n <= 3 ? 0 : 12, 0};   // n = 4 0.62 -> 0.77, n = 6 0.68 -> 0.77, n = 8 0.70 -> 0.72
     return n >= 24 ? rps::LaunchTuning{2, 2, 0, 0} : rps::LaunchTuning{4, 4, 12, 0};
 }
 
