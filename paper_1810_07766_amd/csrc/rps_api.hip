@@ -176,6 +176,23 @@ rps::LaunchTuning tiled_tuning(int n, bool bf16, int grad_mode) {
     return rps::LaunchTuning{4, n >= 16 && (n < 23 || n == 32) ? 14 : 12, 0, 0};
 }
 
+// Occupancy cap of the gradient averaging (it reads X and G: twice the bytes of the averaging alone per
+// wavefront step), from a sweep over 2-64 workers.  Tile-major: single wavefronts with about 34 KB of X in
+// flight per compute unit (8 for 4 KB steps: n = 8 0.80 -> 0.84 of the HBM peak, n = 16 0.82 -> 0.85 against a
+// fixed 12; 6 for the 6-8 KB steps above 32 workers: n = 64 0.78 -> 0.83, bf16 0.73 -> 0.82); fp32 at 28-32
+// (and up to 2) workers: no cap, i.e. one workgroup of 14.  Row-major (workgroups of 4, never fewer than two per compute
+// unit): more of them for the short tiles of few workers (n = 3 0.67 -> 0.80, fp32 n = 6 0.70 -> 0.77), no cap
+// from 48 workers on (fp32 n = 48 0.51 -> 0.61).
+int gradavg_cap(const rps_ctx *ctx) {
+    const int n = ctx->n;
+    if (ctx->flags & RPS_FLAG_LAYOUT_TILED) {
+        if (ctx->dtype == RPS_DTYPE_F32 && (n <= 2 || (n >= 28 && n <= 32))) return 0;
+        const int step_bytes = (8 / rps::gradavg_lane_groups(n)) * n * RPS_TILE_BYTES;
+        return std::min(16, std::max(6, (34816 + step_bytes / 2) / step_bytes));
+    }
+    return n <= 3 ? 24 : (n <= 6 && ctx->dtype == RPS_DTYPE_F32 ? 16 : (n >= 48 ? 0 : 8));
+}
+
 rps::LaunchTuning tuning_for(const rps_ctx *ctx, int grad_mode) {
     if (ctx->tune_set) return ctx->tune;
     if (ctx->flags & RPS_FLAG_LAYOUT_TILED) return tiled_tuning(ctx->n, ctx->dtype == RPS_DTYPE_BF16, grad_mode);
@@ -631,11 +648,7 @@ int rps_round_gradient_averaging(rps_ctx *ctx, void *X, const void *G, uint64_t 
     const int rc = prepare_outcome(ctx, step, prm, tab);
     if (rc != RPS_OK) return rc;
     return commit_outcome(ctx, step, prm, timed_launch(ctx, [&] {
-        // tile-major fp32 with 24 or more workers: no cap (one wide workgroup per compute unit); other tile-major
-        // cases: single wavefronts, at most 12 per compute unit; row-major: the cap of the round on a gradient buffer
-        const int cap = ctx->tune_set ? ctx->tune.max_waves_per_cu
-                        : ((ctx->flags & RPS_FLAG_LAYOUT_TILED) ? (ctx->dtype == RPS_DTYPE_F32 && ctx->n >= 24 ? 0 : 12)
-                                                                : default_tuning(ctx->n, ctx->dtype, rps::kGradBuffer).max_waves_per_cu);
+        const int cap = ctx->tune_set ? ctx->tune.max_waves_per_cu : gradavg_cap(ctx);
         return rps::launch_gradavg(ctx->dtype, X, G, tab, prm, ctx->max_block_cols, cap, ctx->stream);
     }));
 }

@@ -98,6 +98,12 @@ inline NarrowShape narrow_shape(int n, int elem_bytes) {
 // and all entry points of one dtype must share one summation order (fused == unfused bit for bit).
 inline bool narrow_split(int n, int elem_bytes) { return elem_bytes == 4 && n >= 57; }
 
+// Tile-major gradient averaging: lane groups per tile (a lane holds up to two row pairs, or walks more).
+inline int gradavg_lane_groups(int n) {
+    const int pairs = (n + 1) / 2, need = (pairs + 1) / 2;
+    return need > 4 ? 8 : (need > 2 ? 4 : (need > 1 ? 2 : 1));
+}
+
 // Host side of the synthetic gradient noise: the kNoiseGrid radius values sqrt(-2 ln((k + 1/2)/kNoiseGrid))
 // and the kNoiseGrid (cos, sin) pairs of 2 pi (a + 1/2)/kNoiseGrid, each the nearest fp32.
 void build_noise_cells(float *radius, float *cos_sin);

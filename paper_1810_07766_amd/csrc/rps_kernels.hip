@@ -1837,8 +1837,7 @@ hipError_t launch_gradavg(int dtype, void *X, const void *G, const RoundTable *t
     const int vec = dtype == 0 ? 4 : 8;
     if (prm.tiled) {
         // lane groups per tile as in launch_round_narrow: a lane gets two row pairs where the workers allow it
-        const int pairs = (prm.n + 1) / 2, need = (pairs + 1) / 2;
-        const int pg = need > 4 ? 8 : (need > 2 ? 4 : (need > 1 ? 2 : 1));
+        const int pg = gradavg_lane_groups(prm.n);
         const int64_t width = (int64_t)(8 / pg) * kTiledLanes * vec;   // columns per wavefront
         const int64_t steps = (max_block_cols + 2 * width - 2) / width;
         // no cap asked for (the default for fp32 with 24 or more workers: +3 % there, nothing or a loss with
