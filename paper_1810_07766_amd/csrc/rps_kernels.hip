@@ -1631,50 +1631,56 @@ __device__ __forceinline__ void consensus_tile(const ST *__restrict__ X, const R
     }
 }
 
-// The same statistics on the tiled layout.  A wavefront takes U adjacent tiles at a time; lane group
-// lg = lane / 8 holds rows lg, lg + 8, ... (ROWS of them) of its 16-byte column group in each tile,
-// all U * ROWS loads are issued up front (4 or 8 KB in flight per wavefront: U = 4 tiles of up to
-// 8 workers, 2 of up to 16, one of more).  The pivot row 0 is what lane group 0 loaded: the other
-// groups get it by a lane shuffle.  Per column, sum_i y_i^2 needs no exchange (every lane adds its own
-// rows' share to its running total), sum_i y_i is combined over the lane groups by a butterfly and
-// the lanes of group 0 carry the column's -(sum y)^2 / n and mean^2.
-template <typename ST, bool FULL, int ROWS, int U>
+// The same statistics on the tiled layout.  A wavefront step is U units; in a unit a tile takes PG of the
+// 8 lane groups (8 / PG adjacent tiles share it: with 1, 2 or up to 4 workers a tile needs only 1, 2 or 4
+// groups -- dealt one tile per unit, such a step moved 0.5-2 KB and ran at 0.05-0.2 of the HBM peak); lane
+// group lg of a tile holds rows lg, lg + PG, ... (ROWS of them) of its 16-byte column group, all U * ROWS
+// loads are issued up front (about 4 KB in flight per wavefront, 8 KB above 32 workers).  The pivot row 0
+// is what the tile's first lane group loaded: the others get it by a lane shuffle.  Per column,
+// sum_i y_i^2 needs no exchange (every lane adds its own rows' share to its running total), sum_i y_i is
+// combined over the tile's lane groups by a butterfly and the lanes of its first group carry the column's
+// -(sum y)^2 / n and mean^2.
+template <typename ST, bool FULL, int PG, int ROWS, int U>
 __device__ __forceinline__ void consensus_tiles_tiled(const ST *__restrict__ X, const RoundParams &prm, int64_t tile_index,
                                                       int lane, double &dist, double &msq) {
     using S = Storage<ST>;
     using Raw = typename S::Raw;
     constexpr int VEC = S::VEC;
-    constexpr int LPR = kTiledLanes, GROUPS = 64 / LPR, TILE = LPR * VEC;
+    constexpr int LPR = kTiledLanes, TILE = LPR * VEC;
+    constexpr int TPU = (64 / LPR) / PG;   // tiles that share the wavefront in one of its U units
     const int n = prm.n;
-    const int lg = lane / LPR, sub = lane % LPR;
-    const ST *Xt = X + tile_index * TILE * n;   // wave-uniform: first tile of the unit
+    const int lgw = lane / LPR, sub = lane % LPR;
+    const int lg = lgw % PG, tw = lgw / PG;   // the lane's group inside its tile, its tile inside the unit
+    const ST *Xt = X + tile_index * TILE * n;   // wave-uniform: first tile of the step
     const uint32_t tile_elems = (uint32_t)n * TILE;
     const int64_t ntiles = (prm.N + TILE - 1) / TILE;
-    int tiles = (int)(ntiles - tile_index < U ? ntiles - tile_index : U);   // wave-uniform
+    int tiles = (int)(ntiles - tile_index < U * TPU ? ntiles - tile_index : U * TPU);   // wave-uniform
     const uint32_t limit = (uint32_t)tiles * tile_elems * (uint32_t)sizeof(ST);
     Raw x[U][ROWS];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        const int64_t c0 = (tile_index + u) * TILE + sub * VEC;
+        const int t = u * TPU + tw;   // the lane's tile among the step's
+        const int64_t c0 = (tile_index + t) * TILE + sub * VEC;
 #pragma unroll
         for (int k = 0; k < ROWS; ++k) {
-            const int i = lg + GROUPS * k;
+            const int i = lg + PG * k;
             // rows past n and tiles past the last one: an offset at the buffer's bound (FULL: the
             // hardware returns zeros without touching memory) / an empty column range (element-wise)
-            const bool live = i < n && u < tiles;
-            const uint32_t off = live ? (uint32_t)u * tile_elems + (uint32_t)i * TILE + sub * VEC : limit / (uint32_t)sizeof(ST);
+            const bool live = i < n && t < tiles;
+            const uint32_t off = live ? (uint32_t)t * tile_elems + (uint32_t)i * TILE + sub * VEC : limit / (uint32_t)sizeof(ST);
             x[u][k] = load_seg<ST, FULL>(Xt, FULL || live ? off : 0u, limit, c0, 0, live ? prm.N : 0);
         }
     }
     const double inv_n = 1.0 / (double)n;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        if (u < tiles) {   // wave-uniform
+        if (u * TPU < tiles) {   // wave-uniform; a lane whose own tile lies past the last one holds zeros and adds 0
             float p[VEC], v[VEC];
             u32x4 bits;
             __builtin_memcpy(&bits, &x[u][0], sizeof(bits));
-            bits.x = __shfl(bits.x, sub, 64); bits.y = __shfl(bits.y, sub, 64);
-            bits.z = __shfl(bits.z, sub, 64); bits.w = __shfl(bits.w, sub, 64);
+            const int pivot = tw * PG * LPR + sub;   // the lane of the tile's first group: row 0
+            bits.x = __shfl(bits.x, pivot, 64); bits.y = __shfl(bits.y, pivot, 64);
+            bits.z = __shfl(bits.z, pivot, 64); bits.w = __shfl(bits.w, pivot, 64);
             Raw praw;
             __builtin_memcpy(&praw, &bits, sizeof(praw));
             S::unpack(praw, p);                 // row 0 of this lane's column group
@@ -1683,7 +1689,7 @@ __device__ __forceinline__ void consensus_tiles_tiled(const ST *__restrict__ X, 
             for (int e = 0; e < VEC; ++e) s1[e] = 0.0;
 #pragma unroll
             for (int k = 0; k < ROWS; ++k) {
-                if (lg + GROUPS * k < n) {
+                if (lg + PG * k < n) {
                     S::unpack(x[u][k], v);
 #pragma unroll
                     for (int e = 0; e < VEC; ++e) {   // columns outside [0, N) were loaded as 0, their pivot too
@@ -1693,11 +1699,10 @@ __device__ __forceinline__ void consensus_tiles_tiled(const ST *__restrict__ X, 
                     }
                 }
             }
+            // over the tile's lane groups on the cross-lane VALU paths (no LDS permutes: a tile of few workers is
+            // 1 KB or less, and this is its fixed cost)
 #pragma unroll
-            for (int o = LPR; o < 64; o <<= 1) {
-#pragma unroll
-                for (int e = 0; e < VEC; ++e) s1[e] += __shfl_xor(s1[e], o, 64);
-            }
+            for (int e = 0; e < VEC; ++e) s1[e] = sum_lane_groups<PG>(s1[e]);
             if (lg == 0) {
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) {
@@ -1711,18 +1716,19 @@ __device__ __forceinline__ void consensus_tiles_tiled(const ST *__restrict__ X, 
     }
 }
 
-template <typename ST, int ROWS, int U>
+template <typename ST, int PG, int ROWS, int U>
 __device__ __forceinline__ void consensus_walk_tiled(const ST *__restrict__ X, const RoundParams &prm, int wave, int lane,
                                                      double &dist, double &msq) {
     constexpr int TILE = kTiledLanes * Storage<ST>::VEC;
+    constexpr int STEP = U * ((64 / kTiledLanes) / PG);   // tiles per wavefront step
     const int64_t ntiles = (prm.N + TILE - 1) / TILE;
     for (int it = 0;; ++it) {
-        const int64_t t = unit_index(it, 4, wave) * U;
+        const int64_t t = unit_index(it, 4, wave) * STEP;
         if (t >= ntiles) break;   // wave-uniform; later steps lie further on
-        if (prm.vec_ok && (t + U) * TILE <= prm.N)
-            consensus_tiles_tiled<ST, true, ROWS, U>(X, prm, t, lane, dist, msq);
+        if (prm.vec_ok && (t + STEP) * TILE <= prm.N)
+            consensus_tiles_tiled<ST, true, PG, ROWS, U>(X, prm, t, lane, dist, msq);
         else
-            consensus_tiles_tiled<ST, false, ROWS, U>(X, prm, t, lane, dist, msq);
+            consensus_tiles_tiled<ST, false, PG, ROWS, U>(X, prm, t, lane, dist, msq);
     }
 }
 
@@ -1735,14 +1741,22 @@ __global__ __launch_bounds__(256) void consensus_kernel(const ST *__restrict__ X
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     double dist = 0.0, msq = 0.0;
     if (prm.tiled) {
-        if (prm.n <= 8)
-            consensus_walk_tiled<ST, 1, 4>(X, prm, wave, lane, dist, msq);
+        // about 4 KB per wavefront step whatever n is: with up to 4 workers a tile takes 4, 2 or 1 of the 8
+        // lane groups (2, 4 or 8 tiles share a unit), and a step is 4 / 2 / 1 units
+        if (prm.n <= 1)
+            consensus_walk_tiled<ST, 1, 1, 4>(X, prm, wave, lane, dist, msq);
+        else if (prm.n <= 2)
+            consensus_walk_tiled<ST, 2, 1, 4>(X, prm, wave, lane, dist, msq);
+        else if (prm.n <= 4)
+            consensus_walk_tiled<ST, 4, 1, 4>(X, prm, wave, lane, dist, msq);
+        else if (prm.n <= 8)
+            consensus_walk_tiled<ST, 8, 1, 4>(X, prm, wave, lane, dist, msq);
         else if (prm.n <= 16)
-            consensus_walk_tiled<ST, 2, 2>(X, prm, wave, lane, dist, msq);
+            consensus_walk_tiled<ST, 8, 2, 2>(X, prm, wave, lane, dist, msq);
         else if (prm.n <= 32)
-            consensus_walk_tiled<ST, 4, 1>(X, prm, wave, lane, dist, msq);
+            consensus_walk_tiled<ST, 8, 4, 1>(X, prm, wave, lane, dist, msq);
         else
-            consensus_walk_tiled<ST, 8, 1>(X, prm, wave, lane, dist, msq);
+            consensus_walk_tiled<ST, 8, 8, 1>(X, prm, wave, lane, dist, msq);
     } else {
         constexpr int TILE = 64 * VEC;
         const int64_t ntiles = (prm.N + TILE - 1) / TILE;
@@ -1979,9 +1993,10 @@ hipError_t static_scratch(int device, double **out) {
 
 hipError_t launch_consensus(int dtype, const void *X, const RoundParams &prm, double *partials, int max_partials,
                             double *out, hipStream_t stream) {
-    // units of one wavefront step: a tile of 64 lanes x 16 bytes (row-major), or 4 / 2 / 1 tiles of 128 bytes (tiled)
+    // units of one wavefront step: a tile of 64 lanes x 16 bytes (row-major), or 32 ... 1 tiles of 128 bytes (tiled)
     int64_t tile = dtype == 0 ? 256 : 512;
-    if (prm.tiled) tile = (tile / 8) * (prm.n <= 8 ? 4 : (prm.n <= 16 ? 2 : 1));
+    if (prm.tiled)   // as consensus_kernel deals them out
+        tile = (tile / 8) * (prm.n <= 1 ? 32 : (prm.n <= 2 ? 16 : (prm.n <= 4 ? 8 : (prm.n <= 8 ? 4 : (prm.n <= 16 ? 2 : 1)))));
     const int64_t ntiles = (prm.N + tile - 1) / tile;
     int64_t wgs = ((ntiles + 3) / 4 + 7) & ~(int64_t)7;   // unit_index(): a multiple of 8 workgroups
     if (wgs > max_partials) wgs = max_partials;
