@@ -1898,7 +1898,8 @@ hipError_t launch_gradavg(int dtype, void *X, const void *G, const RoundTable *t
     return hipGetLastError();
 }
 
-// Re-arrangement between the two layouts.  A wavefront owns 1 KB of the tile-major array in storage
+constexpr int kConvertUnits = 4;
+// Re-arrangement between the two layouts.  A wavefront unit is 1 KB of the tile-major array in storage
 // order (8 segments of 128 bytes: lane / 8 -> segment, lane % 8 -> 16-byte group) and the matching
 // 128-byte pieces of up to 8 rows of the row-major array.  TO_TILED: padding columns of the last
 // tile are written as zeros.  Byte-wise copy: ELEM is the element size.
@@ -1906,34 +1907,43 @@ template <int ELEM, bool TO_TILED>
 __global__ __launch_bounds__(256) void convert_layout_kernel(void *__restrict__ dst, const void *__restrict__ src, int64_t N,
                                                              int64_t pitch, int n, int aligned) {
     constexpr int LPR = kTiledLanes, VEC = 16 / ELEM, TILE = LPR * VEC;
-    const int64_t q = linear_block() * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    constexpr int U = kConvertUnits;   // 1 KB units per wavefront, adjacent in the tile-major array: all loads, then all stores
+    const int64_t q0 = (linear_block() * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6)) * U;
     const int lane = threadIdx.x & 63;
-    const int64_t seg0 = q * (64 / LPR);
-    int64_t tile = seg0 / n;
-    int i = (int)(seg0 % n) + lane / LPR;
-    while (i >= n) {
-        i -= n;
-        ++tile;
-    }
-    const int64_t c0 = tile * TILE + (lane % LPR) * VEC;
-    if (tile * TILE >= N) return;   // past the last tile
-    const int64_t t_off = ((seg0 + lane / LPR) * TILE + (lane % LPR) * VEC) * ELEM;   // bytes, tile-major array
-    const int64_t r_off = ((int64_t)i * pitch + c0) * ELEM;                           // bytes, row-major array
     char *d = (char *)dst;
     const char *sp = (const char *)src;
-    if (aligned && c0 + VEC <= N) {
-        if (TO_TILED)
-            *reinterpret_cast<u32x4 *>(d + t_off) = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(sp + r_off));
-        else
-            *reinterpret_cast<u32x4 *>(d + r_off) = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(sp + t_off));
-        return;
+    int64_t t_off[U], r_off[U], c0[U];
+    bool live[U], whole[U];
+    u32x4 v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int64_t seg0 = (q0 + u) * (64 / LPR);
+        int64_t tile = seg0 / n;
+        int i = (int)(seg0 % n) + lane / LPR;
+        while (i >= n) {
+            i -= n;
+            ++tile;
+        }
+        c0[u] = tile * TILE + (lane % LPR) * VEC;
+        live[u] = tile * TILE < N;   // not past the last tile
+        whole[u] = live[u] && aligned && c0[u] + VEC <= N;
+        t_off[u] = ((seg0 + lane / LPR) * TILE + (lane % LPR) * VEC) * ELEM;   // bytes, tile-major array
+        r_off[u] = ((int64_t)i * pitch + c0[u]) * ELEM;                         // bytes, row-major array
+        if (whole[u]) v[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(sp + (TO_TILED ? r_off[u] : t_off[u])));
     }
-    for (int e = 0; e < VEC; ++e) {
-        for (int b = 0; b < ELEM; ++b) {
-            if (TO_TILED)
-                d[t_off + e * ELEM + b] = c0 + e < N ? sp[r_off + e * ELEM + b] : (char)0;
-            else if (c0 + e < N)
-                d[r_off + e * ELEM + b] = sp[t_off + e * ELEM + b];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        if (whole[u]) {
+            __builtin_nontemporal_store(v[u], reinterpret_cast<u32x4 *>(d + (TO_TILED ? t_off[u] : r_off[u])));
+        } else if (live[u]) {
+            for (int e = 0; e < VEC; ++e) {
+                for (int b = 0; b < ELEM; ++b) {
+                    if (TO_TILED)
+                        d[t_off[u] + e * ELEM + b] = c0[u] + e < N ? sp[r_off[u] + e * ELEM + b] : (char)0;
+                    else if (c0[u] + e < N)
+                        d[r_off[u] + e * ELEM + b] = sp[t_off[u] + e * ELEM + b];
+                }
+            }
         }
     }
 }
@@ -1943,8 +1953,8 @@ hipError_t launch_convert_layout(int dtype, void *dst, const void *src, int64_t 
     const int elem = dtype == 0 ? 4 : 2;
     const int64_t T = kTiledLanes * (16 / elem);
     const int64_t tiles = (N + T - 1) / T;
-    const int64_t kb = (tiles * n * kTiledLanes + 63) / 64;
-    const dim3 grid = folded_grid((kb + 3) / 4, 1);
+    const int64_t kb = (tiles * n * kTiledLanes + 63) / 64;   // 1 KB units
+    const dim3 grid = folded_grid((kb + 4 * kConvertUnits - 1) / (4 * kConvertUnits), 1);
     if (dtype == 0) {
         if (to_tiled)
             hipLaunchKernelGGL((convert_layout_kernel<4, true>), grid, dim3(256), 0, stream, dst, src, N, pitch, n, (int)aligned);
