@@ -115,7 +115,7 @@ rps::LaunchTuning default_tuning(int32_t n, int32_t dtype, int grad_mode) {
         return rps::LaunchTuning{2, 1, 5, 0};
     }
     // in-register gradient: the workgroup's wavefronts share the LDS copy of the noise cells
-    if (bf16) return n <= 4 ? rps::LaunchTuning{4, 8, 0, 0} : rps::LaunchTuning{2, 4, 0, 0};   // n = 4 0.69 -> 0.73
+    if (bf16) return n <= 4 ? rps::LaunchTuning{n <= 2 ? 2 : 4, 8, 0, 0} : rps::LaunchTuning{2, 4, 0, 0};   // n = 4 0.69 -> 0.73
     if (n <= 8) return rps::LaunchTuning{2, 8, n <= 3 ? 0 : 12, 0};   // n = 4 0.62 -> 0.77, n = 6 0.68 -> 0.77, n = 8 0.70 -> 0.72
     return n >= 24 ? rps::LaunchTuning{2, 2, 0, 0} : rps::LaunchTuning{4, 4, 12, 0};
 }
