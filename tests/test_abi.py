@@ -156,3 +156,16 @@ def test_host_copy_of_the_mask_generator_equals_the_oracle():
             assert e.code == rps.RPS_EINVAL
         else:
             raise AssertionError(f"accepted {bad}")
+
+
+def test_launch_shape_sweep_grid_is_within_the_tuning_interface():
+    """The sweep utility imports without a GPU and only proposes shapes that rps_set_launch_tuning
+    accepts (rows per chunk 2 or 4, 1..16 wavefronts per workgroup, cap >= 0, 0..64 steps)."""
+    from paper_1810_07766_amd import sweep_launch_shapes as sweep
+    for tiled in (True, False):
+        for n in (1, 2, 8, 32, 33, 64):
+            for what in ("round, in-register gradient", "averaging alone", "round, gradient buffer", "gradient averaging"):
+                grid = sweep._grid(what, n, tiled)
+                assert len(grid) >= 5 and len(set(grid)) == len(grid)
+                for rows, wpb, cap, steps in grid:
+                    assert rows in (2, 4) and 1 <= wpb <= 16 and 0 <= cap <= 64 and 0 <= steps <= 64
