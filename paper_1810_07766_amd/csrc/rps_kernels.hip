@@ -1314,7 +1314,7 @@ hipError_t launch_round_split(ST *X, const ST *G, const RoundTable *tab, RoundPa
 // still 3-4 % faster in workgroups of 12 or 14 than in single wavefronts (a workgroup's wavefronts
 // start together on adjacent tiles of their XCD); the averaging alone is fastest in single
 // wavefronts under its occupancy cap.  Row-major, where a tile is n KB: 2, 4 or 8 wavefronts share
-// the cells; the others keep one wavefront per workgroup (or 4, a tuning option).
+// the cells; the others keep one wavefront per workgroup, or 4 (bf16 on a gradient buffer from 32 workers on).
 template <typename ST, int GRAD>
 hipError_t launch_round_t(ST *X, const ST *G, const RoundTable *tab, const RoundParams &prm, int64_t max_block_cols,
                           const LaunchTuning &tune, hipStream_t stream) {
