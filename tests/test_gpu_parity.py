@@ -661,15 +661,15 @@ def test_side_stream_and_interleaved_contexts(rps):
         c.destroy()
 
 
-@pytest.mark.parametrize("tiled", [False, True])
-def test_rounds_can_be_captured_in_a_hip_graph(rps, tiled):
+@pytest.mark.parametrize("tiled,n", [(False, 16), (True, 16), (True, 64)])   # 64 tile-major: two wavefronts share a tile
+def test_rounds_can_be_captured_in_a_hip_graph(rps, tiled, n):
     """The round enqueues kernels only (no allocation, no synchronisation, no memset), so a caller
     may capture a sequence of rounds in a HIP graph: four rounds captured once, replayed three times
     from the same start, every replay equal to the eager result bit for bit.  Between the replays
     the context does eager work whose RESULTS are checked against the oracle: the step the previous
     eager call prepared in advance, a repeated step, the unfused average -- a replay must never
     change the outcome an eager call sees (Alg. 1 steps 6-7: a function of (seed, step) only)."""
-    n, N, p, gamma, seed = 16, 16 * 8192, 0.1, 0.1, 21
+    N, p, gamma, seed = n * 8192, 0.1, 0.1, 21
     off = workloads.block_offsets(n, N)
     X0 = workloads.gaussian_model(n, N, seed=8)
     flags = rps.RPS_FLAG_LAYOUT_TILED if tiled else 0
