@@ -1631,15 +1631,16 @@ __device__ __forceinline__ void consensus_tile(const ST *__restrict__ X, const R
     }
 }
 
-// The same statistics on the tiled layout.  A wavefront step is U units; in a unit a tile takes PG of the
-// 8 lane groups (8 / PG adjacent tiles share it: with 1, 2 or up to 4 workers a tile needs only 1, 2 or 4
-// groups -- dealt one tile per unit, such a step moved 0.5-2 KB and ran at 0.05-0.2 of the HBM peak); lane
-// group lg of a tile holds rows lg, lg + PG, ... (ROWS of them) of its 16-byte column group, all U * ROWS
-// loads are issued up front (about 4 KB in flight per wavefront, 8 KB above 32 workers).  The pivot row 0
-// is what the tile's first lane group loaded: the others get it by a lane shuffle.  Per column,
-// sum_i y_i^2 needs no exchange (every lane adds its own rows' share to its running total), sum_i y_i is
-// combined over the tile's lane groups by a butterfly and the lanes of its first group carry the column's
-// -(sum y)^2 / n and mean^2.
+// The same statistics on the tiled layout with 1 or 2 workers.  A wavefront step is U units; in a unit a
+// tile takes PG of the 8 lane groups (8 / PG adjacent tiles share it); lane group lg of a tile holds rows
+// lg, lg + PG, ... (ROWS of them) of its 16-byte column group, all U * ROWS loads are issued up front
+// (4 KB in flight per wavefront).  The pivot row 0 is what the tile's first lane group loaded: the others
+// get it by a lane shuffle.  Per column, sum_i y_i^2 needs no exchange (every lane adds its own rows'
+// share to its running total), sum_i y_i is combined over the tile's lane groups on the cross-lane VALU
+// paths and the lanes of its first group carry the column's -(sum y)^2 / n and mean^2.  (With more
+// workers this arrangement -- rows dealt over lane groups -- paid a shuffle, a cross-group sum and the
+// closing arithmetic per tile of 1-4 KB: 0.44-0.58 of the HBM peak at 6-8 fp32 workers, 0.21-0.51 for
+// bf16 up to 32; consensus_tiles_by_column below replaced it there.)
 template <typename ST, bool FULL, int PG, int ROWS, int U>
 __device__ __forceinline__ void consensus_tiles_tiled(const ST *__restrict__ X, const RoundParams &prm, int64_t tile_index,
                                                       int lane, double &dist, double &msq) {
@@ -1716,6 +1717,84 @@ __device__ __forceinline__ void consensus_tiles_tiled(const ST *__restrict__ X, 
     }
 }
 
+// The tiled layout walked by columns: a wavefront step is 8 adjacent tiles, lane group lane / 8 takes
+// one of them and its 8 lanes the tile's eight 16-byte column groups, and every lane walks ALL n rows of
+// its own columns (R loads in flight, 128 bytes apart) -- so a column's sums stay in one lane: no pivot
+// shuffle, no sum across lane groups, and the per-column closing arithmetic is paid once per n rows.  A
+// wavefront load instruction fetches eight whole 128-byte segments n * 128 bytes apart; over the n rows
+// the wavefront covers one contiguous run of 8 * n * 128 bytes.
+template <typename ST, bool FULL>
+__device__ __forceinline__ void consensus_tiles_by_column(const ST *__restrict__ X, const RoundParams &prm, int64_t tile_index,
+                                                          int lane, double &dist, double &msq) {
+    using S = Storage<ST>;
+    using Raw = typename S::Raw;
+    constexpr int VEC = S::VEC;
+    constexpr int LPR = kTiledLanes, TILE = LPR * VEC, STEP = 64 / LPR, R = 8;
+    const int n = prm.n;
+    const int tw = lane / LPR, sub = lane % LPR;
+    const ST *Xt = X + tile_index * TILE * n;   // wave-uniform: first tile of the step
+    const uint32_t tile_elems = (uint32_t)n * TILE;
+    const int64_t ntiles = (prm.N + TILE - 1) / TILE;
+    const int tiles = (int)(ntiles - tile_index < STEP ? ntiles - tile_index : STEP);   // wave-uniform
+    const uint32_t limit = (uint32_t)tiles * tile_elems * (uint32_t)sizeof(ST);
+    const bool live = tw < tiles;   // a lane whose tile lies past the last one loads zeros and adds 0
+    const int64_t c0 = (tile_index + tw) * TILE + sub * VEC;
+    const uint32_t base = (uint32_t)tw * tile_elems + sub * VEC;
+    const auto load = [&](int i) {
+        // tiles past the last one: an offset at the buffer's bound (FULL: the hardware returns zeros
+        // without touching memory) / an empty column range (element-wise)
+        const uint32_t off = live ? base + (uint32_t)i * TILE : limit / (uint32_t)sizeof(ST);
+        return load_seg<ST, FULL>(Xt, FULL || live ? off : 0u, limit, c0, 0, live ? prm.N : 0);
+    };
+    float p[VEC], v[VEC];
+    S::unpack(load(0), p);   // row 0 is the pivot of the lane's columns
+    double s1[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) s1[e] = 0.0;
+    for (int i = 1; i < n; i += R) {   // chunks of up to R rows, all of a chunk's loads issued before the arithmetic
+        Raw x[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+            if (i + r < n) x[r] = load(i + r);   // wave-uniform
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            if (i + r < n) {
+                S::unpack(x[r], v);
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) {   // columns outside [0, N) were loaded as 0, their pivot too
+                    const double y = (double)v[e] - (double)p[e];
+                    s1[e] += y;
+                    dist = __builtin_fma(y, y, dist);
+                }
+            }
+        }
+    }
+    const double inv_n = 1.0 / (double)n;
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+        const double m = s1[e] * inv_n;
+        dist = __builtin_fma(-s1[e], m, dist);
+        const double mean = (double)p[e] + m;
+        msq = __builtin_fma(mean, mean, msq);
+    }
+}
+
+template <typename ST>
+__device__ __forceinline__ void consensus_walk_by_column(const ST *__restrict__ X, const RoundParams &prm, int wave, int lane,
+                                                         double &dist, double &msq) {
+    constexpr int TILE = kTiledLanes * Storage<ST>::VEC;
+    constexpr int STEP = 64 / kTiledLanes;
+    const int64_t ntiles = (prm.N + TILE - 1) / TILE;
+    for (int it = 0;; ++it) {
+        const int64_t t = unit_index(it, 4, wave) * STEP;
+        if (t >= ntiles) break;   // wave-uniform; later steps lie further on
+        if (prm.vec_ok && (t + STEP) * TILE <= prm.N)
+            consensus_tiles_by_column<ST, true>(X, prm, t, lane, dist, msq);
+        else
+            consensus_tiles_by_column<ST, false>(X, prm, t, lane, dist, msq);
+    }
+}
+
 template <typename ST, int PG, int ROWS, int U>
 __device__ __forceinline__ void consensus_walk_tiled(const ST *__restrict__ X, const RoundParams &prm, int wave, int lane,
                                                      double &dist, double &msq) {
@@ -1741,22 +1820,14 @@ __global__ __launch_bounds__(256) void consensus_kernel(const ST *__restrict__ X
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     double dist = 0.0, msq = 0.0;
     if (prm.tiled) {
-        // about 4 KB per wavefront step whatever n is: with up to 4 workers a tile takes 4, 2 or 1 of the 8
-        // lane groups (2, 4 or 8 tiles share a unit), and a step is 4 / 2 / 1 units
+        // from 3 workers on every lane walks all rows of its own columns; with 1 or 2 workers that would be 1-2 KB
+        // per wavefront step, and a tile is dealt to 1 or 2 lane groups instead (4 units of 8 or 4 tiles: 4 KB)
         if (prm.n <= 1)
             consensus_walk_tiled<ST, 1, 1, 4>(X, prm, wave, lane, dist, msq);
         else if (prm.n <= 2)
             consensus_walk_tiled<ST, 2, 1, 4>(X, prm, wave, lane, dist, msq);
-        else if (prm.n <= 4)
-            consensus_walk_tiled<ST, 4, 1, 4>(X, prm, wave, lane, dist, msq);
-        else if (prm.n <= 8)
-            consensus_walk_tiled<ST, 8, 1, 4>(X, prm, wave, lane, dist, msq);
-        else if (prm.n <= 16)
-            consensus_walk_tiled<ST, 8, 2, 2>(X, prm, wave, lane, dist, msq);
-        else if (prm.n <= 32)
-            consensus_walk_tiled<ST, 8, 4, 1>(X, prm, wave, lane, dist, msq);
         else
-            consensus_walk_tiled<ST, 8, 8, 1>(X, prm, wave, lane, dist, msq);
+            consensus_walk_by_column<ST>(X, prm, wave, lane, dist, msq);
     } else {
         constexpr int TILE = 64 * VEC;
         const int64_t ntiles = (prm.N + TILE - 1) / TILE;
@@ -2003,10 +2074,9 @@ hipError_t static_scratch(int device, double **out) {
 
 hipError_t launch_consensus(int dtype, const void *X, const RoundParams &prm, double *partials, int max_partials,
                             double *out, hipStream_t stream) {
-    // units of one wavefront step: a tile of 64 lanes x 16 bytes (row-major), or 32 ... 1 tiles of 128 bytes (tiled)
+    // units of one wavefront step: a tile of 64 lanes x 16 bytes (row-major), or 32 / 16 / 8 tiles of 128 bytes (tiled)
     int64_t tile = dtype == 0 ? 256 : 512;
-    if (prm.tiled)   // as consensus_kernel deals them out
-        tile = (tile / 8) * (prm.n <= 1 ? 32 : (prm.n <= 2 ? 16 : (prm.n <= 4 ? 8 : (prm.n <= 8 ? 4 : (prm.n <= 16 ? 2 : 1)))));
+    if (prm.tiled) tile = (tile / 8) * (prm.n <= 1 ? 32 : (prm.n <= 2 ? 16 : 8));   // as consensus_kernel deals them out
     const int64_t ntiles = (prm.N + tile - 1) / tile;
     int64_t wgs = ((ntiles + 3) / 4 + 7) & ~(int64_t)7;   // unit_index(): a multiple of 8 workgroups
     if (wgs > max_partials) wgs = max_partials;
