@@ -1585,7 +1585,7 @@ __device__ __forceinline__ void consensus_tile(const ST *__restrict__ X, const R
                                                double &dist, double &msq) {
     using S = Storage<ST>;
     constexpr int VEC = S::VEC;
-    constexpr int R = 4;
+    constexpr int R = 8;
     const int n = prm.n;
     const ST *row = X + lc.tile0;
     float p[VEC];
@@ -1593,32 +1593,24 @@ __device__ __forceinline__ void consensus_tile(const ST *__restrict__ X, const R
     double s1[VEC], s2[VEC];
 #pragma unroll
     for (int e = 0; e < VEC; ++e) s1[e] = s2[e] = 0.0;
-    int i = 1;
     row += prm.stride;
-    for (; i + R <= n; i += R) {
+    for (int i = 1; i < n; i += R, row += (int64_t)R * prm.stride) {   // chunks of up to R rows: loads first
         typename S::Raw x[R];
 #pragma unroll
-        for (int r = 0; r < R; ++r, row += prm.stride) x[r] = load_raw<ST, FULL>(row, lc);
+        for (int r = 0; r < R; ++r)
+            if (i + r < n) x[r] = load_raw<ST, FULL>(row + (int64_t)r * prm.stride, lc);   // wave-uniform
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            float v[VEC];
-            S::unpack(x[r], v);
+            if (i + r < n) {
+                float v[VEC];
+                S::unpack(x[r], v);
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) {
-                const double y = (double)v[e] - (double)p[e];
-                s1[e] += y;
-                s2[e] = __builtin_fma(y, y, s2[e]);
+                for (int e = 0; e < VEC; ++e) {
+                    const double y = (double)v[e] - (double)p[e];
+                    s1[e] += y;
+                    s2[e] = __builtin_fma(y, y, s2[e]);
+                }
             }
-        }
-    }
-    for (; i < n; ++i, row += prm.stride) {
-        float v[VEC];
-        S::unpack(load_raw<ST, FULL>(row, lc), v);
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) {
-            const double y = (double)v[e] - (double)p[e];
-            s1[e] += y;
-            s2[e] = __builtin_fma(y, y, s2[e]);
         }
     }
     const double inv_n = 1.0 / (double)n;
