@@ -168,16 +168,16 @@ rps::LaunchTuning tiled_tuning(int n, bool bf16, int grad_mode) {
     // in-register gradient: the workgroup's wavefronts share one LDS copy of the noise cells.  fp32 (81-90
     // registers): one workgroup of 14 per compute unit (12 below 16 workers; also 12 at 23-31 workers, whose
     // tiles leave row slots idle: n = 24 0.73 -> 0.76, n = 28 0.76 -> 0.78); three row pairs (125
-    // registers): two workgroups of 8 (n = 18 0.72 -> 0.77, n = 20 0.74 -> 0.77).  bf16 (128-139 registers,
-    // 200 on three row pairs): two workgroups of 8, one of 12 up to 16 workers, workgroups of 4 on three
-    // row pairs (n = 10 0.61 -> 0.65, n = 12 0.69 -> 0.72, n = 24 0.68 -> 0.70)
+    // registers): two workgroups of 8 (n = 18 0.72 -> 0.77, n = 20 0.74 -> 0.77).  bf16 (112-128 registers,
+    // 150 on three row pairs): two workgroups of 8; up to 16 workers one of 12, two of 8 or four of 4 as
+    // the tile takes 1, 2 or 4 lane groups; workgroups of 4 on three row pairs
     // Steps per wavefront (0 = the launcher's default: 1 for fp32, 2 for bf16): more where a step is well under
     // 4 KB, so that a workgroup's copy of the noise cells is spread over enough data (fp32 n = 1 0.52 -> 0.70,
     // n = 2 0.79 -> 0.82, n = 5 0.71 -> 0.75)
     const int per_4k = std::min(4, (4096 + step_bytes / 2) / step_bytes);
     const int steps = per_4k > (bf16 ? 2 : 1) ? per_4k : 0;
     if (three) return rps::LaunchTuning{4, bf16 ? 4 : 8, 0, steps};
-    if (bf16) return rps::LaunchTuning{4, n > 16 ? 8 : (shape.lane_groups == 4 ? 4 : 12), 0, steps};   // 13-16 workers: 0.70 -> 0.72 in workgroups of 4
+    if (bf16) return rps::LaunchTuning{4, n > 16 ? 8 : (shape.lane_groups == 4 ? 4 : (shape.lane_groups == 2 ? 8 : 12)), 0, steps};   // up to 16 workers: 119-120 registers
     return rps::LaunchTuning{4, n >= 16 && (n < 23 || n == 32) ? 14 : 12, 0, steps};
 }
 

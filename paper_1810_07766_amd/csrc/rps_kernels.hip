@@ -854,16 +854,33 @@ struct NarrowTile {
     }
 
     __device__ __forceinline__ void process_chunk(int k0, const Raw x[2 * CP], const Raw g[CG], Acc acc[VEC]) const {
-        // the noise does not depend on the loaded values: all of it first, under the loads' latency
-        float za[CP][VEC], zb[CP][VEC];
-        if (GRAD == kGradSynthetic) {
+        if (GRAD == kGradSynthetic && sizeof(ST) == 2 && (CP >= 3 || (CP == 2 && PG < 8))) {
+            // bf16 (8 values per lane and row, bound by this arithmetic rather than by the loads) on three row pairs,
+            // or on two with fewer than 8 lane groups: pair by pair, so that only one pair's noise is live -- 200 -> 150
+            // and 139 -> 119 registers per lane, i.e. 12 instead of 8 and 16 instead of 12 wavefronts per compute
+            // unit (n = 18 0.57 -> 0.64 of the HBM peak, n = 20 0.62 -> 0.67, n = 16 0.73 -> 0.76); the first pair's
+            // noise still runs under the loads' latency.  (Two pairs on all 8 lane groups, 17-32 workers, already fit
+            // 128 registers and are 3 % faster with all the noise first.)
 #pragma unroll
-            for (int q = 0; q < CP; ++q) noise_rows<VEC>(prm, lds, pair0 + (row_a(k0 + q) >> 1), quad_hi, quad_lo, za[q], zb[q]);
-        }
+            for (int q = 0; q < CP; ++q) {
+                float za[VEC], zb[VEC];
+                noise_rows<VEC>(prm, lds, pair0 + (row_a(k0 + q) >> 1), quad_hi, quad_lo, za, zb);
+                row(k0 + q, 0, x[2 * q], g[0], za, acc);
+                row(k0 + q, 1, x[2 * q + 1], g[0], zb, acc);
+            }
+        } else {
+            // the noise does not depend on the loaded values: all of it first, under the loads' latency
+            float za[CP][VEC], zb[CP][VEC];
+            if (GRAD == kGradSynthetic) {
 #pragma unroll
-        for (int q = 0; q < CP; ++q) {
-            row(k0 + q, 0, x[2 * q], g[GRAD == kGradBuffer ? 2 * q : 0], za[q], acc);
-            row(k0 + q, 1, x[2 * q + 1], g[GRAD == kGradBuffer ? 2 * q + 1 : 0], zb[q], acc);
+                for (int q = 0; q < CP; ++q)
+                    noise_rows<VEC>(prm, lds, pair0 + (row_a(k0 + q) >> 1), quad_hi, quad_lo, za[q], zb[q]);
+            }
+#pragma unroll
+            for (int q = 0; q < CP; ++q) {
+                row(k0 + q, 0, x[2 * q], g[GRAD == kGradBuffer ? 2 * q : 0], za[q], acc);
+                row(k0 + q, 1, x[2 * q + 1], g[GRAD == kGradBuffer ? 2 * q + 1 : 0], zb[q], acc);
+            }
         }
 #pragma unroll
         for (int q = 0; q < 2 * CP; ++q) asm volatile("" ::"v"(x[q]));   // see process_chunk of the wide kernel
